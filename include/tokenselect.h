@@ -1,0 +1,132 @@
+/*
+ * tokenselect.h -- C ABI of the MI355X (gfx950) TokenSelect hot path.
+ *
+ * One decode step of one attention layer (Fig. 4; Algorithm 1) is five calls on one HIP stream:
+ *
+ *   ts_selcache_check     Algorithm 1, the condition and the C_Q / first-flag update
+ *   ts_paged_qk_scores    Algorithm 2 (Paged Dot Product Kernel) + per-head softmax statistics
+ *   ts_soft_vote          Eq. 5, per-head softmax over tokens summed over heads
+ *   ts_topk               the TopK of Eq. 5 (radix select, ties to the lower token index)
+ *   ts_sparse_paged_attn  Eq. 2, attention over the selected tokens read through the page table
+ *
+ * Conventions
+ *   - Every pointer marked [device] is caller-owned device memory; [host] is host memory.
+ *     The library never allocates, frees, synchronises the stream or reads device memory on the
+ *     host.  `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - Every function returns TS_OK (0) or a negative ts_status.  Argument errors are detected on
+ *     the host before anything is launched; nothing has been written in that case.
+ *   - Inputs containing NaN/Inf give unspecified results (no fault).
+ *   - Sequences whose skip[b] byte is non-zero are left untouched by the three selection calls
+ *     (their previous idx / count stay valid: Algorithm 1's "I <- C_I" branch).
+ *   - Calls that share a workspace must not overlap in time (one stream, or ordered streams).
+ *
+ * Paged KV layout (the paper's K in R^{N_kv x H_kv x D} with index list I, Algorithm 2, grouped in
+ * pages): pool[num_pages][page_size][H_kv][D]; logical token t of sequence b lives in physical slot
+ * page_indices[page_indptr[b] + t / page_size] * page_size + t % page_size.
+ * GQA: query head h reads KV head h / (H / H_kv).
+ */
+#ifndef TOKENSELECT_H_
+#define TOKENSELECT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum ts_status {
+  TS_OK = 0,
+  TS_ERR_INVALID_ARG = -1, /* NULL pointer, non-positive size, H % H_kv != 0, k <= 0, ...         */
+  TS_ERR_UNSUPPORTED = -2, /* shape / dtype / page size outside what the kernels are built for    */
+  TS_ERR_WORKSPACE = -3,   /* workspace missing or smaller than ts_workspace_bytes()              */
+  TS_ERR_HIP = -4          /* a HIP launch reported an error                                      */
+} ts_status;
+
+typedef enum ts_dtype { TS_F32 = 0, TS_BF16 = 1 } ts_dtype;
+
+/* Shape and paged-pool description shared by all calls.  Passed by const pointer [host]. */
+typedef struct ts_problem {
+  int32_t batch;        /* B  >= 1                                                               */
+  int32_t chunk;        /* C  queries per sequence; 1 = decode                                   */
+  int32_t num_q_heads;  /* H  (<= 128)                                                           */
+  int32_t num_kv_heads; /* H_kv, a power of two, H % H_kv == 0, H / H_kv <= 8                    */
+  int32_t head_dim;     /* D  in {64, 128}                                                       */
+  int32_t page_size;    /* P  a power of two with P * min(H_kv, 8) % 8 == 0 (16 in the configs)   */
+  int32_t max_seq_len;  /* host-known upper bound on every seq_lens[b]; also the row stride of    */
+                        /* scores[B][H][max_seq_len] and votes[B][max_seq_len]                    */
+  int32_t dtype;        /* ts_dtype of q, k_pool, v_pool, cached_q and out                        */
+  const void* k_pool;   /* [device] [num_pages][P][H_kv][D]                                      */
+  const void* v_pool;   /* [device] same layout (may be NULL for calls that do not read V)        */
+  const int32_t* page_indptr;  /* [device] [B+1] CSR offsets into page_indices                    */
+  const int32_t* page_indices; /* [device] physical page ids in logical order                     */
+  const int32_t* seq_lens;     /* [device] [B] cached tokens N_b (0 <= N_b <= max_seq_len)        */
+} ts_problem;
+
+/* Library version (major*10000 + minor*100 + patch).  Host only. */
+int32_t ts_version(void);
+
+/* Static string for a ts_status value.  Host only. */
+const char* ts_strerror(int32_t status);
+
+/* Bytes of device workspace that the calls below need for this problem when selecting at most
+ * `k` tokens.  One workspace serves all five calls of a step.  [host] out. */
+int32_t ts_workspace_bytes(const ts_problem* p, int32_t k, size_t* bytes);
+
+/* Clears a fresh workspace (launches a fill kernel on `stream`; safe under graph capture).  Must
+ * run once before the first use of a workspace; the kernels leave it ready for the next call. */
+int32_t ts_workspace_init(void* ws, size_t ws_bytes, void* stream);
+
+/* Algorithm 2 (Paged Dot Product Kernel).  For every sequence b, head h, cached token t < N_b:
+ *   scores[b][h][t] = < q[b][0][h][:], K[slot(b,t)][h / G][:] >          (raw, unscaled)
+ * and, feeding Eq. 5, per (b,h):
+ *   row_stats[b][h][0] = max_t scores[b][h][t]
+ *   row_stats[b][h][1] = sum_t exp(score_scale * (scores[b][h][t] - max))   (0 when N_b == 0)
+ * q [device] [B][C][H][D]; scores [device] float [B][H][max_seq_len] (entries t >= N_b untouched);
+ * row_stats [device] float [B][H][2]; score_scale >= 0 (Eq. 5 as printed uses 1).
+ * Decode only: chunk must be 1 (TS_ERR_UNSUPPORTED otherwise). */
+int32_t ts_paged_qk_scores(const ts_problem* p, const void* q, float* scores, float* row_stats, float score_scale,
+                           const uint8_t* skip /* [device] [B] or NULL */, void* ws, size_t ws_bytes, void* stream);
+
+/* Eq. 5 (head soft vote):  votes[b][t] = sum_h exp(score_scale*(scores[b][h][t] - max_h)) / sumexp_h
+ * for t < N_b, computed in double precision from the float scores and rounded once to float.
+ * votes [device] float [B][max_seq_len] (entries t >= N_b untouched). */
+int32_t ts_soft_vote(const ts_problem* p, const float* scores, const float* row_stats, float score_scale,
+                     float* votes, const uint8_t* skip, void* stream);
+
+/* TopK of Eq. 3-5 over votes[b][0..N_b): the min(k, N_b) largest values, equal values taken in
+ * order of increasing token index, written as ascending logical token ids.
+ * idx [device] int32 [B][k] (slots past the count are set to -1); count [device] int32 [B].
+ * -0.0 compares equal to +0.0. */
+int32_t ts_topk(const ts_problem* p, const float* votes, int32_t k, int32_t* idx, int32_t* count,
+                const uint8_t* skip, void* ws, size_t ws_bytes, void* stream);
+
+/* Algorithm 1 (Selection Cache), condition and state update, per sequence b:
+ *   reuse[b] = (first[b] == 0) and cos(q[b], cached_q[b]) >= theta      (one cosine over H*D values,
+ *   double precision; a zero-norm operand gives cos = 0)
+ *   on a miss: cached_q[b] <- q[b], first[b] <- 0.
+ * Passing reuse as `skip` to the three calls above and keeping idx/count as the cached C_I gives
+ * the whole algorithm.  q, cached_q [device] [B][H][D] in p->dtype (chunk must be 1);
+ * first [device] uint8 [B] in/out; reuse [device] uint8 [B] out. */
+int32_t ts_selcache_check(const ts_problem* p, const void* q, void* cached_q, uint8_t* first, float theta,
+                          uint8_t* reuse, void* stream);
+
+/* Eq. 2 (selective sparse attention), decode form (chunk == 1): for every b, h
+ *   out[b][0][h][:] = sum_j softmax_j( <q[b][0][h], K[slot(b, idx[b][j])][h/G]> * sm_scale ) * V[slot(b, idx[b][j])][h/G]
+ * over j < count[b]; float accumulation, result rounded to p->dtype.  idx [device] int32 [B][k]
+ * (logical token ids, k = idx_stride); count [device] int32 [B]; out [device] [B][C][H][D];
+ * lse [device] float [B][C][H] or NULL (log-sum-exp of the scaled logits).  count[b] == 0 gives
+ * out = 0 and lse = -inf. */
+int32_t ts_sparse_paged_attn(const ts_problem* p, const void* q, const int32_t* idx, int32_t idx_stride,
+                             const int32_t* count, float sm_scale, void* out, float* lse, void* ws,
+                             size_t ws_bytes, void* stream);
+
+/* Tuning knob for benchmarks and tests (process-wide, not thread-safe, not part of the method):
+ * variant 0 = score pass with fma arithmetic, 1 = packed bf16 dot2 arithmetic (bf16 inputs only);
+ * wg = workgroups per sequence in the score pass, 0 = automatic.  Host only. */
+int32_t ts_debug_set_score_variant(int32_t variant, int32_t wg);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TOKENSELECT_H_ */

@@ -1,0 +1,156 @@
+"""ctypes binding of include/tokenselect.h: argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU (PyTorch is used for device memory
+and streams, nothing else) and forwards their data pointers; all arithmetic runs in the HIP kernels
+of libtokenselect.so.  There is no CPU fallback: if the library is missing, load() raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import re
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libtokenselect.so")
+_HEADER = os.path.join(os.path.dirname(_HERE), "include", "tokenselect.h")
+
+TS_F32, TS_BF16 = 0, 1
+
+
+class TokenSelectError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s (%d)" % (where, ts_strerror(status), status))
+
+
+class _CProblem(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("chunk", ctypes.c_int32), ("num_q_heads", ctypes.c_int32),
+        ("num_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("page_size", ctypes.c_int32),
+        ("max_seq_len", ctypes.c_int32), ("dtype", ctypes.c_int32),
+        ("k_pool", ctypes.c_void_p), ("v_pool", ctypes.c_void_p), ("page_indptr", ctypes.c_void_p),
+        ("page_indices", ctypes.c_void_p), ("seq_lens", ctypes.c_void_p),
+    ]
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def declared_symbols():
+    """Names of the functions include/tokenselect.h declares."""
+    text = open(_HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ts_[a-z_]+)\s*\(", text)))
+
+
+def load():
+    """Loads libtokenselect.so (built by paper_2411_02886_amd.build).  Raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError("%s is missing: run `python -m paper_2411_02886_amd.build` (no CPU fallback exists)"
+                                    % _LIB_PATH)
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, i32, f32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
+        pp = ctypes.POINTER(_CProblem)
+        L.ts_version.restype = i32
+        L.ts_strerror.restype = ctypes.c_char_p
+        L.ts_strerror.argtypes = [i32]
+        L.ts_workspace_bytes.argtypes = [pp, i32, ctypes.POINTER(sz)]
+        L.ts_workspace_init.argtypes = [vp, sz, vp]
+        L.ts_paged_qk_scores.argtypes = [pp, vp, vp, vp, f32, vp, vp, sz, vp]
+        L.ts_soft_vote.argtypes = [pp, vp, vp, f32, vp, vp, vp]
+        L.ts_topk.argtypes = [pp, vp, i32, vp, vp, vp, vp, sz, vp]
+        L.ts_selcache_check.argtypes = [pp, vp, vp, vp, f32, vp, vp]
+        L.ts_sparse_paged_attn.argtypes = [pp, vp, vp, i32, vp, f32, vp, vp, vp, sz, vp]
+        L.ts_debug_set_score_variant.argtypes = [i32, i32]
+        for name in ("ts_workspace_bytes", "ts_workspace_init", "ts_paged_qk_scores", "ts_soft_vote", "ts_topk",
+                     "ts_selcache_check", "ts_sparse_paged_attn", "ts_debug_set_score_variant"):
+            getattr(L, name).restype = i32
+        _lib = L
+    return _lib
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    return getattr(stream, "cuda_stream", stream) or None
+
+
+def _ok(status: int, where: str) -> None:
+    if status != 0:
+        raise TokenSelectError(status, where)
+
+
+class Problem:
+    """ts_problem plus references that keep the tensors it points at alive."""
+
+    def __init__(self, *, batch, chunk=1, num_q_heads, num_kv_heads, head_dim, page_size, max_seq_len, dtype,
+                 k_pool, v_pool, page_indptr, page_indices, seq_lens):
+        self._keep = (k_pool, v_pool, page_indptr, page_indices, seq_lens)
+        self.c = _CProblem(batch, chunk, num_q_heads, num_kv_heads, head_dim, page_size, max_seq_len, dtype,
+                           _ptr(k_pool), _ptr(v_pool), _ptr(page_indptr), _ptr(page_indices), _ptr(seq_lens))
+
+    def ref(self):
+        return ctypes.byref(self.c)
+
+
+def ts_version() -> int:
+    return int(load().ts_version())
+
+
+def ts_strerror(status: int) -> str:
+    return load().ts_strerror(int(status)).decode()
+
+
+def ts_workspace_bytes(p: Problem, k: int) -> int:
+    out = ctypes.c_size_t(0)
+    _ok(load().ts_workspace_bytes(p.ref(), int(k), ctypes.byref(out)), "ts_workspace_bytes")
+    return int(out.value)
+
+
+def ts_workspace_init(ws, stream=None) -> None:
+    _ok(load().ts_workspace_init(_ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "ts_workspace_init")
+
+
+def ts_debug_set_score_variant(variant: int, wg: int = 0) -> None:
+    _ok(load().ts_debug_set_score_variant(int(variant), int(wg)), "ts_debug_set_score_variant")
+
+
+def ts_paged_qk_scores(p: Problem, q, scores, row_stats, score_scale: float, skip, ws, stream=None) -> None:
+    _ok(load().ts_paged_qk_scores(p.ref(), _ptr(q), _ptr(scores), _ptr(row_stats), float(score_scale), _ptr(skip),
+                                  _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)),
+        "ts_paged_qk_scores")
+
+
+def ts_soft_vote(p: Problem, scores, row_stats, score_scale: float, votes, skip, stream=None) -> None:
+    _ok(load().ts_soft_vote(p.ref(), _ptr(scores), _ptr(row_stats), float(score_scale), _ptr(votes), _ptr(skip),
+                            _stream(stream)), "ts_soft_vote")
+
+
+def ts_topk(p: Problem, votes, k: int, idx, count, skip, ws, stream=None) -> None:
+    _ok(load().ts_topk(p.ref(), _ptr(votes), int(k), _ptr(idx), _ptr(count), _ptr(skip), _ptr(ws),
+                       ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)), "ts_topk")
+
+
+def ts_selcache_check(p: Problem, q, cached_q, first, theta: float, reuse, stream=None) -> None:
+    _ok(load().ts_selcache_check(p.ref(), _ptr(q), _ptr(cached_q), _ptr(first), float(theta), _ptr(reuse),
+                                 _stream(stream)), "ts_selcache_check")
+
+
+def ts_sparse_paged_attn(p: Problem, q, idx, idx_stride: int, count, sm_scale: float, out, lse, ws,
+                         stream=None) -> None:
+    _ok(load().ts_sparse_paged_attn(p.ref(), _ptr(q), _ptr(idx), int(idx_stride), _ptr(count), float(sm_scale),
+                                    _ptr(out), _ptr(lse), _ptr(ws),
+                                    ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)),
+        "ts_sparse_paged_attn")

@@ -1,0 +1,181 @@
+// C ABI of the library: argument validation, workspace carving and kernel launches.
+#include "ts_kernels.h"
+
+namespace ts {
+
+__global__ void fill_zero_kernel(uint32_t* p, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0u;
+}
+
+static int ilog2(int x) { int s = 0; while ((1 << s) < x) ++s; return s; }
+static bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+
+// shape checks shared by all calls; returns TS_OK or an error
+static int32_t check_problem(const ts_problem* p) {
+  if (p == nullptr) return TS_ERR_INVALID_ARG;
+  if (p->batch < 1 || p->chunk < 1 || p->num_q_heads < 1 || p->num_kv_heads < 1 || p->head_dim < 1 ||
+      p->page_size < 1 || p->max_seq_len < 1)
+    return TS_ERR_INVALID_ARG;
+  if (p->num_q_heads % p->num_kv_heads != 0) return TS_ERR_INVALID_ARG;
+  if (p->dtype != TS_F32 && p->dtype != TS_BF16) return TS_ERR_INVALID_ARG;
+  if (p->page_indptr == nullptr || p->page_indices == nullptr || p->seq_lens == nullptr) return TS_ERR_INVALID_ARG;
+  if (p->head_dim != 64 && p->head_dim != 128) return TS_ERR_UNSUPPORTED;
+  if (p->num_q_heads > 128) return TS_ERR_UNSUPPORTED;
+  if (!is_pow2(p->num_kv_heads)) return TS_ERR_UNSUPPORTED;
+  if (p->num_q_heads / p->num_kv_heads > 8) return TS_ERR_UNSUPPORTED;
+  if (!is_pow2(p->page_size)) return TS_ERR_UNSUPPORTED;
+  const int hb = p->num_kv_heads < 8 ? p->num_kv_heads : 8;
+  if ((p->page_size * hb) % 8 != 0 && p->page_size != 1) return TS_ERR_UNSUPPORTED;
+  if ((int64_t)p->batch * p->num_q_heads * (int64_t)p->max_seq_len > ((int64_t)1 << 40)) return TS_ERR_UNSUPPORTED;
+  return TS_OK;
+}
+
+static int g_score_variant = 0;   // 0 = fma, 1 = packed bf16 dot2 (tuning knob, see ts_debug_set_score_variant)
+static int g_score_wg = 0;        // 0 = automatic
+
+}  // namespace ts
+
+using namespace ts;
+
+extern "C" {
+
+int32_t ts_version(void) { return 100; }
+
+const char* ts_strerror(int32_t status) {
+  switch (status) {
+    case TS_OK: return "ok";
+    case TS_ERR_INVALID_ARG: return "invalid argument";
+    case TS_ERR_UNSUPPORTED: return "unsupported shape, dtype or page size";
+    case TS_ERR_WORKSPACE: return "workspace missing or too small";
+    case TS_ERR_HIP: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+int32_t ts_workspace_bytes(const ts_problem* p, int32_t k, size_t* bytes) {
+  if (bytes == nullptr || k < 1) return TS_ERR_INVALID_ARG;
+  const int32_t st = check_problem(p);
+  if (st != TS_OK) return st;
+  *bytes = ws_layout(p, k).total;
+  return TS_OK;
+}
+
+int32_t ts_workspace_init(void* ws, size_t ws_bytes, void* stream) {
+  if (ws == nullptr || ws_bytes == 0 || (ws_bytes & 3) != 0 || ((uintptr_t)ws & 255) != 0) return TS_ERR_INVALID_ARG;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(256), dim3(256), 0, (hipStream_t)stream, (uint32_t*)ws, ws_bytes / 4);
+  return hipGetLastError() == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
+/* Tuning knobs used by the benchmark and the tests to compare kernel variants; not part of the
+ * method.  variant: 0 = fma arithmetic, 1 = packed bf16 dot2; wg: workgroups per sequence in the
+ * score pass (0 = automatic). */
+int32_t ts_debug_set_score_variant(int32_t variant, int32_t wg) {
+  if (variant < 0 || variant > 1 || wg < 0 || wg > kScoreMaxWg) return TS_ERR_INVALID_ARG;
+  g_score_variant = variant; g_score_wg = wg;
+  return TS_OK;
+}
+
+int32_t ts_paged_qk_scores(const ts_problem* p, const void* q, float* scores, float* row_stats, float score_scale,
+                           const uint8_t* skip, void* ws, size_t ws_bytes, void* stream) {
+  int32_t st = check_problem(p);
+  if (st != TS_OK) return st;
+  if (q == nullptr || scores == nullptr || row_stats == nullptr || p->k_pool == nullptr) return TS_ERR_INVALID_ARG;
+  if (!(score_scale >= 0.f) || !(score_scale < 1e30f)) return TS_ERR_INVALID_ARG;
+  if (p->chunk != 1) return TS_ERR_UNSUPPORTED;
+  const WsLayout w = ws_layout(p, 1);
+  if (ws == nullptr || ((uintptr_t)ws & 255) != 0 || ws_bytes < w.topk_blk) return TS_ERR_WORKSPACE;  // needs the sections up to score_partials
+  const int G = p->num_q_heads / p->num_kv_heads;
+  ScoreArgs a{};
+  a.q = (const uint8_t*)q; a.k_pool = (const uint8_t*)p->k_pool;
+  a.page_indptr = p->page_indptr; a.page_indices = p->page_indices; a.seq_lens = p->seq_lens; a.skip = skip;
+  a.scores = scores; a.row_stats = row_stats;
+  a.partials = (float*)((uint8_t*)ws + w.score_partials);
+  a.counters = (uint32_t*)((uint8_t*)ws + w.score_counters);
+  a.H = p->num_q_heads; a.H_kv = p->num_kv_heads; a.P = p->page_size; a.p_shift = ilog2(p->page_size);
+  a.max_seq_len = p->max_seq_len;
+  a.HB = p->num_kv_heads < 8 ? p->num_kv_heads : 8; a.hb_shift = ilog2(a.HB); a.NU = p->num_kv_heads / a.HB;
+  a.uniform_page = p->page_size >= (8 / a.HB);
+  a.vec_store = (p->max_seq_len % 4 == 0) && (((uintptr_t)scores & 15) == 0);
+  a.scale = score_scale; a.c2 = score_scale * 1.44269504088896340736f;
+  const int ntiles = (p->max_seq_len + kScoreTileTokens - 1) / kScoreTileTokens * a.NU;
+  int wg = g_score_wg > 0 ? g_score_wg : (ntiles + 3) / 4;
+  int cap = kScoreMaxWg / (p->batch < 1 ? 1 : p->batch);
+  if (cap < 64) cap = 64;
+  if (g_score_wg == 0 && wg > cap) wg = cap;
+  if (wg > kScoreMaxWg) wg = kScoreMaxWg;
+  if (wg < 1) wg = 1;
+  const size_t lds = (size_t)4 * (a.HB * G * kScoreLdsStride + a.H * 16) * sizeof(float);
+  if (lds > 64 * 1024) return TS_ERR_UNSUPPORTED;
+  const int variant = (p->dtype == TS_BF16) ? g_score_variant : 0;
+  const hipError_t e = launch_score_decode(p->dtype, p->head_dim, G, variant, a, dim3(wg, p->batch), lds, (hipStream_t)stream);
+  return e == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
+int32_t ts_soft_vote(const ts_problem* p, const float* scores, const float* row_stats, float score_scale,
+                     float* votes, const uint8_t* skip, void* stream) {
+  int32_t st = check_problem(p);
+  if (st != TS_OK) return st;
+  if (scores == nullptr || row_stats == nullptr || votes == nullptr) return TS_ERR_INVALID_ARG;
+  if (!(score_scale >= 0.f) || !(score_scale < 1e30f)) return TS_ERR_INVALID_ARG;
+  if (p->chunk != 1) return TS_ERR_UNSUPPORTED;
+  VoteArgs a{};
+  a.scores = scores; a.row_stats = row_stats; a.votes = votes; a.seq_lens = p->seq_lens; a.skip = skip;
+  a.H = p->num_q_heads; a.max_seq_len = p->max_seq_len; a.scale = score_scale;
+  return launch_soft_vote(a, p->batch, (hipStream_t)stream) == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
+int32_t ts_topk(const ts_problem* p, const float* votes, int32_t k, int32_t* idx, int32_t* count,
+                const uint8_t* skip, void* ws, size_t ws_bytes, void* stream) {
+  int32_t st = check_problem(p);
+  if (st != TS_OK) return st;
+  if (votes == nullptr || idx == nullptr || count == nullptr || k < 1) return TS_ERR_INVALID_ARG;
+  const WsLayout w = ws_layout(p, k);
+  if (ws == nullptr || ((uintptr_t)ws & 255) != 0 || ws_bytes < w.attn_out) return TS_ERR_WORKSPACE;
+  TopkArgs a{};
+  a.votes = votes; a.seq_lens = p->seq_lens; a.skip = skip; a.idx = idx; a.count = count;
+  a.hist = (uint32_t*)((uint8_t*)ws + w.topk_hist);
+  a.state = (uint32_t*)((uint8_t*)ws + w.topk_state);
+  a.blk = (uint32_t*)((uint8_t*)ws + w.topk_blk);
+  a.counters = (uint32_t*)((uint8_t*)ws + w.topk_counters);
+  a.k = k; a.max_seq_len = p->max_seq_len; a.nblk = w.topk_nblk;
+  return launch_topk(a, p->batch, (hipStream_t)stream) == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
+int32_t ts_selcache_check(const ts_problem* p, const void* q, void* cached_q, uint8_t* first, float theta,
+                          uint8_t* reuse, void* stream) {
+  int32_t st = check_problem(p);
+  if (st != TS_OK) return st;
+  if (q == nullptr || cached_q == nullptr || first == nullptr || reuse == nullptr) return TS_ERR_INVALID_ARG;
+  if (!(theta == theta)) return TS_ERR_INVALID_ARG;
+  if (p->chunk != 1) return TS_ERR_UNSUPPORTED;
+  SelcacheArgs a{};
+  a.q = (const uint8_t*)q; a.cached_q = (uint8_t*)cached_q; a.first = first; a.reuse = reuse;
+  a.n = p->num_q_heads * p->head_dim; a.dtype = p->dtype; a.theta = theta;
+  return launch_selcache(a, p->batch, (hipStream_t)stream) == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
+int32_t ts_sparse_paged_attn(const ts_problem* p, const void* q, const int32_t* idx, int32_t idx_stride,
+                             const int32_t* count, float sm_scale, void* out, float* lse, void* ws,
+                             size_t ws_bytes, void* stream) {
+  int32_t st = check_problem(p);
+  if (st != TS_OK) return st;
+  if (q == nullptr || idx == nullptr || count == nullptr || out == nullptr || idx_stride < 1) return TS_ERR_INVALID_ARG;
+  if (p->k_pool == nullptr || p->v_pool == nullptr) return TS_ERR_INVALID_ARG;
+  if (!(sm_scale == sm_scale)) return TS_ERR_INVALID_ARG;
+  if (p->chunk != 1) return TS_ERR_UNSUPPORTED;
+  const WsLayout w = ws_layout(p, idx_stride);
+  if (ws == nullptr || ((uintptr_t)ws & 255) != 0 || ws_bytes < w.total) return TS_ERR_WORKSPACE;
+  AttnArgs a{};
+  a.q = (const uint8_t*)q; a.k_pool = (const uint8_t*)p->k_pool; a.v_pool = (const uint8_t*)p->v_pool;
+  a.page_indptr = p->page_indptr; a.page_indices = p->page_indices; a.seq_lens = p->seq_lens;
+  a.idx = idx; a.count = count; a.out = (uint8_t*)out; a.lse = lse;
+  a.part_out = (float*)((uint8_t*)ws + w.attn_out);
+  a.part_ml = (float*)((uint8_t*)ws + w.attn_ml);
+  a.counters = (uint32_t*)((uint8_t*)ws + w.attn_counters);
+  a.H = p->num_q_heads; a.H_kv = p->num_kv_heads; a.P = p->page_size; a.p_shift = ilog2(p->page_size);
+  a.idx_stride = idx_stride; a.nsplit = w.attn_nsplit; a.max_seq_len = p->max_seq_len; a.sm_scale = sm_scale;
+  const int G = p->num_q_heads / p->num_kv_heads;
+  return launch_sparse_attn_decode(p->dtype, p->head_dim, G, a, p->batch, (hipStream_t)stream) == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
+}  // extern "C"

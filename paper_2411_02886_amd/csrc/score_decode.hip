@@ -1,0 +1,299 @@
+// Decode score pass: Algorithm 2 (Paged Dot Product Kernel) re-designed for gfx950, fused with the
+// per-head softmax statistics that Eq. 5 needs.
+//
+// HBM-bound streaming design.  A wave owns a tile of 32 logical tokens x HB = min(H_kv, 8) KV heads.
+// Eight lanes share one K row (one token, one KV head): each lane loads 16-byte pieces of the row
+// (a load instruction of the wave covers eight rows x 128 contiguous bytes, i.e. whole cache lines),
+// multiplies them with the G query heads of that KV head kept in registers (the GQA group shares
+// every K byte that is loaded), and the eight partial sums are combined with three DPP steps.
+// The G x 32 x HB scores of the tile are staged in LDS so that they leave as 128-byte runs per head,
+// and the same staged values update running (max, sum-exp) statistics.  The workgroups' partial
+// statistics are merged by the last workgroup of a sequence to finish.
+#include "ts_kernels.h"
+
+namespace ts {
+
+
+template <int DT> struct Elt;
+template <> struct Elt<TS_F32> { static constexpr int size = 4; };
+template <> struct Elt<TS_BF16> { static constexpr int size = 2; };
+
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+
+// One 16-byte piece of a K row times the matching piece of one query head.
+template <int DT, bool DOT2> struct Piece;
+template <> struct Piece<TS_F32, false> {
+  struct Q { float v[4]; };
+  static __device__ __forceinline__ Q prep(uint4 w) {
+    Q q; q.v[0] = __uint_as_float(w.x); q.v[1] = __uint_as_float(w.y); q.v[2] = __uint_as_float(w.z); q.v[3] = __uint_as_float(w.w);
+    return q;
+  }
+  static __device__ __forceinline__ float dot(uint4 k, const Q& q, float acc) {
+    acc = fmaf(__uint_as_float(k.x), q.v[0], acc);
+    acc = fmaf(__uint_as_float(k.y), q.v[1], acc);
+    acc = fmaf(__uint_as_float(k.z), q.v[2], acc);
+    acc = fmaf(__uint_as_float(k.w), q.v[3], acc);
+    return acc;
+  }
+};
+template <> struct Piece<TS_BF16, false> {
+  struct Q { float v[8]; };
+  static __device__ __forceinline__ Q prep(uint4 w) {
+    Q q;
+    q.v[0] = bf16_lo(w.x); q.v[1] = bf16_hi(w.x); q.v[2] = bf16_lo(w.y); q.v[3] = bf16_hi(w.y);
+    q.v[4] = bf16_lo(w.z); q.v[5] = bf16_hi(w.z); q.v[6] = bf16_lo(w.w); q.v[7] = bf16_hi(w.w);
+    return q;
+  }
+  static __device__ __forceinline__ float dot(uint4 k, const Q& q, float acc) {
+    // bf16 x bf16 products are exact in float; each fma rounds once
+    acc = fmaf(bf16_lo(k.x), q.v[0], acc); acc = fmaf(bf16_hi(k.x), q.v[1], acc);
+    acc = fmaf(bf16_lo(k.y), q.v[2], acc); acc = fmaf(bf16_hi(k.y), q.v[3], acc);
+    acc = fmaf(bf16_lo(k.z), q.v[4], acc); acc = fmaf(bf16_hi(k.z), q.v[5], acc);
+    acc = fmaf(bf16_lo(k.w), q.v[6], acc); acc = fmaf(bf16_hi(k.w), q.v[7], acc);
+    return acc;
+  }
+};
+template <> struct Piece<TS_BF16, true> {
+  struct Q { uint4 w; };
+  static __device__ __forceinline__ Q prep(uint4 w) { Q q; q.w = w; return q; }
+  static __device__ __forceinline__ float d2(uint32_t a, uint32_t b, float acc) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), acc, false);
+  }
+  static __device__ __forceinline__ float dot(uint4 k, const Q& q, float acc) {
+    acc = d2(k.x, q.w.x, acc); acc = d2(k.y, q.w.y, acc); acc = d2(k.z, q.w.z, acc); acc = d2(k.w, q.w.w, acc);
+    return acc;
+  }
+};
+
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int DT, int D, int G, bool DOT2>
+__global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
+  constexpr int ES = Elt<DT>::size;
+  constexpr int RB = D * ES;          // bytes per K row
+  constexpr int L = RB / 128;         // 16-byte loads per lane per row
+  constexpr int TT = kScoreTileTokens;
+  constexpr int LS = kScoreLdsStride;
+  constexpr int U = 4;                // wave steps in flight
+  using P_ = Piece<DT, DOT2>;
+  extern __shared__ float smem[];
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int j = lane & 7, r = lane >> 3;
+  const int b = blockIdx.y;
+  if (a.skip != nullptr && a.skip[b] != 0) return;
+  const int N = min(max(a.seq_lens[b], 0), a.max_seq_len);
+  const int H = a.H, HB = a.HB, HBG = HB * G;
+  const int wave_floats = HBG * LS + H * 16;
+  float* tile = smem + wave * wave_floats;   // [HBG][LS] staged scores of the current tile
+  float* st = tile + HBG * LS;               // [H][8] running (max, sum-exp) pairs of this wave
+  for (int i = lane; i < H * 8; i += 64) { st[2 * i] = -INFINITY; st[2 * i + 1] = 0.f; }
+
+  const int tps_shift = 3 - a.hb_shift;      // log2(tokens per wave step)
+  const int STEPS = TT >> tps_shift;
+  const int kvh_l = r & (HB - 1);
+  const int tok_in_step = r >> a.hb_shift;
+  const int ntiles = ((N + TT - 1) / TT) * a.NU;
+  const int nwaves = gridDim.x * 4;
+  const int indptr = a.page_indptr[b];
+  const int npages = (N + a.P - 1) >> a.p_shift;
+  const size_t stride = (size_t)a.max_seq_len;
+  const float c2 = a.c2;
+
+  typename P_::Q qreg[G][L];
+  int q_loaded_for = -1;
+
+  for (int tile_id = blockIdx.x * 4 + wave; tile_id < ntiles; tile_id += nwaves) {
+    const int u = tile_id & (a.NU - 1);
+    const int t0 = (tile_id / a.NU) * TT;
+    const int kvh = u * HB + kvh_l;
+    if (u != q_loaded_for) {
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int i = 0; i < L; ++i) {
+          const uint8_t* qp = a.q + ((size_t)b * H + (size_t)kvh * G + g) * RB + i * 128 + j * 16;
+          qreg[g][i] = P_::prep(*reinterpret_cast<const uint4*>(qp));
+        }
+      q_loaded_for = u;
+    }
+    // physical page of each of the tile's 32 tokens, one per lane (lanes 32..63 mirror 0..31)
+    int pidv;
+    {
+      const int pg = (t0 + (lane & 31)) >> a.p_shift;
+      pidv = a.page_indices[indptr + min(pg, npages - 1)];
+    }
+
+    for (int s0 = 0; s0 < STEPS; s0 += U) {
+      uint4 kr[U][L];
+#pragma unroll
+      for (int uu = 0; uu < U; ++uu) {
+        const int tl = ((s0 + uu) << tps_shift) + tok_in_step;
+        int pid;
+        if (a.uniform_page) pid = __builtin_amdgcn_readlane(pidv, (s0 + uu) << tps_shift);
+        else pid = __shfl(pidv, tl);
+        const int t = t0 + tl;
+        const uint8_t* kp = a.k_pool + (((size_t)pid << a.p_shift) + (size_t)(t & (a.P - 1))) * ((size_t)a.H_kv * RB) +
+                            (size_t)kvh * RB + j * 16;
+#pragma unroll
+        for (int i = 0; i < L; ++i) kr[uu][i] = *reinterpret_cast<const uint4*>(kp + i * 128);
+      }
+#pragma unroll
+      for (int uu = 0; uu < U; ++uu) {
+        const int tl = ((s0 + uu) << tps_shift) + tok_in_step;
+        float acc[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+          float s = 0.f;
+#pragma unroll
+          for (int i = 0; i < L; ++i) s = P_::dot(kr[uu][i], qreg[g][i], s);
+          acc[g] = group8_sum(s);
+        }
+        float v = acc[0];
+#pragma unroll
+        for (int g = 1; g < G; ++g) v = (j == g) ? acc[g] : v;
+        if (j < G) tile[(kvh_l * G + j) * LS + tl] = v;
+      }
+    }
+    wave_lds_sync();
+
+    // epilogue: scores leave as 16-byte pieces (eight lanes = 128 contiguous bytes of one head row)
+    const int nchunks = HBG * (TT / 4);
+    for (int c = lane; c < nchunks; c += 64) {
+      const int hl = c >> 3, q4 = c & 7;
+      const int t = t0 + q4 * 4;
+      if (t < N) {
+        const float4 v = *reinterpret_cast<const float4*>(&tile[hl * LS + q4 * 4]);
+        const int h = u * HBG + hl;
+        const int nv = min(4, N - t);
+        float* dst = a.scores + ((size_t)b * H + h) * stride + t;
+        if (nv == 4 && a.vec_store) {
+          *reinterpret_cast<float4*>(dst) = v;
+        } else {
+          dst[0] = v.x;
+          if (nv > 1) dst[1] = v.y;
+          if (nv > 2) dst[2] = v.z;
+          if (nv > 3) dst[3] = v.w;
+        }
+        float xm = v.x;
+        if (nv > 1) xm = fmaxf(xm, v.y);
+        if (nv > 2) xm = fmaxf(xm, v.z);
+        if (nv > 3) xm = fmaxf(xm, v.w);
+        float2 ml = *reinterpret_cast<float2*>(&st[(h * 8 + q4) * 2]);
+        const float mn = fmaxf(ml.x, xm);
+        float l = (ml.x == -INFINITY) ? 0.f : ml.y * __builtin_amdgcn_exp2f(c2 * (ml.x - mn));
+        l += __builtin_amdgcn_exp2f(c2 * (v.x - mn));
+        if (nv > 1) l += __builtin_amdgcn_exp2f(c2 * (v.y - mn));
+        if (nv > 2) l += __builtin_amdgcn_exp2f(c2 * (v.z - mn));
+        if (nv > 3) l += __builtin_amdgcn_exp2f(c2 * (v.w - mn));
+        ml.x = mn; ml.y = l;
+        *reinterpret_cast<float2*>(&st[(h * 8 + q4) * 2]) = ml;
+      }
+    }
+    wave_lds_sync();
+  }
+
+  // ---- merge the 4 waves x 8 lanes of statistics of this workgroup, publish the partial
+  __syncthreads();
+  for (int h = threadIdx.x; h < H; h += 256) {
+    float m = -INFINITY;
+    for (int w = 0; w < 4; ++w)
+      for (int e = 0; e < 8; ++e) m = fmaxf(m, smem[w * wave_floats + HBG * LS + (h * 8 + e) * 2]);
+    float l = 0.f;
+    for (int w = 0; w < 4; ++w)
+      for (int e = 0; e < 8; ++e) {
+        const float mi = smem[w * wave_floats + HBG * LS + (h * 8 + e) * 2];
+        const float li = smem[w * wave_floats + HBG * LS + (h * 8 + e) * 2 + 1];
+        if (mi != -INFINITY) l += li * __builtin_amdgcn_exp2f(c2 * (mi - m));
+      }
+    float* pp = a.partials + (((size_t)b * kScoreMaxWg + blockIdx.x) * H + h) * 2;
+    pp[0] = m; pp[1] = l;
+  }
+  __shared__ int is_last;
+  fence_device();
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const uint32_t old = atomicAdd(&a.counters[b], 1u);
+    is_last = (old == gridDim.x - 1);
+  }
+  __syncthreads();
+  if (!is_last) return;
+  fence_device();
+  // ---- last workgroup of this sequence: merge all partials (double precision, exact exp)
+  const int sub = threadIdx.x & 7;
+  const double sc = (double)a.scale;
+  for (int h0 = 0; h0 < H; h0 += 32) {
+    const int h = h0 + (threadIdx.x >> 3);
+    float m = -INFINITY;
+    double l = 0.0;
+    if (h < H) {
+      for (int p = sub; p < (int)gridDim.x; p += 8) {
+        const float* pp = a.partials + (((size_t)b * kScoreMaxWg + p) * H + h) * 2;
+        const float mp = __hip_atomic_load(pp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const float lp = __hip_atomic_load(pp + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (mp == -INFINITY) continue;
+        if (mp > m) { l = (m == -INFINITY) ? 0.0 : l * exp(sc * ((double)m - (double)mp)); m = mp; }
+        l += (double)lp * exp(sc * ((double)mp - (double)m));
+      }
+    }
+    // combine the 8 sub-lanes (they sit in one aligned lane group)
+#pragma unroll
+    for (int off = 1; off < 8; off <<= 1) {
+      const float mo = __shfl_xor(m, off);
+      const double lo = __shfl_xor(l, off);
+      const float mn = fmaxf(m, mo);
+      double acc = 0.0;
+      if (m != -INFINITY) acc += l * exp(sc * ((double)m - (double)mn));
+      if (mo != -INFINITY) acc += lo * exp(sc * ((double)mo - (double)mn));
+      m = mn; l = acc;
+    }
+    if (h < H && sub == 0) {
+      a.row_stats[((size_t)b * H + h) * 2] = m;
+      a.row_stats[((size_t)b * H + h) * 2 + 1] = (float)l;
+    }
+  }
+  if (threadIdx.x == 0) a.counters[b] = 0u;   // ready for the next call
+}
+
+// ------------------------------------------------------------------------------------------------
+template <int DT, int D, int G, bool DOT2>
+static hipError_t launch_one(const ScoreArgs& a, dim3 grid, size_t lds, hipStream_t s) {
+  hipLaunchKernelGGL((score_decode_kernel<DT, D, G, DOT2>), grid, dim3(256), lds, s, a);
+  return hipGetLastError();
+}
+
+template <int DT, int D, bool DOT2>
+static hipError_t launch_g(int G, const ScoreArgs& a, dim3 grid, size_t lds, hipStream_t s) {
+  switch (G) {
+    case 1: return launch_one<DT, D, 1, DOT2>(a, grid, lds, s);
+    case 2: return launch_one<DT, D, 2, DOT2>(a, grid, lds, s);
+    case 3: return launch_one<DT, D, 3, DOT2>(a, grid, lds, s);
+    case 4: return launch_one<DT, D, 4, DOT2>(a, grid, lds, s);
+    case 5: return launch_one<DT, D, 5, DOT2>(a, grid, lds, s);
+    case 6: return launch_one<DT, D, 6, DOT2>(a, grid, lds, s);
+    case 7: return launch_one<DT, D, 7, DOT2>(a, grid, lds, s);
+    case 8: return launch_one<DT, D, 8, DOT2>(a, grid, lds, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+// variant: 0 = fma arithmetic, 1 = packed bf16 dot2 (bf16 only)
+hipError_t launch_score_decode(int dtype, int D, int G, int variant, const ScoreArgs& a, dim3 grid, size_t lds,
+                               hipStream_t s) {
+  if (dtype == TS_F32) {
+    if (D == 64) return launch_g<TS_F32, 64, false>(G, a, grid, lds, s);
+    return launch_g<TS_F32, 128, false>(G, a, grid, lds, s);
+  }
+  if (variant == 1) {
+    if (D == 64) return launch_g<TS_BF16, 64, true>(G, a, grid, lds, s);
+    return launch_g<TS_BF16, 128, true>(G, a, grid, lds, s);
+  }
+  if (D == 64) return launch_g<TS_BF16, 64, false>(G, a, grid, lds, s);
+  return launch_g<TS_BF16, 128, false>(G, a, grid, lds, s);
+}
+
+}  // namespace ts

@@ -1,0 +1,105 @@
+// Shared device helpers and workspace layout for the TokenSelect gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "tokenselect.h"
+
+namespace ts {
+
+constexpr int kWave = 64;
+constexpr int kScoreTileTokens = 32;   // tokens per wave tile in the score pass
+constexpr int kScoreLdsStride = 36;    // floats per head row of the staged score tile (16 B aligned)
+constexpr int kScoreMaxWg = 1024;      // upper bound on workgroups per sequence in the score pass
+constexpr int kTopkBins = 2048;        // 11-bit radix digit
+constexpr int kTopkChunk = 2048;       // keys per workgroup in the top-k passes
+constexpr int kAttnChunk = 64;         // selected tokens per workgroup in sparse attention
+
+// ---------------------------------------------------------------- workspace layout (host + device)
+struct WsLayout {
+  size_t score_partials;   // float [B][kScoreMaxWg][H][2]
+  size_t score_counters;   // uint32 [B]
+  size_t topk_hist;        // uint32 [B][kTopkBins]
+  size_t topk_state;       // uint32 [B][4] : prefix, k_remaining, k_effective, unused
+  size_t topk_blk;         // uint32 [B][nblk][2] : per-block (greater, equal) counts -> exclusive offsets
+  size_t topk_counters;    // uint32 [B][2]
+  size_t attn_out;         // float [B][H][nsplit][D]
+  size_t attn_ml;          // float [B][H][nsplit][2]
+  size_t attn_counters;    // uint32 [B][H_kv]
+  size_t total;
+  int topk_nblk;
+  int attn_nsplit;
+};
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+inline WsLayout ws_layout(const ts_problem* p, int k) {
+  WsLayout w{};
+  const size_t B = (size_t)p->batch, H = (size_t)p->num_q_heads, D = (size_t)p->head_dim;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+  w.topk_nblk = (p->max_seq_len + kTopkChunk - 1) / kTopkChunk;
+  if (w.topk_nblk < 1) w.topk_nblk = 1;
+  w.attn_nsplit = (k + kAttnChunk - 1) / kAttnChunk;
+  if (w.attn_nsplit < 1) w.attn_nsplit = 1;
+  // counters and histograms first: they are the part that must start (and is left) zeroed
+  w.score_counters = take(B * 4);
+  w.topk_hist = take(B * kTopkBins * 4);
+  w.topk_counters = take(B * 2 * 4);
+  w.attn_counters = take(B * (size_t)p->num_kv_heads * 4);
+  w.topk_state = take(B * 4 * 4);
+  w.score_partials = take(B * kScoreMaxWg * H * 2 * 4);
+  w.topk_blk = take(B * (size_t)w.topk_nblk * 2 * 4);
+  w.attn_out = take(B * H * (size_t)w.attn_nsplit * D * 4);
+  w.attn_ml = take(B * H * (size_t)w.attn_nsplit * 2 * 4);
+  w.total = off;
+  return w;
+}
+
+#ifdef __HIPCC__
+// ---------------------------------------------------------------- device helpers
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// round-to-nearest-even float -> bf16 bits (finite inputs)
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+// sum over the 8 lanes of an aligned lane group; every lane of the group gets the total
+__device__ __forceinline__ float group8_sum(float v) {
+  v += dpp_f32<0xB1>(v);    // quad_perm [1,0,3,2]
+  v += dpp_f32<0x4E>(v);    // quad_perm [2,3,0,1]
+  v += dpp_f32<0x141>(v);   // row_half_mirror
+  return v;
+}
+__device__ __forceinline__ float group16_sum(float v) {
+  v = group8_sum(v);
+  v += dpp_f32<0x140>(v);   // row_mirror
+  return v;
+}
+__device__ __forceinline__ float group8_max(float v) {
+  v = fmaxf(v, dpp_f32<0xB1>(v));
+  v = fmaxf(v, dpp_f32<0x4E>(v));
+  v = fmaxf(v, dpp_f32<0x141>(v));
+  return v;
+}
+
+// order-preserving key of a float: larger float <=> larger unsigned key; -0.0 maps onto +0.0
+__device__ __forceinline__ uint32_t float_key(float v) {
+  uint32_t u = __float_as_uint(v);
+  if (u == 0x80000000u) u = 0u;
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// agent-scope release/acquire fence around the "last workgroup finishes the job" counters
+__device__ __forceinline__ void fence_device() { __threadfence(); }
+#endif  // __HIPCC__
+
+}  // namespace ts

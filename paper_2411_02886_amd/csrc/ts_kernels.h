@@ -1,0 +1,83 @@
+// Kernel argument blocks and launch entry points shared by the host API and the kernel files.
+#pragma once
+#include "ts_common.h"
+
+namespace ts {
+
+struct ScoreArgs {
+  const uint8_t* q;
+  const uint8_t* k_pool;
+  const int32_t* page_indptr;
+  const int32_t* page_indices;
+  const int32_t* seq_lens;
+  const uint8_t* skip;
+  float* scores;
+  float* row_stats;
+  float* partials;
+  uint32_t* counters;
+  int H, H_kv, P, p_shift, max_seq_len;
+  int HB, hb_shift, NU;   // KV heads per wave tile (min(H_kv, 8)), its log2, H_kv / HB
+  int uniform_page;       // every step of a wave reads one page (P >= tokens per step)
+  int vec_store;          // scores rows are 16-byte aligned
+  float scale, c2;        // score_scale and score_scale * log2(e)
+};
+
+struct VoteArgs {
+  const float* scores;
+  const float* row_stats;
+  float* votes;
+  const int32_t* seq_lens;
+  const uint8_t* skip;
+  int H, max_seq_len;
+  float scale;
+};
+
+struct TopkArgs {
+  const float* votes;
+  const int32_t* seq_lens;
+  const uint8_t* skip;
+  int32_t* idx;
+  int32_t* count;
+  uint32_t* hist;       // [B][kTopkBins]
+  uint32_t* state;      // [B][4] prefix, k_remaining, k_effective
+  uint32_t* blk;        // [B][nblk][2]
+  uint32_t* counters;   // [B][2]
+  int k, max_seq_len, nblk;
+};
+
+struct SelcacheArgs {
+  const uint8_t* q;
+  uint8_t* cached_q;
+  uint8_t* first;
+  uint8_t* reuse;
+  int n;          // H * D elements per sequence
+  int dtype;
+  float theta;
+};
+
+struct AttnArgs {
+  const uint8_t* q;
+  const uint8_t* k_pool;
+  const uint8_t* v_pool;
+  const int32_t* page_indptr;
+  const int32_t* page_indices;
+  const int32_t* seq_lens;
+  const int32_t* idx;
+  const int32_t* count;
+  uint8_t* out;
+  float* lse;
+  float* part_out;     // [B][H][nsplit][D]
+  float* part_ml;      // [B][H][nsplit][2]
+  uint32_t* counters;  // [B][H_kv]
+  int H, H_kv, P, p_shift, idx_stride, nsplit, max_seq_len;
+  float sm_scale;
+};
+
+// variant: 0 = fma arithmetic, 1 = packed bf16 dot2 (bf16 only)
+hipError_t launch_score_decode(int dtype, int D, int G, int variant, const ScoreArgs& a, dim3 grid, size_t lds, hipStream_t s);
+hipError_t launch_soft_vote(const VoteArgs& a, int B, hipStream_t s);
+hipError_t launch_topk(const TopkArgs& a, int B, hipStream_t s);
+hipError_t launch_selcache(const SelcacheArgs& a, int B, hipStream_t s);
+hipError_t launch_sparse_attn_decode(int dtype, int D, int G, const AttnArgs& a, int B, hipStream_t s);
+
+}  // namespace ts

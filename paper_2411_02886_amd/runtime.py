@@ -1,0 +1,98 @@
+"""Device-side buffers for one attention layer's decode loop and the five-call step.
+
+Orchestration only: uploads a paged workload given as numpy arrays, allocates the intermediate
+buffers with torch (device memory) and issues the C-ABI calls in the order of Fig. 4 / Algorithm 1.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as ts
+
+
+def to_device(a: np.ndarray, device="cuda:0") -> torch.Tensor:
+    """numpy -> device tensor; uint16 (bf16 bit patterns) travel as int16 raw bits."""
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint16:
+        a = a.view(np.int16)
+    return torch.from_numpy(a).to(device)
+
+
+def to_host(t: torch.Tensor, bits16: bool = False) -> np.ndarray:
+    a = t.detach().cpu().numpy()
+    return a.view(np.uint16) if bits16 else a
+
+
+class DecodeLayer:
+    """Paged KV pool of B sequences on the GPU plus every buffer the decode step needs."""
+
+    def __init__(self, *, dtype, H, H_kv, D, P, k, k_pool, v_pool, page_indptr, page_indices, seq_lens,
+                 max_seq_len=None, device="cuda:0"):
+        self.device = device
+        self.dtype, self.H, self.H_kv, self.D, self.P, self.k = dtype, H, H_kv, D, P, k
+        self.B = int(len(seq_lens))
+        self.k_pool = k_pool if torch.is_tensor(k_pool) else to_device(k_pool, device)
+        self.v_pool = v_pool if torch.is_tensor(v_pool) else to_device(v_pool, device)
+        self.page_indptr = to_device(np.asarray(page_indptr, dtype=np.int32), device)
+        self.page_indices = to_device(np.asarray(page_indices, dtype=np.int32), device)
+        self.seq_lens = to_device(np.asarray(seq_lens, dtype=np.int32), device)
+        self.max_seq_len = int(max_seq_len if max_seq_len is not None else max(1, int(np.max(seq_lens))))
+        self._make_problem()
+        B, Hq, M = self.B, H, self.max_seq_len
+        self.scores = torch.empty((B, Hq, M), dtype=torch.float32, device=device)
+        self.row_stats = torch.empty((B, Hq, 2), dtype=torch.float32, device=device)
+        self.votes = torch.empty((B, M), dtype=torch.float32, device=device)
+        self.idx = torch.full((B, k), -1, dtype=torch.int32, device=device)
+        self.count = torch.zeros((B,), dtype=torch.int32, device=device)
+        edt = torch.int16 if dtype == ts.TS_BF16 else torch.float32
+        self.out = torch.zeros((B, 1, Hq, D), dtype=edt, device=device)
+        self.lse = torch.empty((B, 1, Hq), dtype=torch.float32, device=device)
+        self.cached_q = torch.zeros((B, Hq, D), dtype=edt, device=device)
+        self.first = torch.ones((B,), dtype=torch.uint8, device=device)
+        self.reuse = torch.zeros((B,), dtype=torch.uint8, device=device)
+        nbytes = ts.ts_workspace_bytes(self.problem, k)
+        self.ws = torch.empty((nbytes + 255) // 256 * 64, dtype=torch.int32, device=device)
+        ts.ts_workspace_init(self.ws)
+
+    def _make_problem(self):
+        self.problem = ts.Problem(batch=self.B, chunk=1, num_q_heads=self.H, num_kv_heads=self.H_kv, head_dim=self.D,
+                                  page_size=self.P, max_seq_len=self.max_seq_len, dtype=self.dtype,
+                                  k_pool=self.k_pool, v_pool=self.v_pool, page_indptr=self.page_indptr,
+                                  page_indices=self.page_indices, seq_lens=self.seq_lens)
+
+    @classmethod
+    def from_workload(cls, w, device="cuda:0", max_seq_len=None):
+        return cls(dtype=w.dtype, H=w.H, H_kv=w.H_kv, D=w.D, P=w.P, k=w.k, k_pool=w.k_pool, v_pool=w.v_pool,
+                   page_indptr=w.page_indptr, page_indices=w.page_indices, seq_lens=w.seq_lens,
+                   max_seq_len=max_seq_len, device=device)
+
+    def swap_pool(self, k_pool: torch.Tensor, v_pool: torch.Tensor, page_indices: torch.Tensor = None):
+        """Points the layer at another resident pool of the same shape (benchmark cache rotation)."""
+        self.k_pool, self.v_pool = k_pool, v_pool
+        if page_indices is not None:
+            self.page_indices = page_indices
+        self._make_problem()
+
+    # ---- the five calls
+    def selcache_check(self, q, theta):
+        ts.ts_selcache_check(self.problem, q, self.cached_q, self.first, theta, self.reuse)
+
+    def select(self, q, score_scale=1.0, skip=None):
+        ts.ts_paged_qk_scores(self.problem, q, self.scores, self.row_stats, score_scale, skip, self.ws)
+        ts.ts_soft_vote(self.problem, self.scores, self.row_stats, score_scale, self.votes, skip)
+        ts.ts_topk(self.problem, self.votes, self.k, self.idx, self.count, skip, self.ws)
+
+    def attend(self, q, sm_scale):
+        ts.ts_sparse_paged_attn(self.problem, q, self.idx, self.k, self.count, sm_scale, self.out, self.lse, self.ws)
+
+    def step(self, q, *, theta=None, score_scale=1.0, sm_scale=None):
+        """One decode step: Selection Cache check (when theta is given), selection on a miss, sparse
+        attention.  No host synchronisation."""
+        sm = sm_scale if sm_scale is not None else 1.0 / float(np.sqrt(self.D))
+        skip = None
+        if theta is not None:
+            self.selcache_check(q, theta)
+            skip = self.reuse
+        self.select(q, score_scale, skip)
+        self.attend(q, sm)

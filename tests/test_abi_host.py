@@ -1,0 +1,66 @@
+"""Host-only checks of the C ABI: the library loads, exports every declared symbol, and rejects bad
+arguments before touching the GPU (no kernel is launched by any of these calls)."""
+import ctypes
+
+import numpy as np
+import pytest
+
+import paper_2411_02886_amd as ts
+from paper_2411_02886_amd.binding import _CProblem
+
+
+def cproblem(**kw):
+    base = dict(batch=1, chunk=1, num_q_heads=8, num_kv_heads=2, head_dim=64, page_size=16, max_seq_len=4096,
+                dtype=ts.TS_F32, k_pool=0x1000, v_pool=0x1000, page_indptr=0x1000, page_indices=0x1000, seq_lens=0x1000)
+    base.update(kw)
+    return _CProblem(**base)
+
+
+def test_library_exports_every_declared_symbol():
+    L = ts.load()
+    names = ts.declared_symbols()
+    assert {"ts_paged_qk_scores", "ts_soft_vote", "ts_topk", "ts_selcache_check", "ts_sparse_paged_attn",
+            "ts_workspace_bytes", "ts_workspace_init", "ts_version", "ts_strerror"} <= set(names)
+    for n in names:
+        assert hasattr(L, n), n
+    assert ts.ts_version() >= 100
+    assert ts.ts_strerror(0) == "ok" and "unsupported" in ts.ts_strerror(-2)
+
+
+def test_workspace_bytes_and_shape_validation():
+    L = ts.load()
+    out = ctypes.c_size_t(0)
+    assert L.ts_workspace_bytes(ctypes.byref(cproblem()), 256, ctypes.byref(out)) == 0 and out.value > 0
+    small = out.value
+    assert L.ts_workspace_bytes(ctypes.byref(cproblem(max_seq_len=1 << 20)), 4096, ctypes.byref(out)) == 0
+    assert out.value > small
+    bad = [dict(num_q_heads=7), dict(batch=0), dict(dtype=5), dict(page_indptr=None), dict(max_seq_len=0)]
+    for kw in bad:
+        assert L.ts_workspace_bytes(ctypes.byref(cproblem(**kw)), 256, ctypes.byref(out)) == -1, kw
+    unsup = [dict(head_dim=96), dict(num_kv_heads=3, num_q_heads=6), dict(page_size=12), dict(num_q_heads=32, num_kv_heads=2),
+             dict(num_q_heads=256, num_kv_heads=32)]
+    for kw in unsup:
+        assert L.ts_workspace_bytes(ctypes.byref(cproblem(**kw)), 256, ctypes.byref(out)) == -2, kw
+    assert L.ts_workspace_bytes(ctypes.byref(cproblem()), 0, ctypes.byref(out)) == -1
+    assert L.ts_workspace_bytes(None, 4, ctypes.byref(out)) == -1
+
+
+def test_calls_reject_bad_arguments_without_launching():
+    L = ts.load()
+    p = ctypes.byref(cproblem())
+    ws, big = 0x10000, 1 << 30
+    assert L.ts_paged_qk_scores(p, None, 0x1000, 0x1000, 1.0, None, ws, big, None) == -1
+    assert L.ts_paged_qk_scores(p, 0x1000, 0x1000, 0x1000, -1.0, None, ws, big, None) == -1
+    assert L.ts_paged_qk_scores(p, 0x1000, 0x1000, 0x1000, float("nan"), None, ws, big, None) == -1
+    assert L.ts_paged_qk_scores(p, 0x1000, 0x1000, 0x1000, 1.0, None, None, 0, None) == -3
+    assert L.ts_paged_qk_scores(p, 0x1000, 0x1000, 0x1000, 1.0, None, ws, 16, None) == -3
+    assert L.ts_paged_qk_scores(ctypes.byref(cproblem(chunk=4)), 0x1000, 0x1000, 0x1000, 1.0, None, ws, big, None) == -2
+    assert L.ts_soft_vote(p, 0x1000, None, 1.0, 0x1000, None, None) == -1
+    assert L.ts_topk(p, 0x1000, 0, 0x1000, 0x1000, None, ws, big, None) == -1
+    assert L.ts_topk(p, 0x1000, 16, 0x1000, 0x1000, None, ws, 8, None) == -3
+    assert L.ts_selcache_check(p, 0x1000, 0x1000, None, 0.9, 0x1000, None) == -1
+    assert L.ts_sparse_paged_attn(p, 0x1000, 0x1000, 0, 0x1000, 0.125, 0x1000, None, ws, big, None) == -1
+    assert L.ts_sparse_paged_attn(ctypes.byref(cproblem(v_pool=None)), 0x1000, 0x1000, 16, 0x1000, 0.125, 0x1000, None, ws, big, None) == -1
+    assert L.ts_sparse_paged_attn(p, 0x1000, 0x1000, 16, 0x1000, 0.125, 0x1000, None, ws, 64, None) == -3
+    assert L.ts_workspace_init(None, 1024, None) == -1
+    assert L.ts_debug_set_score_variant(7, 0) == -1

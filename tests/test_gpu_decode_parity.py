@@ -1,0 +1,165 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs -- element by element at sizes that span several tiles and ragged tails, plus edge cases."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads as W
+from parity_util import check_decode_against_oracle, compare_index_sets, oracle_decode
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2411_02886_amd as ts
+    ts.load()
+    return ts
+
+
+def make_layer(w, **kw):
+    from paper_2411_02886_amd.runtime import DecodeLayer, to_device
+    layer = DecodeLayer.from_workload(w, **kw)
+    return layer, to_device(w.q)
+
+
+def test_config1_tiny_fp32(gpu):
+    w = W.config1()
+    layer, q = make_layer(w)
+    for scale in (1.0, 1.0 / math.sqrt(w.D)):
+        print("cfg1 scale", scale, flush=True)
+        check_decode_against_oracle(w, layer, q, score_scale=scale, label="cfg1 c=%.3f" % scale)
+
+
+@pytest.mark.parametrize("variant", [0, 1])
+def test_config2_shape_bf16_reduced_length(gpu, variant):
+    # config 2's head shapes at 5000 tokens (not a multiple of the 32-token tile nor of the page)
+    gpu.ts_debug_set_score_variant(variant, 0)
+    try:
+        w = W.config2(N=5000, k=300, seed=77)
+        layer, q = make_layer(w)
+        for scale in (1.0, 1.0 / math.sqrt(w.D)):
+            print("cfg2-small variant", variant, "scale", scale, flush=True)
+            check_decode_against_oracle(w, layer, q, score_scale=scale, label="cfg2s v%d c=%.3f" % (variant, scale))
+    finally:
+        gpu.ts_debug_set_score_variant(0, 0)
+
+
+SHAPES = [
+    # dtype, H, H_kv, D, P, N, k
+    (W.F32, 4, 1, 64, 16, 777, 50),        # one KV head: four tokens per wave step
+    (W.F32, 8, 8, 128, 16, 300, 64),       # G = 1, fp32 D = 128 (four loads per row)
+    (W.BF16, 28, 4, 128, 16, 2500, 128),   # config 4's group of seven
+    (W.BF16, 16, 2, 64, 16, 1000, 100),    # G = 8, D = 64 bf16 (one load per row)
+    (W.BF16, 32, 16, 128, 16, 600, 64),    # 16 KV heads: two head blocks per token tile
+    (W.BF16, 32, 8, 128, 1, 333, 40),      # page size 1 (the paper's own setting)
+    (W.F32, 8, 2, 64, 4, 515, 33),         # small pages, H_kv = 2
+    (W.BF16, 8, 4, 128, 2, 130, 130),      # page size 2, k == N
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "dt%d_H%d_%d_D%d_P%d_N%d_k%d" % s)
+def test_shapes(gpu, shape):
+    dtype, H, H_kv, D, P, N, k = shape
+    print("shape", shape, flush=True)
+    w = W.make_workload("shape", dtype=dtype, H=H, H_kv=H_kv, D=D, P=P, seq_lens=[N], k=k, beta=3.0,
+                        planted_per_head=2, seed=N + H)
+    layer, q = make_layer(w)
+    check_decode_against_oracle(w, layer, q, score_scale=1.0 / math.sqrt(D), label=str(shape))
+
+
+def test_ragged_batch_with_empty_and_short_sequences(gpu):
+    lens = [0, 1, 31, 32, 33, 2049, 700, 15]
+    w = W.make_workload("ragged", dtype=W.BF16, B=len(lens), H=8, H_kv=2, D=128, P=16, seq_lens=lens, k=40,
+                        beta=3.0, planted_per_head=0, seed=5)
+    layer, q = make_layer(w)
+    print("ragged batch", lens, flush=True)
+    check_decode_against_oracle(w, layer, q, score_scale=0.1, label="ragged")
+
+
+def test_odd_row_stride_uses_scalar_stores(gpu):
+    w = W.make_workload("odd", dtype=W.F32, H=4, H_kv=2, D=64, P=16, seq_lens=[203], k=20, seed=12)
+    layer, q = make_layer(w, max_seq_len=205)
+    check_decode_against_oracle(w, layer, q, score_scale=0.125, label="odd stride")
+
+
+def test_ties_go_to_lower_index_and_zero_query(gpu):
+    # duplicated K rows give bitwise identical votes; a zero query makes every vote equal
+    w = W.make_workload("ties", dtype=W.F32, H=4, H_kv=2, D=64, P=16, seq_lens=[400], k=10, seed=31)
+    kl = w.k_pool.reshape(-1, w.H_kv, w.D)
+    slots = w.slots_of(0)
+    ora0 = oracle_decode(w, 0, score_scale=0.125, k=400)
+    order = np.argsort(-ora0["votes"], kind="stable")
+    top = order[9]                      # the 10th best token: copy it onto three other tokens
+    for t in (5, 17, 333):
+        kl[slots[t]] = kl[slots[top]]
+    layer, q = make_layer(w)
+    check_decode_against_oracle(w, layer, q, score_scale=0.125, label="ties")
+    w.q[:] = 0
+    layer, q = make_layer(w)
+    check_decode_against_oracle(w, layer, q, score_scale=1.0, label="zero query")
+    from paper_2411_02886_amd.runtime import to_host
+    assert to_host(layer.idx)[0].tolist() == list(range(10))
+
+
+def test_k_larger_than_n_equals_full_attention(gpu):
+    w = W.make_workload("full", dtype=W.F32, H=8, H_kv=2, D=64, P=16, seq_lens=[150], k=256, seed=41)
+    layer, q = make_layer(w)
+    check_decode_against_oracle(w, layer, q, score_scale=0.125, label="k>N")
+    from paper_2411_02886_amd.runtime import to_host
+    full = oracle.full_attn(np.ascontiguousarray(w.q[0, 0]), w.k_pool, w.v_pool, w.dtype, w.H_kv, w.P, w.pages_of(0), 150,
+                            float(np.float32(1 / math.sqrt(64))))
+    assert np.abs(to_host(layer.out)[0, 0] - full).max() < 1e-4
+
+
+def test_selection_cache_loop_matches_algorithm_1(gpu):
+    from paper_2411_02886_amd.runtime import to_device, to_host
+    steps, theta = 12, 0.9
+    w = W.make_workload("sc", dtype=W.BF16, B=3, H=8, H_kv=2, D=128, P=16, seq_lens=[300, 1000, 64], k=32, seed=19,
+                        beta=3.0, planted_per_head=1)
+    qs = W.ar1_queries(w, steps, rho=0.95)
+    layer, _ = make_layer(w)
+    # oracle state per sequence
+    cq = [np.zeros((w.H, w.D), np.uint16) for _ in range(w.B)]
+    first = [np.ones(1, np.uint8) for _ in range(w.B)]
+    cidx = [np.full(w.k, -1, np.int32) for _ in range(w.B)]
+    ccnt = [np.zeros(1, np.int32) for _ in range(w.B)]
+    hits = 0
+    for t in range(steps):
+        print("selcache step", t, flush=True)
+        qd = to_device(qs[t])
+        layer.step(qd, theta=theta, score_scale=0.1)
+        torch.cuda.synchronize()
+        reuse_g = to_host(layer.reuse); idx_g = to_host(layer.idx); cnt_g = to_host(layer.count)
+        out_g = to_host(layer.out, bits16=True)
+        for b in range(w.B):
+            qb = np.ascontiguousarray(qs[t][b, 0])
+            sel = lambda qq, b=b: oracle.select(qq, w.k_pool, w.dtype, w.H_kv, w.P, w.pages_of(b), int(w.seq_lens[b]), w.k,
+                                                score_scale=float(np.float32(0.1)))
+            i_o, c_o, r_o = oracle.selcache_step(qb, cq[b], cidx[b], ccnt[b], first[b], float(np.float32(theta)), sel)
+            assert bool(reuse_g[b]) == r_o, (t, b)
+            hits += r_o
+            assert cnt_g[b] == c_o and np.array_equal(idx_g[b], i_o), (t, b)
+            o_ref = oracle.sparse_attn(qb, w.k_pool, w.v_pool, w.dtype, w.H_kv, w.P, w.pages_of(b), i_o, c_o,
+                                       float(np.float32(1 / math.sqrt(w.D))))
+            assert np.abs(W.as_f32(out_g[b, 0], w.dtype) - o_ref).max() <= 2e-2, (t, b)
+        assert np.array_equal(to_host(layer.cached_q, bits16=True), np.stack(cq)), t
+    assert 0 < hits < steps * w.B          # the run exercises both branches
+
+
+def test_kernels_are_deterministic(gpu):
+    from paper_2411_02886_amd.runtime import to_host
+    w = W.config2(N=3000, k=200, seed=3)
+    layer, q = make_layer(w)
+    outs = []
+    for _ in range(2):
+        layer.step(q, score_scale=1.0)
+        torch.cuda.synchronize()
+        outs.append([to_host(x).copy() for x in (layer.scores, layer.row_stats, layer.votes, layer.idx, layer.out)])
+    for a, b in zip(*outs):
+        assert np.array_equal(a, b)
