@@ -1,0 +1,186 @@
+#!/usr/bin/env python3
+"""Benchmark of the TokenSelect decode hot path on one MI355X.
+
+A "step" is one pass of the whole path over one batch of synthetic input already resident in HBM:
+Selection Cache check (Alg. 1) -> paged q.k score pass (Alg. 2) -> head soft vote (Eq. 5) -> top-k
+-> sparse paged attention (Eq. 2).  Default workload: configuration 2 (Llama-3-8B-shaped layer,
+bf16, 131072 cached tokens in 16-token pages, k = 2048).  To keep neither the L2s nor the 256 MB
+last-level cache warm, the steps rotate over R physical copies of the pool (same logical sequence,
+different random page permutation each) and over R different queries, so that every step is a
+Selection Cache miss (cosine of independent queries ~ 0 < theta = 0.9) and scans all cached tokens.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 4])
+    ap.add_argument("--pools", type=int, default=0, help="physical pool copies to rotate over (0 = enough for >= 2 GiB)")
+    ap.add_argument("--variant", type=int, default=-1, help="score-pass arithmetic: 0 fma, 1 bf16 dot2, -1 library default")
+    ap.add_argument("--score-wg", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tokens", type=int, default=0, help="override the number of cached tokens (profiling only)")
+    return ap.parse_args()
+
+
+def cpu_baseline(w, budget_s=12.0):
+    """The oracle as it stands, timed on this host for whole decode steps of the same workload."""
+    import oracle
+    N = int(w.seq_lens[0])
+    qb = np.ascontiguousarray(w.q[0, 0])
+    sm = float(np.float32(1.0 / math.sqrt(w.D)))
+    times = []
+    t_all = time.perf_counter()
+    while True:
+        t0 = time.perf_counter()
+        idx, cnt = oracle.select(qb, w.k_pool, w.dtype, w.H_kv, w.P, w.pages_of(0), N, w.k)
+        oracle.sparse_attn(qb, w.k_pool, w.v_pool, w.dtype, w.H_kv, w.P, w.pages_of(0), idx, cnt, sm)
+        times.append(time.perf_counter() - t0)
+        if time.perf_counter() - t_all > budget_s or len(times) >= 50:
+            break
+    t = float(np.median(times))
+    return {"value": N / t, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "%d full decode steps (selection + sparse attention) of the same workload, median %.3f s/step"
+                      % (len(times), t),
+            "steps_per_s": 1.0 / t}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus %d is not supported (see DESIGN.md, 'More than one GPU')"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import workloads as W
+    import paper_2411_02886_amd as ts
+    from paper_2411_02886_amd.runtime import DecodeLayer, to_device, to_host
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    ts.load()
+    dev = "cuda:0"
+    kw = {"N": args.tokens} if args.tokens else {}
+    w = W.CONFIGS[args.config](**kw)
+    N = int(w.seq_lens[0])
+    if args.variant >= 0 or args.score_wg:
+        ts.ts_debug_set_score_variant(max(args.variant, 0), args.score_wg)
+    layer = DecodeLayer.from_workload(w, device=dev)
+    esize = w.esize()
+    k_bytes = N * w.H_kv * w.D * esize                      # algorithmic bytes of the score pass
+    pool_bytes = w.k_pool.nbytes + w.v_pool.nbytes
+    R = args.pools if args.pools > 0 else max(2, int(math.ceil(2 * 2**30 / pool_bytes)))
+    R = min(R, 8)
+
+    # R physical copies of the same logical sequence, each under its own page permutation
+    rng = np.random.Generator(np.random.PCG64(w.seed + 424242))
+    pools = [(layer.k_pool, layer.v_pool, layer.page_indices)]
+    pi0 = layer.page_indices.long()
+    for r in range(1, R):
+        perm = to_device(rng.permutation(w.num_pages)[: pi0.numel()].astype(np.int32), dev)
+        kp = torch.empty_like(layer.k_pool); vp = torch.empty_like(layer.v_pool)
+        kp.index_copy_(0, perm.long(), layer.k_pool.index_select(0, pi0))
+        vp.index_copy_(0, perm.long(), layer.v_pool.index_select(0, pi0))
+        pools.append((kp, vp, perm))
+    qs = [to_device(w.q, dev)]
+    for r in range(1, R):
+        qs.append(to_device(W.store(rng.standard_normal(w.q.shape, dtype=np.float32), w.dtype), dev))
+    torch.cuda.synchronize()
+
+    sm = 1.0 / math.sqrt(w.D)
+    theta, scale = 0.9, 1.0
+
+    problems = []
+    for kp, vp, pi in pools:
+        layer.swap_pool(kp, vp, pi)
+        problems.append(layer.problem)
+    stream = torch.cuda.current_stream()
+
+    def step(i, ev=None):
+        p = problems[i % R]
+        q = qs[i % R]
+        ts.ts_selcache_check(p, q, layer.cached_q, layer.first, theta, layer.reuse, stream)
+        if ev is not None:
+            ev[0].record(stream)
+        ts.ts_paged_qk_scores(p, q, layer.scores, layer.row_stats, scale, layer.reuse, layer.ws, stream)
+        if ev is not None:
+            ev[1].record(stream)
+        ts.ts_soft_vote(p, layer.scores, layer.row_stats, scale, layer.votes, layer.reuse, stream)
+        ts.ts_topk(p, layer.votes, layer.k, layer.idx, layer.count, layer.reuse, layer.ws, stream)
+        ts.ts_sparse_paged_attn(p, q, layer.idx, layer.k, layer.count, sm, layer.out, layer.lse, layer.ws, stream)
+
+    # sanity before timing: paging invariance across the pool copies (same query -> same selection)
+    ref_idx = None
+    for r in range(min(R, 2)):
+        kp, vp, pi = pools[r]
+        layer.swap_pool(kp, vp, pi)
+        layer.first.fill_(1)
+        layer.step(qs[0], theta=theta, score_scale=scale, sm_scale=sm)
+        torch.cuda.synchronize()
+        got = to_host(layer.idx).copy()
+        if ref_idx is None:
+            ref_idx = got
+        assert np.array_equal(got, ref_idx), "selection changed with the physical page layout"
+    layer.first.fill_(1)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, events[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    misses = int((to_host(layer.reuse) == 0).sum())
+    assert misses == w.B, "the benchmark step must be a Selection Cache miss"
+    ms_step = (t1 - t0) * 1e3 / args.steps
+    score_ms = np.array([a.elapsed_time(b) for a, b in events], dtype=np.float64)
+    score_avg_ms = float(score_ms.mean())
+    achieved = k_bytes / (score_avg_ms * 1e-3) / 1e9
+
+    res = {
+        "metric": "KV tokens scanned/s (whole decode step: Selection Cache check + score pass + soft vote + top-k + sparse attention)",
+        "value": N / (ms_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.dtype == W.BF16 else "f32", "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.B, "cached_tokens": N, "num_q_heads": w.H, "num_kv_heads": w.H_kv,
+                   "head_dim": w.D, "page_size": w.P, "k": w.k, "score_scale": scale, "theta": theta,
+                   "pool_copies_rotated": R, "selection_cache": "every step is a miss"},
+        "decode_steps_per_s": 1e3 / ms_step,
+        "roofline": {"bound": "hbm", "kernel": "score_decode_kernel (ts_paged_qk_scores)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None, "algorithmic_bytes_per_launch": k_bytes,
+                     "avg_launch_ms": score_avg_ms, "median_launch_ms": float(np.median(score_ms)),
+                     "min_launch_ms": float(score_ms.min()),
+                     "score_pass_tokens_per_s": N / (score_avg_ms * 1e-3)},
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -8,7 +8,7 @@
 // every K byte that is loaded), and the eight partial sums are combined with three DPP steps.
 // The G x 32 x HB scores of the tile are staged in LDS so that they leave as 128-byte runs per head,
 // and the same staged values update running (max, sum-exp) statistics.  The workgroups' partial
-// statistics are merged by the last workgroup of a sequence to finish.
+// statistics are merged by a second, tiny kernel (one workgroup per head).
 #include "ts_kernels.h"
 
 namespace ts {
@@ -213,56 +213,56 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
     float* pp = a.partials + (((size_t)b * kScoreMaxWg + blockIdx.x) * H + h) * 2;
     pp[0] = m; pp[1] = l;
   }
-  __shared__ int is_last;
-  fence_device();
+}
+
+// Merges the per-workgroup (max, sum-exp) partials of one (sequence, head) into row_stats.
+// One workgroup per (head, sequence); every partial is loaded at once (one memory round trip), the
+// rescaling exponentials and the sum are double precision.
+__global__ __launch_bounds__(256) void score_stats_merge_kernel(ScoreArgs a, int nparts) {
+  __shared__ float s_m[4];
+  __shared__ double s_l[4];
+  const int h = blockIdx.x, b = blockIdx.y;
+  if (a.skip != nullptr && a.skip[b] != 0) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  constexpr int PER = kScoreMaxWg / 256;
+  float mp[PER], lp[PER];
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int p = threadIdx.x + 256 * i;
+    mp[i] = -INFINITY; lp[i] = 0.f;
+    if (p < nparts) {
+      const float2 v = *reinterpret_cast<const float2*>(a.partials + (((size_t)b * kScoreMaxWg + p) * a.H + h) * 2);
+      mp[i] = v.x; lp[i] = v.y;
+    }
+  }
+  float m = mp[0];
+#pragma unroll
+  for (int i = 1; i < PER; ++i) m = fmaxf(m, mp[i]);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+  if (lane == 0) s_m[wave] = m;
+  __syncthreads();
+  m = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));
+  const double sc = (double)a.scale;
+  double l = 0.0;
+#pragma unroll
+  for (int i = 0; i < PER; ++i)
+    if (mp[i] != -INFINITY) l += (double)lp[i] * exp_f64(sc * ((double)mp[i] - (double)m));
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) l += __shfl_xor(l, off);
+  if (lane == 0) s_l[wave] = l;
   __syncthreads();
   if (threadIdx.x == 0) {
-    const uint32_t old = atomicAdd(&a.counters[b], 1u);
-    is_last = (old == gridDim.x - 1);
+    a.row_stats[((size_t)b * a.H + h) * 2] = m;
+    a.row_stats[((size_t)b * a.H + h) * 2 + 1] = (float)(s_l[0] + s_l[1] + s_l[2] + s_l[3]);
   }
-  __syncthreads();
-  if (!is_last) return;
-  fence_device();
-  // ---- last workgroup of this sequence: merge all partials (double precision, exact exp)
-  const int sub = threadIdx.x & 7;
-  const double sc = (double)a.scale;
-  for (int h0 = 0; h0 < H; h0 += 32) {
-    const int h = h0 + (threadIdx.x >> 3);
-    float m = -INFINITY;
-    double l = 0.0;
-    if (h < H) {
-      for (int p = sub; p < (int)gridDim.x; p += 8) {
-        const float* pp = a.partials + (((size_t)b * kScoreMaxWg + p) * H + h) * 2;
-        const float mp = __hip_atomic_load(pp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const float lp = __hip_atomic_load(pp + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (mp == -INFINITY) continue;
-        if (mp > m) { l = (m == -INFINITY) ? 0.0 : l * exp(sc * ((double)m - (double)mp)); m = mp; }
-        l += (double)lp * exp(sc * ((double)mp - (double)m));
-      }
-    }
-    // combine the 8 sub-lanes (they sit in one aligned lane group)
-#pragma unroll
-    for (int off = 1; off < 8; off <<= 1) {
-      const float mo = __shfl_xor(m, off);
-      const double lo = __shfl_xor(l, off);
-      const float mn = fmaxf(m, mo);
-      double acc = 0.0;
-      if (m != -INFINITY) acc += l * exp(sc * ((double)m - (double)mn));
-      if (mo != -INFINITY) acc += lo * exp(sc * ((double)mo - (double)mn));
-      m = mn; l = acc;
-    }
-    if (h < H && sub == 0) {
-      a.row_stats[((size_t)b * H + h) * 2] = m;
-      a.row_stats[((size_t)b * H + h) * 2 + 1] = (float)l;
-    }
-  }
-  if (threadIdx.x == 0) a.counters[b] = 0u;   // ready for the next call
 }
 
 // ------------------------------------------------------------------------------------------------
 template <int DT, int D, int G, bool DOT2>
 static hipError_t launch_one(const ScoreArgs& a, dim3 grid, size_t lds, hipStream_t s) {
   hipLaunchKernelGGL((score_decode_kernel<DT, D, G, DOT2>), grid, dim3(256), lds, s, a);
+  hipLaunchKernelGGL(score_stats_merge_kernel, dim3(a.H, grid.y), dim3(256), 0, s, a, (int)grid.x);
   return hipGetLastError();
 }
 

@@ -98,6 +98,29 @@ __device__ __forceinline__ uint32_t float_key(float v) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// exp(x) for x <= 0 (larger x also fine up to ~700); result below 1e-300 flushes to 0
+__device__ __forceinline__ double exp_f64(double x) {
+  if (x < -690.0) return 0.0;
+  const double n = rint(x * 1.44269504088896340736);
+  double r = fma(n, -6.93147180369123816490e-01, x);
+  r = fma(n, -1.90821492927058770002e-10, r);
+  // Taylor series on |r| <= 0.347, degree 11: truncation below 3e-14 relative
+  double p = 1.0 / 39916800.0;
+  p = fma(p, r, 1.0 / 3628800.0);
+  p = fma(p, r, 1.0 / 362880.0);
+  p = fma(p, r, 1.0 / 40320.0);
+  p = fma(p, r, 1.0 / 5040.0);
+  p = fma(p, r, 1.0 / 720.0);
+  p = fma(p, r, 1.0 / 120.0);
+  p = fma(p, r, 1.0 / 24.0);
+  p = fma(p, r, 1.0 / 6.0);
+  p = fma(p, r, 0.5);
+  p = fma(p, r, 1.0);
+  p = fma(p, r, 1.0);
+  const long long bits = ((long long)n + 1023LL) << 52;   // 2^n, n >= -996 here
+  return p * __longlong_as_double(bits);
+}
+
 // agent-scope release/acquire fence around the "last workgroup finishes the job" counters
 __device__ __forceinline__ void fence_device() { __threadfence(); }
 #endif  // __HIPCC__
