@@ -90,7 +90,6 @@ int32_t ts_paged_qk_scores(const ts_problem* p, const void* q, float* scores, fl
   a.page_indptr = p->page_indptr; a.page_indices = p->page_indices; a.seq_lens = p->seq_lens; a.skip = skip;
   a.scores = scores; a.row_stats = row_stats;
   a.partials = (float*)((uint8_t*)ws + w.score_partials);
-  a.counters = (uint32_t*)((uint8_t*)ws + w.score_counters);
   a.H = p->num_q_heads; a.H_kv = p->num_kv_heads; a.P = p->page_size; a.p_shift = ilog2(p->page_size);
   a.max_seq_len = p->max_seq_len;
   a.HB = p->num_kv_heads < 8 ? p->num_kv_heads : 8; a.hb_shift = ilog2(a.HB); a.NU = p->num_kv_heads / a.HB;
@@ -136,7 +135,6 @@ int32_t ts_topk(const ts_problem* p, const float* votes, int32_t k, int32_t* idx
   a.hist = (uint32_t*)((uint8_t*)ws + w.topk_hist);
   a.state = (uint32_t*)((uint8_t*)ws + w.topk_state);
   a.blk = (uint32_t*)((uint8_t*)ws + w.topk_blk);
-  a.counters = (uint32_t*)((uint8_t*)ws + w.topk_counters);
   a.k = k; a.max_seq_len = p->max_seq_len; a.nblk = w.topk_nblk;
   return launch_topk(a, p->batch, (hipStream_t)stream) == hipSuccess ? TS_OK : TS_ERR_HIP;
 }
@@ -164,6 +162,7 @@ int32_t ts_sparse_paged_attn(const ts_problem* p, const void* q, const int32_t* 
   if (!(sm_scale == sm_scale)) return TS_ERR_INVALID_ARG;
   if (p->chunk != 1) return TS_ERR_UNSUPPORTED;
   const WsLayout w = ws_layout(p, idx_stride);
+  if (w.attn_nsplit > kAttnMaxSplit) return TS_ERR_UNSUPPORTED;
   if (ws == nullptr || ((uintptr_t)ws & 255) != 0 || ws_bytes < w.total) return TS_ERR_WORKSPACE;
   AttnArgs a{};
   a.q = (const uint8_t*)q; a.k_pool = (const uint8_t*)p->k_pool; a.v_pool = (const uint8_t*)p->v_pool;
@@ -171,7 +170,6 @@ int32_t ts_sparse_paged_attn(const ts_problem* p, const void* q, const int32_t* 
   a.idx = idx; a.count = count; a.out = (uint8_t*)out; a.lse = lse;
   a.part_out = (float*)((uint8_t*)ws + w.attn_out);
   a.part_ml = (float*)((uint8_t*)ws + w.attn_ml);
-  a.counters = (uint32_t*)((uint8_t*)ws + w.attn_counters);
   a.H = p->num_q_heads; a.H_kv = p->num_kv_heads; a.P = p->page_size; a.p_shift = ilog2(p->page_size);
   a.idx_stride = idx_stride; a.nsplit = w.attn_nsplit; a.max_seq_len = p->max_seq_len; a.sm_scale = sm_scale;
   const int G = p->num_q_heads / p->num_kv_heads;

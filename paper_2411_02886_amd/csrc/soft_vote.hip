@@ -16,27 +16,31 @@ __global__ __launch_bounds__(256) void soft_vote_kernel(VoteArgs a) {
   const int b = blockIdx.y;
   if (a.skip != nullptr && a.skip[b] != 0) return;
   const int N = min(max(a.seq_lens[b], 0), a.max_seq_len);
-  const int t = blockIdx.x * 256 + threadIdx.x;
   if (blockIdx.x * 256 >= N) return;
-  for (int h = threadIdx.x; h < a.H; h += 256) {
-    s_m[h] = (double)a.row_stats[((size_t)b * a.H + h) * 2];
-    s_inv[h] = 1.0 / (double)a.row_stats[((size_t)b * a.H + h) * 2 + 1];
-  }
-  __syncthreads();
-  if (t >= N) return;
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  const int tc = min(t, N - 1);                     // out-of-range threads shadow the last token
   const double c = (double)a.scale;
-  const float* sp = a.scores + (size_t)b * a.H * a.max_seq_len + t;
+  const float* sp = a.scores + (size_t)b * a.H * a.max_seq_len + tc;
+  // statistics of every head: issued together with the first batch of score loads
+  const float2 stv = *reinterpret_cast<const float2*>(a.row_stats + ((size_t)b * a.H + min((int)threadIdx.x, a.H - 1)) * 2);
+  const float st_m = stv.x, st_l = stv.y;
   double vote = 0.0;
-  int h = 0;
-  for (; h + 8 <= a.H; h += 8) {
-    float s[8];
+  for (int h0 = 0; h0 < a.H; h0 += 32) {
+    float s[32];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) s[e] = sp[(size_t)(h + e) * a.max_seq_len];
+    for (int e = 0; e < 32; ++e) s[e] = sp[(size_t)min(h0 + e, a.H - 1) * a.max_seq_len];   // clamped: no branch between loads
+    if (h0 == 0) {
+      if (threadIdx.x < a.H) { s_m[threadIdx.x] = (double)st_m; s_inv[threadIdx.x] = 1.0 / (double)st_l; }
+      __syncthreads();
+    }
 #pragma unroll
-    for (int e = 0; e < 8; ++e) vote = fma(exp_f64(c * ((double)s[e] - s_m[h + e])), s_inv[h + e], vote);
+    for (int e = 0; e < 32; ++e) {
+      const int hh = min(h0 + e, a.H - 1);
+      const double w = (h0 + e < a.H) ? s_inv[hh] : 0.0;
+      vote = fma(exp_f64(c * ((double)s[e] - s_m[hh])), w, vote);
+    }
   }
-  for (; h < a.H; ++h) vote = fma(exp_f64(c * ((double)sp[(size_t)h * a.max_seq_len] - s_m[h])), s_inv[h], vote);
-  a.votes[(size_t)b * a.max_seq_len + t] = (float)vote;
+  if (t < N) a.votes[(size_t)b * a.max_seq_len + t] = (float)vote;
 }
 
 hipError_t launch_soft_vote(const VoteArgs& a, int B, hipStream_t s) {

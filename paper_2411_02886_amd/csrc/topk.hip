@@ -1,11 +1,12 @@
 // TopK of Eq. 3-5 as an exact radix select over 32-bit order-preserving keys.
 //
 // Three histogram passes (11 + 11 + 10 bits) find the key of the k-th largest value: every
-// workgroup histograms its 2048-key chunk in LDS, adds the non-empty bins to a global histogram,
-// and the last workgroup to finish walks the histogram from the top and fixes the next digit.
-// A counting pass then gives every chunk the number of keys above / equal to that key before it,
-// and the emit pass writes the winners in token order: all keys above the threshold plus the
-// first (k - #above) keys equal to it.  That is the "lower token index wins ties" rule and yields
+// workgroup histograms its 2048-key chunk in LDS and adds the non-empty bins to a global histogram;
+// the next kernel's workgroups each walk that (8 KiB, cache-resident) histogram from the top and fix
+// the digit for themselves, so no kernel waits on another workgroup and nothing but the kernel
+// boundary orders the passes.  A counting pass then records per chunk the number of keys above /
+// equal to the threshold key, and the emit pass writes the winners in token order: all keys above
+// the threshold plus the first (k - #above) keys equal to it.  That is the "lower token index wins ties" rule and yields
 // ascending indices without a sort.
 #include "ts_kernels.h"
 
@@ -35,167 +36,210 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* t
   return base + incl - v;
 }
 
-__device__ __forceinline__ bool arrive_last(uint32_t* counter, uint32_t nblocks) {
-  __shared__ int s_last;
-  fence_device();
-  __syncthreads();
-  if (threadIdx.x == 0) s_last = (atomicAdd(counter, 1u) == nblocks - 1);
-  __syncthreads();
-  const bool last = s_last != 0;
-  if (last) fence_device();
-  return last;
-}
-
-template <int PASS>
-__global__ __launch_bounds__(256) void topk_hist_kernel(TopkArgs a) {
-  constexpr int SHIFT = PASS == 0 ? 21 : (PASS == 1 ? 10 : 0);
-  constexpr int NB = PASS == 2 ? 1024 : 2048;
-  constexpr int HI_SHIFT = PASS == 1 ? 21 : 10;   // bits above this pass's digit (PASS > 0)
-  __shared__ uint32_t h[kTopkBins];
-  __shared__ uint32_t scan_lds[8];
-  const int b = blockIdx.y;
-  if (a.skip != nullptr && a.skip[b] != 0) return;
-  const int N = min(max(a.seq_lens[b], 0), a.max_seq_len);
-  for (int i = threadIdx.x; i < NB; i += 256) h[i] = 0;
-  __syncthreads();
-  const uint32_t prefix = PASS > 0 ? a.state[b * 4 + 0] : 0u;
-  const float* v = a.votes + (size_t)b * a.max_seq_len;
-  const int base = blockIdx.x * kTopkChunk;
-#pragma unroll
-  for (int i = 0; i < kTopkChunk / 256; ++i) {
-    const int t = base + i * 256 + threadIdx.x;
-    if (t < N) {
-      const uint32_t key = float_key(v[t]);
-      if (PASS == 0 || (key >> HI_SHIFT) == (prefix >> HI_SHIFT)) atomicAdd(&h[(key >> SHIFT) & (NB - 1)], 1u);
-    }
-  }
-  __syncthreads();
-  uint32_t* gh = a.hist + (size_t)b * kTopkBins;
-  for (int i = threadIdx.x; i < NB; i += 256)
-    if (h[i] != 0) atomicAdd(&gh[i], h[i]);
-  if (!arrive_last(&a.counters[b * 2], gridDim.x)) return;
-
-  // last workgroup: walk the global histogram from the top bin down
-  uint32_t k_rem;
-  if (PASS == 0) k_rem = (uint32_t)min(a.k, N); else k_rem = a.state[b * 4 + 1];
+// Walks a global histogram from its top bin down and finds the bin holding the k_rem-th largest key.
+// All 256 threads call it and all get the result: digit and the rank remaining inside that bin.
+// An empty selection (k_rem == 0) returns digit = NB (no key can match it).
+template <int NB>
+__device__ __forceinline__ void find_digit(const uint32_t* gh, uint32_t k_rem, uint32_t* digit, uint32_t* k_next,
+                                           uint32_t* lds /* >= 8 words */) {
   constexpr int PER = NB / 256;
   uint32_t c[PER];
   uint32_t sum = 0;
 #pragma unroll
   for (int e = 0; e < PER; ++e) {   // thread 0 owns the top PER bins, in descending order
-    const int bin = NB - 1 - (threadIdx.x * PER + e);
-    c[e] = __hip_atomic_load(&gh[bin], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    c[e] = gh[NB - 1 - (threadIdx.x * PER + e)];
     sum += c[e];
   }
   uint32_t total;
-  uint32_t above = block_exclusive_scan(sum, &total, scan_lds);
-  if (k_rem == 0) {
-    if (threadIdx.x == 0) {
-      a.state[b * 4 + 0] = 0xffffffffu; a.state[b * 4 + 1] = 0u;
-      if (PASS == 0) a.state[b * 4 + 2] = 0u;
-    }
-  } else {
+  uint32_t above = block_exclusive_scan(sum, &total, lds);
+  __syncthreads();
+  if (threadIdx.x == 0) { lds[5] = NB; lds[6] = 0u; }
+  __syncthreads();
+  if (k_rem != 0) {
 #pragma unroll
     for (int e = 0; e < PER; ++e) {
-      if (above < k_rem && k_rem <= above + c[e]) {
-        const uint32_t bin = NB - 1 - (threadIdx.x * PER + e);
-        a.state[b * 4 + 0] = prefix | (bin << SHIFT);
-        a.state[b * 4 + 1] = k_rem - above;
-        if (PASS == 0) a.state[b * 4 + 2] = k_rem;
-      }
+      if (above < k_rem && k_rem <= above + c[e]) { lds[5] = NB - 1 - (threadIdx.x * PER + e); lds[6] = k_rem - above; }
       above += c[e];
     }
   }
-#pragma unroll
-  for (int e = 0; e < PER; ++e) gh[NB - 1 - (threadIdx.x * PER + e)] = 0u;
-  if (threadIdx.x == 0) a.counters[b * 2] = 0u;
+  __syncthreads();
+  *digit = lds[5];
+  *k_next = lds[6];
+  __syncthreads();
 }
 
-// per chunk: how many keys are above / equal to the threshold; last workgroup turns the per-chunk
-// counts into exclusive offsets and publishes count[b]
-__global__ __launch_bounds__(256) void topk_count_kernel(TopkArgs a) {
-  __shared__ uint32_t scan_lds[8];
-  __shared__ uint32_t red[8];
-  const int b = blockIdx.y;
-  if (a.skip != nullptr && a.skip[b] != 0) return;
-  const int N = min(max(a.seq_lens[b], 0), a.max_seq_len);
-  const uint32_t thr = a.state[b * 4 + 0];
-  const float* v = a.votes + (size_t)b * a.max_seq_len;
-  const int base = blockIdx.x * kTopkChunk;
-  uint32_t gt = 0, eq = 0;
+// state words per sequence
+enum { ST_PREFIX0 = 0, ST_KREM0 = 1, ST_KEFF = 2, ST_PREFIX1 = 3, ST_KREM1 = 4, ST_THR = 5, ST_NEED_EQ = 6, ST_NONE = 7 };
+
+__device__ __forceinline__ void load_keys(const float* v, int base, int N, uint32_t* key, bool* valid) {
 #pragma unroll
   for (int i = 0; i < kTopkChunk / 256; ++i) {
     const int t = base + i * 256 + threadIdx.x;
-    if (t < N) {
-      const uint32_t key = float_key(v[t]);
-      gt += key > thr;
-      eq += key == thr;
+    valid[i] = t < N;
+    key[i] = valid[i] ? float_key(v[t]) : 0u;
+  }
+}
+
+__device__ __forceinline__ void flush_hist(const uint32_t* h, uint32_t* gh, int nb) {
+  for (int i = threadIdx.x; i < nb; i += 256)
+    if (h[i] != 0) atomicAdd(&gh[i], h[i]);
+}
+
+// pass 0: histogram of the top 11 key bits
+__global__ __launch_bounds__(256) void topk_hist0_kernel(TopkArgs a) {
+  __shared__ uint32_t h[kTopkBins];
+  const int b = blockIdx.y;
+  if (a.skip != nullptr && a.skip[b] != 0) return;
+  const int N = min(max(a.seq_lens[b], 0), a.max_seq_len);
+  const int base = blockIdx.x * kTopkChunk;
+  if (base >= N) return;
+  uint32_t key[kTopkChunk / 256]; bool valid[kTopkChunk / 256];
+  load_keys(a.votes + (size_t)b * a.max_seq_len, base, N, key, valid);
+  for (int i = threadIdx.x; i < kTopkBins; i += 256) h[i] = 0;
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < kTopkChunk / 256; ++i)
+    if (valid[i]) atomicAdd(&h[key[i] >> 21], 1u);
+  __syncthreads();
+  flush_hist(h, a.hist + ((size_t)b * 3 + 0) * kTopkBins, kTopkBins);
+}
+
+// pass 1: fix digit 0 from histogram 0, histogram the next 11 bits of the keys that carry it
+__global__ __launch_bounds__(256) void topk_hist1_kernel(TopkArgs a) {
+  __shared__ uint32_t h[kTopkBins];
+  __shared__ uint32_t lds[8];
+  const int b = blockIdx.y;
+  if (a.skip != nullptr && a.skip[b] != 0) return;
+  const int N = min(max(a.seq_lens[b], 0), a.max_seq_len);
+  const int base = blockIdx.x * kTopkChunk;
+  if (base >= N && blockIdx.x != 0) return;
+  uint32_t key[kTopkChunk / 256]; bool valid[kTopkChunk / 256];
+  load_keys(a.votes + (size_t)b * a.max_seq_len, base, N, key, valid);
+  for (int i = threadIdx.x; i < kTopkBins; i += 256) h[i] = 0;
+  const uint32_t k_eff = (uint32_t)min(a.k, N);
+  uint32_t d0, krem0;
+  find_digit<kTopkBins>(a.hist + ((size_t)b * 3 + 0) * kTopkBins, k_eff, &d0, &krem0, lds);
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    a.state[b * 8 + ST_PREFIX0] = d0 << 21; a.state[b * 8 + ST_KREM0] = krem0; a.state[b * 8 + ST_KEFF] = k_eff;
+  }
+#pragma unroll
+  for (int i = 0; i < kTopkChunk / 256; ++i)
+    if (valid[i] && (key[i] >> 21) == d0) atomicAdd(&h[(key[i] >> 10) & 2047u], 1u);
+  __syncthreads();
+  flush_hist(h, a.hist + ((size_t)b * 3 + 1) * kTopkBins, kTopkBins);
+}
+
+// pass 2: fix digit 1, histogram the last 10 bits; histogram 0 is no longer needed and is cleared
+__global__ __launch_bounds__(256) void topk_hist2_kernel(TopkArgs a) {
+  __shared__ uint32_t h[1024];
+  __shared__ uint32_t lds[8];
+  const int b = blockIdx.y;
+  if (a.skip != nullptr && a.skip[b] != 0) return;
+  const int N = min(max(a.seq_lens[b], 0), a.max_seq_len);
+  const int base = blockIdx.x * kTopkChunk;
+  if (base >= N && blockIdx.x != 0) return;
+  uint32_t key[kTopkChunk / 256]; bool valid[kTopkChunk / 256];
+  load_keys(a.votes + (size_t)b * a.max_seq_len, base, N, key, valid);
+  for (int i = threadIdx.x; i < 1024; i += 256) h[i] = 0;
+  const uint32_t prefix0 = a.state[b * 8 + ST_PREFIX0], krem0 = a.state[b * 8 + ST_KREM0];
+  uint32_t d1, krem1;
+  find_digit<kTopkBins>(a.hist + ((size_t)b * 3 + 1) * kTopkBins, krem0, &d1, &krem1, lds);
+  // an empty selection keeps an impossible prefix so that nothing matches below
+  const bool none = krem0 == 0;
+  const uint32_t prefix1 = prefix0 | ((d1 & 2047u) << 10);
+  if (blockIdx.x == 0) {
+    if (threadIdx.x == 0) { a.state[b * 8 + ST_PREFIX1] = prefix1; a.state[b * 8 + ST_KREM1] = none ? 0u : krem1; }
+    uint32_t* g0 = a.hist + ((size_t)b * 3 + 0) * kTopkBins;
+    for (int i = threadIdx.x; i < kTopkBins; i += 256) g0[i] = 0u;
+  }
+#pragma unroll
+  for (int i = 0; i < kTopkChunk / 256; ++i)
+    if (valid[i] && !none && (key[i] >> 10) == (prefix1 >> 10)) atomicAdd(&h[key[i] & 1023u], 1u);
+  __syncthreads();
+  flush_hist(h, a.hist + ((size_t)b * 3 + 2) * kTopkBins, 1024);
+}
+
+// fix the last digit (the threshold key is now exact) and count, per chunk, the keys above / equal to it
+__global__ __launch_bounds__(256) void topk_count_kernel(TopkArgs a) {
+  __shared__ uint32_t lds[8];
+  __shared__ uint32_t red[4];
+  const int b = blockIdx.y;
+  if (a.skip != nullptr && a.skip[b] != 0) return;
+  const int N = min(max(a.seq_lens[b], 0), a.max_seq_len);
+  const int base = blockIdx.x * kTopkChunk;
+  uint32_t key[kTopkChunk / 256]; bool valid[kTopkChunk / 256];
+  load_keys(a.votes + (size_t)b * a.max_seq_len, base, N, key, valid);
+  const uint32_t prefix1 = a.state[b * 8 + ST_PREFIX1], krem1 = a.state[b * 8 + ST_KREM1];
+  uint32_t d2, need_eq;
+  find_digit<1024>(a.hist + ((size_t)b * 3 + 2) * kTopkBins, krem1, &d2, &need_eq, lds);
+  const bool none = krem1 == 0;
+  const uint32_t thr = none ? 0xffffffffu : (prefix1 | (d2 & 1023u));
+  if (none) need_eq = 0;
+  if (blockIdx.x == 0) {
+    if (threadIdx.x == 0) {
+      a.state[b * 8 + ST_THR] = thr; a.state[b * 8 + ST_NEED_EQ] = need_eq; a.state[b * 8 + ST_NONE] = none;
     }
+    uint32_t* g1 = a.hist + ((size_t)b * 3 + 1) * kTopkBins;
+    for (int i = threadIdx.x; i < kTopkBins; i += 256) g1[i] = 0u;
+  }
+  uint32_t gt = 0, eq = 0;
+#pragma unroll
+  for (int i = 0; i < kTopkChunk / 256; ++i) {
+    gt += valid[i] && !none && key[i] > thr;
+    eq += valid[i] && !none && key[i] == thr;
   }
   uint32_t packed = gt | (eq << 16);   // a chunk holds 2048 keys: both counts fit in 16 bits
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) packed += __shfl_xor(packed, off);
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = packed;
   __syncthreads();
-  uint32_t* blk = a.blk + (size_t)b * a.nblk * 2;
-  if (threadIdx.x == 0) {
-    const uint32_t s = red[0] + red[1] + red[2] + red[3];
-    blk[blockIdx.x * 2 + 0] = s & 0xffffu;
-    blk[blockIdx.x * 2 + 1] = s >> 16;
-  }
-  if (!arrive_last(&a.counters[b * 2 + 1], gridDim.x)) return;
-  uint32_t carry_gt = 0, carry_eq = 0;
-  for (int i0 = 0; i0 < (int)gridDim.x; i0 += 256) {
-    const int i = i0 + threadIdx.x;
-    uint32_t g = 0, e = 0;
-    if (i < (int)gridDim.x) {
-      g = __hip_atomic_load(&blk[i * 2 + 0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      e = __hip_atomic_load(&blk[i * 2 + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    uint32_t tg, te;
-    const uint32_t xg = block_exclusive_scan(g, &tg, scan_lds);
-    const uint32_t xe = block_exclusive_scan(e, &te, scan_lds);
-    if (i < (int)gridDim.x) { blk[i * 2 + 0] = carry_gt + xg; blk[i * 2 + 1] = carry_eq + xe; }
-    carry_gt += tg; carry_eq += te;
-  }
-  if (threadIdx.x == 0) {
-    a.count[b] = (int32_t)a.state[b * 4 + 2];
-    a.counters[b * 2 + 1] = 0u;
-  }
+  if (threadIdx.x == 0) a.blk[(size_t)b * a.nblk + blockIdx.x] = red[0] + red[1] + red[2] + red[3];
 }
 
-// winners of a chunk, in token order
+// winners of a chunk, in token order; every workgroup sums the counts of the chunks before it
 __global__ __launch_bounds__(256) void topk_emit_kernel(TopkArgs a) {
   __shared__ uint32_t scan_lds[8];
+  __shared__ uint32_t red[2][4];
   const int b = blockIdx.y;
   if (a.skip != nullptr && a.skip[b] != 0) return;
   const int N = min(max(a.seq_lens[b], 0), a.max_seq_len);
-  const uint32_t thr = a.state[b * 4 + 0];
-  const uint32_t need_eq = a.state[b * 4 + 1];
-  const int k_eff = (int)a.state[b * 4 + 2];
+  const uint32_t thr = a.state[b * 8 + ST_THR];
+  const uint32_t need_eq = a.state[b * 8 + ST_NEED_EQ];
+  const bool none = a.state[b * 8 + ST_NONE] != 0;
+  const int k_eff = (int)a.state[b * 8 + ST_KEFF];
   int32_t* out = a.idx + (size_t)b * a.k;
-  if (blockIdx.x == 0)
+  if (blockIdx.x == 0) {
     for (int i = k_eff + threadIdx.x; i < a.k; i += 256) out[i] = -1;
+    if (threadIdx.x == 0) a.count[b] = k_eff;
+    uint32_t* g2 = a.hist + ((size_t)b * 3 + 2) * kTopkBins;
+    for (int i = threadIdx.x; i < 1024; i += 256) g2[i] = 0u;
+  }
   const int base = blockIdx.x * kTopkChunk;
-  if (base >= N) return;
+  if (base >= N || none) return;
   const float* v = a.votes + (size_t)b * a.max_seq_len;
   constexpr int PER = kTopkChunk / 256;
   const int t0 = base + threadIdx.x * PER;   // PER consecutive tokens per thread: order is preserved
   uint32_t key[PER];
+#pragma unroll
+  for (int e = 0; e < PER; ++e) key[e] = (t0 + e) < N ? float_key(v[t0 + e]) : 0u;
+  // counts of all earlier chunks (gt in the low half is too narrow for a sum: add the halves apart)
+  uint32_t pg = 0, pe = 0;
+  const uint32_t* blk = a.blk + (size_t)b * a.nblk;
+  for (int i = threadIdx.x; i < (int)blockIdx.x; i += 256) { const uint32_t x = blk[i]; pg += x & 0xffffu; pe += x >> 16; }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) { pg += __shfl_xor(pg, off); pe += __shfl_xor(pe, off); }
+  if ((threadIdx.x & 63) == 0) { red[0][threadIdx.x >> 6] = pg; red[1][threadIdx.x >> 6] = pe; }
   uint32_t gt = 0, eq = 0;
 #pragma unroll
   for (int e = 0; e < PER; ++e) {
-    const int t = t0 + e;
-    key[e] = t < N ? float_key(v[t]) : 0u;
-    const bool valid = t < N;
+    const bool valid = (t0 + e) < N;
     gt += valid && key[e] > thr;
     eq += valid && key[e] == thr;
   }
   uint32_t total;
-  const uint32_t ex = block_exclusive_scan(gt | (eq << 16), &total, scan_lds);
-  const uint32_t* blk = a.blk + ((size_t)b * a.nblk + blockIdx.x) * 2;
-  uint32_t gt_before = blk[0] + (ex & 0xffffu);
-  uint32_t eq_before = blk[1] + (ex >> 16);
+  const uint32_t ex = block_exclusive_scan(gt | (eq << 16), &total, scan_lds);   // has the barriers red[] needs
+  uint32_t gt_before = red[0][0] + red[0][1] + red[0][2] + red[0][3] + (ex & 0xffffu);
+  uint32_t eq_before = red[1][0] + red[1][1] + red[1][2] + red[1][3] + (ex >> 16);
 #pragma unroll
   for (int e = 0; e < PER; ++e) {
     const int t = t0 + e;
@@ -213,9 +257,9 @@ __global__ __launch_bounds__(256) void topk_emit_kernel(TopkArgs a) {
 
 hipError_t launch_topk(const TopkArgs& a, int B, hipStream_t s) {
   dim3 grid(a.nblk, B);
-  hipLaunchKernelGGL(topk_hist_kernel<0>, grid, dim3(256), 0, s, a);
-  hipLaunchKernelGGL(topk_hist_kernel<1>, grid, dim3(256), 0, s, a);
-  hipLaunchKernelGGL(topk_hist_kernel<2>, grid, dim3(256), 0, s, a);
+  hipLaunchKernelGGL(topk_hist0_kernel, grid, dim3(256), 0, s, a);
+  hipLaunchKernelGGL(topk_hist1_kernel, grid, dim3(256), 0, s, a);
+  hipLaunchKernelGGL(topk_hist2_kernel, grid, dim3(256), 0, s, a);
   hipLaunchKernelGGL(topk_count_kernel, grid, dim3(256), 0, s, a);
   hipLaunchKernelGGL(topk_emit_kernel, grid, dim3(256), 0, s, a);
   return hipGetLastError();

@@ -13,19 +13,17 @@ constexpr int kScoreLdsStride = 36;    // floats per head row of the staged scor
 constexpr int kScoreMaxWg = 1024;      // upper bound on workgroups per sequence in the score pass
 constexpr int kTopkBins = 2048;        // 11-bit radix digit
 constexpr int kTopkChunk = 2048;       // keys per workgroup in the top-k passes
-constexpr int kAttnChunk = 64;         // selected tokens per workgroup in sparse attention
+constexpr int kAttnChunk = 128;        // selected tokens per workgroup in sparse attention
+constexpr int kAttnMaxSplit = 256;     // splits the merge kernel can stage (k <= 32768)
 
 // ---------------------------------------------------------------- workspace layout (host + device)
 struct WsLayout {
+  size_t topk_hist;        // uint32 [B][3][kTopkBins] : one histogram per radix pass (must start zeroed)
+  size_t topk_state;       // uint32 [B][8] : digits and remaining ranks fixed so far
   size_t score_partials;   // float [B][kScoreMaxWg][H][2]
-  size_t score_counters;   // uint32 [B]
-  size_t topk_hist;        // uint32 [B][kTopkBins]
-  size_t topk_state;       // uint32 [B][4] : prefix, k_remaining, k_effective, unused
-  size_t topk_blk;         // uint32 [B][nblk][2] : per-block (greater, equal) counts -> exclusive offsets
-  size_t topk_counters;    // uint32 [B][2]
+  size_t topk_blk;         // uint32 [B][nblk] : per-chunk (above | equal << 16) counts
   size_t attn_out;         // float [B][H][nsplit][D]
   size_t attn_ml;          // float [B][H][nsplit][2]
-  size_t attn_counters;    // uint32 [B][H_kv]
   size_t total;
   int topk_nblk;
   int attn_nsplit;
@@ -42,14 +40,11 @@ inline WsLayout ws_layout(const ts_problem* p, int k) {
   if (w.topk_nblk < 1) w.topk_nblk = 1;
   w.attn_nsplit = (k + kAttnChunk - 1) / kAttnChunk;
   if (w.attn_nsplit < 1) w.attn_nsplit = 1;
-  // counters and histograms first: they are the part that must start (and is left) zeroed
-  w.score_counters = take(B * 4);
-  w.topk_hist = take(B * kTopkBins * 4);
-  w.topk_counters = take(B * 2 * 4);
-  w.attn_counters = take(B * (size_t)p->num_kv_heads * 4);
-  w.topk_state = take(B * 4 * 4);
+  // the histograms come first: they are the part that must start (and is left) zeroed
+  w.topk_hist = take(B * 3 * kTopkBins * 4);
+  w.topk_state = take(B * 8 * 4);
   w.score_partials = take(B * kScoreMaxWg * H * 2 * 4);
-  w.topk_blk = take(B * (size_t)w.topk_nblk * 2 * 4);
+  w.topk_blk = take(B * (size_t)w.topk_nblk * 4);
   w.attn_out = take(B * H * (size_t)w.attn_nsplit * D * 4);
   w.attn_ml = take(B * H * (size_t)w.attn_nsplit * 2 * 4);
   w.total = off;
@@ -100,7 +95,8 @@ __device__ __forceinline__ uint32_t float_key(float v) {
 
 // exp(x) for x <= 0 (larger x also fine up to ~700); result below 1e-300 flushes to 0
 __device__ __forceinline__ double exp_f64(double x) {
-  if (x < -690.0) return 0.0;
+  const bool tiny = x < -690.0;
+  x = tiny ? -690.0 : x;
   const double n = rint(x * 1.44269504088896340736);
   double r = fma(n, -6.93147180369123816490e-01, x);
   r = fma(n, -1.90821492927058770002e-10, r);
@@ -118,11 +114,9 @@ __device__ __forceinline__ double exp_f64(double x) {
   p = fma(p, r, 1.0);
   p = fma(p, r, 1.0);
   const long long bits = ((long long)n + 1023LL) << 52;   // 2^n, n >= -996 here
-  return p * __longlong_as_double(bits);
+  return tiny ? 0.0 : p * __longlong_as_double(bits);
 }
 
-// agent-scope release/acquire fence around the "last workgroup finishes the job" counters
-__device__ __forceinline__ void fence_device() { __threadfence(); }
 #endif  // __HIPCC__
 
 }  // namespace ts

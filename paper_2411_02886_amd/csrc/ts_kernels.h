@@ -14,7 +14,6 @@ struct ScoreArgs {
   float* scores;
   float* row_stats;
   float* partials;
-  uint32_t* counters;
   int H, H_kv, P, p_shift, max_seq_len;
   int HB, hb_shift, NU;   // KV heads per wave tile (min(H_kv, 8)), its log2, H_kv / HB
   int uniform_page;       // every step of a wave reads one page (P >= tokens per step)
@@ -38,10 +37,9 @@ struct TopkArgs {
   const uint8_t* skip;
   int32_t* idx;
   int32_t* count;
-  uint32_t* hist;       // [B][kTopkBins]
-  uint32_t* state;      // [B][4] prefix, k_remaining, k_effective
-  uint32_t* blk;        // [B][nblk][2]
-  uint32_t* counters;   // [B][2]
+  uint32_t* hist;       // [B][3][kTopkBins]
+  uint32_t* state;      // [B][8]
+  uint32_t* blk;        // [B][nblk]
   int k, max_seq_len, nblk;
 };
 
@@ -68,7 +66,6 @@ struct AttnArgs {
   float* lse;
   float* part_out;     // [B][H][nsplit][D]
   float* part_ml;      // [B][H][nsplit][2]
-  uint32_t* counters;  // [B][H_kv]
   int H, H_kv, P, p_shift, idx_stride, nsplit, max_seq_len;
   float sm_scale;
 };
