@@ -53,8 +53,8 @@ typedef struct ts_problem {
   int32_t num_kv_heads; /* H_kv, a power of two, H % H_kv == 0, H / H_kv <= 8                    */
   int32_t head_dim;     /* D  in {64, 128}                                                       */
   int32_t page_size;    /* P  a power of two with P * min(H_kv, 8) % 8 == 0 (16 in the configs)   */
-  int32_t max_seq_len;  /* host-known upper bound on every seq_lens[b]; also the row stride of    */
-                        /* scores[B][H][max_seq_len] and votes[B][max_seq_len]                    */
+  int32_t max_seq_len;  /* host-known upper bound on every seq_lens[b]; also the token extent of   */
+                        /* scores[B][max_seq_len][H] and votes[B][max_seq_len]                    */
   int32_t dtype;        /* ts_dtype of q, k_pool, v_pool, cached_q and out                        */
   const void* k_pool;   /* [device] [num_pages][P][H_kv][D]                                      */
   const void* v_pool;   /* [device] same layout (may be NULL for calls that do not read V)        */
@@ -78,17 +78,18 @@ int32_t ts_workspace_bytes(const ts_problem* p, int32_t k, size_t* bytes);
 int32_t ts_workspace_init(void* ws, size_t ws_bytes, void* stream);
 
 /* Algorithm 2 (Paged Dot Product Kernel).  For every sequence b, head h, cached token t < N_b:
- *   scores[b][h][t] = < q[b][0][h][:], K[slot(b,t)][h / G][:] >          (raw, unscaled)
+ *   scores[b][t][h] = < q[b][0][h][:], K[slot(b,t)][h / G][:] >          (raw, unscaled; the matrix
+ *   S of Algorithm 2 stored token-major so that it streams out in contiguous bursts)
  * and, feeding Eq. 5, per (b,h):
- *   row_stats[b][h][0] = max_t scores[b][h][t]
- *   row_stats[b][h][1] = sum_t exp(score_scale * (scores[b][h][t] - max))   (0 when N_b == 0)
- * q [device] [B][C][H][D]; scores [device] float [B][H][max_seq_len] (entries t >= N_b untouched);
+ *   row_stats[b][h][0] = max_t scores[b][t][h]
+ *   row_stats[b][h][1] = sum_t exp(score_scale * (scores[b][t][h] - max))   (0 when N_b == 0)
+ * q [device] [B][C][H][D]; scores [device] float [B][max_seq_len][H] (rows t >= N_b untouched);
  * row_stats [device] float [B][H][2]; score_scale >= 0 (Eq. 5 as printed uses 1).
  * Decode only: chunk must be 1 (TS_ERR_UNSUPPORTED otherwise). */
 int32_t ts_paged_qk_scores(const ts_problem* p, const void* q, float* scores, float* row_stats, float score_scale,
                            const uint8_t* skip /* [device] [B] or NULL */, void* ws, size_t ws_bytes, void* stream);
 
-/* Eq. 5 (head soft vote):  votes[b][t] = sum_h exp(score_scale*(scores[b][h][t] - max_h)) / sumexp_h
+/* Eq. 5 (head soft vote):  votes[b][t] = sum_h exp(score_scale*(scores[b][t][h] - max_h)) / sumexp_h
  * for t < N_b, computed in double precision from the float scores and rounded once to float.
  * votes [device] float [B][max_seq_len] (entries t >= N_b untouched). */
 int32_t ts_soft_vote(const ts_problem* p, const float* scores, const float* row_stats, float score_scale,

@@ -21,7 +21,7 @@ static int32_t check_problem(const ts_problem* p) {
   if (p->page_indptr == nullptr || p->page_indices == nullptr || p->seq_lens == nullptr) return TS_ERR_INVALID_ARG;
   if (p->head_dim != 64 && p->head_dim != 128) return TS_ERR_UNSUPPORTED;
   if (p->num_q_heads > 128) return TS_ERR_UNSUPPORTED;
-  if (!is_pow2(p->num_kv_heads)) return TS_ERR_UNSUPPORTED;
+  if (!is_pow2(p->num_kv_heads) || p->num_kv_heads > 32) return TS_ERR_UNSUPPORTED;
   if (p->num_q_heads / p->num_kv_heads > 8) return TS_ERR_UNSUPPORTED;
   if (!is_pow2(p->page_size)) return TS_ERR_UNSUPPORTED;
   const int hb = p->num_kv_heads < 8 ? p->num_kv_heads : 8;
@@ -94,7 +94,7 @@ int32_t ts_paged_qk_scores(const ts_problem* p, const void* q, float* scores, fl
   a.max_seq_len = p->max_seq_len;
   a.HB = p->num_kv_heads < 8 ? p->num_kv_heads : 8; a.hb_shift = ilog2(a.HB); a.NU = p->num_kv_heads / a.HB;
   a.uniform_page = p->page_size >= (8 / a.HB);
-  a.vec_store = (p->max_seq_len % 4 == 0) && (((uintptr_t)scores & 15) == 0);
+  a.vec_store = (p->num_q_heads % 4 == 0) && ((a.HB * G) % 4 == 0) && (((uintptr_t)scores & 15) == 0);
   a.scale = score_scale; a.c2 = score_scale * 1.44269504088896340736f;
   const int ntiles = (p->max_seq_len + kScoreTileTokens - 1) / kScoreTileTokens * a.NU;
   int wg = g_score_wg > 0 ? g_score_wg : (ntiles + 3) / 4;
@@ -103,8 +103,8 @@ int32_t ts_paged_qk_scores(const ts_problem* p, const void* q, float* scores, fl
   if (g_score_wg == 0 && wg > cap) wg = cap;
   if (wg > kScoreMaxWg) wg = kScoreMaxWg;
   if (wg < 1) wg = 1;
-  const size_t lds = (size_t)4 * (a.HB * G * kScoreLdsStride + a.H * 16) * sizeof(float);
-  if (lds > 64 * 1024) return TS_ERR_UNSUPPORTED;
+  size_t lds = (size_t)4 * kScoreTileTokens * ((a.HB * G + 3) & ~3) * sizeof(float);
+  if (lds < 8192) lds = 8192;   // the closing statistics exchange needs 4 x 64 x 8 floats
   const int variant = (p->dtype == TS_BF16) ? g_score_variant : 0;
   const hipError_t e = launch_score_decode(p->dtype, p->head_dim, G, variant, a, dim3(wg, p->batch), lds, (hipStream_t)stream);
   return e == hipSuccess ? TS_OK : TS_ERR_HIP;

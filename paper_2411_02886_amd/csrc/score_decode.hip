@@ -6,8 +6,9 @@
 // (a load instruction of the wave covers eight rows x 128 contiguous bytes, i.e. whole cache lines),
 // multiplies them with the G query heads of that KV head kept in registers (the GQA group shares
 // every K byte that is loaded), and the eight partial sums are combined with three DPP steps.
-// The G x 32 x HB scores of the tile are staged in LDS so that they leave as 128-byte runs per head,
-// and the same staged values update running (max, sum-exp) statistics.  The workgroups' partial
+// The 32 x HB x G scores of the tile are staged in LDS token-major and leave as one contiguous run
+// (scores are stored [token][head], so a tile is a single 4 KiB burst for 32 heads); the same staged
+// values update running (max, sum-exp) statistics that a lane keeps in registers for its four heads.  The workgroups' partial
 // statistics are merged by a second, tiny kernel (one workgroup per head).
 #include "ts_kernels.h"
 
@@ -77,9 +78,9 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
   constexpr int RB = D * ES;          // bytes per K row
   constexpr int L = RB / 128;         // 16-byte loads per lane per row
   constexpr int TT = kScoreTileTokens;
-  constexpr int LS = kScoreLdsStride;
   constexpr int U = 4;                // wave steps in flight
   using P_ = Piece<DT, DOT2>;
+  typedef unsigned v4u __attribute__((ext_vector_type(4)));
   extern __shared__ float smem[];
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -88,39 +89,43 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
   if (a.skip != nullptr && a.skip[b] != 0) return;
   const int N = min(max(a.seq_lens[b], 0), a.max_seq_len);
   const int H = a.H, HB = a.HB, HBG = HB * G;
-  const int wave_floats = HBG * LS + H * 16;
-  float* tile = smem + wave * wave_floats;   // [HBG][LS] staged scores of the current tile
-  float* st = tile + HBG * LS;               // [H][8] running (max, sum-exp) pairs of this wave
-  for (int i = lane; i < H * 8; i += 64) { st[2 * i] = -INFINITY; st[2 * i + 1] = 0.f; }
+  const int HS = (HBG + 3) & ~3;             // floats per token row of the staged tile
+  float* tile = smem + wave * (TT * HS);     // [TT][HS] scores of the current tile, token-major
 
   const int tps_shift = 3 - a.hb_shift;      // log2(tokens per wave step)
   const int STEPS = TT >> tps_shift;
   const int kvh_l = r & (HB - 1);
   const int tok_in_step = r >> a.hb_shift;
-  const int ntiles = ((N + TT - 1) / TT) * a.NU;
-  const int nwaves = gridDim.x * 4;
+  const int u = wave & (a.NU - 1);           // block of HB KV heads this wave stays with
+  const int kvh = u * HB + kvh_l;
+  const int h_base = u * HBG;
+  const int ntt = (N + TT - 1) / TT;
+  const int tt_step = (gridDim.x * 4) / a.NU;
   const int indptr = a.page_indptr[b];
   const int npages = (N + a.P - 1) >> a.p_shift;
-  const size_t stride = (size_t)a.max_seq_len;
   const float c2 = a.c2;
 
-  typename P_::Q qreg[G][L];
-  int q_loaded_for = -1;
+  // epilogue mapping: a lane owns one 16-byte chunk (four heads) of a token row, always the same heads
+  const int CPT = HS >> 2;                   // chunks per token row
+  const int TPP = 64 / CPT;                  // token rows per epilogue pass
+  const int e_sub = lane / CPT, e_hq = lane - e_sub * CPT;
+  const bool e_active = e_sub < TPP;
+  const int e_nvh = min(4, HBG - e_hq * 4);  // heads of this chunk that exist
+  float rm[4], rl[4];                        // running (max, sum-exp) of the lane's four heads
+#pragma unroll
+  for (int c = 0; c < 4; ++c) { rm[c] = -INFINITY; rl[c] = 0.f; }
 
-  for (int tile_id = blockIdx.x * 4 + wave; tile_id < ntiles; tile_id += nwaves) {
-    const int u = tile_id & (a.NU - 1);
-    const int t0 = (tile_id / a.NU) * TT;
-    const int kvh = u * HB + kvh_l;
-    if (u != q_loaded_for) {
+  typename P_::Q qreg[G][L];
 #pragma unroll
-      for (int g = 0; g < G; ++g)
+  for (int g = 0; g < G; ++g)
 #pragma unroll
-        for (int i = 0; i < L; ++i) {
-          const uint8_t* qp = a.q + ((size_t)b * H + (size_t)kvh * G + g) * RB + i * 128 + j * 16;
-          qreg[g][i] = P_::prep(*reinterpret_cast<const uint4*>(qp));
-        }
-      q_loaded_for = u;
+    for (int i = 0; i < L; ++i) {
+      const uint8_t* qp = a.q + ((size_t)b * H + (size_t)kvh * G + g) * RB + i * 128 + j * 16;
+      qreg[g][i] = P_::prep(*reinterpret_cast<const uint4*>(qp));
     }
+
+  for (int tt = (blockIdx.x * 4 + wave) / a.NU; tt < ntt; tt += tt_step) {
+    const int t0 = tt * TT;
     // physical page of each of the tile's 32 tokens, one per lane (lanes 32..63 mirror 0..31)
     int pidv;
     {
@@ -140,7 +145,11 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
         const uint8_t* kp = a.k_pool + (((size_t)pid << a.p_shift) + (size_t)(t & (a.P - 1))) * ((size_t)a.H_kv * RB) +
                             (size_t)kvh * RB + j * 16;
 #pragma unroll
-        for (int i = 0; i < L; ++i) kr[uu][i] = *reinterpret_cast<const uint4*>(kp + i * 128);
+        for (int i = 0; i < L; ++i) {
+          // K is read once per call: a non-temporal load keeps it from displacing the staged scores
+          const v4u w = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(kp + i * 128));
+          kr[uu][i] = make_uint4(w.x, w.y, w.z, w.w);
+        }
       }
 #pragma unroll
       for (int uu = 0; uu < U; ++uu) {
@@ -156,60 +165,70 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
         float v = acc[0];
 #pragma unroll
         for (int g = 1; g < G; ++g) v = (j == g) ? acc[g] : v;
-        if (j < G) tile[(kvh_l * G + j) * LS + tl] = v;
+        if (j < G) tile[tl * HS + kvh_l * G + j] = v;
       }
     }
     wave_lds_sync();
 
-    // epilogue: scores leave as 16-byte pieces (eight lanes = 128 contiguous bytes of one head row)
-    const int nchunks = HBG * (TT / 4);
-    for (int c = lane; c < nchunks; c += 64) {
-      const int hl = c >> 3, q4 = c & 7;
-      const int t = t0 + q4 * 4;
-      if (t < N) {
-        const float4 v = *reinterpret_cast<const float4*>(&tile[hl * LS + q4 * 4]);
-        const int h = u * HBG + hl;
-        const int nv = min(4, N - t);
-        float* dst = a.scores + ((size_t)b * H + h) * stride + t;
-        if (nv == 4 && a.vec_store) {
-          *reinterpret_cast<float4*>(dst) = v;
+    // epilogue: the tile leaves as one contiguous run of token rows; the same values feed the statistics
+    for (int tok0 = 0; tok0 < TT; tok0 += TPP) {
+      const int tok = tok0 + e_sub;
+      const int t = t0 + tok;
+      if (e_active && tok < TT && t < N) {
+        const float4 v4 = *reinterpret_cast<const float4*>(&tile[tok * HS + e_hq * 4]);
+        const float x[4] = {v4.x, v4.y, v4.z, v4.w};
+        float* dst = a.scores + ((size_t)b * a.max_seq_len + t) * H + h_base + e_hq * 4;
+        if (a.vec_store) {
+          *reinterpret_cast<float4*>(dst) = v4;
         } else {
-          dst[0] = v.x;
-          if (nv > 1) dst[1] = v.y;
-          if (nv > 2) dst[2] = v.z;
-          if (nv > 3) dst[3] = v.w;
+#pragma unroll
+          for (int c = 0; c < 4; ++c)
+            if (c < e_nvh) dst[c] = x[c];
         }
-        float xm = v.x;
-        if (nv > 1) xm = fmaxf(xm, v.y);
-        if (nv > 2) xm = fmaxf(xm, v.z);
-        if (nv > 3) xm = fmaxf(xm, v.w);
-        float2 ml = *reinterpret_cast<float2*>(&st[(h * 8 + q4) * 2]);
-        const float mn = fmaxf(ml.x, xm);
-        float l = (ml.x == -INFINITY) ? 0.f : ml.y * __builtin_amdgcn_exp2f(c2 * (ml.x - mn));
-        l += __builtin_amdgcn_exp2f(c2 * (v.x - mn));
-        if (nv > 1) l += __builtin_amdgcn_exp2f(c2 * (v.y - mn));
-        if (nv > 2) l += __builtin_amdgcn_exp2f(c2 * (v.z - mn));
-        if (nv > 3) l += __builtin_amdgcn_exp2f(c2 * (v.w - mn));
-        ml.x = mn; ml.y = l;
-        *reinterpret_cast<float2*>(&st[(h * 8 + q4) * 2]) = ml;
+        bool grow = false;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) grow |= (c < e_nvh) && (x[c] > rm[c]);
+        if (__builtin_amdgcn_ballot_w64(grow) != 0) {     // rare after the first tiles: rescale to the new maxima
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            if (c < e_nvh) {
+              const float mn = fmaxf(rm[c], x[c]);
+              rl[c] = (rm[c] == -INFINITY) ? 0.f : rl[c] * __builtin_amdgcn_exp2f(c2 * (rm[c] - mn));
+              rm[c] = mn;
+            }
+          }
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+          if (c < e_nvh) rl[c] += __builtin_amdgcn_exp2f(c2 * (x[c] - rm[c]));
       }
     }
     wave_lds_sync();
   }
 
-  // ---- merge the 4 waves x 8 lanes of statistics of this workgroup, publish the partial
+  // ---- merge the lanes' statistics of this workgroup per head, publish the partial
+  __syncthreads();
+  float* st = smem;                          // [4 waves][64 lanes][4 heads][2]
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    st[((wave * 64 + lane) * 4 + c) * 2] = rm[c];
+    st[((wave * 64 + lane) * 4 + c) * 2 + 1] = rl[c];
+  }
   __syncthreads();
   for (int h = threadIdx.x; h < H; h += 256) {
+    const int uh = h / HBG, hl = h - uh * HBG, hq = hl >> 2, c = hl & 3;
     float m = -INFINITY;
     for (int w = 0; w < 4; ++w)
-      for (int e = 0; e < 8; ++e) m = fmaxf(m, smem[w * wave_floats + HBG * LS + (h * 8 + e) * 2]);
+      if ((w & (a.NU - 1)) == uh)
+        for (int sub = 0; sub < TPP; ++sub) m = fmaxf(m, st[((w * 64 + sub * CPT + hq) * 4 + c) * 2]);
     float l = 0.f;
     for (int w = 0; w < 4; ++w)
-      for (int e = 0; e < 8; ++e) {
-        const float mi = smem[w * wave_floats + HBG * LS + (h * 8 + e) * 2];
-        const float li = smem[w * wave_floats + HBG * LS + (h * 8 + e) * 2 + 1];
-        if (mi != -INFINITY) l += li * __builtin_amdgcn_exp2f(c2 * (mi - m));
-      }
+      if ((w & (a.NU - 1)) == uh)
+        for (int sub = 0; sub < TPP; ++sub) {
+          const float mi = st[((w * 64 + sub * CPT + hq) * 4 + c) * 2];
+          const float li = st[((w * 64 + sub * CPT + hq) * 4 + c) * 2 + 1];
+          if (mi != -INFINITY) l += li * __builtin_amdgcn_exp2f(c2 * (mi - m));
+        }
     float* pp = a.partials + (((size_t)b * kScoreMaxWg + blockIdx.x) * H + h) * 2;
     pp[0] = m; pp[1] = l;
   }

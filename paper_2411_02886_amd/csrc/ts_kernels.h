@@ -17,7 +17,7 @@ struct ScoreArgs {
   int H, H_kv, P, p_shift, max_seq_len;
   int HB, hb_shift, NU;   // KV heads per wave tile (min(H_kv, 8)), its log2, H_kv / HB
   int uniform_page;       // every step of a wave reads one page (P >= tokens per step)
-  int vec_store;          // scores rows are 16-byte aligned
+  int vec_store;          // score rows can be written as 16-byte pieces
   float scale, c2;        // score_scale and score_scale * log2(e)
 };
 

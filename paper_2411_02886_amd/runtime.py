@@ -40,7 +40,7 @@ class DecodeLayer:
         self.max_seq_len = int(max_seq_len if max_seq_len is not None else max(1, int(np.max(seq_lens))))
         self._make_problem()
         B, Hq, M = self.B, H, self.max_seq_len
-        self.scores = torch.empty((B, Hq, M), dtype=torch.float32, device=device)
+        self.scores = torch.empty((B, M, Hq), dtype=torch.float32, device=device)
         self.row_stats = torch.empty((B, Hq, 2), dtype=torch.float32, device=device)
         self.votes = torch.empty((B, M), dtype=torch.float32, device=device)
         self.idx = torch.full((B, k), -1, dtype=torch.int32, device=device)

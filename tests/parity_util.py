@@ -75,12 +75,12 @@ def check_decode_against_oracle(w, layer, q_dev, *, score_scale=1.0, attn_tol=No
             assert np.all(W.as_f32(out_g[b, 0], w.dtype) == 0), lab
             continue
         # 1. scores (Alg. 2): float accumulation of D exact products; a few ulp of the largest score
-        Sg = S_g[b, :, :N].astype(np.float64)
+        Sg = np.ascontiguousarray(S_g[b, :N, :].T).astype(np.float64)      # stored [token][head]
         tolS = expect_tol_S if expect_tol_S is not None else 6 * ulp32(np.abs(ora["S"]).max())
         errS = np.abs(Sg - ora["S"]).max()
         assert errS <= tolS, (lab, "scores", errS, tolS)
         # 2. statistics: max is exactly the max of the stored scores; sum-exp matches a double recomputation
-        assert np.array_equal(st_g[b, :, 0], S_g[b, :, :N].max(axis=1)), lab
+        assert np.array_equal(st_g[b, :, 0], S_g[b, :N, :].max(axis=0)), lab
         z = np.exp(c * (Sg - Sg.max(axis=1, keepdims=True))).sum(axis=1)
         np.testing.assert_allclose(st_g[b, :, 1], z, rtol=5e-6, err_msg=lab)
         # 3. votes (Eq. 5): against the oracle formula applied to the GPU's own scores, and the invariant

@@ -60,6 +60,10 @@ SHAPES = [
     (W.BF16, 32, 8, 128, 1, 333, 40),      # page size 1 (the paper's own setting)
     (W.F32, 8, 2, 64, 4, 515, 33),         # small pages, H_kv = 2
     (W.BF16, 8, 4, 128, 2, 130, 130),      # page size 2, k == N
+    (W.F32, 6, 2, 64, 16, 450, 30),        # G = 3: head rows that are no multiple of 16 bytes
+    (W.BF16, 2, 2, 128, 16, 200, 16),      # two heads in all
+    (W.BF16, 64, 32, 64, 16, 260, 20),     # 32 KV heads: four head blocks
+    (W.BF16, 128, 16, 128, 16, 180, 20),   # 128 query heads, G = 8
 ]
 
 
@@ -82,10 +86,10 @@ def test_ragged_batch_with_empty_and_short_sequences(gpu):
     check_decode_against_oracle(w, layer, q, score_scale=0.1, label="ragged")
 
 
-def test_odd_row_stride_uses_scalar_stores(gpu):
+def test_max_seq_len_larger_than_every_sequence(gpu):
     w = W.make_workload("odd", dtype=W.F32, H=4, H_kv=2, D=64, P=16, seq_lens=[203], k=20, seed=12)
     layer, q = make_layer(w, max_seq_len=205)
-    check_decode_against_oracle(w, layer, q, score_scale=0.125, label="odd stride")
+    check_decode_against_oracle(w, layer, q, score_scale=0.125, label="odd extent")
 
 
 def test_ties_go_to_lower_index_and_zero_query(gpu):
