@@ -124,53 +124,60 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
       qreg[g][i] = P_::prep(*reinterpret_cast<const uint4*>(qp));
     }
 
-  for (int tt = (blockIdx.x * 4 + wave) / a.NU; tt < ntt; tt += tt_step) {
+  // ---- software-pipelined stream of blocks (U wave steps = U x 8 K rows each): the loads of block
+  // n+1 are in flight while block n is multiplied, across tile boundaries as well
+  const int NBLK = STEPS / U;                // blocks per tile (STEPS is 4, 8, 16 or 32)
+  const int tt_first = (blockIdx.x * 4 + wave) / a.NU;
+  const int my_tiles = tt_first < ntt ? (ntt - tt_first + tt_step - 1) / tt_step : 0;
+  const int total_blocks = my_tiles * NBLK;
+
+  // physical page of each of a tile's 32 tokens, one per lane (lanes 32..63 mirror 0..31)
+  auto load_pids = [&](int tt) -> int {
+    const int pg = (tt * TT + (lane & 31)) >> a.p_shift;
+    return a.page_indices[indptr + min(pg, npages - 1)];
+  };
+  auto issue = [&](uint4 (&kr)[U][L], int tt, int blk, int pidv) {
+    const int t0 = tt * TT, s0 = blk * U;
+#pragma unroll
+    for (int uu = 0; uu < U; ++uu) {
+      const int tl = ((s0 + uu) << tps_shift) + tok_in_step;
+      int pid;
+      if (a.uniform_page) pid = __builtin_amdgcn_readlane(pidv, (s0 + uu) << tps_shift);
+      else pid = __shfl(pidv, tl);
+      const int t = t0 + tl;
+      const uint8_t* kp = a.k_pool + (((size_t)pid << a.p_shift) + (size_t)(t & (a.P - 1))) * ((size_t)a.H_kv * RB) +
+                          (size_t)kvh * RB + j * 16;
+#pragma unroll
+      for (int i = 0; i < L; ++i) {
+        // K is read once per call: a non-temporal load keeps it from displacing the staged scores
+        const v4u w = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(kp + i * 128));
+        kr[uu][i] = make_uint4(w.x, w.y, w.z, w.w);
+      }
+    }
+  };
+  auto compute = [&](const uint4 (&kr)[U][L], int blk) {
+    const int s0 = blk * U;
+#pragma unroll
+    for (int uu = 0; uu < U; ++uu) {
+      const int tl = ((s0 + uu) << tps_shift) + tok_in_step;
+      float acc[G];
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        float sc = 0.f;
+#pragma unroll
+        for (int i = 0; i < L; ++i) sc = P_::dot(kr[uu][i], qreg[g][i], sc);
+        acc[g] = group8_sum(sc);
+      }
+      float v = acc[0];
+#pragma unroll
+      for (int g = 1; g < G; ++g) v = (j == g) ? acc[g] : v;
+      if (j < G) tile[tl * HS + kvh_l * G + j] = v;
+    }
+  };
+  // the tile leaves as one contiguous run of token rows; the same values feed the statistics
+  auto epilogue = [&](int tt) {
     const int t0 = tt * TT;
-    // physical page of each of the tile's 32 tokens, one per lane (lanes 32..63 mirror 0..31)
-    int pidv;
-    {
-      const int pg = (t0 + (lane & 31)) >> a.p_shift;
-      pidv = a.page_indices[indptr + min(pg, npages - 1)];
-    }
-
-    for (int s0 = 0; s0 < STEPS; s0 += U) {
-      uint4 kr[U][L];
-#pragma unroll
-      for (int uu = 0; uu < U; ++uu) {
-        const int tl = ((s0 + uu) << tps_shift) + tok_in_step;
-        int pid;
-        if (a.uniform_page) pid = __builtin_amdgcn_readlane(pidv, (s0 + uu) << tps_shift);
-        else pid = __shfl(pidv, tl);
-        const int t = t0 + tl;
-        const uint8_t* kp = a.k_pool + (((size_t)pid << a.p_shift) + (size_t)(t & (a.P - 1))) * ((size_t)a.H_kv * RB) +
-                            (size_t)kvh * RB + j * 16;
-#pragma unroll
-        for (int i = 0; i < L; ++i) {
-          // K is read once per call: a non-temporal load keeps it from displacing the staged scores
-          const v4u w = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(kp + i * 128));
-          kr[uu][i] = make_uint4(w.x, w.y, w.z, w.w);
-        }
-      }
-#pragma unroll
-      for (int uu = 0; uu < U; ++uu) {
-        const int tl = ((s0 + uu) << tps_shift) + tok_in_step;
-        float acc[G];
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-          float s = 0.f;
-#pragma unroll
-          for (int i = 0; i < L; ++i) s = P_::dot(kr[uu][i], qreg[g][i], s);
-          acc[g] = group8_sum(s);
-        }
-        float v = acc[0];
-#pragma unroll
-        for (int g = 1; g < G; ++g) v = (j == g) ? acc[g] : v;
-        if (j < G) tile[tl * HS + kvh_l * G + j] = v;
-      }
-    }
     wave_lds_sync();
-
-    // epilogue: the tile leaves as one contiguous run of token rows; the same values feed the statistics
     for (int tok0 = 0; tok0 < TT; tok0 += TPP) {
       const int tok = tok0 + e_sub;
       const int t = t0 + tok;
@@ -204,6 +211,37 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
       }
     }
     wave_lds_sync();
+  };
+
+  uint4 bufA[U][L], bufB[U][L];
+  int i_tt = tt_first, i_blk = 0, c_tt = tt_first, c_blk = 0;
+  int i_pid = 0, i_pid_next = 0;
+  auto advance_issue = [&]() {
+    if (++i_blk == NBLK) {
+      i_blk = 0; i_tt += tt_step;
+      i_pid = i_pid_next;
+      i_pid_next = load_pids(min(i_tt + tt_step, ntt - 1));   // one tile ahead: never on the critical path
+    }
+  };
+  auto advance_compute = [&]() {
+    if (++c_blk == NBLK) { epilogue(c_tt); c_blk = 0; c_tt += tt_step; }
+  };
+  if (total_blocks > 0) {
+    i_pid = load_pids(i_tt);
+    i_pid_next = load_pids(min(i_tt + tt_step, ntt - 1));
+    issue(bufA, i_tt, i_blk, i_pid);
+    advance_issue();
+  }
+  for (int gb = 0; gb < total_blocks; gb += 2) {
+    const bool haveB = gb + 1 < total_blocks;
+    if (haveB) { issue(bufB, i_tt, i_blk, i_pid); advance_issue(); }
+    compute(bufA, c_blk);
+    advance_compute();
+    if (haveB) {
+      if (gb + 2 < total_blocks) { issue(bufA, i_tt, i_blk, i_pid); advance_issue(); }
+      compute(bufB, c_blk);
+      advance_compute();
+    }
   }
 
   // ---- merge the lanes' statistics of this workgroup per head, publish the partial

@@ -156,6 +156,92 @@ def test_selection_cache_loop_matches_algorithm_1(gpu):
     assert 0 < hits < steps * w.B          # the run exercises both branches
 
 
+def planted_stats(w, idx, cnt):
+    pl = set(np.concatenate(list(w.planted[0])).tolist())
+    sel = set(idx[:cnt].tolist())
+    return len(pl & sel) / max(1, len(pl)), len(pl & sel) / max(1, cnt)
+
+
+@pytest.mark.timeout(600)
+def test_config2_full_size(gpu):
+    # configuration 2 as bench.py times it: 131072 tokens, k = 2048, library-default launch shape
+    w = W.config2()
+    layer, q = make_layer(w)
+    print("cfg2 full size", flush=True)
+    exc = check_decode_against_oracle(w, layer, q, score_scale=1.0, label="cfg2 full")
+    from paper_2411_02886_amd.runtime import to_host
+    ora = oracle_decode(w, 0)
+    rg, pg = planted_stats(w, to_host(layer.idx)[0], int(to_host(layer.count)[0]))
+    ro, po = planted_stats(w, ora["idx"], ora["count"])
+    print("cfg2 planted recall/precision gpu %.4f/%.4f oracle %.4f/%.4f, tolerated exceptions %d" % (rg, pg, ro, po, len(exc)))
+    if not exc:
+        assert (rg, pg) == (ro, po)
+
+
+@pytest.mark.timeout(900)
+def test_config4_full_size(gpu):
+    # configuration 4: 1048576 tokens, 28 query heads over 4 KV heads, k = 4096
+    w = W.config4()
+    layer, q = make_layer(w)
+    print("cfg4 full size", flush=True)
+    exc = check_decode_against_oracle(w, layer, q, score_scale=1.0, label="cfg4 full")
+    from paper_2411_02886_amd.runtime import to_host
+    ora = oracle_decode(w, 0)
+    rg, pg = planted_stats(w, to_host(layer.idx)[0], int(to_host(layer.count)[0]))
+    ro, po = planted_stats(w, ora["idx"], ora["count"])
+    print("cfg4 planted recall/precision gpu %.4f/%.4f oracle %.4f/%.4f, tolerated exceptions %d" % (rg, pg, ro, po, len(exc)))
+    if not exc:
+        assert (rg, pg) == (ro, po)
+
+
+def test_config3_shape_decode_run_with_appended_tokens(gpu):
+    # configuration 3 at reduced lengths: ragged batch, AR(1) queries, one K/V row appended per
+    # sequence per step, theta = 0.9; Algorithm 1 (anchor = query of the last reselect) on both sides
+    from paper_2411_02886_amd.runtime import to_device, to_host
+    steps, theta, scale = 24, 0.9, 1.0
+    w = W.config3(seed=1003, B=4, lo=700, hi=3000, steps=steps, k=128)
+    qs = W.ar1_queries(w, steps, rho=0.95)
+    ks, vs = W.appended_kv(w, steps)
+    layer, _ = make_layer(w, max_seq_len=int(w.seq_lens.max()) + steps)
+    lens = w.seq_lens.copy()
+    cq = [np.zeros((w.H, w.D), np.uint16) for _ in range(w.B)]
+    first = [np.ones(1, np.uint8) for _ in range(w.B)]
+    cidx = [np.full(w.k, -1, np.int32) for _ in range(w.B)]
+    ccnt = [np.zeros(1, np.int32) for _ in range(w.B)]
+    kflat = w.k_pool.reshape(-1, w.H_kv, w.D); vflat = w.v_pool.reshape(-1, w.H_kv, w.D)
+    kdev = layer.k_pool.view(-1, w.H_kv, w.D); vdev = layer.v_pool.view(-1, w.H_kv, w.D)
+    reuse_total = 0
+    for t in range(steps):
+        print("cfg3 step", t, flush=True)
+        # append the current token's K/V row (it is part of the cached tokens the query looks at)
+        for b in range(w.B):
+            pos = int(lens[b])
+            slot = int(w.pages_of(b)[pos // w.P]) * w.P + pos % w.P
+            kflat[slot] = ks[t, b]; vflat[slot] = vs[t, b]
+            kdev[slot] = to_device(ks[t, b]); vdev[slot] = to_device(vs[t, b])
+            lens[b] += 1
+        layer.seq_lens.copy_(to_device(lens))
+        qd = to_device(qs[t])
+        layer.step(qd, theta=theta, score_scale=scale)
+        torch.cuda.synchronize()
+        reuse_g = to_host(layer.reuse); idx_g = to_host(layer.idx); cnt_g = to_host(layer.count)
+        out_g = to_host(layer.out, bits16=True)
+        for b in range(w.B):
+            qb = np.ascontiguousarray(qs[t][b, 0])
+            sel = lambda qq, b=b: oracle.select(qq, w.k_pool, w.dtype, w.H_kv, w.P, w.pages_of(b), int(lens[b]), w.k,
+                                                score_scale=float(np.float32(scale)))
+            i_o, c_o, r_o = oracle.selcache_step(qb, cq[b], cidx[b], ccnt[b], first[b], float(np.float32(theta)), sel)
+            assert bool(reuse_g[b]) == r_o, (t, b)
+            reuse_total += r_o
+            assert cnt_g[b] == c_o and np.array_equal(idx_g[b], i_o), (t, b)
+            o_ref = oracle.sparse_attn(qb, w.k_pool, w.v_pool, w.dtype, w.H_kv, w.P, w.pages_of(b), i_o, c_o,
+                                       float(np.float32(1 / math.sqrt(w.D))))
+            assert np.abs(W.as_f32(out_g[b, 0], w.dtype) - o_ref).max() <= 2e-2, (t, b)
+    rate = reuse_total / (steps * w.B)
+    print("cfg3 reuse rate %.3f" % rate)
+    assert 0.2 < rate < 0.9
+
+
 def test_kernels_are_deterministic(gpu):
     from paper_2411_02886_amd.runtime import to_host
     w = W.config2(N=3000, k=200, seed=3)

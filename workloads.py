@@ -25,7 +25,13 @@ from __future__ import annotations
 from dataclasses import dataclass, field
 from typing import Dict, List, Optional
 
+import os
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
+
+_CHUNK_PAGES = 256          # pages per independently seeded chunk of K/V rows
+_WORKERS = max(1, min(16, (os.cpu_count() or 1)))
 
 F32 = 0
 BF16 = 1
@@ -188,22 +194,46 @@ def make_workload(name: str, *, dtype: int, B: int = 1, C: int = 1, H: int, H_kv
         n = int(seq_lens[b])
         npg = pages_per_seq[b]
         cap = npg * P
-        kl = rng.standard_normal((cap, H_kv, D), dtype=np.float32)
-        vl = rng.standard_normal((cap, H_kv, D), dtype=np.float32)
         npl = planted_per_head if isinstance(planted_per_head, int) else int(planted_per_head[b])
         nplant = n if plant_limit is None else min(n, int(plant_limit))
         pl = _choose_planted(rng, nplant, H, npl, non_contiguous) if nplant > 0 else np.zeros((H, 0), dtype=np.int64)
+        planted_all.append(pl)
+        # planted (token, kv head) -> direction added to K, grouped by page-chunk for the workers below
+        bumps = []
         if beta != 0.0 and pl.size:
             for h in range(H):
                 for c in range(min(C, pl.shape[1])):
                     qh = q32[b, c, h]
                     u = (np.float32(beta) * qh / np.float32(np.linalg.norm(qh.astype(np.float64)))).astype(np.float32)
-                    kl[pl[h, c::C], h // G, :] += u
-        planted_all.append(pl)
+                    bumps.append((pl[h, c::C], h // G, u))
         pg = page_indices[page_indptr[b]:page_indptr[b + 1]]
-        k_pool[pg] = store(kl, dtype).reshape(npg, P, H_kv, D)
-        v_pool[pg] = store(vl, dtype).reshape(npg, P, H_kv, D)
-        del kl, vl
+        # K and V rows are drawn in chunks of _CHUNK_PAGES pages, each chunk from its own child stream
+        # (SeedSequence(seed, spawn_key=(b, chunk))) so that chunks can be filled by a thread pool
+        nchunks = (npg + _CHUNK_PAGES - 1) // _CHUNK_PAGES
+        # planted tokens of a chunk: (local token, kv head, vector)
+        per_chunk = [[] for _ in range(nchunks)]
+        ctoks = _CHUNK_PAGES * P
+        for toks, hkv, u in bumps:
+            ci = toks // ctoks
+            for cidx in np.unique(ci):
+                per_chunk[int(cidx)].append((toks[ci == cidx] - int(cidx) * ctoks, hkv, u))
+
+        def fill(ci, b=b, pg=pg, per_chunk=per_chunk, npg=npg):
+            p0, p1 = ci * _CHUNK_PAGES, min(npg, (ci + 1) * _CHUNK_PAGES)
+            g = np.random.Generator(np.random.PCG64(np.random.SeedSequence(seed, spawn_key=(b + 1, ci))))
+            kl = g.standard_normal(((p1 - p0) * P, H_kv, D), dtype=np.float32)
+            vl = g.standard_normal(((p1 - p0) * P, H_kv, D), dtype=np.float32)
+            for toks, hkv, u in per_chunk[ci]:
+                kl[toks, hkv, :] += u
+            k_pool[pg[p0:p1]] = store(kl, dtype).reshape(p1 - p0, P, H_kv, D)
+            v_pool[pg[p0:p1]] = store(vl, dtype).reshape(p1 - p0, P, H_kv, D)
+
+        if nchunks > 1:
+            with ThreadPoolExecutor(max_workers=_WORKERS) as ex:
+                list(ex.map(fill, range(nchunks)))
+        else:
+            for ci in range(nchunks):
+                fill(ci)
     return Workload(name=name, dtype=dtype, B=B, C=C, H=H, H_kv=H_kv, D=D, P=P, k=k,
                     seq_lens=seq_lens, q=store(q32, dtype), k_pool=k_pool, v_pool=v_pool,
                     page_indptr=page_indptr, page_indices=page_indices, planted=planted_all,
