@@ -83,7 +83,7 @@ def main():
     w = W.CONFIGS[args.config](**kw)
     N = int(w.seq_lens[0])
     if args.variant >= 0 or args.score_wg:
-        ts.ts_debug_set_score_variant(max(args.variant, 0), args.score_wg)
+        ts.ts_debug_set_score_variant(args.variant if args.variant >= 0 else 1, args.score_wg)
     layer = DecodeLayer.from_workload(w, device=dev)
     esize = w.esize()
     k_bytes = N * w.H_kv * w.D * esize                      # algorithmic bytes of the score pass

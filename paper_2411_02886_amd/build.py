@@ -19,7 +19,7 @@ SOURCES = ["api.hip", "score_decode.hip", "soft_vote.hip", "topk.hip", "selcache
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wall", "-Wno-unused-function"]
+         "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wall", "-Wno-unused-function"] + os.environ.get("TS_EXTRA_FLAGS", "").split()
 
 
 def _deps():

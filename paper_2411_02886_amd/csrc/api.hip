@@ -30,7 +30,7 @@ static int32_t check_problem(const ts_problem* p) {
   return TS_OK;
 }
 
-static int g_score_variant = 0;   // 0 = fma, 1 = packed bf16 dot2 (tuning knob, see ts_debug_set_score_variant)
+static int g_score_variant = 1;   // 0 = fma, 1 = packed bf16 dot2 (tuning knob, see ts_debug_set_score_variant)
 static int g_score_wg = 0;        // 0 = automatic
 
 }  // namespace ts

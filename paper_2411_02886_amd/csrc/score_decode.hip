@@ -78,7 +78,7 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
   constexpr int RB = D * ES;          // bytes per K row
   constexpr int L = RB / 128;         // 16-byte loads per lane per row
   constexpr int TT = kScoreTileTokens;
-  constexpr int U = 4;                // wave steps in flight
+  constexpr int U = 4;                // wave steps (8 K rows each) per block of loads
   using P_ = Piece<DT, DOT2>;
   typedef unsigned v4u __attribute__((ext_vector_type(4)));
   extern __shared__ float smem[];
@@ -124,8 +124,10 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
       qreg[g][i] = P_::prep(*reinterpret_cast<const uint4*>(qp));
     }
 
-  // ---- software-pipelined stream of blocks (U wave steps = U x 8 K rows each): the loads of block
-  // n+1 are in flight while block n is multiplied, across tile boundaries as well
+  // ---- the wave's work as one stream of blocks (U wave steps = U x 8 K rows = 8 KiB each) that runs
+  // across tile boundaries; page ids are fetched one tile ahead.  Measured on MI355X: keeping a second
+  // block in flight per wave (register double buffering) or a larger U changes nothing -- occupancy
+  // already covers the latency -- so the simple form with the fewest registers is kept.
   const int NBLK = STEPS / U;                // blocks per tile (STEPS is 4, 8, 16 or 32)
   const int tt_first = (blockIdx.x * 4 + wave) / a.NU;
   const int my_tiles = tt_first < ntt ? (ntt - tt_first + tt_step - 1) / tt_step : 0;
@@ -213,7 +215,7 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
     wave_lds_sync();
   };
 
-  uint4 bufA[U][L], bufB[U][L];
+  uint4 buf[U][L];
   int i_tt = tt_first, i_blk = 0, c_tt = tt_first, c_blk = 0;
   int i_pid = 0, i_pid_next = 0;
   auto advance_issue = [&]() {
@@ -229,19 +231,13 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
   if (total_blocks > 0) {
     i_pid = load_pids(i_tt);
     i_pid_next = load_pids(min(i_tt + tt_step, ntt - 1));
-    issue(bufA, i_tt, i_blk, i_pid);
+    issue(buf, i_tt, i_blk, i_pid);
     advance_issue();
   }
-  for (int gb = 0; gb < total_blocks; gb += 2) {
-    const bool haveB = gb + 1 < total_blocks;
-    if (haveB) { issue(bufB, i_tt, i_blk, i_pid); advance_issue(); }
-    compute(bufA, c_blk);
+  for (int gb = 0; gb < total_blocks; ++gb) {
+    compute(buf, c_blk);
     advance_compute();
-    if (haveB) {
-      if (gb + 2 < total_blocks) { issue(bufA, i_tt, i_blk, i_pid); advance_issue(); }
-      compute(bufB, c_blk);
-      advance_compute();
-    }
+    if (gb + 1 < total_blocks) { issue(buf, i_tt, i_blk, i_pid); advance_issue(); }
   }
 
   // ---- merge the lanes' statistics of this workgroup per head, publish the partial

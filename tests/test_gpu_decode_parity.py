@@ -47,7 +47,7 @@ def test_config2_shape_bf16_reduced_length(gpu, variant):
             print("cfg2-small variant", variant, "scale", scale, flush=True)
             check_decode_against_oracle(w, layer, q, score_scale=scale, label="cfg2s v%d c=%.3f" % (variant, scale))
     finally:
-        gpu.ts_debug_set_score_variant(0, 0)
+        gpu.ts_debug_set_score_variant(1, 0)          # back to the library default
 
 
 SHAPES = [
