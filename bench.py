@@ -27,6 +27,9 @@ if ROOT not in sys.path:
 import numpy as np  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the score kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what
+# the same counters read for plain copy kernels of known size (profiles/decode_step_cfg2_hbm_traffic.md)
+MEASURED_TRAFFIC_BYTES = {2: int((128.17 * 1.98 + 16.25 * 1.00) * 2**20)}
 
 
 def parse():
@@ -121,10 +124,10 @@ def main():
         ts.ts_selcache_check(p, q, layer.cached_q, layer.first, theta, layer.reuse, stream)
         if ev is not None:
             ev[0].record(stream)
-        ts.ts_paged_qk_scores(p, q, layer.scores, layer.row_stats, scale, layer.reuse, layer.ws, stream)
+        ts.ts_paged_qk_scores(p, q, layer.scores, scale, layer.reuse, layer.ws, stream)
         if ev is not None:
             ev[1].record(stream)
-        ts.ts_soft_vote(p, layer.scores, layer.row_stats, scale, layer.votes, layer.reuse, stream)
+        ts.ts_soft_vote(p, layer.scores, scale, layer.row_stats, layer.votes, layer.reuse, layer.ws, stream)
         ts.ts_topk(p, layer.votes, layer.k, layer.idx, layer.count, layer.reuse, layer.ws, stream)
         ts.ts_sparse_paged_attn(p, q, layer.idx, layer.k, layer.count, sm, layer.out, layer.lse, layer.ws, stream)
 
@@ -170,9 +173,10 @@ def main():
                    "head_dim": w.D, "page_size": w.P, "k": w.k, "score_scale": scale, "theta": theta,
                    "pool_copies_rotated": R, "selection_cache": "every step is a miss"},
         "decode_steps_per_s": 1e3 / ms_step,
-        "roofline": {"bound": "hbm", "kernel": "score_decode_kernel (ts_paged_qk_scores)",
+        "roofline": {"bound": "hbm", "kernel": "ts::score_decode_kernel (the one launch of ts_paged_qk_scores)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None, "algorithmic_bytes_per_launch": k_bytes,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.config) if not args.tokens else None,
+                     "algorithmic_bytes_per_launch": k_bytes,
                      "avg_launch_ms": score_avg_ms, "median_launch_ms": float(np.median(score_ms)),
                      "min_launch_ms": float(score_ms.min()),
                      "score_pass_tokens_per_s": N / (score_avg_ms * 1e-3)},

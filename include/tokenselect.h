@@ -80,20 +80,25 @@ int32_t ts_workspace_init(void* ws, size_t ws_bytes, void* stream);
 /* Algorithm 2 (Paged Dot Product Kernel).  For every sequence b, head h, cached token t < N_b:
  *   scores[b][t][h] = < q[b][0][h][:], K[slot(b,t)][h / G][:] >          (raw, unscaled; the matrix
  *   S of Algorithm 2 stored token-major so that it streams out in contiguous bursts)
- * and, feeding Eq. 5, per (b,h):
- *   row_stats[b][h][0] = max_t scores[b][t][h]
- *   row_stats[b][h][1] = sum_t exp(score_scale * (scores[b][t][h] - max))   (0 when N_b == 0)
+ * and, feeding Eq. 5, per-workgroup partial softmax statistics (running max and sum of
+ * exp(score_scale * (score - max)) per head) are left in the workspace for ts_soft_vote.
  * q [device] [B][C][H][D]; scores [device] float [B][max_seq_len][H] (rows t >= N_b untouched);
- * row_stats [device] float [B][H][2]; score_scale >= 0 (Eq. 5 as printed uses 1).
+ * score_scale >= 0 (Eq. 5 as printed uses 1).  One kernel launch.
  * Decode only: chunk must be 1 (TS_ERR_UNSUPPORTED otherwise). */
-int32_t ts_paged_qk_scores(const ts_problem* p, const void* q, float* scores, float* row_stats, float score_scale,
+int32_t ts_paged_qk_scores(const ts_problem* p, const void* q, float* scores, float score_scale,
                            const uint8_t* skip /* [device] [B] or NULL */, void* ws, size_t ws_bytes, void* stream);
 
-/* Eq. 5 (head soft vote):  votes[b][t] = sum_h exp(score_scale*(scores[b][t][h] - max_h)) / sumexp_h
- * for t < N_b, computed in double precision from the float scores and rounded once to float.
- * votes [device] float [B][max_seq_len] (entries t >= N_b untouched). */
-int32_t ts_soft_vote(const ts_problem* p, const float* scores, const float* row_stats, float score_scale,
-                     float* votes, const uint8_t* skip, void* stream);
+/* Eq. 5 (head soft vote).  First merges the partial statistics that the preceding
+ * ts_paged_qk_scores call (same problem, same workspace, same score_scale) left behind into
+ *   row_stats[b][h][0] = max_t scores[b][t][h]
+ *   row_stats[b][h][1] = sum_t exp(score_scale * (scores[b][t][h] - max))
+ * then computes
+ *   votes[b][t] = sum_h exp(score_scale*(scores[b][t][h] - max_h)) / sumexp_h        for t < N_b
+ * in double precision from the float scores, rounded once to float.
+ * row_stats [device] float [B][H][2] out; votes [device] float [B][max_seq_len] (entries t >= N_b
+ * untouched). */
+int32_t ts_soft_vote(const ts_problem* p, const float* scores, float score_scale, float* row_stats, float* votes,
+                     const uint8_t* skip, void* ws, size_t ws_bytes, void* stream);
 
 /* TopK of Eq. 3-5 over votes[b][0..N_b): the min(k, N_b) largest values, equal values taken in
  * order of increasing token index, written as ascending logical token ids.

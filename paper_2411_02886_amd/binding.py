@@ -63,8 +63,8 @@ def load():
         L.ts_strerror.argtypes = [i32]
         L.ts_workspace_bytes.argtypes = [pp, i32, ctypes.POINTER(sz)]
         L.ts_workspace_init.argtypes = [vp, sz, vp]
-        L.ts_paged_qk_scores.argtypes = [pp, vp, vp, vp, f32, vp, vp, sz, vp]
-        L.ts_soft_vote.argtypes = [pp, vp, vp, f32, vp, vp, vp]
+        L.ts_paged_qk_scores.argtypes = [pp, vp, vp, f32, vp, vp, sz, vp]
+        L.ts_soft_vote.argtypes = [pp, vp, f32, vp, vp, vp, vp, sz, vp]
         L.ts_topk.argtypes = [pp, vp, i32, vp, vp, vp, vp, sz, vp]
         L.ts_selcache_check.argtypes = [pp, vp, vp, vp, f32, vp, vp]
         L.ts_sparse_paged_attn.argtypes = [pp, vp, vp, i32, vp, f32, vp, vp, vp, sz, vp]
@@ -127,15 +127,18 @@ def ts_debug_set_score_variant(variant: int, wg: int = 0) -> None:
     _ok(load().ts_debug_set_score_variant(int(variant), int(wg)), "ts_debug_set_score_variant")
 
 
-def ts_paged_qk_scores(p: Problem, q, scores, row_stats, score_scale: float, skip, ws, stream=None) -> None:
-    _ok(load().ts_paged_qk_scores(p.ref(), _ptr(q), _ptr(scores), _ptr(row_stats), float(score_scale), _ptr(skip),
-                                  _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)),
-        "ts_paged_qk_scores")
+def _nbytes(ws) -> int:
+    return ws.numel() * ws.element_size() if ws is not None else 0
 
 
-def ts_soft_vote(p: Problem, scores, row_stats, score_scale: float, votes, skip, stream=None) -> None:
-    _ok(load().ts_soft_vote(p.ref(), _ptr(scores), _ptr(row_stats), float(score_scale), _ptr(votes), _ptr(skip),
-                            _stream(stream)), "ts_soft_vote")
+def ts_paged_qk_scores(p: Problem, q, scores, score_scale: float, skip, ws, stream=None) -> None:
+    _ok(load().ts_paged_qk_scores(p.ref(), _ptr(q), _ptr(scores), float(score_scale), _ptr(skip), _ptr(ws), _nbytes(ws),
+                                  _stream(stream)), "ts_paged_qk_scores")
+
+
+def ts_soft_vote(p: Problem, scores, score_scale: float, row_stats, votes, skip, ws, stream=None) -> None:
+    _ok(load().ts_soft_vote(p.ref(), _ptr(scores), float(score_scale), _ptr(row_stats), _ptr(votes), _ptr(skip),
+                            _ptr(ws), _nbytes(ws), _stream(stream)), "ts_soft_vote")
 
 
 def ts_topk(p: Problem, votes, k: int, idx, count, skip, ws, stream=None) -> None:

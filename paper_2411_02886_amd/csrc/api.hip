@@ -7,6 +7,23 @@ __global__ void fill_zero_kernel(uint32_t* p, size_t n) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0u;
 }
 
+static int g_score_variant = 1;   // 0 = fma, 1 = packed bf16 dot2 (tuning knob, see ts_debug_set_score_variant)
+static int g_score_wg = 0;        // 0 = automatic
+
+// workgroups per sequence of the score pass (also the number of statistics partials it leaves)
+static int score_workgroups(const ts_problem* p) {
+  const int hb = p->num_kv_heads < 8 ? p->num_kv_heads : 8;
+  const int nu = p->num_kv_heads / hb;
+  const int ntiles = (p->max_seq_len + kScoreTileTokens - 1) / kScoreTileTokens * nu;
+  int wg = g_score_wg > 0 ? g_score_wg : (ntiles + 3) / 4;
+  int cap = kScoreMaxWg / (p->batch < 1 ? 1 : p->batch);
+  if (cap < 64) cap = 64;
+  if (g_score_wg == 0 && wg > cap) wg = cap;
+  if (wg > kScoreMaxWg) wg = kScoreMaxWg;
+  if (wg < 1) wg = 1;
+  return wg;
+}
+
 static int ilog2(int x) { int s = 0; while ((1 << s) < x) ++s; return s; }
 static bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 
@@ -29,9 +46,6 @@ static int32_t check_problem(const ts_problem* p) {
   if ((int64_t)p->batch * p->num_q_heads * (int64_t)p->max_seq_len > ((int64_t)1 << 40)) return TS_ERR_UNSUPPORTED;
   return TS_OK;
 }
-
-static int g_score_variant = 1;   // 0 = fma, 1 = packed bf16 dot2 (tuning knob, see ts_debug_set_score_variant)
-static int g_score_wg = 0;        // 0 = automatic
 
 }  // namespace ts
 
@@ -75,11 +89,11 @@ int32_t ts_debug_set_score_variant(int32_t variant, int32_t wg) {
   return TS_OK;
 }
 
-int32_t ts_paged_qk_scores(const ts_problem* p, const void* q, float* scores, float* row_stats, float score_scale,
+int32_t ts_paged_qk_scores(const ts_problem* p, const void* q, float* scores, float score_scale,
                            const uint8_t* skip, void* ws, size_t ws_bytes, void* stream) {
   int32_t st = check_problem(p);
   if (st != TS_OK) return st;
-  if (q == nullptr || scores == nullptr || row_stats == nullptr || p->k_pool == nullptr) return TS_ERR_INVALID_ARG;
+  if (q == nullptr || scores == nullptr || p->k_pool == nullptr) return TS_ERR_INVALID_ARG;
   if (!(score_scale >= 0.f) || !(score_scale < 1e30f)) return TS_ERR_INVALID_ARG;
   if (p->chunk != 1) return TS_ERR_UNSUPPORTED;
   const WsLayout w = ws_layout(p, 1);
@@ -88,7 +102,7 @@ int32_t ts_paged_qk_scores(const ts_problem* p, const void* q, float* scores, fl
   ScoreArgs a{};
   a.q = (const uint8_t*)q; a.k_pool = (const uint8_t*)p->k_pool;
   a.page_indptr = p->page_indptr; a.page_indices = p->page_indices; a.seq_lens = p->seq_lens; a.skip = skip;
-  a.scores = scores; a.row_stats = row_stats;
+  a.scores = scores;
   a.partials = (float*)((uint8_t*)ws + w.score_partials);
   a.H = p->num_q_heads; a.H_kv = p->num_kv_heads; a.P = p->page_size; a.p_shift = ilog2(p->page_size);
   a.max_seq_len = p->max_seq_len;
@@ -96,13 +110,7 @@ int32_t ts_paged_qk_scores(const ts_problem* p, const void* q, float* scores, fl
   a.uniform_page = p->page_size >= (8 / a.HB);
   a.vec_store = (p->num_q_heads % 4 == 0) && ((a.HB * G) % 4 == 0) && (((uintptr_t)scores & 15) == 0);
   a.scale = score_scale; a.c2 = score_scale * 1.44269504088896340736f;
-  const int ntiles = (p->max_seq_len + kScoreTileTokens - 1) / kScoreTileTokens * a.NU;
-  int wg = g_score_wg > 0 ? g_score_wg : (ntiles + 3) / 4;
-  int cap = kScoreMaxWg / (p->batch < 1 ? 1 : p->batch);
-  if (cap < 64) cap = 64;
-  if (g_score_wg == 0 && wg > cap) wg = cap;
-  if (wg > kScoreMaxWg) wg = kScoreMaxWg;
-  if (wg < 1) wg = 1;
+  const int wg = score_workgroups(p);
   size_t lds = (size_t)4 * kScoreTileTokens * ((a.HB * G + 3) & ~3) * sizeof(float);
   if (lds < 8192) lds = 8192;   // the closing statistics exchange needs 4 x 64 x 8 floats
   const int variant = (p->dtype == TS_BF16) ? g_score_variant : 0;
@@ -110,15 +118,18 @@ int32_t ts_paged_qk_scores(const ts_problem* p, const void* q, float* scores, fl
   return e == hipSuccess ? TS_OK : TS_ERR_HIP;
 }
 
-int32_t ts_soft_vote(const ts_problem* p, const float* scores, const float* row_stats, float score_scale,
-                     float* votes, const uint8_t* skip, void* stream) {
+int32_t ts_soft_vote(const ts_problem* p, const float* scores, float score_scale, float* row_stats, float* votes,
+                     const uint8_t* skip, void* ws, size_t ws_bytes, void* stream) {
   int32_t st = check_problem(p);
   if (st != TS_OK) return st;
   if (scores == nullptr || row_stats == nullptr || votes == nullptr) return TS_ERR_INVALID_ARG;
   if (!(score_scale >= 0.f) || !(score_scale < 1e30f)) return TS_ERR_INVALID_ARG;
   if (p->chunk != 1) return TS_ERR_UNSUPPORTED;
+  const WsLayout w = ws_layout(p, 1);
+  if (ws == nullptr || ((uintptr_t)ws & 255) != 0 || ws_bytes < w.topk_blk) return TS_ERR_WORKSPACE;
   VoteArgs a{};
-  a.scores = scores; a.row_stats = row_stats; a.votes = votes; a.seq_lens = p->seq_lens; a.skip = skip;
+  a.partials = (const float*)((uint8_t*)ws + w.score_partials); a.nparts = score_workgroups(p);
+  a.scores = scores; a.row_stats = row_stats; a.row_stats_out = row_stats; a.votes = votes; a.seq_lens = p->seq_lens; a.skip = skip;
   a.H = p->num_q_heads; a.max_seq_len = p->max_seq_len; a.scale = score_scale;
   return launch_soft_vote(a, p->batch, (hipStream_t)stream) == hipSuccess ? TS_OK : TS_ERR_HIP;
 }

@@ -8,8 +8,7 @@
 // every K byte that is loaded), and the eight partial sums are combined with three DPP steps.
 // The 32 x HB x G scores of the tile are staged in LDS token-major and leave as one contiguous run
 // (scores are stored [token][head], so a tile is a single 4 KiB burst for 32 heads); the same staged
-// values update running (max, sum-exp) statistics that a lane keeps in registers for its four heads.  The workgroups' partial
-// statistics are merged by a second, tiny kernel (one workgroup per head).
+// values update running (max, sum-exp) statistics that a lane keeps in registers for its four heads.
 #include "ts_kernels.h"
 
 namespace ts {
@@ -268,54 +267,10 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
   }
 }
 
-// Merges the per-workgroup (max, sum-exp) partials of one (sequence, head) into row_stats.
-// One workgroup per (head, sequence); every partial is loaded at once (one memory round trip), the
-// rescaling exponentials and the sum are double precision.
-__global__ __launch_bounds__(256) void score_stats_merge_kernel(ScoreArgs a, int nparts) {
-  __shared__ float s_m[4];
-  __shared__ double s_l[4];
-  const int h = blockIdx.x, b = blockIdx.y;
-  if (a.skip != nullptr && a.skip[b] != 0) return;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  constexpr int PER = kScoreMaxWg / 256;
-  float mp[PER], lp[PER];
-#pragma unroll
-  for (int i = 0; i < PER; ++i) {
-    const int p = threadIdx.x + 256 * i;
-    mp[i] = -INFINITY; lp[i] = 0.f;
-    if (p < nparts) {
-      const float2 v = *reinterpret_cast<const float2*>(a.partials + (((size_t)b * kScoreMaxWg + p) * a.H + h) * 2);
-      mp[i] = v.x; lp[i] = v.y;
-    }
-  }
-  float m = mp[0];
-#pragma unroll
-  for (int i = 1; i < PER; ++i) m = fmaxf(m, mp[i]);
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
-  if (lane == 0) s_m[wave] = m;
-  __syncthreads();
-  m = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));
-  const double sc = (double)a.scale;
-  double l = 0.0;
-#pragma unroll
-  for (int i = 0; i < PER; ++i)
-    if (mp[i] != -INFINITY) l += (double)lp[i] * exp_f64(sc * ((double)mp[i] - (double)m));
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) l += __shfl_xor(l, off);
-  if (lane == 0) s_l[wave] = l;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    a.row_stats[((size_t)b * a.H + h) * 2] = m;
-    a.row_stats[((size_t)b * a.H + h) * 2 + 1] = (float)(s_l[0] + s_l[1] + s_l[2] + s_l[3]);
-  }
-}
-
 // ------------------------------------------------------------------------------------------------
 template <int DT, int D, int G, bool DOT2>
 static hipError_t launch_one(const ScoreArgs& a, dim3 grid, size_t lds, hipStream_t s) {
   hipLaunchKernelGGL((score_decode_kernel<DT, D, G, DOT2>), grid, dim3(256), lds, s, a);
-  hipLaunchKernelGGL(score_stats_merge_kernel, dim3(a.H, grid.y), dim3(256), 0, s, a, (int)grid.x);
   return hipGetLastError();
 }
 

@@ -10,6 +10,50 @@
 namespace ts {
 
 
+// Merges the per-workgroup (max, sum-exp) partials of one (sequence, head) into row_stats.
+// One workgroup per (head, sequence); every partial is loaded at once (one memory round trip), the
+// rescaling exponentials and the sum are double precision.
+__global__ __launch_bounds__(256) void score_stats_merge_kernel(VoteArgs a) {
+  const int nparts = a.nparts;
+  __shared__ float s_m[4];
+  __shared__ double s_l[4];
+  const int h = blockIdx.x, b = blockIdx.y;
+  if (a.skip != nullptr && a.skip[b] != 0) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  constexpr int PER = kScoreMaxWg / 256;
+  float mp[PER], lp[PER];
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int p = threadIdx.x + 256 * i;
+    mp[i] = -INFINITY; lp[i] = 0.f;
+    if (p < nparts) {
+      const float2 v = *reinterpret_cast<const float2*>(a.partials + (((size_t)b * kScoreMaxWg + p) * a.H + h) * 2);
+      mp[i] = v.x; lp[i] = v.y;
+    }
+  }
+  float m = mp[0];
+#pragma unroll
+  for (int i = 1; i < PER; ++i) m = fmaxf(m, mp[i]);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+  if (lane == 0) s_m[wave] = m;
+  __syncthreads();
+  m = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));
+  const double sc = (double)a.scale;
+  double l = 0.0;
+#pragma unroll
+  for (int i = 0; i < PER; ++i)
+    if (mp[i] != -INFINITY) l += (double)lp[i] * exp_f64(sc * ((double)mp[i] - (double)m));
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) l += __shfl_xor(l, off);
+  if (lane == 0) s_l[wave] = l;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    a.row_stats_out[((size_t)b * a.H + h) * 2] = m;
+    a.row_stats_out[((size_t)b * a.H + h) * 2 + 1] = (float)(s_l[0] + s_l[1] + s_l[2] + s_l[3]);
+  }
+}
+
 // LPT lanes share one token row of H scores (stored [token][head]); a lane owns CPL 16-byte chunks.
 template <int CPL, bool VEC>
 __global__ __launch_bounds__(256) void soft_vote_kernel(VoteArgs a, int lpt_shift) {
@@ -64,6 +108,7 @@ hipError_t launch_soft_vote(const VoteArgs& a, int B, hipStream_t s) {
   while ((1 << lpt_shift) < hq && lpt_shift < 3) ++lpt_shift;
   const int cpl = (hq + (1 << lpt_shift) - 1) >> lpt_shift;   // 1, 2 or 4 for H <= 128
   const bool vec = (a.H % 4 == 0) && (((uintptr_t)a.scores & 15) == 0);
+  hipLaunchKernelGGL(score_stats_merge_kernel, dim3(a.H, B), dim3(256), 0, s, a);
   dim3 grid((a.max_seq_len + (256 >> lpt_shift) - 1) / (256 >> lpt_shift), B);
 #define TS_VOTE(C, V) hipLaunchKernelGGL((soft_vote_kernel<C, V>), grid, dim3(256), 0, s, a, lpt_shift)
   if (cpl <= 1) { if (vec) TS_VOTE(1, true); else TS_VOTE(1, false); }

@@ -12,8 +12,7 @@ struct ScoreArgs {
   const int32_t* seq_lens;
   const uint8_t* skip;
   float* scores;
-  float* row_stats;
-  float* partials;
+  float* partials;        // [B][kScoreMaxWg][H][2] per-workgroup (max, sum-exp)
   int H, H_kv, P, p_shift, max_seq_len;
   int HB, hb_shift, NU;   // KV heads per wave tile (min(H_kv, 8)), its log2, H_kv / HB
   int uniform_page;       // every step of a wave reads one page (P >= tokens per step)
@@ -23,7 +22,10 @@ struct ScoreArgs {
 
 struct VoteArgs {
   const float* scores;
-  const float* row_stats;
+  const float* partials;  // per-workgroup statistics left by the score pass
+  int nparts;             // workgroups per sequence the score pass ran with
+  float* row_stats_out;   // merged (max, sum-exp) per head, written by the merge kernel
+  const float* row_stats; // same buffer, read by the vote kernel
   float* votes;
   const int32_t* seq_lens;
   const uint8_t* skip;

@@ -79,8 +79,8 @@ class DecodeLayer:
         ts.ts_selcache_check(self.problem, q, self.cached_q, self.first, theta, self.reuse)
 
     def select(self, q, score_scale=1.0, skip=None):
-        ts.ts_paged_qk_scores(self.problem, q, self.scores, self.row_stats, score_scale, skip, self.ws)
-        ts.ts_soft_vote(self.problem, self.scores, self.row_stats, score_scale, self.votes, skip)
+        ts.ts_paged_qk_scores(self.problem, q, self.scores, score_scale, skip, self.ws)
+        ts.ts_soft_vote(self.problem, self.scores, score_scale, self.row_stats, self.votes, skip, self.ws)
         ts.ts_topk(self.problem, self.votes, self.k, self.idx, self.count, skip, self.ws)
 
     def attend(self, q, sm_scale):

@@ -49,13 +49,14 @@ def test_calls_reject_bad_arguments_without_launching():
     L = ts.load()
     p = ctypes.byref(cproblem())
     ws, big = 0x10000, 1 << 30
-    assert L.ts_paged_qk_scores(p, None, 0x1000, 0x1000, 1.0, None, ws, big, None) == -1
-    assert L.ts_paged_qk_scores(p, 0x1000, 0x1000, 0x1000, -1.0, None, ws, big, None) == -1
-    assert L.ts_paged_qk_scores(p, 0x1000, 0x1000, 0x1000, float("nan"), None, ws, big, None) == -1
-    assert L.ts_paged_qk_scores(p, 0x1000, 0x1000, 0x1000, 1.0, None, None, 0, None) == -3
-    assert L.ts_paged_qk_scores(p, 0x1000, 0x1000, 0x1000, 1.0, None, ws, 16, None) == -3
-    assert L.ts_paged_qk_scores(ctypes.byref(cproblem(chunk=4)), 0x1000, 0x1000, 0x1000, 1.0, None, ws, big, None) == -2
-    assert L.ts_soft_vote(p, 0x1000, None, 1.0, 0x1000, None, None) == -1
+    assert L.ts_paged_qk_scores(p, None, 0x1000, 1.0, None, ws, big, None) == -1
+    assert L.ts_paged_qk_scores(p, 0x1000, 0x1000, -1.0, None, ws, big, None) == -1
+    assert L.ts_paged_qk_scores(p, 0x1000, 0x1000, float("nan"), None, ws, big, None) == -1
+    assert L.ts_paged_qk_scores(p, 0x1000, 0x1000, 1.0, None, None, 0, None) == -3
+    assert L.ts_paged_qk_scores(p, 0x1000, 0x1000, 1.0, None, ws, 16, None) == -3
+    assert L.ts_paged_qk_scores(ctypes.byref(cproblem(chunk=4)), 0x1000, 0x1000, 1.0, None, ws, big, None) == -2
+    assert L.ts_soft_vote(p, 0x1000, 1.0, None, 0x1000, None, ws, big, None) == -1
+    assert L.ts_soft_vote(p, 0x1000, 1.0, 0x1000, 0x1000, None, ws, 16, None) == -3
     assert L.ts_topk(p, 0x1000, 0, 0x1000, 0x1000, None, ws, big, None) == -1
     assert L.ts_topk(p, 0x1000, 16, 0x1000, 0x1000, None, ws, 8, None) == -3
     assert L.ts_selcache_check(p, 0x1000, 0x1000, None, 0.9, 0x1000, None) == -1
