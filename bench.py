@@ -37,7 +37,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 4])
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4],
+                    help="2 (default) is the headline workload; 3 is the Selection Cache decode run")
     ap.add_argument("--pools", type=int, default=0, help="physical pool copies to rotate over (0 = enough for >= 2 GiB)")
     ap.add_argument("--variant", type=int, default=-1, help="score-pass arithmetic: 0 fma, 1 bf16 dot2, -1 library default")
     ap.add_argument("--score-wg", type=int, default=0)
@@ -68,12 +69,70 @@ def cpu_baseline(w, budget_s=12.0):
             "steps_per_s": 1.0 / t}
 
 
+def selection_cache_run(args):
+    """Configuration 3: B = 8 sequences of 16384..65536 cached tokens, 64 consecutive decode steps with
+    AR(1) queries, one K/V row appended per sequence per step, theta = 0.9.  Reports the reuse rate
+    (Algorithm 1: C_Q is the query of the last reselect) and decode steps/s."""
+    import torch
+    import workloads as W
+    import paper_2411_02886_amd as ts
+    from paper_2411_02886_amd.runtime import DecodeLayer, to_device, to_host
+    dev = "cuda:0"
+    w = W.config3()
+    steps = int(w.extra["steps"])
+    qs = [to_device(q, dev) for q in W.ar1_queries(w, steps, rho=0.95)]
+    ks, vs = W.appended_kv(w, steps)
+    ksd, vsd = to_device(ks, dev), to_device(vs, dev)
+    layer = DecodeLayer.from_workload(w, device=dev, max_seq_len=int(w.seq_lens.max()) + steps)
+    slots = np.empty((steps, w.B), dtype=np.int64)
+    for b in range(w.B):
+        pos = int(w.seq_lens[b]) + np.arange(steps)
+        slots[:, b] = w.pages_of(b).astype(np.int64)[pos // w.P] * w.P + pos % w.P
+    slots_d = torch.from_numpy(slots).to(dev)
+    kflat = layer.k_pool.view(-1, w.H_kv, w.D); vflat = layer.v_pool.view(-1, w.H_kv, w.D)
+    len0 = layer.seq_lens.clone()
+    sm, theta, scale = 1.0 / math.sqrt(w.D), 0.9, 1.0
+    reuse_log = torch.zeros((steps, w.B), dtype=torch.uint8, device=dev)
+
+    def run():
+        layer.seq_lens.copy_(len0); layer.first.fill_(1)
+        for t in range(steps):
+            kflat.index_copy_(0, slots_d[t], ksd[t]); vflat.index_copy_(0, slots_d[t], vsd[t])   # append this step's K/V rows
+            layer.seq_lens.add_(1)
+            layer.step(qs[t], theta=theta, score_scale=scale, sm_scale=sm)
+            reuse_log[t].copy_(layer.reuse)
+
+    run(); torch.cuda.synchronize()
+    reps = max(1, args.steps // steps)
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        run()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / reps
+    reuse = to_host(reuse_log).astype(bool)
+    lens = w.seq_lens.astype(np.int64)[None, :] + 1 + np.arange(steps)[:, None]
+    scanned = int((lens * (~reuse)).sum())
+    res = {"metric": "decode steps/s over the Selection Cache run (batch of 8 sequences per step)",
+           "value": steps / dt, "unit": "batch-steps/s", "n_gpus": 1, "steps": steps * reps, "warmup": steps,
+           "ms_per_step": dt * 1e3 / steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": w.name, "batch": w.B, "cached_tokens": [int(x) for x in w.seq_lens], "k": w.k,
+                      "theta": theta, "score_scale": scale, "query_process": "AR(1) rho=0.95", "steps_per_run": steps,
+                      "anchor": "query of the last reselect (Algorithm 1)"},
+           "reuse_rate": float(reuse.mean()), "sequence_steps_per_s": steps * w.B / dt,
+           "tokens_scanned_per_s": scanned / dt,
+           "note": "host-driven loop: 12 library launches + 4 torch launches per step, no graph capture"}
+    print(json.dumps(res))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus %d is not supported (see DESIGN.md, 'More than one GPU')"
               % args.gpus, file=sys.stderr)
         sys.exit(2)
+    if args.config == 3:
+        return selection_cache_run(args)
     import torch
     import workloads as W
     import paper_2411_02886_amd as ts
