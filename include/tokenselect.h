@@ -127,6 +127,23 @@ int32_t ts_sparse_paged_attn(const ts_problem* p, const void* q, const int32_t* 
                              const int32_t* count, float sm_scale, void* out, float* lse, void* ws,
                              size_t ws_bytes, void* stream);
 
+/* ---- Chunked prefill (chunk = C > 1, bf16): the C queries of a chunk are the last C tokens of their
+ * sequence (seq_lens counts them); selection looks at the N_b - C cached tokens before them.
+ * Sec. 5.2 selects once per chunk; here every query of the chunk votes (Eq. 5 per query) and the
+ * votes are summed over heads and over the chunk's queries:
+ *   votes[b][t] = sum_{c < C} sum_h softmax_t(score_scale * <q[b][c][h], K[t][h/G]>)[t],  t < N_b - C.
+ * The score matrix is computed on the matrix cores (MFMA) and never stored: two sweeps over K.
+ *
+ * ts_chunk_row_stats  sweep 1: row_stats[b][c][h] = (max_t s, sum_t exp(score_scale * (s - max))).
+ * ts_chunk_soft_vote  sweep 2: votes as above from the same q, row_stats and score_scale.
+ * ts_topk with the same problem (chunk > 1) then ranks only the N_b - C cached tokens.
+ * q [device] [B][C][H][D]; row_stats [device] float [B][C][H][2]; votes [device] float [B][max_seq_len]
+ * (entries t >= N_b - C untouched).  fp32 inputs: TS_ERR_UNSUPPORTED. */
+int32_t ts_chunk_row_stats(const ts_problem* p, const void* q, float score_scale, float* row_stats, void* ws,
+                           size_t ws_bytes, void* stream);
+int32_t ts_chunk_soft_vote(const ts_problem* p, const void* q, const float* row_stats, float score_scale, float* votes,
+                           void* ws, size_t ws_bytes, void* stream);
+
 /* Tuning knob for benchmarks and tests (process-wide, not thread-safe, not part of the method):
  * variant 0 = score pass with fma arithmetic, 1 = packed bf16 dot2 arithmetic (bf16 inputs only; the
  * default for bf16: same measured accuracy, fewer registers);

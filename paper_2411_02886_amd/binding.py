@@ -68,9 +68,12 @@ def load():
         L.ts_topk.argtypes = [pp, vp, i32, vp, vp, vp, vp, sz, vp]
         L.ts_selcache_check.argtypes = [pp, vp, vp, vp, f32, vp, vp]
         L.ts_sparse_paged_attn.argtypes = [pp, vp, vp, i32, vp, f32, vp, vp, vp, sz, vp]
+        L.ts_chunk_row_stats.argtypes = [pp, vp, f32, vp, vp, sz, vp]
+        L.ts_chunk_soft_vote.argtypes = [pp, vp, vp, f32, vp, vp, sz, vp]
         L.ts_debug_set_score_variant.argtypes = [i32, i32]
         for name in ("ts_workspace_bytes", "ts_workspace_init", "ts_paged_qk_scores", "ts_soft_vote", "ts_topk",
-                     "ts_selcache_check", "ts_sparse_paged_attn", "ts_debug_set_score_variant"):
+                     "ts_selcache_check", "ts_sparse_paged_attn", "ts_debug_set_score_variant", "ts_chunk_row_stats",
+                     "ts_chunk_soft_vote"):
             getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -139,6 +142,16 @@ def ts_paged_qk_scores(p: Problem, q, scores, score_scale: float, skip, ws, stre
 def ts_soft_vote(p: Problem, scores, score_scale: float, row_stats, votes, skip, ws, stream=None) -> None:
     _ok(load().ts_soft_vote(p.ref(), _ptr(scores), float(score_scale), _ptr(row_stats), _ptr(votes), _ptr(skip),
                             _ptr(ws), _nbytes(ws), _stream(stream)), "ts_soft_vote")
+
+
+def ts_chunk_row_stats(p: Problem, q, score_scale: float, row_stats, ws, stream=None) -> None:
+    _ok(load().ts_chunk_row_stats(p.ref(), _ptr(q), float(score_scale), _ptr(row_stats), _ptr(ws), _nbytes(ws),
+                                  _stream(stream)), "ts_chunk_row_stats")
+
+
+def ts_chunk_soft_vote(p: Problem, q, row_stats, score_scale: float, votes, ws, stream=None) -> None:
+    _ok(load().ts_chunk_soft_vote(p.ref(), _ptr(q), _ptr(row_stats), float(score_scale), _ptr(votes), _ptr(ws),
+                                  _nbytes(ws), _stream(stream)), "ts_chunk_soft_vote")
 
 
 def ts_topk(p: Problem, votes, k: int, idx, count, skip, ws, stream=None) -> None:

@@ -142,12 +142,53 @@ int32_t ts_topk(const ts_problem* p, const float* votes, int32_t k, int32_t* idx
   const WsLayout w = ws_layout(p, k);
   if (ws == nullptr || ((uintptr_t)ws & 255) != 0 || ws_bytes < w.attn_out) return TS_ERR_WORKSPACE;
   TopkArgs a{};
+  a.tail = p->chunk > 1 ? p->chunk : 0;
   a.votes = votes; a.seq_lens = p->seq_lens; a.skip = skip; a.idx = idx; a.count = count;
   a.hist = (uint32_t*)((uint8_t*)ws + w.topk_hist);
   a.state = (uint32_t*)((uint8_t*)ws + w.topk_state);
   a.blk = (uint32_t*)((uint8_t*)ws + w.topk_blk);
   a.k = k; a.max_seq_len = p->max_seq_len; a.nblk = w.topk_nblk;
   return launch_topk(a, p->batch, (hipStream_t)stream) == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
+static int32_t fill_prefill_args(const ts_problem* p, const void* q, float score_scale, void* ws, size_t ws_bytes,
+                                 PrefillArgs* a) {
+  int32_t st = check_problem(p);
+  if (st != TS_OK) return st;
+  if (q == nullptr || p->k_pool == nullptr) return TS_ERR_INVALID_ARG;
+  if (!(score_scale >= 0.f) || !(score_scale < 1e30f)) return TS_ERR_INVALID_ARG;
+  if (p->chunk < 2 || p->dtype != TS_BF16) return TS_ERR_UNSUPPORTED;
+  const WsLayout w = ws_layout(p, 1);
+  if (ws == nullptr || ((uintptr_t)ws & 255) != 0 || ws_bytes < w.total) return TS_ERR_WORKSPACE;
+  a->q = (const uint8_t*)q; a->k_pool = (const uint8_t*)p->k_pool;
+  a->page_indptr = p->page_indptr; a->page_indices = p->page_indices; a->seq_lens = p->seq_lens;
+  a->stat_part = (float*)((uint8_t*)ws + w.pf_stat_part);
+  a->vote_part = (float*)((uint8_t*)ws + w.pf_vote_part);
+  a->B = p->batch; a->C = p->chunk; a->H = p->num_q_heads; a->H_kv = p->num_kv_heads;
+  a->G = p->num_q_heads / p->num_kv_heads; a->D = p->head_dim; a->P = p->page_size; a->p_shift = ilog2(p->page_size);
+  a->max_seq_len = p->max_seq_len; a->RB = w.pf_rb; a->TS = w.pf_ts;
+  a->scale = score_scale; a->c2 = score_scale * 1.44269504088896340736f;
+  return TS_OK;
+}
+
+int32_t ts_chunk_row_stats(const ts_problem* p, const void* q, float score_scale, float* row_stats, void* ws,
+                           size_t ws_bytes, void* stream) {
+  PrefillArgs a{};
+  const int32_t st = fill_prefill_args(p, q, score_scale, ws, ws_bytes, &a);
+  if (st != TS_OK) return st;
+  if (row_stats == nullptr) return TS_ERR_INVALID_ARG;
+  a.row_stats_out = row_stats; a.row_stats = row_stats;
+  return launch_prefill_stats(a, (hipStream_t)stream) == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
+int32_t ts_chunk_soft_vote(const ts_problem* p, const void* q, const float* row_stats, float score_scale, float* votes,
+                           void* ws, size_t ws_bytes, void* stream) {
+  PrefillArgs a{};
+  const int32_t st = fill_prefill_args(p, q, score_scale, ws, ws_bytes, &a);
+  if (st != TS_OK) return st;
+  if (row_stats == nullptr || votes == nullptr) return TS_ERR_INVALID_ARG;
+  a.row_stats = row_stats; a.votes = votes;
+  return launch_prefill_votes(a, (hipStream_t)stream) == hipSuccess ? TS_OK : TS_ERR_HIP;
 }
 
 int32_t ts_selcache_check(const ts_problem* p, const void* q, void* cached_q, uint8_t* first, float theta,

@@ -1,0 +1,286 @@
+// Chunked-prefill selection (Sec. 5.2 with per-query votes): for the C queries of a chunk,
+//   votes[t] = sum_{c < C} sum_h softmax_t(scale * S[c][h][:])[t]    over the cached tokens t,
+// with S = Q K^T computed on the matrix cores and never written to memory.  Two sweeps over K:
+//   sweep 1  per-row (query, head) running max and sum-exp        -> row_stats
+//   sweep 2  e = exp(scale * (s - max_row)) / sumexp_row summed over the rows of a tile column -> votes
+// Both sweeps run the same instruction sequence for S, so a score has the same bits in both.
+//
+// Work split.  For one KV head the G query heads x C queries are 'rows' that all meet the same K
+// rows.  A workgroup (4 waves) owns 256 rows (64 per wave = two 32-row MFMA blocks, query fragments
+// pinned in registers) and walks a range of 64-token tiles: the K tile is staged once in LDS (16-byte
+// coalesced global loads, row stride padded to 272 B so that the 16-byte fragment reads are
+// conflict-free), every wave reads its B fragments from there and issues 2 x 2 x (D/16)
+// v_mfma_f32_32x32x16_bf16.  The next tile's K rows are in flight in registers while the current one
+// is multiplied.  Workgroups that share a K range are placed on the same XCD and adjacent in launch
+// order, so that one of them pulls a tile from HBM and the others find it in that XCD's L2.
+#include "ts_kernels.h"
+
+namespace ts {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+
+constexpr int kPfRowsPerWg = 256;
+constexpr int kPfTile = 64;            // tokens per tile
+
+// XCD-aware decode of the linear workgroup id: (row block, group) with group = (sequence, KV head, split)
+__device__ __forceinline__ bool pf_decode_block(const PrefillArgs& a, int* rb, int* b, int* kvh, int* split) {
+  const int L = blockIdx.x;
+  const int xcd = L & 7, jq = L >> 3;
+  *rb = jq % a.RB;
+  const int group = (jq / a.RB) * 8 + xcd;
+  if (group >= a.B * a.H_kv * a.TS) return false;
+  *split = group % a.TS;
+  const int r = group / a.TS;
+  *kvh = r % a.H_kv;
+  *b = r / a.H_kv;
+  return true;
+}
+
+template <int D, int SWEEP>
+__global__ __launch_bounds__(256) void prefill_qk_kernel(PrefillArgs a) {
+  constexpr int KS = D / 16;                    // MFMA k-steps
+  constexpr int RBYTES = D * 2;                 // bytes per K row
+  constexpr int PPR = RBYTES / 16;              // 16-byte pieces per row
+  constexpr int RPP = 256 / PPR;                // rows staged per pass of the workgroup
+  constexpr int NLD = kPfTile / RPP;            // staging loads per thread per tile
+  constexpr int LROW = RBYTES + 16;             // padded LDS row
+  __shared__ __attribute__((aligned(16))) uint8_t s_k[2][kPfTile * LROW];
+  __shared__ float s_col[2][4][kPfTile];
+
+  int rb, b, kvh, split;
+  if (!pf_decode_block(a, &rb, &b, &kvh, &split)) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int C = a.C, G = a.G, H = a.H;
+  const int Nc = min(max(a.seq_lens[b] - C, 0), a.max_seq_len);     // cached tokens the selection looks at
+  const int ntile = (Nc + kPfTile - 1) / kPfTile;
+  const int tps = (ntile + a.TS - 1) / a.TS;
+  const int tile_begin = split * tps, tile_end = min(ntile, tile_begin + tps);
+  const int indptr = a.page_indptr[b];
+  const int nrows = C * G;
+  const float c2 = a.c2;
+
+  // ---- query fragments: A[m][k], lane holds row m = lane % 32, k = 8 * (lane / 32) .. + 8 of each k-step
+  const int half = lane >> 5, col = lane & 31;
+  bf16x8_t afrag[2][KS];
+  int row_of[2];                                 // global row of this lane's A row per block (for loads only)
+#pragma unroll
+  for (int mb = 0; mb < 2; ++mb) {
+    const int row = rb * kPfRowsPerWg + wave * 64 + mb * 32 + col;
+    row_of[mb] = row;
+    const bool valid = row < nrows;
+    const int c = valid ? row / G : 0, g = valid ? row % G : 0;
+    const uint8_t* qp = a.q + ((((size_t)b * C + c) * H + (size_t)kvh * G + g) * D + 8 * half) * 2;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (valid) v = *reinterpret_cast<const uint4*>(qp + ks * 32);
+      afrag[mb][ks] = __builtin_bit_cast(bf16x8_t, v);
+    }
+  }
+  (void)row_of;
+
+  // ---- per-row state.  In the MFMA result a lane holds, for column `col`, the 16 rows
+  // 8 * i + 4 * half + j (i, j < 4) of each 32-row block: 32 rows per lane.
+  float rm[2][16], rl[2][16];                    // sweep 1: running max / sum-exp; sweep 2: rm = offset, rl unused
+#pragma unroll
+  for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int row = rb * kPfRowsPerWg + wave * 64 + mb * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
+      if (SWEEP == 1) { rm[mb][e] = -INFINITY; rl[mb][e] = 0.f; }
+      else {
+        // e = exp2(c2 * s - off) with off = c2 * max + log2(sumexp); rows past the end never vote
+        float off = INFINITY;
+        if (row < nrows) {
+          const int c = row / G, g = row % G;
+          const float2 st = *reinterpret_cast<const float2*>(a.row_stats + (((size_t)b * C + c) * H + kvh * G + g) * 2);
+          off = c2 * st.x + __builtin_amdgcn_logf(st.y);   // v_log_f32 is log2
+        }
+        rm[mb][e] = off; rl[mb][e] = 0.f;
+      }
+    }
+
+  // ---- K staging: thread -> (row within pass, 16-byte piece)
+  const int st_row = threadIdx.x / PPR, st_piece = threadIdx.x % PPR;
+  uint4 kreg[NLD];
+  auto fetch = [&](int tile) {
+#pragma unroll
+    for (int it = 0; it < NLD; ++it) {
+      int t = tile * kPfTile + st_row + it * RPP;
+      t = min(t, Nc - 1);                                     // the last tile may be ragged: shadow the last token
+      const int page = a.page_indices[indptr + (t >> a.p_shift)];
+      const uint8_t* kp = a.k_pool + ((((size_t)page << a.p_shift) + (t & (a.P - 1))) * a.H_kv + kvh) * RBYTES + st_piece * 16;
+      kreg[it] = *reinterpret_cast<const uint4*>(kp);
+    }
+  };
+  auto stage = [&](int buf) {
+#pragma unroll
+    for (int it = 0; it < NLD; ++it)
+      *reinterpret_cast<uint4*>(&s_k[buf][(st_row + it * RPP) * LROW + st_piece * 16]) = kreg[it];
+  };
+
+  if (tile_begin < tile_end) {
+    fetch(tile_begin);
+    stage(0);
+    if (tile_begin + 1 < tile_end) fetch(tile_begin + 1);
+  }
+  __syncthreads();
+
+  float* vout = (SWEEP == 2) ? a.vote_part + ((size_t)b * a.RB * a.H_kv + (size_t)rb * a.H_kv + kvh) * a.max_seq_len : nullptr;
+
+  for (int tile = tile_begin; tile < tile_end; ++tile) {
+    const int buf = (tile - tile_begin) & 1;
+    if (tile + 1 < tile_end) stage(buf ^ 1);                 // rows fetched during the previous iteration
+    if (tile + 2 < tile_end) fetch(tile + 2);
+
+    f32x16_t acc[2][2];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[mb][nb][e] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb) {
+        // B[k][n] = K[token n][d k]: lane holds token n = col, d = 16 * ks + 8 * half .. + 8
+        const uint4 bv = *reinterpret_cast<const uint4*>(&s_k[buf][(nb * 32 + col) * LROW + (ks * 2 + half) * 16]);
+        const bf16x8_t bfrag = __builtin_bit_cast(bf16x8_t, bv);
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+          acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[mb][ks], bfrag, acc[mb][nb], 0, 0, 0);
+      }
+    }
+
+    const int t_base = tile * kPfTile;
+    if (SWEEP == 1) {
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb) {
+        const bool cvalid = (t_base + nb * 32 + col) < Nc;
+        bool grow = false;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) grow |= cvalid && (acc[mb][nb][e] > rm[mb][e]);
+        if (__builtin_amdgcn_ballot_w64(grow) != 0) {          // rare after the first tiles
+#pragma unroll
+          for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+              const float x = cvalid ? acc[mb][nb][e] : -INFINITY;
+              const float mn = fmaxf(rm[mb][e], x);
+              rl[mb][e] = (rm[mb][e] == -INFINITY) ? 0.f : rl[mb][e] * __builtin_amdgcn_exp2f(c2 * (rm[mb][e] - mn));
+              rm[mb][e] = mn;
+            }
+        }
+        if (cvalid) {
+#pragma unroll
+          for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) rl[mb][e] += __builtin_amdgcn_exp2f(c2 * (acc[mb][nb][e] - rm[mb][e]));
+        }
+      }
+    } else {
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb) {
+        float cs = 0.f;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) cs += __builtin_amdgcn_exp2f(fmaf(c2, acc[mb][nb][e], -rm[mb][e]));
+        cs += __shfl_xor(cs, 32);                              // the other 16 rows of each block
+        if (half == 0) s_col[buf][wave][nb * 32 + col] = cs;
+      }
+    }
+    __syncthreads();
+    if (SWEEP == 2 && threadIdx.x < kPfTile) {
+      const int t = t_base + threadIdx.x;
+      if (t < Nc) vout[t] = (s_col[buf][0][threadIdx.x] + s_col[buf][1][threadIdx.x]) + (s_col[buf][2][threadIdx.x] + s_col[buf][3][threadIdx.x]);
+    }
+  }
+
+  if (SWEEP == 1) {
+    // a row's statistics are spread over the 32 lanes of its half-wave (one column each): merge them
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        float m = rm[mb][e], l = rl[mb][e];
+#pragma unroll
+        for (int off = 1; off < 32; off <<= 1) {
+          const float mo = __shfl_xor(m, off), lo = __shfl_xor(l, off);
+          const float mn = fmaxf(m, mo);
+          const float la = (m == -INFINITY) ? 0.f : l * __builtin_amdgcn_exp2f(c2 * (m - mn));
+          const float lb = (mo == -INFINITY) ? 0.f : lo * __builtin_amdgcn_exp2f(c2 * (mo - mn));
+          m = mn; l = la + lb;
+        }
+        const int row = rb * kPfRowsPerWg + wave * 64 + mb * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
+        if (col == 0 && row < nrows) {
+          const int c = row / G, g = row % G;
+          float* pp = a.stat_part + ((((size_t)b * a.TS + split) * C + c) * H + kvh * G + g) * 2;
+          pp[0] = m; pp[1] = l;
+        }
+      }
+  }
+}
+
+// row_stats[b][c][h] = merge over the token splits of the sweep-1 partials
+__global__ __launch_bounds__(256) void prefill_stats_merge_kernel(PrefillArgs a) {
+  const int i = blockIdx.x * 256 + threadIdx.x;          // (b, c, h) flattened
+  const int n = a.B * a.C * a.H;
+  if (i >= n) return;
+  const int b = i / (a.C * a.H), ch = i % (a.C * a.H);
+  float m = -INFINITY;
+  for (int s = 0; s < a.TS; ++s) m = fmaxf(m, a.stat_part[(((size_t)b * a.TS + s) * a.C * a.H + ch) * 2]);
+  const double sc = (double)a.scale;
+  double l = 0.0;
+  for (int s = 0; s < a.TS; ++s) {
+    const float2 v = *reinterpret_cast<const float2*>(a.stat_part + (((size_t)b * a.TS + s) * a.C * a.H + ch) * 2);
+    if (v.x != -INFINITY) l += (double)v.y * exp_f64(sc * ((double)v.x - (double)m));
+  }
+  a.row_stats_out[(size_t)i * 2] = m;
+  a.row_stats_out[(size_t)i * 2 + 1] = (float)l;
+}
+
+// votes[b][t] = sum over the (row block, KV head) partial vote vectors, double accumulation
+__global__ __launch_bounds__(256) void prefill_vote_reduce_kernel(PrefillArgs a) {
+  const int b = blockIdx.y;
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  const int Nc = min(max(a.seq_lens[b] - a.C, 0), a.max_seq_len);
+  if (t >= Nc) return;
+  const int np = a.RB * a.H_kv;
+  const float* p = a.vote_part + (size_t)b * np * a.max_seq_len + t;
+  double v = 0.0;
+  int i = 0;
+  for (; i + 8 <= np; i += 8) {
+    float x[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = p[(size_t)(i + e) * a.max_seq_len];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v += (double)x[e];
+  }
+  for (; i < np; ++i) v += (double)p[(size_t)i * a.max_seq_len];
+  a.votes[(size_t)b * a.max_seq_len + t] = (float)v;
+}
+
+hipError_t launch_prefill_stats(const PrefillArgs& a, hipStream_t s) {
+  const int groups = a.B * a.H_kv * a.TS;
+  const int grid = (groups + 7) / 8 * 8 * a.RB;
+  if (a.D == 128) hipLaunchKernelGGL((prefill_qk_kernel<128, 1>), dim3(grid), dim3(256), 0, s, a);
+  else hipLaunchKernelGGL((prefill_qk_kernel<64, 1>), dim3(grid), dim3(256), 0, s, a);
+  hipLaunchKernelGGL(prefill_stats_merge_kernel, dim3((a.B * a.C * a.H + 255) / 256), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_prefill_votes(const PrefillArgs& a, hipStream_t s) {
+  const int groups = a.B * a.H_kv * a.TS;
+  const int grid = (groups + 7) / 8 * 8 * a.RB;
+  if (a.D == 128) hipLaunchKernelGGL((prefill_qk_kernel<128, 2>), dim3(grid), dim3(256), 0, s, a);
+  else hipLaunchKernelGGL((prefill_qk_kernel<64, 2>), dim3(grid), dim3(256), 0, s, a);
+  hipLaunchKernelGGL(prefill_vote_reduce_kernel, dim3((a.max_seq_len + 255) / 256, a.B), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace ts

@@ -90,7 +90,7 @@ __global__ __launch_bounds__(256) void topk_hist0_kernel(TopkArgs a) {
   __shared__ uint32_t h[kTopkBins];
   const int b = blockIdx.y;
   if (a.skip != nullptr && a.skip[b] != 0) return;
-  const int N = min(max(a.seq_lens[b], 0), a.max_seq_len);
+  const int N = min(max(a.seq_lens[b] - a.tail, 0), a.max_seq_len);
   const int base = blockIdx.x * kTopkChunk;
   if (base >= N) return;
   uint32_t key[kTopkChunk / 256]; bool valid[kTopkChunk / 256];
@@ -110,7 +110,7 @@ __global__ __launch_bounds__(256) void topk_hist1_kernel(TopkArgs a) {
   __shared__ uint32_t lds[8];
   const int b = blockIdx.y;
   if (a.skip != nullptr && a.skip[b] != 0) return;
-  const int N = min(max(a.seq_lens[b], 0), a.max_seq_len);
+  const int N = min(max(a.seq_lens[b] - a.tail, 0), a.max_seq_len);
   const int base = blockIdx.x * kTopkChunk;
   if (base >= N && blockIdx.x != 0) return;
   uint32_t key[kTopkChunk / 256]; bool valid[kTopkChunk / 256];
@@ -135,7 +135,7 @@ __global__ __launch_bounds__(256) void topk_hist2_kernel(TopkArgs a) {
   __shared__ uint32_t lds[8];
   const int b = blockIdx.y;
   if (a.skip != nullptr && a.skip[b] != 0) return;
-  const int N = min(max(a.seq_lens[b], 0), a.max_seq_len);
+  const int N = min(max(a.seq_lens[b] - a.tail, 0), a.max_seq_len);
   const int base = blockIdx.x * kTopkChunk;
   if (base >= N && blockIdx.x != 0) return;
   uint32_t key[kTopkChunk / 256]; bool valid[kTopkChunk / 256];
@@ -165,7 +165,7 @@ __global__ __launch_bounds__(256) void topk_count_kernel(TopkArgs a) {
   __shared__ uint32_t red[4];
   const int b = blockIdx.y;
   if (a.skip != nullptr && a.skip[b] != 0) return;
-  const int N = min(max(a.seq_lens[b], 0), a.max_seq_len);
+  const int N = min(max(a.seq_lens[b] - a.tail, 0), a.max_seq_len);
   const int base = blockIdx.x * kTopkChunk;
   uint32_t key[kTopkChunk / 256]; bool valid[kTopkChunk / 256];
   load_keys(a.votes + (size_t)b * a.max_seq_len, base, N, key, valid);
@@ -202,7 +202,7 @@ __global__ __launch_bounds__(256) void topk_emit_kernel(TopkArgs a) {
   __shared__ uint32_t red[2][4];
   const int b = blockIdx.y;
   if (a.skip != nullptr && a.skip[b] != 0) return;
-  const int N = min(max(a.seq_lens[b], 0), a.max_seq_len);
+  const int N = min(max(a.seq_lens[b] - a.tail, 0), a.max_seq_len);
   const uint32_t thr = a.state[b * 8 + ST_THR];
   const uint32_t need_eq = a.state[b * 8 + ST_NEED_EQ];
   const bool none = a.state[b * 8 + ST_NONE] != 0;

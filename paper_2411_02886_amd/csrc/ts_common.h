@@ -24,7 +24,10 @@ struct WsLayout {
   size_t topk_blk;         // uint32 [B][nblk] : per-chunk (above | equal << 16) counts
   size_t attn_out;         // float [B][H][nsplit][D]
   size_t attn_ml;          // float [B][H][nsplit][2]
+  size_t pf_stat_part;     // float [B][TS][C][H][2]            (chunk > 1 only)
+  size_t pf_vote_part;     // float [B][RB * H_kv][max_seq_len] (chunk > 1 only)
   size_t total;
+  int pf_rb, pf_ts;
   int topk_nblk;
   int attn_nsplit;
 };
@@ -45,6 +48,19 @@ inline WsLayout ws_layout(const ts_problem* p, int k) {
   w.topk_state = take(B * 8 * 4);
   w.score_partials = take(B * kScoreMaxWg * H * 2 * 4);
   w.topk_blk = take(B * (size_t)w.topk_nblk * 4);
+  if (p->chunk > 1) {
+    const int G = p->num_q_heads / p->num_kv_heads;
+    w.pf_rb = (p->chunk * G + 255) / 256;
+    const int ntile = (p->max_seq_len + 63) / 64;
+    int ts = 2048 / (p->batch * p->num_kv_heads * w.pf_rb);
+    if (ts > 64) ts = 64;
+    if (ts > ntile) ts = ntile;
+    if (ts < 1) ts = 1;
+    w.pf_ts = ts;
+    w.pf_stat_part = take(B * (size_t)ts * p->chunk * H * 2 * 4);
+    w.pf_vote_part = take(B * (size_t)w.pf_rb * p->num_kv_heads * (size_t)p->max_seq_len * 4);
+  }
+  // the sections that depend on k come last, so that every other offset is the same for any k
   w.attn_out = take(B * H * (size_t)w.attn_nsplit * D * 4);
   w.attn_ml = take(B * H * (size_t)w.attn_nsplit * 2 * 4);
   w.total = off;

@@ -34,6 +34,7 @@ struct VoteArgs {
 };
 
 struct TopkArgs {
+  int tail;             // trailing tokens of every sequence that do not take part (the chunk's own tokens)
   const float* votes;
   const int32_t* seq_lens;
   const uint8_t* skip;
@@ -71,6 +72,27 @@ struct AttnArgs {
   int H, H_kv, P, p_shift, idx_stride, nsplit, max_seq_len;
   float sm_scale;
 };
+
+// chunked-prefill selection (both sweeps)
+struct PrefillArgs {
+  const uint8_t* q;          // [B][C][H][D] bf16
+  const uint8_t* k_pool;
+  const int32_t* page_indptr;
+  const int32_t* page_indices;
+  const int32_t* seq_lens;
+  float* stat_part;          // [B][TS][C][H][2] sweep-1 partial (max, sum-exp) per token split
+  float* row_stats_out;      // [B][C][H][2] merged
+  const float* row_stats;    // [B][C][H][2] read by sweep 2
+  float* vote_part;          // [B][RB * H_kv][max_seq_len] sweep-2 partial votes per (row block, KV head)
+  float* votes;              // [B][max_seq_len]
+  int B, C, H, H_kv, G, D, P, p_shift, max_seq_len;
+  int RB;                    // 256-row blocks per KV head: ceil(C * G / 256)
+  int TS;                    // token splits
+  float scale, c2;
+};
+
+hipError_t launch_prefill_stats(const PrefillArgs& a, hipStream_t s);
+hipError_t launch_prefill_votes(const PrefillArgs& a, hipStream_t s);
 
 // variant: 0 = fma arithmetic, 1 = packed bf16 dot2 (bf16 only)
 hipError_t launch_score_decode(int dtype, int D, int G, int variant, const ScoreArgs& a, dim3 grid, size_t lds, hipStream_t s);

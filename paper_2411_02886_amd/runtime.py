@@ -96,3 +96,41 @@ class DecodeLayer:
             skip = self.reuse
         self.select(q, score_scale, skip)
         self.attend(q, sm)
+
+
+class ChunkSelector:
+    """Chunked-prefill selection for one layer: the C queries of a chunk are the last C tokens of
+    their sequences; two MFMA sweeps give the votes, ts_topk the shared index set."""
+
+    def __init__(self, *, C, H, H_kv, D, P, k, k_pool, v_pool, page_indptr, page_indices, seq_lens, max_seq_len=None,
+                 device="cuda:0"):
+        self.C, self.H, self.H_kv, self.D, self.P, self.k = C, H, H_kv, D, P, k
+        self.B = int(len(seq_lens))
+        self.k_pool = k_pool if torch.is_tensor(k_pool) else to_device(k_pool, device)
+        self.v_pool = v_pool if torch.is_tensor(v_pool) else to_device(v_pool, device)
+        self.page_indptr = to_device(np.asarray(page_indptr, dtype=np.int32), device)
+        self.page_indices = to_device(np.asarray(page_indices, dtype=np.int32), device)
+        self.seq_lens = to_device(np.asarray(seq_lens, dtype=np.int32), device)
+        self.max_seq_len = int(max_seq_len if max_seq_len is not None else max(1, int(np.max(seq_lens))))
+        self.problem = ts.Problem(batch=self.B, chunk=C, num_q_heads=H, num_kv_heads=H_kv, head_dim=D, page_size=P,
+                                  max_seq_len=self.max_seq_len, dtype=ts.TS_BF16, k_pool=self.k_pool,
+                                  v_pool=self.v_pool, page_indptr=self.page_indptr, page_indices=self.page_indices,
+                                  seq_lens=self.seq_lens)
+        B, M = self.B, self.max_seq_len
+        self.row_stats = torch.empty((B, C, H, 2), dtype=torch.float32, device=device)
+        self.votes = torch.zeros((B, M), dtype=torch.float32, device=device)
+        self.idx = torch.full((B, k), -1, dtype=torch.int32, device=device)
+        self.count = torch.zeros((B,), dtype=torch.int32, device=device)
+        nbytes = ts.ts_workspace_bytes(self.problem, k)
+        self.ws = torch.empty((nbytes + 255) // 256 * 64, dtype=torch.int32, device=device)
+        ts.ts_workspace_init(self.ws)
+
+    @classmethod
+    def from_workload(cls, w, k=None, device="cuda:0"):
+        return cls(C=w.C, H=w.H, H_kv=w.H_kv, D=w.D, P=w.P, k=w.k if k is None else k, k_pool=w.k_pool, v_pool=w.v_pool,
+                   page_indptr=w.page_indptr, page_indices=w.page_indices, seq_lens=w.seq_lens, device=device)
+
+    def select(self, q, score_scale=1.0):
+        ts.ts_chunk_row_stats(self.problem, q, score_scale, self.row_stats, self.ws)
+        ts.ts_chunk_soft_vote(self.problem, q, self.row_stats, score_scale, self.votes, self.ws)
+        ts.ts_topk(self.problem, self.votes, self.k, self.idx, self.count, None, self.ws)

@@ -1,0 +1,86 @@
+"""GPU parity of the chunked-prefill selection (MFMA score sweeps, per-query votes summed over the
+chunk, shared top-k) against the CPU oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as W
+from parity_util import compare_index_sets, ulp32
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2411_02886_amd as ts
+    ts.load()
+    return ts
+
+
+def run_chunk_selection(ts, w, k, scale):
+    from paper_2411_02886_amd.runtime import ChunkSelector, to_device, to_host
+    sel = ChunkSelector.from_workload(w, k=k)
+    q = to_device(w.q)
+    sel.select(q, scale)
+    torch.cuda.synchronize()
+    return (to_host(sel.row_stats), to_host(sel.votes), to_host(sel.idx), to_host(sel.count))
+
+
+def check_chunk(ts, w, k, scale, label):
+    st_g, v_g, idx_g, cnt_g = run_chunk_selection(ts, w, k, scale)
+    c = float(np.float32(scale))
+    for b in range(w.B):
+        Nc = int(w.seq_lens[b]) - w.C
+        lab = "%s b=%d Nc=%d" % (label, b, Nc)
+        if Nc <= 0:
+            assert cnt_g[b] == 0 and np.all(idx_g[b] == -1), lab
+            continue
+        votes = np.zeros(Nc)
+        smax = 0.0
+        for ci in range(w.C):
+            S = oracle.paged_qk_scores(np.ascontiguousarray(w.q[b, ci]), w.k_pool, w.dtype, w.H_kv, w.P, w.pages_of(b), Nc)
+            v, m, z = oracle.soft_vote(S, c, with_stats=True)
+            votes += v
+            smax = max(smax, float(np.abs(S).max()))
+            # sweep 1: row max within a few ulp of the largest score, sum-exp to 2e-5 relative
+            assert np.abs(st_g[b, ci, :, 0] * c - m).max() <= 8 * ulp32(smax) * max(c, 1e-3) + 1e-12, (lab, ci, "row max")
+            np.testing.assert_allclose(st_g[b, ci, :, 1], z, rtol=3e-5, err_msg=lab + " sum-exp")
+        # sweep 2: votes; float arithmetic with the fast exponential: 3e-5 relative
+        np.testing.assert_allclose(v_g[b, :Nc], votes, rtol=3e-5, atol=1e-30, err_msg=lab + " votes")
+        assert abs(float(v_g[b, :Nc].astype(np.float64).sum()) - w.C * w.H) < 1e-4 * w.C * w.H, lab
+        # radix select in isolation on the GPU's own votes: bit-exact
+        i_iso, c_iso = oracle.topk(v_g[b, :Nc].astype(np.float64), k)
+        assert cnt_g[b] == c_iso and np.array_equal(idx_g[b], i_iso), (lab, "radix select")
+        # end to end against the oracle's chunk selection (1e-6 band rule)
+        i_o, c_o = oracle.topk(oracle.decision_votes(votes), k)
+        compare_index_sets(idx_g[b], int(cnt_g[b]), dict(idx=i_o, count=c_o, votes=votes), lab)
+
+
+CASES = [
+    # C, H, H_kv, D, P, seq_len (cached = seq_len - C), k, scale
+    (48, 8, 2, 128, 16, 3048, 64, 0.0884),      # fewer rows than one 256-row block, ragged token tiles
+    (128, 32, 8, 128, 16, 5128, 256, 1.0),      # config 5's head shapes, two row blocks per KV head
+    (100, 28, 4, 128, 16, 2100, 100, 0.0884),   # group of seven: row blocks that straddle queries
+    (64, 16, 4, 64, 16, 1500, 50, 0.125),       # head_dim 64
+    (16, 8, 8, 128, 4, 400, 400, 0.0884),       # G = 1, k larger than the cached length
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=lambda c: "C%d_H%d_%d_D%d_P%d_L%d_k%d" % c[:7])
+def test_chunk_selection_shapes(gpu, case):
+    C, H, H_kv, D, P, L, k, scale = case
+    print("chunk case", case, flush=True)
+    w = W.make_workload("chunk", dtype=W.BF16, C=C, H=H, H_kv=H_kv, D=D, P=P, seq_lens=[L], k=k, beta=2.5,
+                        planted_per_head=max(1, (L - C) // 200), plant_limit=L - C, seed=L + C)
+    check_chunk(gpu, w, k, scale, str(case))
+
+
+def test_chunk_selection_ragged_batch(gpu):
+    C = 32
+    lens = [C, C + 1, C + 63, C + 64, C + 65, 900]
+    w = W.make_workload("chunkb", dtype=W.BF16, B=len(lens), C=C, H=8, H_kv=2, D=128, P=16, seq_lens=lens, k=40, seed=3)
+    print("chunk ragged batch", lens, flush=True)
+    check_chunk(gpu, w, 40, 0.0884, "ragged")
