@@ -134,7 +134,8 @@ int32_t ts_sparse_paged_attn(const ts_problem* p, const void* q, const int32_t* 
  *   votes[b][t] = sum_{c < C} sum_h softmax_t(score_scale * <q[b][c][h], K[t][h/G]>)[t],  t < N_b - C.
  * The score matrix is computed on the matrix cores (MFMA) and never stored: two sweeps over K.
  *
- * ts_chunk_row_stats  sweep 1: row_stats[b][c][h] = (max_t s, sum_t exp(score_scale * (s - max))).
+ * ts_chunk_row_stats  sweep 1: row_stats[b][c][h] = L = log2 sum_t 2^(score_scale * log2(e) * s), the base-2
+ *                     log-sum-exp of the row, stored as a (high, low) float pair with high + low = L.
  * ts_chunk_soft_vote  sweep 2: votes as above from the same q, row_stats and score_scale.
  * ts_topk with the same problem (chunk > 1) then ranks only the N_b - C cached tokens.
  * q [device] [B][C][H][D]; row_stats [device] float [B][C][H][2]; votes [device] float [B][max_seq_len]

@@ -1,8 +1,8 @@
 // Chunked-prefill selection (Sec. 5.2 with per-query votes): for the C queries of a chunk,
 //   votes[t] = sum_{c < C} sum_h softmax_t(scale * S[c][h][:])[t]    over the cached tokens t,
 // with S = Q K^T computed on the matrix cores and never written to memory.  Two sweeps over K:
-//   sweep 1  per-row (query, head) running max and sum-exp        -> row_stats
-//   sweep 2  e = exp(scale * (s - max_row)) / sumexp_row summed over the rows of a tile column -> votes
+//   sweep 1  per-row (query, head) log-sum-exp of scale * s over the cached tokens   -> row_stats
+//   sweep 2  e = exp(scale * s - lse_row) summed over the rows of a tile column          -> votes
 // Both sweeps run the same instruction sequence for S, so a score has the same bits in both.
 //
 // Work split.  For one KV head the G query heads x C queries are 'rows' that all meet the same K
@@ -82,48 +82,55 @@ __global__ __launch_bounds__(256) void prefill_qk_kernel(PrefillArgs a) {
 
   // ---- per-row state.  In the MFMA result a lane holds, for column `col`, the 16 rows
   // 8 * i + 4 * half + j (i, j < 4) of each 32-row block: 32 rows per lane.
-  float rm[2][16], rl[2][16];                    // sweep 1: running max / sum-exp; sweep 2: rm = offset, rl unused
+  // Sweep 1 keeps, per lane and row, a reference exponent `off` (log2 units) and the sum of
+  // exp2(c2 * s - off) over the lane's columns; the reference is raised only when an argument would
+  // exceed 2^64 (rare), so the common path is one fma, one exp2 and one add per score.
+  // Sweep 2 holds the row's log2-sum-exp as a (high, low) float pair.
+  float off[2][16], aux[2][16];
 #pragma unroll
   for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
       const int row = rb * kPfRowsPerWg + wave * 64 + mb * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
-      if (SWEEP == 1) { rm[mb][e] = -INFINITY; rl[mb][e] = 0.f; }
+      if (SWEEP == 1) { off[mb][e] = -INFINITY; aux[mb][e] = 0.f; }
       else {
-        // e = exp2(c2 * s - off) with off = c2 * max + log2(sumexp); rows past the end never vote
-        float off = INFINITY;
+        float hi = INFINITY, lo = 0.f;           // rows past the end never vote: exp2(-inf) = 0
         if (row < nrows) {
           const int c = row / G, g = row % G;
           const float2 st = *reinterpret_cast<const float2*>(a.row_stats + (((size_t)b * C + c) * H + kvh * G + g) * 2);
-          off = c2 * st.x + __builtin_amdgcn_logf(st.y);   // v_log_f32 is log2
+          hi = st.x; lo = st.y;
         }
-        rm[mb][e] = off; rl[mb][e] = 0.f;
+        off[mb][e] = hi; aux[mb][e] = lo;
       }
     }
 
   // ---- K staging: thread -> (row within pass, 16-byte piece)
   const int st_row = threadIdx.x / PPR, st_piece = threadIdx.x % PPR;
-  uint4 kreg[NLD];
-  auto fetch = [&](int tile) {
+  struct KRows { uint4 v[NLD]; };
+  auto fetch = [&](int tile) -> KRows {
+    KRows r;
 #pragma unroll
     for (int it = 0; it < NLD; ++it) {
       int t = tile * kPfTile + st_row + it * RPP;
       t = min(t, Nc - 1);                                     // the last tile may be ragged: shadow the last token
       const int page = a.page_indices[indptr + (t >> a.p_shift)];
       const uint8_t* kp = a.k_pool + ((((size_t)page << a.p_shift) + (t & (a.P - 1))) * a.H_kv + kvh) * RBYTES + st_piece * 16;
-      kreg[it] = *reinterpret_cast<const uint4*>(kp);
+      r.v[it] = *reinterpret_cast<const uint4*>(kp);
     }
+    return r;
   };
-  auto stage = [&](int buf) {
+  auto stage = [&](int buf, const KRows& r) {
 #pragma unroll
     for (int it = 0; it < NLD; ++it)
-      *reinterpret_cast<uint4*>(&s_k[buf][(st_row + it * RPP) * LROW + st_piece * 16]) = kreg[it];
+      *reinterpret_cast<uint4*>(&s_k[buf][(st_row + it * RPP) * LROW + st_piece * 16]) = r.v[it];
   };
 
+  KRows kreg;
+#pragma unroll
+  for (int it = 0; it < NLD; ++it) kreg.v[it] = make_uint4(0, 0, 0, 0);
   if (tile_begin < tile_end) {
-    fetch(tile_begin);
-    stage(0);
-    if (tile_begin + 1 < tile_end) fetch(tile_begin + 1);
+    stage(0, fetch(tile_begin));
+    if (tile_begin + 1 < tile_end) kreg = fetch(tile_begin + 1);
   }
   __syncthreads();
 
@@ -131,65 +138,60 @@ __global__ __launch_bounds__(256) void prefill_qk_kernel(PrefillArgs a) {
 
   for (int tile = tile_begin; tile < tile_end; ++tile) {
     const int buf = (tile - tile_begin) & 1;
-    if (tile + 1 < tile_end) stage(buf ^ 1);                 // rows fetched during the previous iteration
-    if (tile + 2 < tile_end) fetch(tile + 2);
+    if (tile + 1 < tile_end) stage(buf ^ 1, kreg);           // rows fetched during the previous iteration
+    if (tile + 2 < tile_end) kreg = fetch(tile + 2);
 
-    f32x16_t acc[2][2];
+    const int t_base = tile * kPfTile;
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
+    for (int nb = 0; nb < 2; ++nb) {
+      f32x16_t acc[2];
 #pragma unroll
-      for (int nb = 0; nb < 2; ++nb)
+      for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc[mb][nb][e] = 0.f;
+        for (int e = 0; e < 16; ++e) acc[mb][e] = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-#pragma unroll
-      for (int nb = 0; nb < 2; ++nb) {
+      for (int ks = 0; ks < KS; ++ks) {
         // B[k][n] = K[token n][d k]: lane holds token n = col, d = 16 * ks + 8 * half .. + 8
         const uint4 bv = *reinterpret_cast<const uint4*>(&s_k[buf][(nb * 32 + col) * LROW + (ks * 2 + half) * 16]);
         const bf16x8_t bfrag = __builtin_bit_cast(bf16x8_t, bv);
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
-          acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[mb][ks], bfrag, acc[mb][nb], 0, 0, 0);
+          acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[mb][ks], bfrag, acc[mb], 0, 0, 0);
       }
-    }
-
-    const int t_base = tile * kPfTile;
-    if (SWEEP == 1) {
-#pragma unroll
-      for (int nb = 0; nb < 2; ++nb) {
-        const bool cvalid = (t_base + nb * 32 + col) < Nc;
-        bool grow = false;
+      const bool cvalid = (t_base + nb * 32 + col) < Nc;
+      if (SWEEP == 1) {
+        float ar[2][16];
+        float amax = -INFINITY;
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) grow |= cvalid && (acc[mb][nb][e] > rm[mb][e]);
-        if (__builtin_amdgcn_ballot_w64(grow) != 0) {          // rare after the first tiles
+          for (int e = 0; e < 16; ++e) {
+            const float v = cvalid ? fmaf(c2, acc[mb][e], -off[mb][e]) : -INFINITY;   // +inf while off is unset
+            ar[mb][e] = v;
+            amax = fmaxf(amax, v);
+          }
+        if (__builtin_amdgcn_ballot_w64(amax > 64.f) != 0) {   // first column of a lane, or a score far above the reference
 #pragma unroll
           for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-              const float x = cvalid ? acc[mb][nb][e] : -INFINITY;
-              const float mn = fmaxf(rm[mb][e], x);
-              rl[mb][e] = (rm[mb][e] == -INFINITY) ? 0.f : rl[mb][e] * __builtin_amdgcn_exp2f(c2 * (rm[mb][e] - mn));
-              rm[mb][e] = mn;
-            }
+            for (int e = 0; e < 16; ++e)
+              if (ar[mb][e] > 64.f) {
+                const float noff = c2 * acc[mb][e];
+                aux[mb][e] = (off[mb][e] == -INFINITY) ? 0.f : aux[mb][e] * __builtin_amdgcn_exp2f(off[mb][e] - noff);
+                off[mb][e] = noff;
+                ar[mb][e] = 0.f;
+              }
         }
-        if (cvalid) {
 #pragma unroll
-          for (int mb = 0; mb < 2; ++mb)
+        for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) rl[mb][e] += __builtin_amdgcn_exp2f(c2 * (acc[mb][nb][e] - rm[mb][e]));
-        }
-      }
-    } else {
-#pragma unroll
-      for (int nb = 0; nb < 2; ++nb) {
+          for (int e = 0; e < 16; ++e) aux[mb][e] += __builtin_amdgcn_exp2f(ar[mb][e]);
+      } else {
         float cs = 0.f;
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) cs += __builtin_amdgcn_exp2f(fmaf(c2, acc[mb][nb][e], -rm[mb][e]));
+          for (int e = 0; e < 16; ++e) cs += __builtin_amdgcn_exp2f(fmaf(c2, acc[mb][e], -off[mb][e]) - aux[mb][e]);
         cs += __shfl_xor(cs, 32);                              // the other 16 rows of each block
         if (half == 0) s_col[buf][wave][nb * 32 + col] = cs;
       }
@@ -202,31 +204,31 @@ __global__ __launch_bounds__(256) void prefill_qk_kernel(PrefillArgs a) {
   }
 
   if (SWEEP == 1) {
-    // a row's statistics are spread over the 32 lanes of its half-wave (one column each): merge them
+    // a row's sums are spread over the 32 lanes of its half-wave (one column each): merge them
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        float m = rm[mb][e], l = rl[mb][e];
+        float m = off[mb][e], l = aux[mb][e];
 #pragma unroll
-        for (int off = 1; off < 32; off <<= 1) {
-          const float mo = __shfl_xor(m, off), lo = __shfl_xor(l, off);
+        for (int o = 1; o < 32; o <<= 1) {
+          const float mo = __shfl_xor(m, o), lo = __shfl_xor(l, o);
           const float mn = fmaxf(m, mo);
-          const float la = (m == -INFINITY) ? 0.f : l * __builtin_amdgcn_exp2f(c2 * (m - mn));
-          const float lb = (mo == -INFINITY) ? 0.f : lo * __builtin_amdgcn_exp2f(c2 * (mo - mn));
+          const float la = (m == -INFINITY) ? 0.f : l * __builtin_amdgcn_exp2f(m - mn);
+          const float lb = (mo == -INFINITY) ? 0.f : lo * __builtin_amdgcn_exp2f(mo - mn);
           m = mn; l = la + lb;
         }
         const int row = rb * kPfRowsPerWg + wave * 64 + mb * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
         if (col == 0 && row < nrows) {
           const int c = row / G, g = row % G;
           float* pp = a.stat_part + ((((size_t)b * a.TS + split) * C + c) * H + kvh * G + g) * 2;
-          pp[0] = m; pp[1] = l;
+          pp[0] = m; pp[1] = l;                                // (reference exponent, sum of exp2(arg - reference))
         }
       }
   }
 }
 
-// row_stats[b][c][h] = merge over the token splits of the sweep-1 partials
+// row_stats[b][c][h] = log2 sum_t exp2(c2 * s_t) as a (high, low) float pair, from the splits' partials
 __global__ __launch_bounds__(256) void prefill_stats_merge_kernel(PrefillArgs a) {
   const int i = blockIdx.x * 256 + threadIdx.x;          // (b, c, h) flattened
   const int n = a.B * a.C * a.H;
@@ -234,14 +236,15 @@ __global__ __launch_bounds__(256) void prefill_stats_merge_kernel(PrefillArgs a)
   const int b = i / (a.C * a.H), ch = i % (a.C * a.H);
   float m = -INFINITY;
   for (int s = 0; s < a.TS; ++s) m = fmaxf(m, a.stat_part[(((size_t)b * a.TS + s) * a.C * a.H + ch) * 2]);
-  const double sc = (double)a.scale;
   double l = 0.0;
   for (int s = 0; s < a.TS; ++s) {
     const float2 v = *reinterpret_cast<const float2*>(a.stat_part + (((size_t)b * a.TS + s) * a.C * a.H + ch) * 2);
-    if (v.x != -INFINITY) l += (double)v.y * exp_f64(sc * ((double)v.x - (double)m));
+    if (v.x != -INFINITY) l += (double)v.y * exp_f64(0.69314718055994530942 * ((double)v.x - (double)m));
   }
-  a.row_stats_out[(size_t)i * 2] = m;
-  a.row_stats_out[(size_t)i * 2 + 1] = (float)l;
+  const double lse2 = (m == -INFINITY) ? -INFINITY : (double)m + log2(l);
+  const float hi = (float)lse2;
+  a.row_stats_out[(size_t)i * 2] = hi;
+  a.row_stats_out[(size_t)i * 2 + 1] = (m == -INFINITY) ? 0.f : (float)(lse2 - (double)hi);
 }
 
 // votes[b][t] = sum over the (row block, KV head) partial vote vectors, double accumulation
