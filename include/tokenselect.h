@@ -122,7 +122,11 @@ int32_t ts_selcache_check(const ts_problem* p, const void* q, void* cached_q, ui
  * over j < count[b]; float accumulation, result rounded to p->dtype.  idx [device] int32 [B][k]
  * (logical token ids, k = idx_stride); count [device] int32 [B]; out [device] [B][C][H][D];
  * lse [device] float [B][C][H] or NULL (log-sum-exp of the scaled logits).  count[b] == 0 gives
- * out = 0 and lse = -inf. */
+ * out = 0 and lse = -inf.
+ * Chunk form (chunk = C > 1, bf16): query c of the chunk (logical token N_b - C + c) attends over the
+ * count[b] selected tokens and the chunk's own tokens 0..c in one joint softmax (Eq. 2's
+ * [K_select, K_current] with a causal mask inside the chunk); the weights that multiply V are rounded
+ * to bf16 (matrix-core operand). */
 int32_t ts_sparse_paged_attn(const ts_problem* p, const void* q, const int32_t* idx, int32_t idx_stride,
                              const int32_t* count, float sm_scale, void* out, float* lse, void* ws,
                              size_t ws_bytes, void* stream);

@@ -212,10 +212,21 @@ int32_t ts_sparse_paged_attn(const ts_problem* p, const void* q, const int32_t* 
   if (q == nullptr || idx == nullptr || count == nullptr || out == nullptr || idx_stride < 1) return TS_ERR_INVALID_ARG;
   if (p->k_pool == nullptr || p->v_pool == nullptr) return TS_ERR_INVALID_ARG;
   if (!(sm_scale == sm_scale)) return TS_ERR_INVALID_ARG;
-  if (p->chunk != 1) return TS_ERR_UNSUPPORTED;
   const WsLayout w = ws_layout(p, idx_stride);
-  if (w.attn_nsplit > kAttnMaxSplit) return TS_ERR_UNSUPPORTED;
   if (ws == nullptr || ((uintptr_t)ws & 255) != 0 || ws_bytes < w.total) return TS_ERR_WORKSPACE;
+  if (p->chunk > 1) {
+    if (p->dtype != TS_BF16) return TS_ERR_UNSUPPORTED;
+    ChunkAttnArgs c{};
+    c.q = (const uint8_t*)q; c.k_pool = (const uint8_t*)p->k_pool; c.v_pool = (const uint8_t*)p->v_pool;
+    c.page_indptr = p->page_indptr; c.page_indices = p->page_indices; c.seq_lens = p->seq_lens;
+    c.idx = idx; c.count = count; c.slots = (int32_t*)((uint8_t*)ws + w.attn_slots);
+    c.out = (uint8_t*)out; c.lse = lse;
+    c.C = p->chunk; c.H = p->num_q_heads; c.H_kv = p->num_kv_heads; c.G = p->num_q_heads / p->num_kv_heads;
+    c.D = p->head_dim; c.P = p->page_size; c.p_shift = ilog2(p->page_size); c.idx_stride = idx_stride;
+    c.max_seq_len = p->max_seq_len; c.sm_scale = sm_scale;
+    return launch_sparse_attn_chunk(c, p->batch, (hipStream_t)stream) == hipSuccess ? TS_OK : TS_ERR_HIP;
+  }
+  if (w.attn_nsplit > kAttnMaxSplit) return TS_ERR_UNSUPPORTED;
   AttnArgs a{};
   a.q = (const uint8_t*)q; a.k_pool = (const uint8_t*)p->k_pool; a.v_pool = (const uint8_t*)p->v_pool;
   a.page_indptr = p->page_indptr; a.page_indices = p->page_indices; a.seq_lens = p->seq_lens;

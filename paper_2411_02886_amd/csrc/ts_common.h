@@ -26,6 +26,7 @@ struct WsLayout {
   size_t attn_ml;          // float [B][H][nsplit][2]
   size_t pf_stat_part;     // float [B][TS][C][H][2]            (chunk > 1 only)
   size_t pf_vote_part;     // float [B][RB * H_kv][max_seq_len] (chunk > 1 only)
+  size_t attn_slots;       // int32 [B][k + C]                  (chunk > 1 only)
   size_t total;
   int pf_rb, pf_ts;
   int topk_nblk;
@@ -63,6 +64,7 @@ inline WsLayout ws_layout(const ts_problem* p, int k) {
   // the sections that depend on k come last, so that every other offset is the same for any k
   w.attn_out = take(B * H * (size_t)w.attn_nsplit * D * 4);
   w.attn_ml = take(B * H * (size_t)w.attn_nsplit * 2 * 4);
+  if (p->chunk > 1) w.attn_slots = take(B * ((size_t)k + p->chunk) * 4);
   w.total = off;
   return w;
 }

@@ -94,6 +94,24 @@ struct PrefillArgs {
 hipError_t launch_prefill_stats(const PrefillArgs& a, hipStream_t s);
 hipError_t launch_prefill_votes(const PrefillArgs& a, hipStream_t s);
 
+// chunk-form sparse attention
+struct ChunkAttnArgs {
+  const uint8_t* q;          // [B][C][H][D] bf16
+  const uint8_t* k_pool;
+  const uint8_t* v_pool;
+  const int32_t* page_indptr;
+  const int32_t* page_indices;
+  const int32_t* seq_lens;
+  const int32_t* idx;
+  const int32_t* count;
+  int32_t* slots;            // [B][idx_stride + C] physical slots of the key list
+  uint8_t* out;              // [B][C][H][D] bf16
+  float* lse;                // [B][C][H] or null
+  int C, H, H_kv, G, D, P, p_shift, idx_stride, max_seq_len;
+  float sm_scale;
+};
+hipError_t launch_sparse_attn_chunk(const ChunkAttnArgs& a, int B, hipStream_t s);
+
 // variant: 0 = fma arithmetic, 1 = packed bf16 dot2 (bf16 only)
 hipError_t launch_score_decode(int dtype, int D, int G, int variant, const ScoreArgs& a, dim3 grid, size_t lds, hipStream_t s);
 hipError_t launch_soft_vote(const VoteArgs& a, int B, hipStream_t s);

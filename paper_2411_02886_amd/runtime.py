@@ -121,6 +121,8 @@ class ChunkSelector:
         self.votes = torch.zeros((B, M), dtype=torch.float32, device=device)
         self.idx = torch.full((B, k), -1, dtype=torch.int32, device=device)
         self.count = torch.zeros((B,), dtype=torch.int32, device=device)
+        self.out = torch.zeros((B, C, H, D), dtype=torch.int16, device=device)
+        self.lse = torch.empty((B, C, H), dtype=torch.float32, device=device)
         nbytes = ts.ts_workspace_bytes(self.problem, k)
         self.ws = torch.empty((nbytes + 255) // 256 * 64, dtype=torch.int32, device=device)
         ts.ts_workspace_init(self.ws)
@@ -134,3 +136,7 @@ class ChunkSelector:
         ts.ts_chunk_row_stats(self.problem, q, score_scale, self.row_stats, self.ws)
         ts.ts_chunk_soft_vote(self.problem, q, self.row_stats, score_scale, self.votes, self.ws)
         ts.ts_topk(self.problem, self.votes, self.k, self.idx, self.count, None, self.ws)
+
+    def attend(self, q, sm_scale=None):
+        sm = sm_scale if sm_scale is not None else 1.0 / float(np.sqrt(self.D))
+        ts.ts_sparse_paged_attn(self.problem, q, self.idx, self.k, self.count, sm, self.out, self.lse, self.ws)

@@ -27,18 +27,30 @@ def run_chunk_selection(ts, w, k, scale):
     sel = ChunkSelector.from_workload(w, k=k)
     q = to_device(w.q)
     sel.select(q, scale)
+    sel.attend(q)
     torch.cuda.synchronize()
-    return (to_host(sel.row_stats), to_host(sel.votes), to_host(sel.idx), to_host(sel.count))
+    return (to_host(sel.row_stats), to_host(sel.votes), to_host(sel.idx), to_host(sel.count),
+            to_host(sel.out, bits16=True), to_host(sel.lse))
 
 
 def check_chunk(ts, w, k, scale, label):
-    st_g, v_g, idx_g, cnt_g = run_chunk_selection(ts, w, k, scale)
+    st_g, v_g, idx_g, cnt_g, out_g, lse_g_attn = run_chunk_selection(ts, w, k, scale)
+    sm = float(np.float32(1.0 / math.sqrt(w.D)))
     c = float(np.float32(scale))
     for b in range(w.B):
         Nc = int(w.seq_lens[b]) - w.C
         lab = "%s b=%d Nc=%d" % (label, b, Nc)
         if Nc <= 0:
             assert cnt_g[b] == 0 and np.all(idx_g[b] == -1), lab
+        # Eq. 2, chunk form: query c over the selected tokens plus the chunk's tokens 0..c (one softmax)
+        for ci in sorted(set([0, 1, w.C // 2, w.C - 1]) if w.C > 8 else range(w.C)):
+            o_ref, l_ref = oracle.sparse_attn(np.ascontiguousarray(w.q[b, ci]), w.k_pool, w.v_pool, w.dtype, w.H_kv, w.P,
+                                              w.pages_of(b), idx_g[b], int(cnt_g[b]), sm, extra_first=max(Nc, 0),
+                                              n_extra=ci + 1, with_lse=True)
+            err = np.abs(W.as_f32(out_g[b, ci], w.dtype).astype(np.float64) - o_ref).max()
+            assert err <= 2e-2, (lab, "chunk attention", ci, err)
+            assert np.abs(lse_g_attn[b, ci] - l_ref).max() <= 2e-2, (lab, "chunk attention lse", ci)
+        if Nc <= 0:
             continue
         votes = np.zeros(Nc)
         smax = 0.0
