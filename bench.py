@@ -37,8 +37,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4],
-                    help="2 (default) is the headline workload; 3 is the Selection Cache decode run")
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5],
+                    help="2 (default) is the headline workload; 3 is the Selection Cache decode run; 5 is chunked prefill")
     ap.add_argument("--pools", type=int, default=0, help="physical pool copies to rotate over (0 = enough for >= 2 GiB)")
     ap.add_argument("--variant", type=int, default=-1, help="score-pass arithmetic: 0 fma, 1 bf16 dot2, -1 library default")
     ap.add_argument("--score-wg", type=int, default=0)
@@ -125,6 +125,52 @@ def selection_cache_run(args):
     print(json.dumps(res))
 
 
+def chunked_prefill_run(args):
+    """Configuration 5: one chunked-prefill step = two MFMA score sweeps (row log-sum-exps, votes summed over
+    heads and over the chunk's 512 queries), shared top-k of 4096, chunk-form sparse attention."""
+    import torch
+    import workloads as W
+    import paper_2411_02886_amd as ts
+    from paper_2411_02886_amd.runtime import ChunkSelector, to_device
+    w = W.config5()
+    N = int(w.extra["n_cached"])
+    sel = ChunkSelector.from_workload(w)
+    q = to_device(w.q)
+    names = ["row_stats", "soft_vote", "topk", "attention"]
+    calls = [lambda: ts.ts_chunk_row_stats(sel.problem, q, 1.0, sel.row_stats, sel.ws),
+             lambda: ts.ts_chunk_soft_vote(sel.problem, q, sel.row_stats, 1.0, sel.votes, sel.ws),
+             lambda: ts.ts_topk(sel.problem, sel.votes, sel.k, sel.idx, sel.count, None, sel.ws),
+             lambda: sel.attend(q)]
+    steps = max(1, min(args.steps, 50)); warm = max(1, min(args.warmup, 5))
+    for _ in range(warm):
+        for f in calls:
+            f()
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(calls) + 1)] for _ in range(steps)]
+    t0 = time.perf_counter()
+    for s in range(steps):
+        ev[s][0].record()
+        for i, f in enumerate(calls):
+            f(); ev[s][i + 1].record()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    per = np.array([[ev[s][i].elapsed_time(ev[s][i + 1]) for i in range(len(calls))] for s in range(steps)]).mean(axis=0)
+    flop = 2.0 * w.C * w.H * w.D * N                                     # one sweep of Q K^T
+    peak = 2500.0
+    tf = flop / (per[1] * 1e-3) / 1e12
+    res = {"metric": "query-token pairs/s of one chunked-prefill step (2 score sweeps + top-k + chunk attention)",
+           "value": w.C * N / dt, "unit": "pairs/s", "n_gpus": 1, "steps": steps, "warmup": warm, "ms_per_step": dt * 1e3,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": w.name, "chunk": w.C, "cached_tokens": N, "num_q_heads": w.H, "num_kv_heads": w.H_kv,
+                      "head_dim": w.D, "k": w.k, "score_scale": 1.0},
+           "ms_per_call": dict(zip(names, [float(x) for x in per])),
+           "roofline": {"bound": "mfma", "kernel": "ts::prefill_qk_kernel<128, 2> (vote sweep of ts_chunk_soft_vote)",
+                        "achieved": tf, "peak": peak, "unit": "TFLOP/s", "frac": tf / peak, "traffic": None,
+                        "flop_per_launch": flop, "exp_per_launch": float(w.C) * w.H * N,
+                        "stats_sweep_tflops": flop / (per[0] * 1e-3) / 1e12}}
+    print(json.dumps(res))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -133,6 +179,8 @@ def main():
         sys.exit(2)
     if args.config == 3:
         return selection_cache_run(args)
+    if args.config == 5:
+        return chunked_prefill_run(args)
     import torch
     import workloads as W
     import paper_2411_02886_amd as ts

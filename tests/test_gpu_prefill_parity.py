@@ -98,3 +98,50 @@ def test_chunk_selection_ragged_batch(gpu):
     w = W.make_workload("chunkb", dtype=W.BF16, B=len(lens), C=C, H=8, H_kv=2, D=128, P=16, seq_lens=lens, k=40, seed=3)
     print("chunk ragged batch", lens, flush=True)
     check_chunk(gpu, w, 40, 0.0884, "ragged")
+
+
+@pytest.mark.timeout(900)
+def test_config5_full_size_sampled(gpu):
+    """Configuration 5 at full size (512 queries x 262144 cached tokens).  The oracle needs minutes for all
+    16384 softmax rows, so the check is on samples: (a) the log-sum-exp of every head of 6 sampled queries
+    against the oracle; (b) the votes of 768 sampled tokens (the GPU's top 256, the first 256 below its
+    threshold, 256 random) recomputed in double from oracle-style scores and the row log-sum-exps;
+    (c) the radix select on the GPU's votes, exact; (d) chunk attention of 3 sampled queries."""
+    from paper_2411_02886_amd.runtime import ChunkSelector, to_device, to_host
+    w = W.config5()
+    N = int(w.extra["n_cached"]); C, H, G, D = w.C, w.H, w.G, w.D
+    print("cfg5 full size: generating done", flush=True)
+    sel = ChunkSelector.from_workload(w)
+    q = to_device(w.q)
+    sel.select(q, 1.0); sel.attend(q)
+    torch.cuda.synchronize()
+    st = to_host(sel.row_stats)[0]; v_g = to_host(sel.votes)[0, :N]; idx_g = to_host(sel.idx)[0]; cnt_g = int(to_host(sel.count)[0])
+    out_g = to_host(sel.out, bits16=True)[0]
+    lse2 = st[..., 0].astype(np.float64) + st[..., 1]                     # [C][H] base-2 log-sum-exp
+    rng = np.random.default_rng(55)
+    # (a) sampled rows
+    for ci in sorted(rng.choice(C, size=6, replace=False).tolist()):
+        S = oracle.paged_qk_scores(np.ascontiguousarray(w.q[0, ci]), w.k_pool, w.dtype, w.H_kv, w.P, w.pages_of(0), N)
+        _, m, z = oracle.soft_vote(S, 1.0, with_stats=True)
+        assert np.abs(lse2[ci] * math.log(2.0) - (m + np.log(z))).max() <= 8 * ulp32(float(np.abs(S).max())) + 2e-5, ci
+    print("cfg5 rows ok", flush=True)
+    # (c) radix select alone
+    i_iso, c_iso = oracle.topk(v_g.astype(np.float64), w.k)
+    assert cnt_g == c_iso and np.array_equal(idx_g, i_iso)
+    # (b) sampled tokens
+    order = np.argsort(-v_g, kind="stable")
+    sample = np.unique(np.concatenate([order[:256], order[w.k:w.k + 256], rng.choice(N, size=256, replace=False)]))
+    slots = w.slots_of(0)[sample]
+    Ks = W.as_f32(w.k_pool, w.dtype).reshape(-1, w.H_kv, D)[slots].astype(np.float64)      # [T][H_kv][D]
+    Q = W.as_f32(w.q, w.dtype)[0].astype(np.float64)                                       # [C][H][D]
+    S = np.einsum("chd,thd->cht", Q, np.repeat(Ks, G, axis=1))                             # [C][H][T]
+    votes_ref = np.exp(S - (lse2 * math.log(2.0))[:, :, None]).sum(axis=(0, 1))
+    np.testing.assert_allclose(v_g[sample], votes_ref, rtol=3e-5, atol=1e-30)
+    assert abs(float(v_g.astype(np.float64).sum()) - C * H) < 1e-4 * C * H
+    print("cfg5 votes ok", flush=True)
+    # (d) chunk attention
+    sm = float(np.float32(1.0 / math.sqrt(D)))
+    for ci in (0, 257, C - 1):
+        o_ref = oracle.sparse_attn(np.ascontiguousarray(w.q[0, ci]), w.k_pool, w.v_pool, w.dtype, w.H_kv, w.P, w.pages_of(0),
+                                   idx_g, cnt_g, sm, extra_first=N, n_extra=ci + 1)
+        assert np.abs(W.as_f32(out_g[ci], w.dtype).astype(np.float64) - o_ref).max() <= 2e-2, ci
