@@ -38,7 +38,8 @@ __device__ __forceinline__ bool pf_decode_block(const PrefillArgs& a, int* rb, i
 }
 
 template <int D, int SWEEP>
-__global__ __launch_bounds__(256) void prefill_qk_kernel(PrefillArgs a) {
+// two workgroups per CU (256 registers per lane): with one the pipeline below has no second wave to hide behind
+__global__ __launch_bounds__(256, 2) void prefill_qk_kernel(PrefillArgs a) {
   constexpr int KS = D / 16;                    // MFMA k-steps
   constexpr int RBYTES = D * 2;                 // bytes per K row
   constexpr int PPR = RBYTES / 16;              // 16-byte pieces per row
@@ -46,7 +47,7 @@ __global__ __launch_bounds__(256) void prefill_qk_kernel(PrefillArgs a) {
   constexpr int NLD = kPfTile / RPP;            // staging loads per thread per tile
   constexpr int LROW = RBYTES + 16;             // padded LDS row
   __shared__ __attribute__((aligned(16))) uint8_t s_k[2][kPfTile * LROW];
-  __shared__ float s_col[2][4][kPfTile];
+  __shared__ float s_col[3][4][kPfTile];
 
   int rb, b, kvh, split;
   if (!pf_decode_block(a, &rb, &b, &kvh, &split)) return;
@@ -85,7 +86,7 @@ __global__ __launch_bounds__(256) void prefill_qk_kernel(PrefillArgs a) {
   // Sweep 1 keeps, per lane and row, a reference exponent `off` (log2 units) and the sum of
   // exp2(c2 * s - off) over the lane's columns; the reference is raised only when an argument would
   // exceed 2^64 (rare), so the common path is one fma, one exp2 and one add per score.
-  // Sweep 2 holds the row's log2-sum-exp as a (high, low) float pair.
+  // Sweep 2 holds the row's log2-sum-exp: the high float as the exponent offset, 2^-low as a weight.
   float off[2][16], aux[2][16];
 #pragma unroll
   for (int mb = 0; mb < 2; ++mb)
@@ -100,7 +101,7 @@ __global__ __launch_bounds__(256) void prefill_qk_kernel(PrefillArgs a) {
           const float2 st = *reinterpret_cast<const float2*>(a.row_stats + (((size_t)b * C + c) * H + kvh * G + g) * 2);
           hi = st.x; lo = st.y;
         }
-        off[mb][e] = hi; aux[mb][e] = lo;
+        off[mb][e] = hi; aux[mb][e] = __builtin_amdgcn_exp2f(-lo);   // |lo| < 2^-17: the factor 2^-lo, exact to an ulp
       }
     }
 
@@ -136,71 +137,89 @@ __global__ __launch_bounds__(256) void prefill_qk_kernel(PrefillArgs a) {
 
   float* vout = (SWEEP == 2) ? a.vote_part + ((size_t)b * a.RB * a.H_kv + (size_t)rb * a.H_kv + kvh) * a.max_seq_len : nullptr;
 
-  for (int tile = tile_begin; tile < tile_end; ++tile) {
-    const int buf = (tile - tile_begin) & 1;
-    if (tile + 1 < tile_end) stage(buf ^ 1, kreg);           // rows fetched during the previous iteration
-    if (tile + 2 < tile_end) kreg = fetch(tile + 2);
-
-    const int t_base = tile * kPfTile;
+  // one 64-row x 32-token block on the matrix cores
+  auto mfma_block = [&](int buf, int nb, f32x16_t (&acc)[2]) {
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-      f32x16_t acc[2];
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[mb][e] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      // B[k][n] = K[token n][d k]: lane holds token n = col, d = 16 * ks + 8 * half .. + 8
+      const uint4 bv = *reinterpret_cast<const uint4*>(&s_k[buf][(nb * 32 + col) * LROW + (ks * 2 + half) * 16]);
+      const bf16x8_t bfrag = __builtin_bit_cast(bf16x8_t, bv);
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+        acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[mb][ks], bfrag, acc[mb], 0, 0, 0);
+    }
+  };
+  // the softmax arithmetic of one block on the vector ALU
+  auto softmax_block = [&](const f32x16_t (&acc)[2], int tile, int nb, int cbuf) {
+    const bool cvalid = (tile * kPfTile + nb * 32 + col) < Nc;
+    if (SWEEP == 1) {
+      float ar[2][16];
+      float amax = -INFINITY;
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc[mb][e] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        // B[k][n] = K[token n][d k]: lane holds token n = col, d = 16 * ks + 8 * half .. + 8
-        const uint4 bv = *reinterpret_cast<const uint4*>(&s_k[buf][(nb * 32 + col) * LROW + (ks * 2 + half) * 16]);
-        const bf16x8_t bfrag = __builtin_bit_cast(bf16x8_t, bv);
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-          acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[mb][ks], bfrag, acc[mb], 0, 0, 0);
-      }
-      const bool cvalid = (t_base + nb * 32 + col) < Nc;
-      if (SWEEP == 1) {
-        float ar[2][16];
-        float amax = -INFINITY;
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const float v = cvalid ? fmaf(c2, acc[mb][e], -off[mb][e]) : -INFINITY;   // +inf while off is unset
-            ar[mb][e] = v;
-            amax = fmaxf(amax, v);
-          }
-        if (__builtin_amdgcn_ballot_w64(amax > 64.f) != 0) {   // first column of a lane, or a score far above the reference
-#pragma unroll
-          for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-            for (int e = 0; e < 16; ++e)
-              if (ar[mb][e] > 64.f) {
-                const float noff = c2 * acc[mb][e];
-                aux[mb][e] = (off[mb][e] == -INFINITY) ? 0.f : aux[mb][e] * __builtin_amdgcn_exp2f(off[mb][e] - noff);
-                off[mb][e] = noff;
-                ar[mb][e] = 0.f;
-              }
+        for (int e = 0; e < 16; ++e) {
+          const float v = cvalid ? fmaf(c2, acc[mb][e], -off[mb][e]) : -INFINITY;   // +inf while off is unset
+          ar[mb][e] = v;
+          amax = fmaxf(amax, v);
         }
+      if (__builtin_amdgcn_ballot_w64(amax > 64.f) != 0) {   // first column of a lane, or a score far above the reference
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) aux[mb][e] += __builtin_amdgcn_exp2f(ar[mb][e]);
-      } else {
-        float cs = 0.f;
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) cs += __builtin_amdgcn_exp2f(fmaf(c2, acc[mb][e], -off[mb][e]) - aux[mb][e]);
-        cs += __shfl_xor(cs, 32);                              // the other 16 rows of each block
-        if (half == 0) s_col[buf][wave][nb * 32 + col] = cs;
+          for (int e = 0; e < 16; ++e)
+            if (ar[mb][e] > 64.f) {
+              const float noff = c2 * acc[mb][e];
+              aux[mb][e] = (off[mb][e] == -INFINITY) ? 0.f : aux[mb][e] * __builtin_amdgcn_exp2f(off[mb][e] - noff);
+              off[mb][e] = noff;
+              ar[mb][e] = 0.f;
+            }
       }
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) aux[mb][e] += __builtin_amdgcn_exp2f(ar[mb][e]);
+    } else {
+      float cs = 0.f;
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) cs = fmaf(__builtin_amdgcn_exp2f(fmaf(c2, acc[mb][e], -off[mb][e])), aux[mb][e], cs);
+      cs += __shfl_xor(cs, 32);                              // the other 16 rows of each block
+      if (half == 0) s_col[cbuf][wave][nb * 32 + col] = cs;
     }
-    __syncthreads();
+  };
+  auto write_votes = [&](int tile, int cbuf) {
     if (SWEEP == 2 && threadIdx.x < kPfTile) {
-      const int t = t_base + threadIdx.x;
-      if (t < Nc) vout[t] = (s_col[buf][0][threadIdx.x] + s_col[buf][1][threadIdx.x]) + (s_col[buf][2][threadIdx.x] + s_col[buf][3][threadIdx.x]);
+      const int t = tile * kPfTile + threadIdx.x;
+      if (t < Nc) vout[t] = (s_col[cbuf][0][threadIdx.x] + s_col[cbuf][1][threadIdx.x]) + (s_col[cbuf][2][threadIdx.x] + s_col[cbuf][3][threadIdx.x]);
     }
+  };
+
+  // Software pipeline over the blocks (tile, first half) (tile, second half) ...: the MFMAs of the next
+  // block are issued before the softmax of the current one, so the matrix cores work while the vector
+  // ALU exponentiates.  One barrier per tile publishes the staged K rows of the next tile.
+  f32x16_t acc0[2], acc1[2];
+  if (tile_begin < tile_end) mfma_block(0, 0, acc0);
+  for (int tile = tile_begin; tile < tile_end; ++tile) {
+    const int it = tile - tile_begin;
+    const int buf = it & 1, cbuf = it % 3;
+    if (tile + 1 < tile_end) stage(buf ^ 1, kreg);           // rows fetched during the previous iteration
+    if (tile + 2 < tile_end) kreg = fetch(tile + 2);
+    mfma_block(buf, 1, acc1);
+    softmax_block(acc0, tile, 0, cbuf);
+    __syncthreads();                                         // next tile's rows are staged; all waves are done with tile - 1
+    if (it > 0) write_votes(tile - 1, (it - 1) % 3);
+    if (tile + 1 < tile_end) mfma_block(buf ^ 1, 0, acc0);
+    softmax_block(acc1, tile, 1, cbuf);
+  }
+  if (tile_begin < tile_end) {
+    __syncthreads();
+    write_votes(tile_end - 1, (tile_end - 1 - tile_begin) % 3);
   }
 
   if (SWEEP == 1) {

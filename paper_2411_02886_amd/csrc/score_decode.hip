@@ -187,7 +187,9 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
         const float x[4] = {v4.x, v4.y, v4.z, v4.w};
         float* dst = a.scores + ((size_t)b * a.max_seq_len + t) * H + h_base + e_hq * 4;
         if (a.vec_store) {
-          *reinterpret_cast<float4*>(dst) = v4;
+          typedef float v4f __attribute__((ext_vector_type(4)));
+          const v4f sv = {v4.x, v4.y, v4.z, v4.w};
+          __builtin_nontemporal_store(sv, reinterpret_cast<v4f*>(dst));   // streamed out; the vote kernel reads it from HBM anyway
         } else {
 #pragma unroll
           for (int c = 0; c < 4; ++c)
