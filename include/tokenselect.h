@@ -152,8 +152,11 @@ int32_t ts_chunk_soft_vote(const ts_problem* p, const void* q, const float* row_
 /* Tuning knob for benchmarks and tests (process-wide, not thread-safe, not part of the method):
  * variant 0 = score pass with fma arithmetic, 1 = packed bf16 dot2 arithmetic (bf16 inputs only; the
  * default for bf16: same measured accuracy, fewer registers);
- * wg = workgroups per sequence in the score pass, 0 = automatic.  Host only. */
-int32_t ts_debug_set_score_variant(int32_t variant, int32_t wg);
+ * wg = workgroups per sequence in the score pass, 0 = automatic;
+ * run_tiles = 32-token tiles a wave stages in LDS before it writes their scores as one run: 1, 2, 4,
+ * or 0 = automatic (longer runs for longer sequences).  Results do not depend on wg or run_tiles.
+ * Host only. */
+int32_t ts_debug_set_score_variant(int32_t variant, int32_t wg, int32_t run_tiles);
 
 #ifdef __cplusplus
 }

@@ -70,7 +70,7 @@ def load():
         L.ts_sparse_paged_attn.argtypes = [pp, vp, vp, i32, vp, f32, vp, vp, vp, sz, vp]
         L.ts_chunk_row_stats.argtypes = [pp, vp, f32, vp, vp, sz, vp]
         L.ts_chunk_soft_vote.argtypes = [pp, vp, vp, f32, vp, vp, sz, vp]
-        L.ts_debug_set_score_variant.argtypes = [i32, i32]
+        L.ts_debug_set_score_variant.argtypes = [i32, i32, i32]
         for name in ("ts_workspace_bytes", "ts_workspace_init", "ts_paged_qk_scores", "ts_soft_vote", "ts_topk",
                      "ts_selcache_check", "ts_sparse_paged_attn", "ts_debug_set_score_variant", "ts_chunk_row_stats",
                      "ts_chunk_soft_vote"):
@@ -126,8 +126,8 @@ def ts_workspace_init(ws, stream=None) -> None:
     _ok(load().ts_workspace_init(_ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "ts_workspace_init")
 
 
-def ts_debug_set_score_variant(variant: int, wg: int = 0) -> None:
-    _ok(load().ts_debug_set_score_variant(int(variant), int(wg)), "ts_debug_set_score_variant")
+def ts_debug_set_score_variant(variant: int, wg: int = 0, run_tiles: int = 0) -> None:
+    _ok(load().ts_debug_set_score_variant(int(variant), int(wg), int(run_tiles)), "ts_debug_set_score_variant")
 
 
 def _nbytes(ws) -> int:

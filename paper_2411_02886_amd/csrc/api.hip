@@ -9,13 +9,41 @@ __global__ void fill_zero_kernel(uint32_t* p, size_t n) {
 
 static int g_score_variant = 1;   // 0 = fma, 1 = packed bf16 dot2 (tuning knob, see ts_debug_set_score_variant)
 static int g_score_wg = 0;        // 0 = automatic
+static int g_score_rr = 0;        // tiles per staged run; 0 = automatic
 
 // workgroups per sequence of the score pass (also the number of statistics partials it leaves)
+// Tiles a wave of the score pass stages before writing them out: longer runs make the score stores
+// fewer, larger bursts (a write stream mixed into the K read stream is what costs bandwidth), but every
+// wave of the machine should still get a run of its own and the staging must fit 64 KiB of LDS.
+static int score_run_tiles(const ts_problem* p) {
+  const int hb = p->num_kv_heads < 8 ? p->num_kv_heads : 8;
+  const int nu = p->num_kv_heads / hb;
+  const int hs = (hb * (p->num_q_heads / p->num_kv_heads) + 3) & ~3;
+  const long ntiles = (long)(p->max_seq_len + kScoreTileTokens - 1) / kScoreTileTokens;
+  for (int rr = 4; rr > 1; rr >>= 1) {
+    const long runs = (ntiles + rr - 1) / rr * nu * p->batch;
+    if (runs >= 4096 && (size_t)4 * rr * kScoreTileTokens * hs * sizeof(float) <= 65536) return rr;
+  }
+  return 1;
+}
+
+// run length in effect: the forced one (tuning knob) halved until its staging fits, else the automatic one
+static int score_run_tiles_eff(const ts_problem* p) {
+  if (g_score_rr <= 0) return score_run_tiles(p);
+  const int hb = p->num_kv_heads < 8 ? p->num_kv_heads : 8;
+  const int hs = (hb * (p->num_q_heads / p->num_kv_heads) + 3) & ~3;
+  int rr = g_score_rr;
+  while (rr > 1 && (size_t)4 * rr * kScoreTileTokens * hs * sizeof(float) > 65536) rr >>= 1;
+  return rr;
+}
+
 static int score_workgroups(const ts_problem* p) {
   const int hb = p->num_kv_heads < 8 ? p->num_kv_heads : 8;
   const int nu = p->num_kv_heads / hb;
-  const int ntiles = (p->max_seq_len + kScoreTileTokens - 1) / kScoreTileTokens * nu;
-  int wg = g_score_wg > 0 ? g_score_wg : (ntiles + 3) / 4;
+  const int rr = score_run_tiles_eff(p);
+  const int ntiles = (p->max_seq_len + kScoreTileTokens - 1) / kScoreTileTokens;
+  const int nruns = (ntiles + rr - 1) / rr * nu;
+  int wg = g_score_wg > 0 ? g_score_wg : (nruns + 3) / 4;
   int cap = kScoreMaxWg / (p->batch < 1 ? 1 : p->batch);
   if (cap < 64) cap = 64;
   if (g_score_wg == 0 && wg > cap) wg = cap;
@@ -83,9 +111,10 @@ int32_t ts_workspace_init(void* ws, size_t ws_bytes, void* stream) {
 /* Tuning knobs used by the benchmark and the tests to compare kernel variants; not part of the
  * method.  variant: 0 = fma arithmetic, 1 = packed bf16 dot2; wg: workgroups per sequence in the
  * score pass (0 = automatic). */
-int32_t ts_debug_set_score_variant(int32_t variant, int32_t wg) {
+int32_t ts_debug_set_score_variant(int32_t variant, int32_t wg, int32_t run_tiles) {
   if (variant < 0 || variant > 1 || wg < 0 || wg > kScoreMaxWg) return TS_ERR_INVALID_ARG;
-  g_score_variant = variant; g_score_wg = wg;
+  if (run_tiles != 0 && run_tiles != 1 && run_tiles != 2 && run_tiles != 4) return TS_ERR_INVALID_ARG;
+  g_score_variant = variant; g_score_wg = wg; g_score_rr = run_tiles;
   return TS_OK;
 }
 
@@ -111,7 +140,8 @@ int32_t ts_paged_qk_scores(const ts_problem* p, const void* q, float* scores, fl
   a.vec_store = (p->num_q_heads % 4 == 0) && ((a.HB * G) % 4 == 0) && (((uintptr_t)scores & 15) == 0);
   a.scale = score_scale; a.c2 = score_scale * 1.44269504088896340736f;
   const int wg = score_workgroups(p);
-  size_t lds = (size_t)4 * kScoreTileTokens * ((a.HB * G + 3) & ~3) * sizeof(float);
+  a.RR = score_run_tiles_eff(p);
+  size_t lds = (size_t)4 * a.RR * kScoreTileTokens * ((a.HB * G + 3) & ~3) * sizeof(float);
   if (lds < 8192) lds = 8192;   // the closing statistics exchange needs 4 x 64 x 8 floats
   const int variant = (p->dtype == TS_BF16) ? g_score_variant : 0;
   const hipError_t e = launch_score_decode(p->dtype, p->head_dim, G, variant, a, dim3(wg, p->batch), lds, (hipStream_t)stream);

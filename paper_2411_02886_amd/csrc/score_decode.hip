@@ -1,14 +1,17 @@
 // Decode score pass: Algorithm 2 (Paged Dot Product Kernel) re-designed for gfx950, fused with the
 // per-head softmax statistics that Eq. 5 needs.
 //
-// HBM-bound streaming design.  A wave owns a tile of 32 logical tokens x HB = min(H_kv, 8) KV heads.
+// HBM-bound streaming design.  A wave owns tiles of 32 logical tokens x HB = min(H_kv, 8) KV heads.
 // Eight lanes share one K row (one token, one KV head): each lane loads 16-byte pieces of the row
 // (a load instruction of the wave covers eight rows x 128 contiguous bytes, i.e. whole cache lines),
 // multiplies them with the G query heads of that KV head kept in registers (the GQA group shares
 // every K byte that is loaded), and the eight partial sums are combined with three DPP steps.
-// The 32 x HB x G scores of the tile are staged in LDS token-major and leave as one contiguous run
-// (scores are stored [token][head], so a tile is a single 4 KiB burst for 32 heads); the same staged
-// values update running (max, sum-exp) statistics that a lane keeps in registers for its four heads.
+// The 32 x HB x G scores of a tile are staged in LDS token-major; a run of 1, 2 or 4 consecutive tiles
+// leaves as one contiguous burst (scores are stored [token][head]; 4-16 KiB for 32 heads) while the
+// loads of the next tile are already in flight, and the same staged values update running
+// (max, sum-exp) statistics that a lane keeps in registers for its four heads.  Longer runs are used for
+// longer sequences: on this memory system a write stream mixed into the read stream costs about three
+// times its bytes, and fewer, larger bursts reduce that.
 #include "ts_kernels.h"
 
 namespace ts {
@@ -89,7 +92,8 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
   const int N = min(max(a.seq_lens[b], 0), a.max_seq_len);
   const int H = a.H, HB = a.HB, HBG = HB * G;
   const int HS = (HBG + 3) & ~3;             // floats per token row of the staged tile
-  float* tile = smem + wave * (TT * HS);     // [TT][HS] scores of the current tile, token-major
+  const int RR = a.RR;                        // tiles a wave stages before it writes them out as one run
+  float* stage = smem + wave * max(RR * TT * HS, 512);   // [RR][TT][HS] staged scores, token-major (>= 512 floats: reused below)
 
   const int tps_shift = 3 - a.hb_shift;      // log2(tokens per wave step)
   const int STEPS = TT >> tps_shift;
@@ -128,9 +132,18 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
   // block in flight per wave (register double buffering) or a larger U changes nothing -- occupancy
   // already covers the latency -- so the simple form with the fewest registers is kept.
   const int NBLK = STEPS / U;                // blocks per tile (STEPS is 4, 8, 16 or 32)
-  const int tt_first = (blockIdx.x * 4 + wave) / a.NU;
-  const int my_tiles = tt_first < ntt ? (ntt - tt_first + tt_step - 1) / tt_step : 0;
+  // A wave owns runs of RR consecutive tiles: run n of the wave is run_first + n * run_step; its i-th tile
+  // overall (i = n * RR + r) is tile (run_first + n * run_step) * RR + r.  The tiles that exist form a prefix.
+  const int nrun = (ntt + RR - 1) / RR;
+  const int run_first = (blockIdx.x * 4 + wave) / a.NU, run_step = tt_step;
+  int my_tiles = 0;
+  if (run_first < nrun) {
+    const int my_runs = (nrun - run_first + run_step - 1) / run_step;
+    const int last_run = run_first + (my_runs - 1) * run_step;
+    my_tiles = (my_runs - 1) * RR + min(RR, ntt - last_run * RR);
+  }
   const int total_blocks = my_tiles * NBLK;
+  auto tile_of = [&](int n, int r) -> int { return (run_first + n * run_step) * RR + r; };
 
   // physical page of each of a tile's 32 tokens, one per lane (lanes 32..63 mirror 0..31)
   auto load_pids = [&](int tt) -> int {
@@ -156,7 +169,7 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
       }
     }
   };
-  auto compute = [&](const uint4 (&kr)[U][L], int blk) {
+  auto compute = [&](const uint4 (&kr)[U][L], int blk, float* tile) {
     const int s0 = blk * U;
 #pragma unroll
     for (int uu = 0; uu < U; ++uu) {
@@ -175,15 +188,14 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
       if (j < G) tile[tl * HS + kvh_l * G + j] = v;
     }
   };
-  // the tile leaves as one contiguous run of token rows; the same values feed the statistics
-  auto epilogue = [&](int tt) {
-    const int t0 = tt * TT;
+  // the staged tiles leave as one contiguous run of token rows; the same values feed the statistics
+  auto epilogue = [&](int t0, int ntok) {
     wave_lds_sync();
-    for (int tok0 = 0; tok0 < TT; tok0 += TPP) {
+    for (int tok0 = 0; tok0 < ntok; tok0 += TPP) {
       const int tok = tok0 + e_sub;
       const int t = t0 + tok;
-      if (e_active && tok < TT && t < N) {
-        const float4 v4 = *reinterpret_cast<const float4*>(&tile[tok * HS + e_hq * 4]);
+      if (e_active && tok < ntok && t < N) {
+        const float4 v4 = *reinterpret_cast<const float4*>(&stage[tok * HS + e_hq * 4]);
         const float x[4] = {v4.x, v4.y, v4.z, v4.w};
         float* dst = a.scores + ((size_t)b * a.max_seq_len + t) * H + h_base + e_hq * 4;
         if (a.vec_store) {
@@ -217,53 +229,77 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
   };
 
   uint4 buf[U][L];
-  int i_tt = tt_first, i_blk = 0, c_tt = tt_first, c_blk = 0;
+  int i_n = 0, i_r = 0, i_blk = 0;           // issue cursor: run, tile in run, block in tile
+  int c_n = 0, c_r = 0, c_blk = 0;           // compute cursor
   int i_pid = 0, i_pid_next = 0;
+  auto next_tile = [&](int n, int r) -> int {  // tile after (n, r) in this wave's order, clamped to an existing one
+    const int t = (r + 1 == RR) ? tile_of(n + 1, 0) : tile_of(n, r + 1);
+    return min(t, ntt - 1);
+  };
   auto advance_issue = [&]() {
     if (++i_blk == NBLK) {
-      i_blk = 0; i_tt += tt_step;
+      i_blk = 0;
+      if (++i_r == RR) { i_r = 0; ++i_n; }
       i_pid = i_pid_next;
-      i_pid_next = load_pids(min(i_tt + tt_step, ntt - 1));   // one tile ahead: never on the critical path
+      i_pid_next = load_pids(next_tile(i_n, i_r));   // one tile ahead: never on the critical path
     }
   };
-  auto advance_compute = [&]() {
-    if (++c_blk == NBLK) { epilogue(c_tt); c_blk = 0; c_tt += tt_step; }
-  };
   if (total_blocks > 0) {
-    i_pid = load_pids(i_tt);
-    i_pid_next = load_pids(min(i_tt + tt_step, ntt - 1));
-    issue(buf, i_tt, i_blk, i_pid);
+    i_pid = load_pids(tile_of(0, 0));
+    i_pid_next = load_pids(next_tile(0, 0));
+    issue(buf, tile_of(0, 0), 0, i_pid);
     advance_issue();
   }
+  int done_tiles = 0;
   for (int gb = 0; gb < total_blocks; ++gb) {
-    compute(buf, c_blk);
-    advance_compute();
-    if (gb + 1 < total_blocks) { issue(buf, i_tt, i_blk, i_pid); advance_issue(); }
+    compute(buf, c_blk, stage + c_r * (TT * HS));
+    // the next block's loads go out before the epilogue, which then runs in their shadow
+    if (gb + 1 < total_blocks) { issue(buf, tile_of(i_n, i_r), i_blk, i_pid); advance_issue(); }
+    if (++c_blk == NBLK) {
+      c_blk = 0; ++done_tiles;
+      if (c_r + 1 == RR || done_tiles == my_tiles) {
+        epilogue(tile_of(c_n, 0) * TT, (c_r + 1) * TT);
+        c_r = 0; ++c_n;
+      } else {
+        ++c_r;
+      }
+    }
   }
 
-  // ---- merge the lanes' statistics of this workgroup per head, publish the partial
-  __syncthreads();
-  float* st = smem;                          // [4 waves][64 lanes][4 heads][2]
+  // ---- merge the lanes' statistics per head: first inside the wave (its own LDS region, no workgroup
+  // barrier), then over the waves of the workgroup that share a head block; publish the partial
+  {
+    float* st = stage;                        // [64 lanes][4 heads][2]; the wave's own staging region is free now
 #pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    st[((wave * 64 + lane) * 4 + c) * 2] = rm[c];
-    st[((wave * 64 + lane) * 4 + c) * 2 + 1] = rl[c];
+    for (int c = 0; c < 4; ++c) {
+      st[(lane * 4 + c) * 2] = rm[c];
+      st[(lane * 4 + c) * 2 + 1] = rl[c];
+    }
+    wave_lds_sync();
+    float m = -INFINITY, l = 0.f;
+    if (lane < HBG) {
+      const int hq = lane >> 2, c = lane & 3;
+      for (int sub = 0; sub < TPP; ++sub) m = fmaxf(m, st[((sub * CPT + hq) * 4 + c) * 2]);
+      for (int sub = 0; sub < TPP; ++sub) {
+        const float2 e = *reinterpret_cast<const float2*>(&st[((sub * CPT + hq) * 4 + c) * 2]);
+        l += (e.x == -INFINITY) ? 0.f : e.y * __builtin_amdgcn_exp2f(c2 * (e.x - m));
+      }
+    }
+    __syncthreads();                          // every wave has read its lane statistics
+    float2* wv = reinterpret_cast<float2*>(smem);   // [4 waves][HBG]
+    if (lane < HBG) wv[wave * HBG + lane] = make_float2(m, l);
+    __syncthreads();
   }
-  __syncthreads();
   for (int h = threadIdx.x; h < H; h += 256) {
-    const int uh = h / HBG, hl = h - uh * HBG, hq = hl >> 2, c = hl & 3;
+    const int uh = h / HBG, hl = h - uh * HBG;
+    const float2* wv = reinterpret_cast<const float2*>(smem);
     float m = -INFINITY;
-    for (int w = 0; w < 4; ++w)
-      if ((w & (a.NU - 1)) == uh)
-        for (int sub = 0; sub < TPP; ++sub) m = fmaxf(m, st[((w * 64 + sub * CPT + hq) * 4 + c) * 2]);
+    for (int w = uh; w < 4; w += a.NU) m = fmaxf(m, wv[w * HBG + hl].x);
     float l = 0.f;
-    for (int w = 0; w < 4; ++w)
-      if ((w & (a.NU - 1)) == uh)
-        for (int sub = 0; sub < TPP; ++sub) {
-          const float mi = st[((w * 64 + sub * CPT + hq) * 4 + c) * 2];
-          const float li = st[((w * 64 + sub * CPT + hq) * 4 + c) * 2 + 1];
-          if (mi != -INFINITY) l += li * __builtin_amdgcn_exp2f(c2 * (mi - m));
-        }
+    for (int w = uh; w < 4; w += a.NU) {
+      const float2 e = wv[w * HBG + hl];
+      l += (e.x == -INFINITY) ? 0.f : e.y * __builtin_amdgcn_exp2f(c2 * (e.x - m));
+    }
     float* pp = a.partials + (((size_t)b * kScoreMaxWg + blockIdx.x) * H + h) * 2;
     pp[0] = m; pp[1] = l;
   }

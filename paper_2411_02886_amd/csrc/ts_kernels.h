@@ -17,6 +17,7 @@ struct ScoreArgs {
   int HB, hb_shift, NU;   // KV heads per wave tile (min(H_kv, 8)), its log2, H_kv / HB
   int uniform_page;       // every step of a wave reads one page (P >= tokens per step)
   int vec_store;          // score rows can be written as 16-byte pieces
+  int RR;                 // consecutive tiles a wave stages in LDS and writes out as one run (1, 2 or 4)
   float scale, c2;        // score_scale and score_scale * log2(e)
 };
 

@@ -64,4 +64,6 @@ def test_calls_reject_bad_arguments_without_launching():
     assert L.ts_sparse_paged_attn(ctypes.byref(cproblem(v_pool=None)), 0x1000, 0x1000, 16, 0x1000, 0.125, 0x1000, None, ws, big, None) == -1
     assert L.ts_sparse_paged_attn(p, 0x1000, 0x1000, 16, 0x1000, 0.125, 0x1000, None, ws, 64, None) == -3
     assert L.ts_workspace_init(None, 1024, None) == -1
-    assert L.ts_debug_set_score_variant(7, 0) == -1
+    assert L.ts_debug_set_score_variant(7, 0, 0) == -1
+    assert L.ts_debug_set_score_variant(1, 0, 3) == -1
+    assert L.ts_debug_set_score_variant(1, 0, 0) == 0

@@ -77,6 +77,30 @@ def test_shapes(gpu, shape):
     check_decode_against_oracle(w, layer, q, score_scale=1.0 / math.sqrt(D), label=str(shape))
 
 
+@pytest.mark.parametrize("run_tiles", [2, 4])
+def test_staged_runs_of_several_tiles(gpu, run_tiles):
+    # the score pass may stage 2 or 4 consecutive 32-token tiles per wave before writing them out (chosen
+    # automatically for long sequences); forced here on short ones, with ragged last runs and a ragged batch
+    gpu.ts_debug_set_score_variant(1, 0, run_tiles)
+    try:
+        for shape in [(W.BF16, 32, 8, 128, 16, 5000, 300), (W.BF16, 28, 4, 128, 16, 2500, 128),
+                      (W.F32, 6, 2, 64, 16, 450, 30), (W.BF16, 64, 32, 64, 16, 260, 20), (W.BF16, 32, 8, 128, 1, 333, 40)]:
+            dtype, H, H_kv, D, P, N, k = shape
+            print("run_tiles", run_tiles, "shape", shape, flush=True)
+            w = W.make_workload("shape", dtype=dtype, H=H, H_kv=H_kv, D=D, P=P, seq_lens=[N], k=k, beta=3.0,
+                                planted_per_head=2, seed=N + H + run_tiles)
+            layer, q = make_layer(w)
+            check_decode_against_oracle(w, layer, q, score_scale=1.0 / math.sqrt(D), label="run%d %s" % (run_tiles, shape))
+        lens = [0, 1, 31, 32, 33, 2049, 700, 15, 129, 64]
+        w = W.make_workload("ragged", dtype=W.BF16, B=len(lens), H=8, H_kv=2, D=128, P=16, seq_lens=lens, k=40,
+                            beta=3.0, planted_per_head=0, seed=6)
+        layer, q = make_layer(w)
+        print("run_tiles", run_tiles, "ragged batch", lens, flush=True)
+        check_decode_against_oracle(w, layer, q, score_scale=0.1, label="ragged run%d" % run_tiles)
+    finally:
+        gpu.ts_debug_set_score_variant(1, 0, 0)
+
+
 def test_ragged_batch_with_empty_and_short_sequences(gpu):
     lens = [0, 1, 31, 32, 33, 2049, 700, 15]
     w = W.make_workload("ragged", dtype=W.BF16, B=len(lens), H=8, H_kv=2, D=128, P=16, seq_lens=lens, k=40,
