@@ -114,9 +114,9 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
   const int e_sub = lane / CPT, e_hq = lane - e_sub * CPT;
   const bool e_active = e_sub < TPP;
   const int e_nvh = min(4, HBG - e_hq * 4);  // heads of this chunk that exist
-  float rm[4], rl[4];                        // running (max, sum-exp) of the lane's four heads
-#pragma unroll
-  for (int c = 0; c < 4; ++c) { rm[c] = -INFINITY; rl[c] = 0.f; }
+  // A lane with j < G always produces the score of the same head (KV head kvh_l, group member j), so it
+  // keeps that head's running (max, sum-exp) over the tokens it sees; the updates sit in the load shadow.
+  float rm = -INFINITY, rl = 0.f;
 
   typename P_::Q qreg[G][L];
 #pragma unroll
@@ -169,7 +169,7 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
       }
     }
   };
-  auto compute = [&](const uint4 (&kr)[U][L], int blk, float* tile) {
+  auto compute = [&](const uint4 (&kr)[U][L], int blk, float* tile, int t0) {
     const int s0 = blk * U;
 #pragma unroll
     for (int uu = 0; uu < U; ++uu) {
@@ -185,10 +185,17 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
       float v = acc[0];
 #pragma unroll
       for (int g = 1; g < G; ++g) v = (j == g) ? acc[g] : v;
+      const bool act = (j < G) && (t0 + tl < N);
       if (j < G) tile[tl * HS + kvh_l * G + j] = v;
+      if (__builtin_amdgcn_ballot_w64(act && v > rm) != 0) {   // rare after the first tiles: rescale to the new maximum
+        const float mn = act ? fmaxf(rm, v) : rm;
+        rl = (rm == -INFINITY) ? 0.f : rl * __builtin_amdgcn_exp2f(c2 * (rm - mn));
+        rm = mn;
+      }
+      if (act) rl += __builtin_amdgcn_exp2f(c2 * (v - rm));
     }
   };
-  // the staged tiles leave as one contiguous run of token rows; the same values feed the statistics
+  // the staged tiles leave as one contiguous run of token rows
   auto epilogue = [&](int t0, int ntok) {
     wave_lds_sync();
     for (int tok0 = 0; tok0 < ntok; tok0 += TPP) {
@@ -196,7 +203,6 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
       const int t = t0 + tok;
       if (e_active && tok < ntok && t < N) {
         const float4 v4 = *reinterpret_cast<const float4*>(&stage[tok * HS + e_hq * 4]);
-        const float x[4] = {v4.x, v4.y, v4.z, v4.w};
         float* dst = a.scores + ((size_t)b * a.max_seq_len + t) * H + h_base + e_hq * 4;
         if (a.vec_store) {
           typedef float v4f __attribute__((ext_vector_type(4)));
@@ -205,24 +211,8 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
         } else {
 #pragma unroll
           for (int c = 0; c < 4; ++c)
-            if (c < e_nvh) dst[c] = x[c];
+            if (c < e_nvh) dst[c] = stage[tok * HS + e_hq * 4 + c];
         }
-        bool grow = false;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) grow |= (c < e_nvh) && (x[c] > rm[c]);
-        if (__builtin_amdgcn_ballot_w64(grow) != 0) {     // rare after the first tiles: rescale to the new maxima
-#pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            if (c < e_nvh) {
-              const float mn = fmaxf(rm[c], x[c]);
-              rl[c] = (rm[c] == -INFINITY) ? 0.f : rl[c] * __builtin_amdgcn_exp2f(c2 * (rm[c] - mn));
-              rm[c] = mn;
-            }
-          }
-        }
-#pragma unroll
-        for (int c = 0; c < 4; ++c)
-          if (c < e_nvh) rl[c] += __builtin_amdgcn_exp2f(c2 * (x[c] - rm[c]));
       }
     }
     wave_lds_sync();
@@ -252,7 +242,7 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
   }
   int done_tiles = 0;
   for (int gb = 0; gb < total_blocks; ++gb) {
-    compute(buf, c_blk, stage + c_r * (TT * HS));
+    compute(buf, c_blk, stage + c_r * (TT * HS), tile_of(c_n, c_r) * TT);
     // the next block's loads go out before the epilogue, which then runs in their shadow
     if (gb + 1 < total_blocks) { issue(buf, tile_of(i_n, i_r), i_blk, i_pid); advance_issue(); }
     if (++c_blk == NBLK) {
@@ -269,19 +259,16 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
   // ---- merge the lanes' statistics per head: first inside the wave (its own LDS region, no workgroup
   // barrier), then over the waves of the workgroup that share a head block; publish the partial
   {
-    float* st = stage;                        // [64 lanes][4 heads][2]; the wave's own staging region is free now
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      st[(lane * 4 + c) * 2] = rm[c];
-      st[(lane * 4 + c) * 2 + 1] = rl[c];
-    }
+    float2* st = reinterpret_cast<float2*>(stage);   // [64 lanes]; the wave's own staging region is free now
+    wave_lds_sync();
+    st[lane] = make_float2(rm, rl);
     wave_lds_sync();
     float m = -INFINITY, l = 0.f;
-    if (lane < HBG) {
-      const int hq = lane >> 2, c = lane & 3;
-      for (int sub = 0; sub < TPP; ++sub) m = fmaxf(m, st[((sub * CPT + hq) * 4 + c) * 2]);
-      for (int sub = 0; sub < TPP; ++sub) {
-        const float2 e = *reinterpret_cast<const float2*>(&st[((sub * CPT + hq) * 4 + c) * 2]);
+    if (lane < HBG) {                         // head (kv, jj) of the wave's block: rows kv, kv + HB, ... produced it
+      const int kv = lane / G, jj = lane - kv * G;
+      for (int rr = kv; rr < 8; rr += HB) m = fmaxf(m, st[rr * 8 + jj].x);
+      for (int rr = kv; rr < 8; rr += HB) {
+        const float2 e = st[rr * 8 + jj];
         l += (e.x == -INFINITY) ? 0.f : e.y * __builtin_amdgcn_exp2f(c2 * (e.x - m));
       }
     }
