@@ -152,12 +152,37 @@ def decision_votes(votes64: np.ndarray) -> np.ndarray:
     return votes64.astype(np.float32).astype(np.float64)
 
 
-def select(q, k_pool, dtype, H_kv, P, page_indices, N, k, score_scale=1.0, details=False):
-    """S(Q, k) of Eq. 5 for one decode query: scores -> soft vote -> top-k.  Returns (idx, count)."""
+def ranked_range(N: int, n_init: int = 0, n_local: int = 0) -> Tuple[int, int]:
+    """[lo, hi): the cached tokens that the selection ranks when the first n_init and the last n_local
+    tokens are attended unconditionally (Sec. 6.1, implementation details: 128 initial and n_local most
+    recent tokens are attended in addition to the k selected ones).  The initial block wins an overlap."""
+    lo = min(max(int(n_init), 0), N)
+    hi = max(lo, N - max(int(n_local), 0))
+    return lo, hi
+
+
+def select(q, k_pool, dtype, H_kv, P, page_indices, N, k, score_scale=1.0, details=False, n_init=0, n_local=0):
+    """S(Q, k) of Eq. 5 for one decode query: scores -> soft vote -> top-k.  Returns (idx, count).
+    With forced tokens (n_init, n_local) the selection function is applied to the K rows of the ranked
+    range only: the softmax of Eq. 5 runs over that range and the k tokens come from it; the returned
+    votes are 0 outside it."""
     S = paged_qk_scores(q, k_pool, dtype, H_kv, P, page_indices, N)
-    votes = soft_vote(S, score_scale)
-    idx, cnt = topk(decision_votes(votes), k)
+    lo, hi = ranked_range(N, n_init, n_local)
+    votes = np.zeros(N, dtype=np.float64)
+    if hi > lo:
+        votes[lo:hi] = soft_vote(np.ascontiguousarray(S[:, lo:hi]), score_scale)
+    idx, cnt = topk(decision_votes(votes[lo:hi]), k)
+    idx = idx.copy()
+    idx[:cnt] += lo
     return (idx, cnt, votes, S) if details else (idx, cnt)
+
+
+def attended_tokens(idx, count, N, n_init=0, n_local=0) -> np.ndarray:
+    """Token list of Eq. 2 with forced tokens: initial block, then the selected tokens, then the most
+    recent block of the *current* length N (a cached selection made at a smaller N stays as it is)."""
+    lo, hi = ranked_range(N, n_init, n_local)
+    return np.concatenate([np.arange(lo, dtype=np.int32), np.asarray(idx[:count], dtype=np.int32),
+                           np.arange(hi, N, dtype=np.int32)])
 
 
 def select_chunk(qc, k_pool, dtype, H_kv, P, page_indices, N, k, score_scale=1.0, details=False):

@@ -332,3 +332,59 @@ def test_chunk_selection_sums_votes_over_queries():
     ref = sum(oracle.soft_vote(oracle.paged_qk_scores(np.ascontiguousarray(w.q[0, c]), w.k_pool, w.dtype, w.H_kv, w.P,
                                                       w.pages_of(0), 80)) for c in range(3))
     assert brute_topk(ref.astype(np.float32), 10) == idx.tolist()
+
+
+# ---------------------------------------------------------------- forced tokens (Sec. 6.1: 128 initial + n_local recent)
+
+def test_ranked_range_cases():
+    assert oracle.ranked_range(1000, 0, 0) == (0, 1000)
+    assert oracle.ranked_range(1000, 128, 512) == (128, 488)
+    assert oracle.ranked_range(600, 128, 512) == (128, 128)      # blocks overlap: nothing left to rank
+    assert oracle.ranked_range(100, 128, 512) == (100, 100)      # the initial block alone covers the sequence
+    assert oracle.ranked_range(0, 128, 512) == (0, 0)
+
+
+@pytest.mark.parametrize("n_init,n_local", [(5, 0), (0, 9), (7, 11)])
+def test_forced_tokens_selection_is_plain_selection_on_the_middle(n_init, n_local):
+    """Ranking [lo, hi) of a sequence must be the plain selection applied to a sequence that holds only
+    those tokens (built here from un-paged copies), shifted by lo -- an independent route to the result."""
+    N, k = 97, 12
+    w = tiny(N=N, P=1, seed=21)                       # one token per page: any sub-range is a page list
+    idx, cnt, votes, S = oracle.select(w.q[0, 0], w.k_pool, w.dtype, w.H_kv, w.P, w.pages_of(0), N, k, details=True,
+                                       n_init=n_init, n_local=n_local)
+    lo, hi = n_init, N - n_local
+    sub_pages = w.pages_of(0)[lo:hi]
+    idx2, cnt2, votes2, _ = oracle.select(w.q[0, 0], w.k_pool, w.dtype, w.H_kv, w.P, sub_pages, hi - lo, k, details=True)
+    assert cnt == cnt2 == k
+    assert (idx[:cnt] - lo).tolist() == idx2[:cnt2].tolist()
+    np.testing.assert_array_equal(votes[lo:hi], votes2)
+    assert not votes[:lo].any() and not votes[hi:].any()
+    assert abs(votes.sum() - w.H) < 1e-12             # each head's softmax runs over the ranked range only
+    # and against numpy directly
+    ref = sp_softmax(S[:, lo:hi], axis=1).sum(axis=0)
+    assert brute_topk(ref.astype(np.float32), k) == (idx[:cnt] - lo).tolist()
+
+
+def test_forced_tokens_attended_list_and_degenerate_cases():
+    N = 60
+    w = tiny(N=N, seed=22)
+    idx, cnt = oracle.select(w.q[0, 0], w.k_pool, w.dtype, w.H_kv, w.P, w.pages_of(0), N, 6, n_init=4, n_local=10)
+    att = oracle.attended_tokens(idx, cnt, N, 4, 10)
+    assert att.tolist() == list(range(4)) + idx[:cnt].tolist() + list(range(50, 60))
+    assert len(set(att.tolist())) == len(att) and np.all(np.diff(att) > 0)       # disjoint blocks, ascending
+    # a selection cached at N = 60 used at N = 63: the recent block follows the current length, the rest stays
+    att2 = oracle.attended_tokens(idx, cnt, 63, 4, 10)
+    assert att2.tolist() == list(range(4)) + idx[:cnt].tolist() + list(range(53, 63))
+    # forced blocks that cover the sequence: nothing is ranked and Eq. 2 becomes Eq. 1 (bitwise: same order)
+    idx0, cnt0 = oracle.select(w.q[0, 0], w.k_pool, w.dtype, w.H_kv, w.P, w.pages_of(0), N, 6, n_init=30, n_local=40)
+    assert cnt0 == 0
+    att0 = oracle.attended_tokens(idx0, cnt0, N, 30, 40)
+    assert att0.tolist() == list(range(N))
+    a = oracle.sparse_attn(w.q[0, 0], w.k_pool, w.v_pool, w.dtype, w.H_kv, w.P, w.pages_of(0), att0, N, 0.25)
+    b = oracle.full_attn(w.q[0, 0], w.k_pool, w.v_pool, w.dtype, w.H_kv, w.P, w.pages_of(0), N, 0.25)
+    assert np.array_equal(a, b)
+    # no forced tokens: unchanged behaviour
+    i1, c1 = oracle.select(w.q[0, 0], w.k_pool, w.dtype, w.H_kv, w.P, w.pages_of(0), N, 6)
+    i2, c2 = oracle.select(w.q[0, 0], w.k_pool, w.dtype, w.H_kv, w.P, w.pages_of(0), N, 6, n_init=0, n_local=0)
+    assert c1 == c2 and i1.tolist() == i2.tolist()
+    assert oracle.attended_tokens(i1, c1, N).tolist() == i1[:c1].tolist()
