@@ -44,6 +44,8 @@ def parse():
     ap.add_argument("--score-wg", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tokens", type=int, default=0, help="override the number of cached tokens (profiling only)")
+    ap.add_argument("--n-init", type=int, default=0, help="forced initial tokens (the paper's runs use 128); default 0 as in the configurations")
+    ap.add_argument("--n-local", type=int, default=0, help="forced most recent tokens (the paper's runs use 512); default 0")
     return ap.parse_args()
 
 
@@ -83,7 +85,8 @@ def selection_cache_run(args):
     qs = [to_device(q, dev) for q in W.ar1_queries(w, steps, rho=0.95)]
     ks, vs = W.appended_kv(w, steps)
     ksd, vsd = to_device(ks, dev), to_device(vs, dev)
-    layer = DecodeLayer.from_workload(w, device=dev, max_seq_len=int(w.seq_lens.max()) + steps)
+    layer = DecodeLayer.from_workload(w, device=dev, max_seq_len=int(w.seq_lens.max()) + steps,
+                                      num_initial=args.n_init, num_local=args.n_local)
     slots = np.empty((steps, w.B), dtype=np.int64)
     for b in range(w.B):
         pos = int(w.seq_lens[b]) + np.arange(steps)
@@ -118,7 +121,8 @@ def selection_cache_run(args):
            "dtype": "bf16", "data": "synthetic",
            "config": {"workload": w.name, "batch": w.B, "cached_tokens": [int(x) for x in w.seq_lens], "k": w.k,
                       "theta": theta, "score_scale": scale, "query_process": "AR(1) rho=0.95", "steps_per_run": steps,
-                      "anchor": "query of the last reselect (Algorithm 1)"},
+                      "anchor": "query of the last reselect (Algorithm 1)",
+                      "forced_initial_tokens": args.n_init, "forced_recent_tokens": args.n_local},
            "reuse_rate": float(reuse.mean()), "sequence_steps_per_s": steps * w.B / dt,
            "tokens_scanned_per_s": scanned / dt,
            "note": "host-driven loop: 12 library launches + 4 torch launches per step, no graph capture"}
@@ -194,7 +198,7 @@ def main():
     N = int(w.seq_lens[0])
     if args.variant >= 0 or args.score_wg:
         ts.ts_debug_set_score_variant(args.variant if args.variant >= 0 else 1, args.score_wg)
-    layer = DecodeLayer.from_workload(w, device=dev)
+    layer = DecodeLayer.from_workload(w, device=dev, num_initial=args.n_init, num_local=args.n_local)
     esize = w.esize()
     k_bytes = N * w.H_kv * w.D * esize                      # algorithmic bytes of the score pass
     pool_bytes = w.k_pool.nbytes + w.v_pool.nbytes
@@ -278,7 +282,8 @@ def main():
         "dtype": "bf16" if w.dtype == W.BF16 else "f32", "data": "synthetic",
         "config": {"workload": w.name, "batch": w.B, "cached_tokens": N, "num_q_heads": w.H, "num_kv_heads": w.H_kv,
                    "head_dim": w.D, "page_size": w.P, "k": w.k, "score_scale": scale, "theta": theta,
-                   "pool_copies_rotated": R, "selection_cache": "every step is a miss"},
+                   "pool_copies_rotated": R, "selection_cache": "every step is a miss",
+                   "forced_initial_tokens": args.n_init, "forced_recent_tokens": args.n_local},
         "decode_steps_per_s": 1e3 / ms_step,
         "roofline": {"bound": "hbm", "kernel": "ts::score_decode_kernel (the one launch of ts_paged_qk_scores)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,

@@ -9,6 +9,9 @@
  *   ts_topk               the TopK of Eq. 5 (radix select, ties to the lower token index)
  *   ts_sparse_paged_attn  Eq. 2, attention over the selected tokens read through the page table
  *
+ * With forced tokens (ts_problem.num_initial / num_local) the same five calls rank only the middle of
+ * each sequence and attend over initial block + selection + most recent block.
+ *
  * Conventions
  *   - Every pointer marked [device] is caller-owned device memory; [host] is host memory.
  *     The library never allocates, frees, synchronises the stream or reads device memory on the
@@ -61,6 +64,15 @@ typedef struct ts_problem {
   const int32_t* page_indptr;  /* [device] [B+1] CSR offsets into page_indices                    */
   const int32_t* page_indices; /* [device] physical page ids in logical order                     */
   const int32_t* seq_lens;     /* [device] [B] cached tokens N_b (0 <= N_b <= max_seq_len)        */
+  /* Forced tokens (Sec. 6.1, implementation details: 128 initial and n_local most recent tokens are
+   * attended in addition to the k selected ones).  With lo_b = min(num_initial, N_b) and
+   * hi_b = max(lo_b, N_b - num_local), the selection function is applied to the ranked range
+   * [lo_b, hi_b) only: the softmax statistics of ts_paged_qk_scores / ts_soft_vote cover that range,
+   * votes outside it are 0, ts_topk returns min(k, hi_b - lo_b) tokens of it, and ts_sparse_paged_attn
+   * attends over tokens [0, lo_b), the selected ones, and [hi_b, N_b) of the *current* N_b (a cached
+   * selection made at a smaller N_b stays valid).  Both 0 = no forced tokens.  Decode only (chunk == 1). */
+  int32_t num_initial;
+  int32_t num_local;
 } ts_problem;
 
 /* Library version (major*10000 + minor*100 + patch).  Host only. */

@@ -31,6 +31,7 @@ class _CProblem(ctypes.Structure):
         ("max_seq_len", ctypes.c_int32), ("dtype", ctypes.c_int32),
         ("k_pool", ctypes.c_void_p), ("v_pool", ctypes.c_void_p), ("page_indptr", ctypes.c_void_p),
         ("page_indices", ctypes.c_void_p), ("seq_lens", ctypes.c_void_p),
+        ("num_initial", ctypes.c_int32), ("num_local", ctypes.c_int32),
     ]
 
 
@@ -99,10 +100,11 @@ class Problem:
     """ts_problem plus references that keep the tensors it points at alive."""
 
     def __init__(self, *, batch, chunk=1, num_q_heads, num_kv_heads, head_dim, page_size, max_seq_len, dtype,
-                 k_pool, v_pool, page_indptr, page_indices, seq_lens):
+                 k_pool, v_pool, page_indptr, page_indices, seq_lens, num_initial=0, num_local=0):
         self._keep = (k_pool, v_pool, page_indptr, page_indices, seq_lens)
         self.c = _CProblem(batch, chunk, num_q_heads, num_kv_heads, head_dim, page_size, max_seq_len, dtype,
-                           _ptr(k_pool), _ptr(v_pool), _ptr(page_indptr), _ptr(page_indices), _ptr(seq_lens))
+                           _ptr(k_pool), _ptr(v_pool), _ptr(page_indptr), _ptr(page_indices), _ptr(seq_lens),
+                           int(num_initial), int(num_local))
 
     def ref(self):
         return ctypes.byref(self.c)

@@ -72,6 +72,9 @@ static int32_t check_problem(const ts_problem* p) {
   const int hb = p->num_kv_heads < 8 ? p->num_kv_heads : 8;
   if ((p->page_size * hb) % 8 != 0 && p->page_size != 1) return TS_ERR_UNSUPPORTED;
   if ((int64_t)p->batch * p->num_q_heads * (int64_t)p->max_seq_len > ((int64_t)1 << 40)) return TS_ERR_UNSUPPORTED;
+  if (p->num_initial < 0 || p->num_local < 0) return TS_ERR_INVALID_ARG;
+  if (p->num_initial > (1 << 20) || p->num_local > (1 << 20)) return TS_ERR_UNSUPPORTED;
+  if ((p->num_initial != 0 || p->num_local != 0) && p->chunk != 1) return TS_ERR_UNSUPPORTED;   // forced tokens: decode only
   return TS_OK;
 }
 
@@ -139,6 +142,7 @@ int32_t ts_paged_qk_scores(const ts_problem* p, const void* q, float* scores, fl
   a.uniform_page = p->page_size >= (8 / a.HB);
   a.vec_store = (p->num_q_heads % 4 == 0) && ((a.HB * G) % 4 == 0) && (((uintptr_t)scores & 15) == 0);
   a.scale = score_scale; a.c2 = score_scale * 1.44269504088896340736f;
+  a.n_init = p->num_initial; a.n_local = p->num_local;
   const int wg = score_workgroups(p);
   a.RR = score_run_tiles_eff(p);
   size_t lds = (size_t)4 * a.RR * kScoreTileTokens * ((a.HB * G + 3) & ~3) * sizeof(float);
@@ -161,6 +165,7 @@ int32_t ts_soft_vote(const ts_problem* p, const float* scores, float score_scale
   a.partials = (const float*)((uint8_t*)ws + w.score_partials); a.nparts = score_workgroups(p);
   a.scores = scores; a.row_stats = row_stats; a.row_stats_out = row_stats; a.votes = votes; a.seq_lens = p->seq_lens; a.skip = skip;
   a.H = p->num_q_heads; a.max_seq_len = p->max_seq_len; a.scale = score_scale;
+  a.n_init = p->num_initial; a.n_local = p->num_local;
   return launch_soft_vote(a, p->batch, (hipStream_t)stream) == hipSuccess ? TS_OK : TS_ERR_HIP;
 }
 
@@ -172,7 +177,8 @@ int32_t ts_topk(const ts_problem* p, const float* votes, int32_t k, int32_t* idx
   const WsLayout w = ws_layout(p, k);
   if (ws == nullptr || ((uintptr_t)ws & 255) != 0 || ws_bytes < w.attn_out) return TS_ERR_WORKSPACE;
   TopkArgs a{};
-  a.tail = p->chunk > 1 ? p->chunk : 0;
+  a.head = p->num_initial;
+  a.tail = p->chunk > 1 ? p->chunk : p->num_local;
   a.votes = votes; a.seq_lens = p->seq_lens; a.skip = skip; a.idx = idx; a.count = count;
   a.hist = (uint32_t*)((uint8_t*)ws + w.topk_hist);
   a.state = (uint32_t*)((uint8_t*)ws + w.topk_state);
@@ -265,6 +271,7 @@ int32_t ts_sparse_paged_attn(const ts_problem* p, const void* q, const int32_t* 
   a.part_ml = (float*)((uint8_t*)ws + w.attn_ml);
   a.H = p->num_q_heads; a.H_kv = p->num_kv_heads; a.P = p->page_size; a.p_shift = ilog2(p->page_size);
   a.idx_stride = idx_stride; a.nsplit = w.attn_nsplit; a.max_seq_len = p->max_seq_len; a.sm_scale = sm_scale;
+  a.n_init = p->num_initial; a.n_local = p->num_local;
   const int G = p->num_q_heads / p->num_kv_heads;
   return launch_sparse_attn_decode(p->dtype, p->head_dim, G, a, p->batch, (hipStream_t)stream) == hipSuccess ? TS_OK : TS_ERR_HIP;
 }

@@ -107,6 +107,7 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
   const int indptr = a.page_indptr[b];
   const int npages = (N + a.P - 1) >> a.p_shift;
   const float c2 = a.c2;
+  const int r_lo = min(a.n_init, N), r_hi = max(r_lo, N - a.n_local);   // ranked range: the statistics cover it only
 
   // epilogue mapping: a lane owns one 16-byte chunk (four heads) of a token row, always the same heads
   const int CPT = HS >> 2;                   // chunks per token row
@@ -185,7 +186,7 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
       float v = acc[0];
 #pragma unroll
       for (int g = 1; g < G; ++g) v = (j == g) ? acc[g] : v;
-      const bool act = (j < G) && (t0 + tl < N);
+      const bool act = (j < G) && (t0 + tl >= r_lo) && (t0 + tl < r_hi);
       if (j < G) tile[tl * HS + kvh_l * G + j] = v;
       if (__builtin_amdgcn_ballot_w64(act && v > rm) != 0) {   // rare after the first tiles: rescale to the new maximum
         const float mn = act ? fmaxf(rm, v) : rm;

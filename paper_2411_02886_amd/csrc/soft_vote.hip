@@ -99,7 +99,8 @@ __global__ __launch_bounds__(256) void soft_vote_kernel(VoteArgs a, int lpt_shif
     }
   }
   for (int off = 1; off < LPT; off <<= 1) vote += __shfl_xor(vote, off);
-  if (t < N && jv == 0) a.votes[(size_t)b * a.max_seq_len + t] = (float)vote;
+  const int r_lo = min(a.n_init, N), r_hi = max(r_lo, N - a.n_local);
+  if (t < N && jv == 0) a.votes[(size_t)b * a.max_seq_len + t] = (t >= r_lo && t < r_hi) ? (float)vote : 0.f;
 }
 
 hipError_t launch_soft_vote(const VoteArgs& a, int B, hipStream_t s) {

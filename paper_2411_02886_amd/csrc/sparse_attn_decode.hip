@@ -45,10 +45,14 @@ __global__ __launch_bounds__(256) void sparse_attn_decode_kernel(AttnArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
   const int H = a.H;
+  // attended list = forced initial tokens [0, f_lo), the cnt selected tokens, forced recent tokens [f_hi, nb)
+  const int nb = min(max(a.seq_lens[b], 0), a.max_seq_len);
+  const int f_lo = min(a.n_init, nb), f_hi = max(f_lo, nb - a.n_local);
   const int cnt = min(max(a.count[b], 0), a.idx_stride);
+  const int total = f_lo + cnt + (nb - f_hi);
   const int j0 = split * CH;
-  const int nj = min(max(cnt - j0, 0), CH);
-  if (nj <= 0) {                       // nothing selected in this split: publish an empty partial
+  const int nj = min(max(total - j0, 0), CH);
+  if (nj <= 0) {                       // nothing attended in this split: publish an empty partial
     if (threadIdx.x < G) {
       float* ml = a.part_ml + (((size_t)b * H + kvh * G + threadIdx.x) * a.nsplit + split) * 2;
       ml[0] = -INFINITY; ml[1] = 0.f;
@@ -58,10 +62,12 @@ __global__ __launch_bounds__(256) void sparse_attn_decode_kernel(AttnArgs a) {
   if (threadIdx.x < CH) {
     long long slot = -1;
     const int jj = j0 + threadIdx.x;
-    if (jj < cnt) {
-      int t = a.idx[(size_t)b * a.idx_stride + jj];
-      const int nb = min(max(a.seq_lens[b], 1), a.max_seq_len);
-      t = min(max(t, 0), nb - 1);                 // a stale or corrupt index must not leave the page table
+    if (jj < total) {
+      int t;
+      if (jj < f_lo) t = jj;
+      else if (jj < f_lo + cnt) t = a.idx[(size_t)b * a.idx_stride + (jj - f_lo)];
+      else t = f_hi + (jj - f_lo - cnt);
+      t = min(max(t, 0), max(nb, 1) - 1);         // a stale or corrupt index must not leave the page table
       const int page = a.page_indices[a.page_indptr[b] + (t >> a.p_shift)];
       slot = ((long long)page << a.p_shift) + (t & (a.P - 1));
     }
@@ -197,8 +203,10 @@ __global__ __launch_bounds__(D) void sparse_attn_merge_kernel(AttnArgs a) {
   const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
   const size_t hb = (size_t)b * a.H + h;
   const float* ml = a.part_ml + hb * a.nsplit * 2;
-  const int cnt = min(max(a.count[b], 0), a.idx_stride);
-  const int ns = min(a.nsplit, (cnt + kAttnChunk - 1) / kAttnChunk);   // splits that hold tokens
+  const int nb = min(max(a.seq_lens[b], 0), a.max_seq_len);
+  const int f_lo = min(a.n_init, nb), f_hi = max(f_lo, nb - a.n_local);
+  const int total = f_lo + min(max(a.count[b], 0), a.idx_stride) + (nb - f_hi);
+  const int ns = min(a.nsplit, (total + kAttnChunk - 1) / kAttnChunk);   // splits that hold tokens
   for (int s = d; s < ns; s += D) {
     const float2 v = *reinterpret_cast<const float2*>(ml + 2 * s);
     s_w[s] = v.x; s_l[s] = v.y;

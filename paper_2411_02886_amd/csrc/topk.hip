@@ -71,11 +71,20 @@ __device__ __forceinline__ void find_digit(const uint32_t* gh, uint32_t k_rem, u
 // state words per sequence
 enum { ST_PREFIX0 = 0, ST_KREM0 = 1, ST_KEFF = 2, ST_PREFIX1 = 3, ST_KREM1 = 4, ST_THR = 5, ST_NEED_EQ = 6, ST_NONE = 7 };
 
-__device__ __forceinline__ void load_keys(const float* v, int base, int N, uint32_t* key, bool* valid) {
+// tokens [LO, N) of a sequence take part: forced initial tokens, the chunk's own tokens and forced recent
+// tokens do not
+__device__ __forceinline__ int ranked_lo(const TopkArgs& a, int b) {
+  return min(a.head, min(max(a.seq_lens[b], 0), a.max_seq_len));
+}
+__device__ __forceinline__ int ranked_hi(const TopkArgs& a, int b, int lo) {
+  return max(lo, min(max(a.seq_lens[b], 0), a.max_seq_len) - a.tail);
+}
+
+__device__ __forceinline__ void load_keys(const float* v, int base, int LO, int N, uint32_t* key, bool* valid) {
 #pragma unroll
   for (int i = 0; i < kTopkChunk / 256; ++i) {
     const int t = base + i * 256 + threadIdx.x;
-    valid[i] = t < N;
+    valid[i] = t >= LO && t < N;
     key[i] = valid[i] ? float_key(v[t]) : 0u;
   }
 }
@@ -90,11 +99,11 @@ __global__ __launch_bounds__(256) void topk_hist0_kernel(TopkArgs a) {
   __shared__ uint32_t h[kTopkBins];
   const int b = blockIdx.y;
   if (a.skip != nullptr && a.skip[b] != 0) return;
-  const int N = min(max(a.seq_lens[b] - a.tail, 0), a.max_seq_len);
+  const int LO = ranked_lo(a, b), N = ranked_hi(a, b, LO);
   const int base = blockIdx.x * kTopkChunk;
   if (base >= N) return;
   uint32_t key[kTopkChunk / 256]; bool valid[kTopkChunk / 256];
-  load_keys(a.votes + (size_t)b * a.max_seq_len, base, N, key, valid);
+  load_keys(a.votes + (size_t)b * a.max_seq_len, base, LO, N, key, valid);
   for (int i = threadIdx.x; i < kTopkBins; i += 256) h[i] = 0;
   __syncthreads();
 #pragma unroll
@@ -110,13 +119,13 @@ __global__ __launch_bounds__(256) void topk_hist1_kernel(TopkArgs a) {
   __shared__ uint32_t lds[8];
   const int b = blockIdx.y;
   if (a.skip != nullptr && a.skip[b] != 0) return;
-  const int N = min(max(a.seq_lens[b] - a.tail, 0), a.max_seq_len);
+  const int LO = ranked_lo(a, b), N = ranked_hi(a, b, LO);
   const int base = blockIdx.x * kTopkChunk;
   if (base >= N && blockIdx.x != 0) return;
   uint32_t key[kTopkChunk / 256]; bool valid[kTopkChunk / 256];
-  load_keys(a.votes + (size_t)b * a.max_seq_len, base, N, key, valid);
+  load_keys(a.votes + (size_t)b * a.max_seq_len, base, LO, N, key, valid);
   for (int i = threadIdx.x; i < kTopkBins; i += 256) h[i] = 0;
-  const uint32_t k_eff = (uint32_t)min(a.k, N);
+  const uint32_t k_eff = (uint32_t)min(a.k, N - LO);
   uint32_t d0, krem0;
   find_digit<kTopkBins>(a.hist + ((size_t)b * 3 + 0) * kTopkBins, k_eff, &d0, &krem0, lds);
   if (blockIdx.x == 0 && threadIdx.x == 0) {
@@ -135,11 +144,11 @@ __global__ __launch_bounds__(256) void topk_hist2_kernel(TopkArgs a) {
   __shared__ uint32_t lds[8];
   const int b = blockIdx.y;
   if (a.skip != nullptr && a.skip[b] != 0) return;
-  const int N = min(max(a.seq_lens[b] - a.tail, 0), a.max_seq_len);
+  const int LO = ranked_lo(a, b), N = ranked_hi(a, b, LO);
   const int base = blockIdx.x * kTopkChunk;
   if (base >= N && blockIdx.x != 0) return;
   uint32_t key[kTopkChunk / 256]; bool valid[kTopkChunk / 256];
-  load_keys(a.votes + (size_t)b * a.max_seq_len, base, N, key, valid);
+  load_keys(a.votes + (size_t)b * a.max_seq_len, base, LO, N, key, valid);
   for (int i = threadIdx.x; i < 1024; i += 256) h[i] = 0;
   const uint32_t prefix0 = a.state[b * 8 + ST_PREFIX0], krem0 = a.state[b * 8 + ST_KREM0];
   uint32_t d1, krem1;
@@ -165,10 +174,10 @@ __global__ __launch_bounds__(256) void topk_count_kernel(TopkArgs a) {
   __shared__ uint32_t red[4];
   const int b = blockIdx.y;
   if (a.skip != nullptr && a.skip[b] != 0) return;
-  const int N = min(max(a.seq_lens[b] - a.tail, 0), a.max_seq_len);
+  const int LO = ranked_lo(a, b), N = ranked_hi(a, b, LO);
   const int base = blockIdx.x * kTopkChunk;
   uint32_t key[kTopkChunk / 256]; bool valid[kTopkChunk / 256];
-  load_keys(a.votes + (size_t)b * a.max_seq_len, base, N, key, valid);
+  load_keys(a.votes + (size_t)b * a.max_seq_len, base, LO, N, key, valid);
   const uint32_t prefix1 = a.state[b * 8 + ST_PREFIX1], krem1 = a.state[b * 8 + ST_KREM1];
   uint32_t d2, need_eq;
   find_digit<1024>(a.hist + ((size_t)b * 3 + 2) * kTopkBins, krem1, &d2, &need_eq, lds);
@@ -202,7 +211,7 @@ __global__ __launch_bounds__(256) void topk_emit_kernel(TopkArgs a) {
   __shared__ uint32_t red[2][4];
   const int b = blockIdx.y;
   if (a.skip != nullptr && a.skip[b] != 0) return;
-  const int N = min(max(a.seq_lens[b] - a.tail, 0), a.max_seq_len);
+  const int LO = ranked_lo(a, b), N = ranked_hi(a, b, LO);
   const uint32_t thr = a.state[b * 8 + ST_THR];
   const uint32_t need_eq = a.state[b * 8 + ST_NEED_EQ];
   const bool none = a.state[b * 8 + ST_NONE] != 0;
@@ -221,7 +230,7 @@ __global__ __launch_bounds__(256) void topk_emit_kernel(TopkArgs a) {
   const int t0 = base + threadIdx.x * PER;   // PER consecutive tokens per thread: order is preserved
   uint32_t key[PER];
 #pragma unroll
-  for (int e = 0; e < PER; ++e) key[e] = (t0 + e) < N ? float_key(v[t0 + e]) : 0u;
+  for (int e = 0; e < PER; ++e) key[e] = ((t0 + e) >= LO && (t0 + e) < N) ? float_key(v[t0 + e]) : 0u;
   // counts of all earlier chunks (gt in the low half is too narrow for a sum: add the halves apart)
   uint32_t pg = 0, pe = 0;
   const uint32_t* blk = a.blk + (size_t)b * a.nblk;
@@ -232,7 +241,7 @@ __global__ __launch_bounds__(256) void topk_emit_kernel(TopkArgs a) {
   uint32_t gt = 0, eq = 0;
 #pragma unroll
   for (int e = 0; e < PER; ++e) {
-    const bool valid = (t0 + e) < N;
+    const bool valid = (t0 + e) >= LO && (t0 + e) < N;
     gt += valid && key[e] > thr;
     eq += valid && key[e] == thr;
   }
@@ -243,7 +252,7 @@ __global__ __launch_bounds__(256) void topk_emit_kernel(TopkArgs a) {
 #pragma unroll
   for (int e = 0; e < PER; ++e) {
     const int t = t0 + e;
-    if (t < N) {
+    if (t >= LO && t < N) {
       if (key[e] > thr) {
         out[gt_before + min(eq_before, need_eq)] = t;
         ++gt_before;

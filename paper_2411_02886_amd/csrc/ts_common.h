@@ -42,7 +42,7 @@ inline WsLayout ws_layout(const ts_problem* p, int k) {
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
   w.topk_nblk = (p->max_seq_len + kTopkChunk - 1) / kTopkChunk;
   if (w.topk_nblk < 1) w.topk_nblk = 1;
-  w.attn_nsplit = (k + kAttnChunk - 1) / kAttnChunk;
+  w.attn_nsplit = (k + p->num_initial + p->num_local + kAttnChunk - 1) / kAttnChunk;   // forced tokens join the list
   if (w.attn_nsplit < 1) w.attn_nsplit = 1;
   // the histograms come first: they are the part that must start (and is left) zeroed
   w.topk_hist = take(B * 3 * kTopkBins * 4);

@@ -18,6 +18,7 @@ struct ScoreArgs {
   int uniform_page;       // every step of a wave reads one page (P >= tokens per step)
   int vec_store;          // score rows can be written as 16-byte pieces
   int RR;                 // consecutive tiles a wave stages in LDS and writes out as one run (1, 2 or 4)
+  int n_init, n_local;    // forced tokens: the statistics cover [min(n_init, N), max(that, N - n_local)) only
   float scale, c2;        // score_scale and score_scale * log2(e)
 };
 
@@ -31,11 +32,13 @@ struct VoteArgs {
   const int32_t* seq_lens;
   const uint8_t* skip;
   int H, max_seq_len;
+  int n_init, n_local;    // forced tokens: votes outside [min(n_init, N), max(that, N - n_local)) are 0
   float scale;
 };
 
 struct TopkArgs {
-  int tail;             // trailing tokens of every sequence that do not take part (the chunk's own tokens)
+  int head;             // leading tokens of every sequence that do not take part (forced initial tokens)
+  int tail;             // trailing tokens that do not take part (the chunk's own tokens / forced recent tokens)
   const float* votes;
   const int32_t* seq_lens;
   const uint8_t* skip;
@@ -71,6 +74,7 @@ struct AttnArgs {
   float* part_out;     // [B][H][nsplit][D]
   float* part_ml;      // [B][H][nsplit][2]
   int H, H_kv, P, p_shift, idx_stride, nsplit, max_seq_len;
+  int n_init, n_local;  // forced tokens attended before / after the selected ones
   float sm_scale;
 };
 

@@ -28,9 +28,10 @@ class DecodeLayer:
     """Paged KV pool of B sequences on the GPU plus every buffer the decode step needs."""
 
     def __init__(self, *, dtype, H, H_kv, D, P, k, k_pool, v_pool, page_indptr, page_indices, seq_lens,
-                 max_seq_len=None, device="cuda:0"):
+                 max_seq_len=None, device="cuda:0", num_initial=0, num_local=0):
         self.device = device
         self.dtype, self.H, self.H_kv, self.D, self.P, self.k = dtype, H, H_kv, D, P, k
+        self.num_initial, self.num_local = int(num_initial), int(num_local)   # forced tokens (Sec. 6.1)
         self.B = int(len(seq_lens))
         self.k_pool = k_pool if torch.is_tensor(k_pool) else to_device(k_pool, device)
         self.v_pool = v_pool if torch.is_tensor(v_pool) else to_device(v_pool, device)
@@ -59,13 +60,14 @@ class DecodeLayer:
         self.problem = ts.Problem(batch=self.B, chunk=1, num_q_heads=self.H, num_kv_heads=self.H_kv, head_dim=self.D,
                                   page_size=self.P, max_seq_len=self.max_seq_len, dtype=self.dtype,
                                   k_pool=self.k_pool, v_pool=self.v_pool, page_indptr=self.page_indptr,
-                                  page_indices=self.page_indices, seq_lens=self.seq_lens)
+                                  page_indices=self.page_indices, seq_lens=self.seq_lens,
+                                  num_initial=self.num_initial, num_local=self.num_local)
 
     @classmethod
-    def from_workload(cls, w, device="cuda:0", max_seq_len=None):
+    def from_workload(cls, w, device="cuda:0", max_seq_len=None, num_initial=0, num_local=0):
         return cls(dtype=w.dtype, H=w.H, H_kv=w.H_kv, D=w.D, P=w.P, k=w.k, k_pool=w.k_pool, v_pool=w.v_pool,
                    page_indptr=w.page_indptr, page_indices=w.page_indices, seq_lens=w.seq_lens,
-                   max_seq_len=max_seq_len, device=device)
+                   max_seq_len=max_seq_len, device=device, num_initial=num_initial, num_local=num_local)
 
     def swap_pool(self, k_pool: torch.Tensor, v_pool: torch.Tensor, page_indices: torch.Tensor = None):
         """Points the layer at another resident pool of the same shape (benchmark cache rotation)."""

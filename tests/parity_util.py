@@ -12,7 +12,7 @@ def ulp32(x: float) -> float:
     return float(np.spacing(np.float32(abs(x))))
 
 
-def oracle_decode(w, b, q=None, score_scale=1.0, sm_scale=None, k=None):
+def oracle_decode(w, b, q=None, score_scale=1.0, sm_scale=None, k=None, n_init=0, n_local=0):
     """Oracle results for sequence b: dict(S, votes, idx, count, out)."""
     N = int(w.seq_lens[b])
     k = w.k if k is None else k
@@ -22,8 +22,10 @@ def oracle_decode(w, b, q=None, score_scale=1.0, sm_scale=None, k=None):
         return dict(S=np.zeros((w.H, 0)), votes=np.zeros(0), idx=np.full(k, -1, np.int32), count=0,
                     out=np.zeros((w.H, w.D)))
     idx, cnt, votes, S = oracle.select(qb, w.k_pool, w.dtype, w.H_kv, w.P, w.pages_of(b), N, k,
-                                       score_scale=float(np.float32(score_scale)), details=True)
-    out = oracle.sparse_attn(qb, w.k_pool, w.v_pool, w.dtype, w.H_kv, w.P, w.pages_of(b), idx, cnt,
+                                       score_scale=float(np.float32(score_scale)), details=True,
+                                       n_init=n_init, n_local=n_local)
+    att = oracle.attended_tokens(idx, cnt, N, n_init, n_local)
+    out = oracle.sparse_attn(qb, w.k_pool, w.v_pool, w.dtype, w.H_kv, w.P, w.pages_of(b), att, len(att),
                              float(np.float32(sm)))
     return dict(S=S, votes=votes, idx=idx, count=cnt, out=out)
 
@@ -51,7 +53,8 @@ def compare_index_sets(gpu_idx, gpu_cnt, ora, label=""):
 
 def check_decode_against_oracle(w, layer, q_dev, *, score_scale=1.0, attn_tol=None, label="", skip_rows=(),
                                 expect_tol_S=None):
-    """Runs select + attend on the GPU for the workload's query and checks every stage."""
+    """Runs select + attend on the GPU for the workload's query and checks every stage.  Forced tokens
+    (layer.num_initial / num_local) restrict statistics, votes and top-k to the ranked range."""
     import torch
     from paper_2411_02886_amd.runtime import to_host
     sm = 1.0 / math.sqrt(w.D)
@@ -68,7 +71,9 @@ def check_decode_against_oracle(w, layer, q_dev, *, score_scale=1.0, attn_tol=No
         if b in skip_rows:
             continue
         N = int(w.seq_lens[b])
-        ora = oracle_decode(w, b, score_scale=score_scale)
+        ni, nl = layer.num_initial, layer.num_local
+        lo, hi = oracle.ranked_range(N, ni, nl)
+        ora = oracle_decode(w, b, score_scale=score_scale, n_init=ni, n_local=nl)
         lab = "%s b=%d N=%d" % (label, b, N)
         if N == 0:
             assert cnt_g[b] == 0 and np.all(idx_g[b] == -1), lab
@@ -79,22 +84,28 @@ def check_decode_against_oracle(w, layer, q_dev, *, score_scale=1.0, attn_tol=No
         tolS = expect_tol_S if expect_tol_S is not None else 6 * ulp32(np.abs(ora["S"]).max())
         errS = np.abs(Sg - ora["S"]).max()
         assert errS <= tolS, (lab, "scores", errS, tolS)
-        # 2. statistics: max is exactly the max of the stored scores; sum-exp matches a double recomputation
-        assert np.array_equal(st_g[b, :, 0], S_g[b, :N, :].max(axis=0)), lab
-        z = np.exp(c * (Sg - Sg.max(axis=1, keepdims=True))).sum(axis=1)
-        np.testing.assert_allclose(st_g[b, :, 1], z, rtol=5e-6, err_msg=lab)
-        # 3. votes (Eq. 5): against the oracle formula applied to the GPU's own scores, and the invariant
-        v_from_gpuS = oracle.soft_vote(Sg, c)
-        np.testing.assert_allclose(v_g[b, :N], v_from_gpuS, rtol=5e-6, atol=1e-44, err_msg=lab)
-        assert abs(float(v_g[b, :N].astype(np.float64).sum()) - w.H) < 1e-4 * w.H, lab
+        # 2. statistics over the ranked range: max is exactly the max of the stored scores; sum-exp matches a
+        #    double recomputation
+        if hi > lo:
+            Sr = Sg[:, lo:hi]
+            assert np.array_equal(st_g[b, :, 0], S_g[b, lo:hi, :].max(axis=0)), lab
+            z = np.exp(c * (Sr - Sr.max(axis=1, keepdims=True))).sum(axis=1)
+            np.testing.assert_allclose(st_g[b, :, 1], z, rtol=5e-6, err_msg=lab)
+            # 3. votes (Eq. 5): against the oracle formula applied to the GPU's own scores, and the invariant
+            v_from_gpuS = oracle.soft_vote(np.ascontiguousarray(Sr), c)
+            np.testing.assert_allclose(v_g[b, lo:hi], v_from_gpuS, rtol=5e-6, atol=1e-44, err_msg=lab)
+            assert abs(float(v_g[b, lo:hi].astype(np.float64).sum()) - w.H) < 1e-4 * w.H, lab
+        assert not v_g[b, :lo].any() and not v_g[b, hi:N].any(), (lab, "votes outside the ranked range must be 0")
         # 4. top-k (radix select) in isolation: bit-exact on the GPU's own votes
-        i_iso, c_iso = oracle.topk(v_g[b, :N].astype(np.float64), layer.k)
+        i_iso, c_iso = oracle.topk(v_g[b, lo:hi].astype(np.float64), layer.k)
+        i_iso = i_iso.copy(); i_iso[:c_iso] += lo
         assert cnt_g[b] == c_iso and np.array_equal(idx_g[b], i_iso), (lab, "radix select")
         # 5. end to end: index set against the oracle's selection (1e-6 band rule)
         exceptions += compare_index_sets(idx_g[b], int(cnt_g[b]), ora, lab)
         # 6. attention (Eq. 2) on the GPU-selected set against the oracle on the same set
         qb = np.ascontiguousarray(w.q[b, 0])
-        o_ref = oracle.sparse_attn(qb, w.k_pool, w.v_pool, w.dtype, w.H_kv, w.P, w.pages_of(b), idx_g[b], int(cnt_g[b]),
+        att = oracle.attended_tokens(idx_g[b], int(cnt_g[b]), N, ni, nl)
+        o_ref = oracle.sparse_attn(qb, w.k_pool, w.v_pool, w.dtype, w.H_kv, w.P, w.pages_of(b), att, len(att),
                                    float(np.float32(sm)))
         o_g = W.as_f32(out_g[b, 0], w.dtype).astype(np.float64)
         err = np.abs(o_g - o_ref).max()

@@ -11,7 +11,8 @@ from paper_2411_02886_amd.binding import _CProblem
 
 def cproblem(**kw):
     base = dict(batch=1, chunk=1, num_q_heads=8, num_kv_heads=2, head_dim=64, page_size=16, max_seq_len=4096,
-                dtype=ts.TS_F32, k_pool=0x1000, v_pool=0x1000, page_indptr=0x1000, page_indices=0x1000, seq_lens=0x1000)
+                dtype=ts.TS_F32, k_pool=0x1000, v_pool=0x1000, page_indptr=0x1000, page_indices=0x1000, seq_lens=0x1000,
+                num_initial=0, num_local=0)
     base.update(kw)
     return _CProblem(**base)
 
@@ -34,11 +35,12 @@ def test_workspace_bytes_and_shape_validation():
     small = out.value
     assert L.ts_workspace_bytes(ctypes.byref(cproblem(max_seq_len=1 << 20)), 4096, ctypes.byref(out)) == 0
     assert out.value > small
-    bad = [dict(num_q_heads=7), dict(batch=0), dict(dtype=5), dict(page_indptr=None), dict(max_seq_len=0)]
+    bad = [dict(num_q_heads=7), dict(batch=0), dict(dtype=5), dict(page_indptr=None), dict(max_seq_len=0),
+           dict(num_initial=-1), dict(num_local=-5)]
     for kw in bad:
         assert L.ts_workspace_bytes(ctypes.byref(cproblem(**kw)), 256, ctypes.byref(out)) == -1, kw
     unsup = [dict(head_dim=96), dict(num_kv_heads=3, num_q_heads=6), dict(page_size=12), dict(num_q_heads=32, num_kv_heads=2),
-             dict(num_q_heads=256, num_kv_heads=32)]
+             dict(num_q_heads=256, num_kv_heads=32), dict(chunk=4, num_initial=128), dict(num_local=1 << 21)]
     for kw in unsup:
         assert L.ts_workspace_bytes(ctypes.byref(cproblem(**kw)), 256, ctypes.byref(out)) == -2, kw
     assert L.ts_workspace_bytes(ctypes.byref(cproblem()), 0, ctypes.byref(out)) == -1

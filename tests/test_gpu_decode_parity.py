@@ -101,6 +101,22 @@ def test_staged_runs_of_several_tiles(gpu, run_tiles):
         gpu.ts_debug_set_score_variant(1, 0, 0)
 
 
+@pytest.mark.parametrize("n_init,n_local", [(128, 512), (5, 0), (0, 33), (16, 100)])
+def test_forced_initial_and_recent_tokens(gpu, n_init, n_local):
+    # Sec. 6.1: initial and most recent tokens are attended in addition to the k selected ones; the
+    # selection ranks only the tokens between them.  Sequences shorter than the forced blocks included.
+    lens = [5000, 640, 700, 130, 100, 0, 1, 641, 2048]
+    w = W.make_workload("forced", dtype=W.BF16, B=len(lens), H=8, H_kv=2, D=128, P=16, seq_lens=lens, k=64,
+                        beta=3.0, planted_per_head=0, seed=31 + n_init)
+    layer, q = make_layer(w, num_initial=n_init, num_local=n_local)
+    print("forced tokens", n_init, n_local, lens, flush=True)
+    check_decode_against_oracle(w, layer, q, score_scale=0.2, label="forced %d+%d" % (n_init, n_local))
+    w = W.make_workload("forced32", dtype=W.F32, H=8, H_kv=2, D=64, P=16, seq_lens=[3000], k=256, beta=3.0,
+                        planted_per_head=4, seed=32)
+    layer, q = make_layer(w, num_initial=n_init, num_local=n_local)
+    check_decode_against_oracle(w, layer, q, score_scale=1.0, label="forced fp32 %d+%d" % (n_init, n_local))
+
+
 def test_ragged_batch_with_empty_and_short_sequences(gpu):
     lens = [0, 1, 31, 32, 33, 2049, 700, 15]
     w = W.make_workload("ragged", dtype=W.BF16, B=len(lens), H=8, H_kv=2, D=128, P=16, seq_lens=lens, k=40,
@@ -218,15 +234,18 @@ def test_config4_full_size(gpu):
         assert (rg, pg) == (ro, po)
 
 
-def test_config3_shape_decode_run_with_appended_tokens(gpu):
+@pytest.mark.parametrize("forced", [(0, 0), (16, 64)], ids=["plain", "forced16+64"])
+def test_config3_shape_decode_run_with_appended_tokens(gpu, forced):
     # configuration 3 at reduced lengths: ragged batch, AR(1) queries, one K/V row appended per
-    # sequence per step, theta = 0.9; Algorithm 1 (anchor = query of the last reselect) on both sides
+    # sequence per step, theta = 0.9; Algorithm 1 (anchor = query of the last reselect) on both sides.
+    # With forced tokens a reused selection stays as cached while the recent block follows the growing length.
     from paper_2411_02886_amd.runtime import to_device, to_host
+    ni, nl = forced
     steps, theta, scale = 24, 0.9, 1.0
     w = W.config3(seed=1003, B=4, lo=700, hi=3000, steps=steps, k=128)
     qs = W.ar1_queries(w, steps, rho=0.95)
     ks, vs = W.appended_kv(w, steps)
-    layer, _ = make_layer(w, max_seq_len=int(w.seq_lens.max()) + steps)
+    layer, _ = make_layer(w, max_seq_len=int(w.seq_lens.max()) + steps, num_initial=ni, num_local=nl)
     lens = w.seq_lens.copy()
     cq = [np.zeros((w.H, w.D), np.uint16) for _ in range(w.B)]
     first = [np.ones(1, np.uint8) for _ in range(w.B)]
@@ -253,12 +272,13 @@ def test_config3_shape_decode_run_with_appended_tokens(gpu):
         for b in range(w.B):
             qb = np.ascontiguousarray(qs[t][b, 0])
             sel = lambda qq, b=b: oracle.select(qq, w.k_pool, w.dtype, w.H_kv, w.P, w.pages_of(b), int(lens[b]), w.k,
-                                                score_scale=float(np.float32(scale)))
+                                                score_scale=float(np.float32(scale)), n_init=ni, n_local=nl)
             i_o, c_o, r_o = oracle.selcache_step(qb, cq[b], cidx[b], ccnt[b], first[b], float(np.float32(theta)), sel)
             assert bool(reuse_g[b]) == r_o, (t, b)
             reuse_total += r_o
             assert cnt_g[b] == c_o and np.array_equal(idx_g[b], i_o), (t, b)
-            o_ref = oracle.sparse_attn(qb, w.k_pool, w.v_pool, w.dtype, w.H_kv, w.P, w.pages_of(b), i_o, c_o,
+            att = oracle.attended_tokens(i_o, c_o, int(lens[b]), ni, nl)
+            o_ref = oracle.sparse_attn(qb, w.k_pool, w.v_pool, w.dtype, w.H_kv, w.P, w.pages_of(b), att, len(att),
                                        float(np.float32(1 / math.sqrt(w.D))))
             assert np.abs(W.as_f32(out_g[b, 0], w.dtype) - o_ref).max() <= 2e-2, (t, b)
     rate = reuse_total / (steps * w.B)
