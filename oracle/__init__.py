@@ -196,6 +196,19 @@ def select_chunk(qc, k_pool, dtype, H_kv, P, page_indices, N, k, score_scale=1.0
     return (idx, cnt, votes) if details else (idx, cnt)
 
 
+def mean_query(qc: np.ndarray, dtype: int) -> np.ndarray:
+    """Sec. 5.2: the mean of the chunk's queries, in the queries' element type.  qc: [C][H][D] -> [H][D]."""
+    qc = _check(qc, dtype)
+    out = np.empty(qc.shape[1:], dtype=qc.dtype)
+    lib().oracle_mean_query(_p(qc), ctypes.c_int(dtype), ctypes.c_int(qc.shape[0]), ctypes.c_int64(out.size), _p(out))
+    return out
+
+
+def select_chunk_mean_query(qc, k_pool, dtype, H_kv, P, page_indices, N, k, score_scale=1.0, details=False):
+    """Sec. 5.2 as printed: one selection per chunk, S applied to the mean query over the N cached tokens."""
+    return select(mean_query(qc, dtype), k_pool, dtype, H_kv, P, page_indices, N, k, score_scale, details)
+
+
 def selcache_step(q, cached_q, cached_idx, cached_cnt, first, theta, select_fn):
     """Algorithm 1 in full.  select_fn(q) -> (idx, count).  State (cached_q, cached_idx, cached_cnt[1],
     first[1]) is updated in place.  Returns (idx, count, reused)."""

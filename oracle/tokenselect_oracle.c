@@ -193,3 +193,27 @@ void oracle_full_attn(const void* q, const void* k_pool, const void* v_pool, int
   }
   free(p);
 }
+
+/* Sec. 5.2 (chunk-wise selection during prefill): the query handed to the selection function is the
+ * mean of the chunk's C queries.  q: [C][n] stored elements (n = H * D); out: [n] in the same element
+ * type.  The mean is formed in double, rounded to float (nearest-even) and, for bfloat16 storage,
+ * rounded once more to bfloat16 (nearest-even): the selection function takes queries in the model's
+ * element type. */
+void oracle_mean_query(const void* q, int dtype, int C, int64_t n, void* out) {
+  for (int64_t i = 0; i < n; ++i) {
+    double s = 0.0;
+    for (int c = 0; c < C; ++c) s += elt(q, dtype, (int64_t)c * n + i);
+    const float f = (float)(s / (double)C);
+    if (dtype == 1) {
+      uint32_t u;
+      memcpy(&u, &f, 4);
+      const uint32_t lower_half = u & 0xffffu;
+      uint32_t top = u >> 16;
+      /* nearest-even: up when the dropped half exceeds one half, or equals it and the kept part is odd */
+      if (lower_half > 0x8000u || (lower_half == 0x8000u && (top & 1u))) top += 1u;
+      ((uint16_t*)out)[i] = (uint16_t)top;
+    } else {
+      ((float*)out)[i] = f;
+    }
+  }
+}

@@ -388,3 +388,45 @@ def test_forced_tokens_attended_list_and_degenerate_cases():
     i2, c2 = oracle.select(w.q[0, 0], w.k_pool, w.dtype, w.H_kv, w.P, w.pages_of(0), N, 6, n_init=0, n_local=0)
     assert c1 == c2 and i1.tolist() == i2.tolist()
     assert oracle.attended_tokens(i1, c1, N).tolist() == i1[:c1].tolist()
+
+
+# ---------------------------------------------------------------- Sec. 5.2: chunk selection with the mean query
+
+def test_mean_query_matches_numpy_and_rounds_to_nearest_even():
+    rng = np.random.Generator(np.random.PCG64(5))
+    q32 = rng.standard_normal((7, 3, 16), dtype=np.float32)
+    np.testing.assert_array_equal(oracle.mean_query(q32, W.F32), q32.astype(np.float64).mean(axis=0).astype(np.float32))
+    qb = W.store(q32, W.BF16)
+    m = oracle.mean_query(qb, W.BF16)
+    exact = W.as_f32(qb, W.BF16).astype(np.float64).mean(axis=0)
+    got = W.as_f32(m, W.BF16).astype(np.float64)
+    assert m.dtype == np.uint16
+    # nearest: within half a bf16 ulp (8 significant bits: ulp = 2^(floor(log2|x|) - 7)) of the exact mean
+    half_ulp = 0.5 * 2.0 ** (np.floor(np.log2(np.abs(exact))) - 7)
+    assert np.all(np.abs(got - exact) <= half_ulp * (1 + 1e-6))
+    # constructed halfway cases: mean of {1, 1 + 2^-7} = 1 + 2^-8 is halfway between bf16 neighbours -> even (1.0);
+    # mean of {1 + 2^-7, 1 + 2^-6} = 1 + 3 * 2^-8 -> halfway again -> even mantissa (1 + 2^-6)
+    vals = np.array([[1.0, 1.0 + 2.0 ** -7], [1.0 + 2.0 ** -7, 1.0 + 2.0 ** -6]], dtype=np.float32)   # [case][c]
+    qh = W.store(np.ascontiguousarray(vals.T).reshape(2, 1, 2), W.BF16)            # C = 2, H = 1, D = 2
+    mh = W.as_f32(oracle.mean_query(qh, W.BF16), W.BF16).reshape(2)
+    assert mh[0] == np.float32(1.0) and mh[1] == np.float32(1.0 + 2.0 ** -6)
+
+
+def test_mean_query_selection_special_cases():
+    w = W.make_workload("c", dtype=W.BF16, C=4, H=4, H_kv=2, D=16, P=4, seq_lens=[90], k=10, seed=9)
+    N = 86
+    # a chunk of one query, or of identical queries, is the decode selection with that query
+    q1 = np.ascontiguousarray(w.q[0, :1])
+    a = oracle.select_chunk_mean_query(q1, w.k_pool, w.dtype, w.H_kv, w.P, w.pages_of(0), N, 10)
+    b = oracle.select(np.ascontiguousarray(w.q[0, 0]), w.k_pool, w.dtype, w.H_kv, w.P, w.pages_of(0), N, 10)
+    assert a[1] == b[1] and a[0].tolist() == b[0].tolist()
+    qrep = np.ascontiguousarray(np.repeat(w.q[0, :1], 4, axis=0))
+    c = oracle.select_chunk_mean_query(qrep, w.k_pool, w.dtype, w.H_kv, w.P, w.pages_of(0), N, 10)
+    assert c[0].tolist() == b[0].tolist()
+    # linearity (fp32 storage, no second rounding to speak of): scores of the mean query = mean of the scores
+    w32 = W.make_workload("c32", dtype=W.F32, C=5, H=4, H_kv=2, D=16, P=4, seq_lens=[70], k=10, seed=10)
+    _, _, _, S = oracle.select_chunk_mean_query(w32.q[0], w32.k_pool, w32.dtype, w32.H_kv, w32.P, w32.pages_of(0), 65, 10,
+                                                details=True)
+    Sm = np.mean([oracle.paged_qk_scores(np.ascontiguousarray(w32.q[0, c]), w32.k_pool, w32.dtype, w32.H_kv, w32.P,
+                                         w32.pages_of(0), 65) for c in range(5)], axis=0)
+    np.testing.assert_allclose(S, Sm, rtol=0, atol=2e-6)
