@@ -172,6 +172,24 @@ def chunked_prefill_run(args):
                         "achieved": tf, "peak": peak, "unit": "TFLOP/s", "frac": tf / peak, "traffic": None,
                         "flop_per_launch": flop, "exp_per_launch": float(w.C) * w.H * N,
                         "stats_sweep_tflops": flop / (per[0] * 1e-3) / 1e12}}
+    # Sec. 5.2 as printed for comparison: one selection per chunk with the mean query (decode path, HBM-bound)
+    idx_pq = set(sel.idx[0, : int(sel.count[0])].tolist())
+    for _ in range(warm):
+        sel.select_mean_query(q, 1.0)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(steps):
+        sel.select_mean_query(q, 1.0)
+    b.record(); torch.cuda.synchronize()
+    idx_mq = set(sel.idx[0, : int(sel.count[0])].tolist())
+    planted = set(np.concatenate(list(w.planted[0])).tolist()) if len(w.planted) else set()
+    res["mean_query_selection"] = {
+        "ms": a.elapsed_time(b) / steps, "per_query_selection_ms": float(per[0] + per[1] + per[2]),
+        "index_overlap_with_per_query_votes": len(idx_pq & idx_mq) / max(1, len(idx_pq)),
+        "planted_among_selected": {"per_query_votes": len(idx_pq & planted) / max(1, len(idx_pq)),
+                                   "mean_query": len(idx_mq & planted) / max(1, len(idx_mq))},
+        "note": "mean of the chunk's 512 queries fed to the decode selection (ts_chunk_mean_query + score pass + vote + top-k)"}
     print(json.dumps(res))
 
 

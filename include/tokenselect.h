@@ -161,6 +161,13 @@ int32_t ts_chunk_row_stats(const ts_problem* p, const void* q, float score_scale
 int32_t ts_chunk_soft_vote(const ts_problem* p, const void* q, const float* row_stats, float score_scale, float* votes,
                            void* ws, size_t ws_bytes, void* stream);
 
+/* Sec. 5.2 as printed (chunk-wise selection with one query per chunk): q_mean[b][0][h][:] = mean over the
+ * chunk's C queries of q[b][c][h][:], formed exactly, rounded to float and then to bf16 (nearest-even).
+ * The result is a decode query: feed it to ts_paged_qk_scores / ts_soft_vote / ts_topk with a chunk == 1
+ * problem over the same pool whose seq_lens hold the cached lengths N_b - C, then attend with the chunk
+ * problem.  q [device] [B][C][H][D] bf16; q_mean [device] [B][1][H][D] bf16.  fp32: TS_ERR_UNSUPPORTED. */
+int32_t ts_chunk_mean_query(const ts_problem* p, const void* q, void* q_mean, void* stream);
+
 /* Tuning knob for benchmarks and tests (process-wide, not thread-safe, not part of the method):
  * variant 0 = score pass with fma arithmetic, 1 = packed bf16 dot2 arithmetic (bf16 inputs only; the
  * default for bf16: same measured accuracy, fewer registers);

@@ -71,10 +71,11 @@ def load():
         L.ts_sparse_paged_attn.argtypes = [pp, vp, vp, i32, vp, f32, vp, vp, vp, sz, vp]
         L.ts_chunk_row_stats.argtypes = [pp, vp, f32, vp, vp, sz, vp]
         L.ts_chunk_soft_vote.argtypes = [pp, vp, vp, f32, vp, vp, sz, vp]
+        L.ts_chunk_mean_query.argtypes = [pp, vp, vp, vp]
         L.ts_debug_set_score_variant.argtypes = [i32, i32, i32]
         for name in ("ts_workspace_bytes", "ts_workspace_init", "ts_paged_qk_scores", "ts_soft_vote", "ts_topk",
                      "ts_selcache_check", "ts_sparse_paged_attn", "ts_debug_set_score_variant", "ts_chunk_row_stats",
-                     "ts_chunk_soft_vote"):
+                     "ts_chunk_soft_vote", "ts_chunk_mean_query"):
             getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -154,6 +155,10 @@ def ts_chunk_row_stats(p: Problem, q, score_scale: float, row_stats, ws, stream=
 def ts_chunk_soft_vote(p: Problem, q, row_stats, score_scale: float, votes, ws, stream=None) -> None:
     _ok(load().ts_chunk_soft_vote(p.ref(), _ptr(q), _ptr(row_stats), float(score_scale), _ptr(votes), _ptr(ws),
                                   _nbytes(ws), _stream(stream)), "ts_chunk_soft_vote")
+
+
+def ts_chunk_mean_query(p: Problem, q, q_mean, stream=None) -> None:
+    _ok(load().ts_chunk_mean_query(p.ref(), _ptr(q), _ptr(q_mean), _stream(stream)), "ts_chunk_mean_query")
 
 
 def ts_topk(p: Problem, votes, k: int, idx, count, skip, ws, stream=None) -> None:

@@ -227,6 +227,15 @@ int32_t ts_chunk_soft_vote(const ts_problem* p, const void* q, const float* row_
   return launch_prefill_votes(a, (hipStream_t)stream) == hipSuccess ? TS_OK : TS_ERR_HIP;
 }
 
+int32_t ts_chunk_mean_query(const ts_problem* p, const void* q, void* q_mean, void* stream) {
+  int32_t st = check_problem(p);
+  if (st != TS_OK) return st;
+  if (q == nullptr || q_mean == nullptr) return TS_ERR_INVALID_ARG;
+  if (p->dtype != TS_BF16 || p->chunk > 65536) return TS_ERR_UNSUPPORTED;
+  return launch_chunk_mean_query(q, q_mean, p->batch, p->chunk, p->num_q_heads * p->head_dim, (hipStream_t)stream) == hipSuccess
+             ? TS_OK : TS_ERR_HIP;
+}
+
 int32_t ts_selcache_check(const ts_problem* p, const void* q, void* cached_q, uint8_t* first, float theta,
                           uint8_t* reuse, void* stream) {
   int32_t st = check_problem(p);

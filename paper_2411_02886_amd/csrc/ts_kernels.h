@@ -123,5 +123,6 @@ hipError_t launch_soft_vote(const VoteArgs& a, int B, hipStream_t s);
 hipError_t launch_topk(const TopkArgs& a, int B, hipStream_t s);
 hipError_t launch_selcache(const SelcacheArgs& a, int B, hipStream_t s);
 hipError_t launch_sparse_attn_decode(int dtype, int D, int G, const AttnArgs& a, int B, hipStream_t s);
+hipError_t launch_chunk_mean_query(const void* q, void* out, int B, int C, int n, hipStream_t s);
 
 }  // namespace ts

@@ -142,3 +142,30 @@ class ChunkSelector:
     def attend(self, q, sm_scale=None):
         sm = sm_scale if sm_scale is not None else 1.0 / float(np.sqrt(self.D))
         ts.ts_sparse_paged_attn(self.problem, q, self.idx, self.k, self.count, sm, self.out, self.lse, self.ws)
+
+    # ---- Sec. 5.2 as printed: one selection per chunk with the mean query, through the decode calls
+    def _mean_query_state(self):
+        if getattr(self, "_mq", None) is None:
+            dev = self.k_pool.device
+            B, M = self.B, self.max_seq_len
+            cached = torch.clamp(self.seq_lens - self.C, min=0).to(torch.int32)
+            prob = ts.Problem(batch=B, chunk=1, num_q_heads=self.H, num_kv_heads=self.H_kv, head_dim=self.D,
+                              page_size=self.P, max_seq_len=M, dtype=ts.TS_BF16, k_pool=self.k_pool, v_pool=self.v_pool,
+                              page_indptr=self.page_indptr, page_indices=self.page_indices, seq_lens=cached)
+            nbytes = ts.ts_workspace_bytes(prob, self.k)
+            ws = torch.empty((nbytes + 255) // 256 * 64, dtype=torch.int32, device=dev)
+            ts.ts_workspace_init(ws)
+            self._mq = dict(problem=prob, cached=cached, ws=ws,
+                            q_mean=torch.zeros((B, 1, self.H, self.D), dtype=torch.int16, device=dev),
+                            scores=torch.empty((B, M, self.H), dtype=torch.float32, device=dev),
+                            row_stats=torch.empty((B, self.H, 2), dtype=torch.float32, device=dev))
+        return self._mq
+
+    def select_mean_query(self, q, score_scale=1.0):
+        """Mean of the chunk's queries -> decode score pass, soft vote and top-k over the cached tokens.
+        Fills self.votes / self.idx / self.count like select()."""
+        m = self._mean_query_state()
+        ts.ts_chunk_mean_query(self.problem, q, m["q_mean"])
+        ts.ts_paged_qk_scores(m["problem"], m["q_mean"], m["scores"], score_scale, None, m["ws"])
+        ts.ts_soft_vote(m["problem"], m["scores"], score_scale, m["row_stats"], self.votes, None, m["ws"])
+        ts.ts_topk(m["problem"], self.votes, self.k, self.idx, self.count, None, m["ws"])

@@ -145,3 +145,57 @@ def test_config5_full_size_sampled(gpu):
         o_ref = oracle.sparse_attn(np.ascontiguousarray(w.q[0, ci]), w.k_pool, w.v_pool, w.dtype, w.H_kv, w.P, w.pages_of(0),
                                    idx_g, cnt_g, sm, extra_first=N, n_extra=ci + 1)
         assert np.abs(W.as_f32(out_g[ci], w.dtype).astype(np.float64) - o_ref).max() <= 2e-2, ci
+
+
+# ---------------------------------------------------------------- Sec. 5.2 as printed: mean-query selection
+
+def check_mean_query(ts, w, k, scale, label):
+    from paper_2411_02886_amd.runtime import ChunkSelector, to_device, to_host
+    sel = ChunkSelector.from_workload(w, k=k)
+    q = to_device(w.q)
+    sel.select_mean_query(q, scale)
+    sel.attend(q)
+    torch.cuda.synchronize()
+    m = sel._mean_query_state()
+    qm_g = to_host(m["q_mean"], bits16=True); S_g = to_host(m["scores"]); v_g = to_host(sel.votes)
+    idx_g = to_host(sel.idx); cnt_g = to_host(sel.count); out_g = to_host(sel.out, bits16=True)
+    c = float(np.float32(scale)); sm = float(np.float32(1.0 / math.sqrt(w.D)))
+    for b in range(w.B):
+        Nc = max(int(w.seq_lens[b]) - w.C, 0)
+        lab = "%s b=%d Nc=%d" % (label, b, Nc)
+        qm_o = oracle.mean_query(np.ascontiguousarray(w.q[b]), w.dtype)
+        assert np.array_equal(qm_g[b, 0], qm_o), (lab, "mean query must match bit for bit")
+        if Nc == 0:
+            assert cnt_g[b] == 0 and np.all(idx_g[b] == -1), lab
+            continue
+        i_o, c_o, votes, S = oracle.select_chunk_mean_query(np.ascontiguousarray(w.q[b]), w.k_pool, w.dtype, w.H_kv, w.P,
+                                                            w.pages_of(b), Nc, k, score_scale=c, details=True)
+        Sg = np.ascontiguousarray(S_g[b, :Nc, :].T).astype(np.float64)
+        assert np.abs(Sg - S).max() <= 6 * ulp32(np.abs(S).max()), (lab, "scores")
+        np.testing.assert_allclose(v_g[b, :Nc], oracle.soft_vote(Sg, c), rtol=5e-6, atol=1e-44, err_msg=lab)
+        i_iso, c_iso = oracle.topk(v_g[b, :Nc].astype(np.float64), k)
+        assert cnt_g[b] == c_iso and np.array_equal(idx_g[b], i_iso), (lab, "radix select")
+        compare_index_sets(idx_g[b], int(cnt_g[b]), dict(idx=i_o, count=c_o, votes=votes), lab)
+        for ci in sorted(set([0, w.C // 2, w.C - 1])):
+            o_ref = oracle.sparse_attn(np.ascontiguousarray(w.q[b, ci]), w.k_pool, w.v_pool, w.dtype, w.H_kv, w.P,
+                                       w.pages_of(b), idx_g[b], int(cnt_g[b]), sm, extra_first=Nc, n_extra=ci + 1)
+            assert np.abs(W.as_f32(out_g[b, ci], w.dtype).astype(np.float64) - o_ref).max() <= 2e-2, (lab, "attention", ci)
+
+
+@pytest.mark.parametrize("case", [(48, 8, 2, 128, 16, 3048, 64, 0.0884), (128, 32, 8, 128, 16, 5128, 256, 1.0),
+                                  (7, 28, 4, 128, 16, 1200, 100, 0.0884), (64, 16, 4, 64, 1, 900, 50, 0.125)],
+                         ids=lambda c: "C%d_H%d_%d_D%d_P%d_L%d_k%d" % c[:7])
+def test_mean_query_selection_shapes(gpu, case):
+    C, H, H_kv, D, P, L, k, scale = case
+    print("mean-query case", case, flush=True)
+    w = W.make_workload("chunkmq", dtype=W.BF16, C=C, H=H, H_kv=H_kv, D=D, P=P, seq_lens=[L], k=k, beta=2.5,
+                        planted_per_head=max(1, (L - C) // 200), plant_limit=L - C, seed=L + C + 1)
+    check_mean_query(gpu, w, k, scale, "mq " + str(case))
+
+
+def test_mean_query_selection_ragged_batch(gpu):
+    C = 32
+    lens = [C, C + 1, C + 63, 900, C + 300]
+    w = W.make_workload("chunkmqb", dtype=W.BF16, B=len(lens), C=C, H=8, H_kv=2, D=128, P=16, seq_lens=lens, k=40, seed=4)
+    print("mean-query ragged batch", lens, flush=True)
+    check_mean_query(gpu, w, 40, 0.0884, "mq ragged")
