@@ -15,6 +15,8 @@ Readings of the paper taken here (each is an explicit argument or a named consta
   * The top-k decision is an integer decided by floating point: it is taken on votes rounded to
     float32, the precision in which the library stores votes (`vote_dtype`).
   * Decode: the cached tokens already contain the current token; nothing is appended in Eq. 2.
+  * Eq. 3 is read as the top-k of the dot products summed over the heads (the form whose weakness the
+    paper describes: heads with large logits dominate); Eq. 4 lets every head vote for k tokens.
   * Chunked prefill (`select_chunk`): votes are summed over heads and over the chunk's queries;
     `select_chunk_mean_query` is the paper's Sec. 5.2 form (mean query fed to the decode selection).
 """
@@ -174,6 +176,41 @@ def select(q, k_pool, dtype, H_kv, P, page_indices, N, k, score_scale=1.0, detai
     idx, cnt = topk(decision_votes(votes[lo:hi]), k)
     idx = idx.copy()
     idx[:cnt] += lo
+    return (idx, cnt, votes, S) if details else (idx, cnt)
+
+
+def sum_vote(S: np.ndarray) -> np.ndarray:
+    """Criticality of Eq. 3 (I_topk): the raw dot products summed over the heads.  S: [H][N] -> [N]."""
+    votes = np.zeros(S.shape[1], dtype=np.float64)
+    for h in range(S.shape[0]):          # head order 0..H-1, as the library sums
+        votes += S[h]
+    return votes
+
+
+def head_vote(S: np.ndarray, k_head: int) -> np.ndarray:
+    """Criticality of Eq. 4 (I_head-vote): every head takes its own top-k_head tokens of its raw dot products
+    (float32 values as stored by the library, ties to the lower token index); a token's vote is the number of
+    heads that took it.  S: [H][N] -> [N] integer-valued."""
+    votes = np.zeros(S.shape[1], dtype=np.float64)
+    for h in range(S.shape[0]):
+        idx, cnt = topk(decision_votes(np.ascontiguousarray(S[h])), k_head)
+        votes[idx[:cnt]] += 1.0
+    return votes
+
+
+def select_with(kind: str, q, k_pool, dtype, H_kv, P, page_indices, N, k, score_scale=1.0, details=False):
+    """The three selection functions of Sec. 5.1 behind one call: kind = "soft" (Eq. 5), "sum" (Eq. 3) or
+    "head" (Eq. 4, every head votes for k tokens).  Returns (idx, count[, votes, S])."""
+    S = paged_qk_scores(q, k_pool, dtype, H_kv, P, page_indices, N)
+    if kind == "soft":
+        votes = soft_vote(S, score_scale)
+    elif kind == "sum":
+        votes = sum_vote(S)
+    elif kind == "head":
+        votes = head_vote(S, k)
+    else:
+        raise ValueError(kind)
+    idx, cnt = topk(decision_votes(votes), k)
     return (idx, cnt, votes, S) if details else (idx, cnt)
 
 

@@ -430,3 +430,59 @@ def test_mean_query_selection_special_cases():
     Sm = np.mean([oracle.paged_qk_scores(np.ascontiguousarray(w32.q[0, c]), w32.k_pool, w32.dtype, w32.H_kv, w32.P,
                                          w32.pages_of(0), 65) for c in range(5)], axis=0)
     np.testing.assert_allclose(S, Sm, rtol=0, atol=2e-6)
+
+
+# ---------------------------------------------------------------- Eq. 3 / Eq. 4: the ablation selection functions
+
+def brute_head_vote(S, k):
+    H, N = S.shape
+    votes = np.zeros(N)
+    for h in range(H):
+        order = sorted(range(N), key=lambda t: (-np.float32(S[h, t]), t))      # descending value, ascending index
+        for t in order[:k]:
+            votes[t] += 1
+    return votes
+
+
+def test_sum_and_head_vote_against_brute_force():
+    w = tiny(N=70, seed=41)
+    S = oracle.paged_qk_scores(w.q[0, 0], w.k_pool, w.dtype, w.H_kv, w.P, w.pages_of(0), 70)
+    np.testing.assert_allclose(oracle.sum_vote(S), S.sum(axis=0), rtol=1e-14)
+    for k in (1, 5, 69, 70, 100):
+        hv = oracle.head_vote(S, k)
+        assert np.array_equal(hv, brute_head_vote(S, k))
+        assert hv.sum() == w.H * min(k, 70) and hv.max() <= w.H
+        for kind, votes in (("sum", S.sum(axis=0)), ("head", hv)):
+            idx, cnt = oracle.select_with(kind, w.q[0, 0], w.k_pool, w.dtype, w.H_kv, w.P, w.pages_of(0), 70, k)
+            assert idx[:cnt].tolist() == brute_topk(votes.astype(np.float32), k)
+    # k >= N: every head takes every token, all votes equal H, ties resolve to the first tokens
+    idx, cnt = oracle.select_with("head", w.q[0, 0], w.k_pool, w.dtype, w.H_kv, w.P, w.pages_of(0), 70, 70)
+    assert cnt == 70 and idx.tolist() == list(range(70))
+
+
+def test_single_head_makes_the_three_selection_functions_agree():
+    # H = 1: Eq. 3, Eq. 4 and Eq. 5 are all the top-k of that head's raw logits
+    w = W.make_workload("h1", dtype=W.F32, H=1, H_kv=1, D=16, P=4, seq_lens=[120], k=9, seed=42)
+    ref = None
+    for kind in ("soft", "sum", "head"):
+        idx, cnt = oracle.select_with(kind, w.q[0, 0], w.k_pool, w.dtype, w.H_kv, w.P, w.pages_of(0), 120, 9)
+        ref = idx.tolist() if ref is None else ref
+        assert cnt == 9 and idx.tolist() == ref, kind
+
+
+def test_head_vote_ties_go_to_lower_index():
+    S = np.array([[1.0, 3.0, 3.0, 0.0, 3.0], [2.0, 2.0, 2.0, 2.0, 2.0]])
+    assert oracle.head_vote(S, 2).tolist() == [1.0, 2.0, 1.0, 0.0, 0.0]   # head 0 takes tokens 1, 2; head 1 takes 0, 1
+
+
+def test_sum_vote_is_dominated_by_a_head_with_large_logits_while_votes_are_not():
+    # the weakness the paper names for Eq. 3: scale one head's query by 50 and its preferences decide Eq. 3,
+    # while Eq. 4 still gives that head one vote per token like every other head
+    w = W.make_workload("dom", dtype=W.F32, H=4, H_kv=4, D=16, P=4, seq_lens=[200], k=10, seed=43)
+    q = w.q[0, 0].copy(); q[0] *= 50.0
+    S = oracle.paged_qk_scores(q, w.k_pool, w.dtype, w.H_kv, w.P, w.pages_of(0), 200)
+    top_h0 = set(brute_topk(S[0].astype(np.float32), 10))
+    i_sum, _ = oracle.select_with("sum", q, w.k_pool, w.dtype, w.H_kv, w.P, w.pages_of(0), 200, 10)
+    assert len(top_h0 & set(i_sum.tolist())) >= 9
+    hv = oracle.head_vote(S, 10)
+    assert hv.max() <= 4 and hv.sum() == 40
