@@ -119,6 +119,22 @@ int32_t ts_soft_vote(const ts_problem* p, const float* scores, float score_scale
 int32_t ts_topk(const ts_problem* p, const float* votes, int32_t k, int32_t* idx, int32_t* count,
                 const uint8_t* skip, void* ws, size_t ws_bytes, void* stream);
 
+/* The two selection functions the paper ablates against Eq. 5 (Sec. 5.1), as other ways to fill `votes`
+ * from the scores of ts_paged_qk_scores; ts_topk then ranks them as usual (decode only, chunk == 1).
+ *
+ * ts_sum_vote   Eq. 3 (I_topk), read as the top-k of the dot products summed over the heads:
+ *                 votes[b][t] = sum_h scores[b][t][h]      (double accumulation in head order, rounded once)
+ * ts_head_vote  Eq. 4 (I_head-vote): every head takes the k_head largest of its own dot products (equal values
+ *               in order of increasing token index) and
+ *                 votes[b][t] = number of heads that took token t     (an integer 0..H stored as float)
+ * Votes outside the ranked range (forced tokens) are 0; sequences with skip[b] != 0 are left untouched.
+ * ts_head_vote needs its own scratch of ts_head_vote_scratch_bytes() bytes [device], 256-byte aligned,
+ * contents irrelevant on entry (a transposed copy of the scores plus B * H radix-select states). */
+int32_t ts_sum_vote(const ts_problem* p, const float* scores, float* votes, const uint8_t* skip, void* stream);
+int32_t ts_head_vote_scratch_bytes(const ts_problem* p, size_t* bytes);
+int32_t ts_head_vote(const ts_problem* p, const float* scores, int32_t k_head, float* votes, const uint8_t* skip,
+                     void* scratch, size_t scratch_bytes, void* stream);
+
 /* Algorithm 1 (Selection Cache), condition and state update, per sequence b:
  *   reuse[b] = (first[b] == 0) and cos(q[b], cached_q[b]) >= theta      (one cosine over H*D values,
  *   double precision; a zero-norm operand gives cos = 0)

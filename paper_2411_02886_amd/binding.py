@@ -72,10 +72,14 @@ def load():
         L.ts_chunk_row_stats.argtypes = [pp, vp, f32, vp, vp, sz, vp]
         L.ts_chunk_soft_vote.argtypes = [pp, vp, vp, f32, vp, vp, sz, vp]
         L.ts_chunk_mean_query.argtypes = [pp, vp, vp, vp]
+        L.ts_sum_vote.argtypes = [pp, vp, vp, vp, vp]
+        L.ts_head_vote_scratch_bytes.argtypes = [pp, ctypes.POINTER(sz)]
+        L.ts_head_vote.argtypes = [pp, vp, i32, vp, vp, vp, sz, vp]
         L.ts_debug_set_score_variant.argtypes = [i32, i32, i32]
         for name in ("ts_workspace_bytes", "ts_workspace_init", "ts_paged_qk_scores", "ts_soft_vote", "ts_topk",
                      "ts_selcache_check", "ts_sparse_paged_attn", "ts_debug_set_score_variant", "ts_chunk_row_stats",
-                     "ts_chunk_soft_vote", "ts_chunk_mean_query"):
+                     "ts_chunk_soft_vote", "ts_chunk_mean_query", "ts_sum_vote", "ts_head_vote_scratch_bytes",
+                     "ts_head_vote"):
             getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -155,6 +159,21 @@ def ts_chunk_row_stats(p: Problem, q, score_scale: float, row_stats, ws, stream=
 def ts_chunk_soft_vote(p: Problem, q, row_stats, score_scale: float, votes, ws, stream=None) -> None:
     _ok(load().ts_chunk_soft_vote(p.ref(), _ptr(q), _ptr(row_stats), float(score_scale), _ptr(votes), _ptr(ws),
                                   _nbytes(ws), _stream(stream)), "ts_chunk_soft_vote")
+
+
+def ts_sum_vote(p: Problem, scores, votes, skip, stream=None) -> None:
+    _ok(load().ts_sum_vote(p.ref(), _ptr(scores), _ptr(votes), _ptr(skip), _stream(stream)), "ts_sum_vote")
+
+
+def ts_head_vote_scratch_bytes(p: Problem) -> int:
+    out = ctypes.c_size_t(0)
+    _ok(load().ts_head_vote_scratch_bytes(p.ref(), ctypes.byref(out)), "ts_head_vote_scratch_bytes")
+    return int(out.value)
+
+
+def ts_head_vote(p: Problem, scores, k_head: int, votes, skip, scratch, stream=None) -> None:
+    _ok(load().ts_head_vote(p.ref(), _ptr(scores), int(k_head), _ptr(votes), _ptr(skip), _ptr(scratch), _nbytes(scratch),
+                            _stream(stream)), "ts_head_vote")
 
 
 def ts_chunk_mean_query(p: Problem, q, q_mean, stream=None) -> None:

@@ -183,8 +183,75 @@ int32_t ts_topk(const ts_problem* p, const float* votes, int32_t k, int32_t* idx
   a.hist = (uint32_t*)((uint8_t*)ws + w.topk_hist);
   a.state = (uint32_t*)((uint8_t*)ws + w.topk_state);
   a.blk = (uint32_t*)((uint8_t*)ws + w.topk_blk);
-  a.k = k; a.max_seq_len = p->max_seq_len; a.nblk = w.topk_nblk;
+  a.k = k; a.max_seq_len = p->max_seq_len; a.nblk = w.topk_nblk; a.heads = 1;
   return launch_topk(a, p->batch, (hipStream_t)stream) == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
+// ---- the ablation selection functions of Sec. 5.1 (Eq. 3, Eq. 4): other ways to fill `votes` for ts_topk
+
+int32_t ts_sum_vote(const ts_problem* p, const float* scores, float* votes, const uint8_t* skip, void* stream) {
+  int32_t st = check_problem(p);
+  if (st != TS_OK) return st;
+  if (scores == nullptr || votes == nullptr) return TS_ERR_INVALID_ARG;
+  if (p->chunk != 1) return TS_ERR_UNSUPPORTED;
+  VoteArgs a{};
+  a.scores = scores; a.votes = votes; a.seq_lens = p->seq_lens; a.skip = skip;
+  a.H = p->num_q_heads; a.max_seq_len = p->max_seq_len; a.n_init = p->num_initial; a.n_local = p->num_local;
+  return launch_sum_vote(a, p->batch, (hipStream_t)stream) == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
+// scratch of ts_head_vote: transposed scores, then histograms / state / chunk counts of B * H radix selects
+struct HeadVoteLayout { size_t st, hist, state, blk, total; int nblk; };
+static HeadVoteLayout head_vote_layout(const ts_problem* p) {
+  HeadVoteLayout l{};
+  const size_t V = (size_t)p->batch * p->num_q_heads;
+  l.nblk = (p->max_seq_len + kTopkChunk - 1) / kTopkChunk;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+  l.st = take(V * (size_t)p->max_seq_len * 4);
+  l.hist = take(V * 3 * kTopkBins * 4);
+  l.state = take(V * 8 * 4);
+  l.blk = take(V * (size_t)l.nblk * 4);
+  l.total = off;
+  return l;
+}
+
+int32_t ts_head_vote_scratch_bytes(const ts_problem* p, size_t* bytes) {
+  if (bytes == nullptr) return TS_ERR_INVALID_ARG;
+  const int32_t st = check_problem(p);
+  if (st != TS_OK) return st;
+  *bytes = head_vote_layout(p).total;
+  return TS_OK;
+}
+
+int32_t ts_head_vote(const ts_problem* p, const float* scores, int32_t k_head, float* votes, const uint8_t* skip,
+                     void* scratch, size_t scratch_bytes, void* stream) {
+  int32_t st = check_problem(p);
+  if (st != TS_OK) return st;
+  if (scores == nullptr || votes == nullptr || k_head < 1) return TS_ERR_INVALID_ARG;
+  if (p->chunk != 1) return TS_ERR_UNSUPPORTED;
+  const HeadVoteLayout l = head_vote_layout(p);
+  if (scratch == nullptr || ((uintptr_t)scratch & 255) != 0 || scratch_bytes < l.total) return TS_ERR_WORKSPACE;
+  if ((size_t)p->batch * p->num_q_heads > 65535) return TS_ERR_UNSUPPORTED;   // grid.y of the radix-select passes
+  hipStream_t s = (hipStream_t)stream;
+  uint8_t* base = (uint8_t*)scratch;
+  VoteArgs v{};
+  v.scores = scores; v.seq_lens = p->seq_lens; v.skip = skip; v.H = p->num_q_heads; v.max_seq_len = p->max_seq_len;
+  if (launch_transpose_scores(v, (float*)(base + l.st), p->batch, s) != hipSuccess) return TS_ERR_HIP;
+  // the histograms must start at zero; the vote counters too (skipped sequences keep their votes)
+  if (launch_fill_u32((uint32_t*)(base + l.hist), (l.state - l.hist) / 4, 0u, s) != hipSuccess) return TS_ERR_HIP;
+  if (skip == nullptr) {
+    if (launch_fill_u32((uint32_t*)votes, (size_t)p->batch * p->max_seq_len, 0u, s) != hipSuccess) return TS_ERR_HIP;
+  } else {
+    VoteArgs z = v; z.votes = votes;
+    if (launch_zero_votes(z, p->batch, s) != hipSuccess) return TS_ERR_HIP;
+  }
+  TopkArgs a{};
+  a.head = p->num_initial; a.tail = p->num_local;
+  a.votes = (const float*)(base + l.st); a.seq_lens = p->seq_lens; a.skip = skip;
+  a.hist = (uint32_t*)(base + l.hist); a.state = (uint32_t*)(base + l.state); a.blk = (uint32_t*)(base + l.blk);
+  a.k = k_head; a.max_seq_len = p->max_seq_len; a.nblk = l.nblk; a.heads = p->num_q_heads; a.vote_acc = votes;
+  return launch_topk(a, p->batch * p->num_q_heads, s) == hipSuccess ? TS_OK : TS_ERR_HIP;
 }
 
 static int32_t fill_prefill_args(const ts_problem* p, const void* q, float score_scale, void* ws, size_t ws_bytes,

@@ -73,11 +73,12 @@ enum { ST_PREFIX0 = 0, ST_KREM0 = 1, ST_KEFF = 2, ST_PREFIX1 = 3, ST_KREM1 = 4, 
 
 // tokens [LO, N) of a sequence take part: forced initial tokens, the chunk's own tokens and forced recent
 // tokens do not
+// (b is the virtual sequence: a.heads of them share one real sequence's length)
 __device__ __forceinline__ int ranked_lo(const TopkArgs& a, int b) {
-  return min(a.head, min(max(a.seq_lens[b], 0), a.max_seq_len));
+  return min(a.head, min(max(a.seq_lens[b / a.heads], 0), a.max_seq_len));
 }
 __device__ __forceinline__ int ranked_hi(const TopkArgs& a, int b, int lo) {
-  return max(lo, min(max(a.seq_lens[b], 0), a.max_seq_len) - a.tail);
+  return max(lo, min(max(a.seq_lens[b / a.heads], 0), a.max_seq_len) - a.tail);
 }
 
 __device__ __forceinline__ void load_keys(const float* v, int base, int LO, int N, uint32_t* key, bool* valid) {
@@ -98,7 +99,7 @@ __device__ __forceinline__ void flush_hist(const uint32_t* h, uint32_t* gh, int 
 __global__ __launch_bounds__(256) void topk_hist0_kernel(TopkArgs a) {
   __shared__ uint32_t h[kTopkBins];
   const int b = blockIdx.y;
-  if (a.skip != nullptr && a.skip[b] != 0) return;
+  if (a.skip != nullptr && a.skip[b / a.heads] != 0) return;
   const int LO = ranked_lo(a, b), N = ranked_hi(a, b, LO);
   const int base = blockIdx.x * kTopkChunk;
   if (base >= N) return;
@@ -118,7 +119,7 @@ __global__ __launch_bounds__(256) void topk_hist1_kernel(TopkArgs a) {
   __shared__ uint32_t h[kTopkBins];
   __shared__ uint32_t lds[8];
   const int b = blockIdx.y;
-  if (a.skip != nullptr && a.skip[b] != 0) return;
+  if (a.skip != nullptr && a.skip[b / a.heads] != 0) return;
   const int LO = ranked_lo(a, b), N = ranked_hi(a, b, LO);
   const int base = blockIdx.x * kTopkChunk;
   if (base >= N && blockIdx.x != 0) return;
@@ -143,7 +144,7 @@ __global__ __launch_bounds__(256) void topk_hist2_kernel(TopkArgs a) {
   __shared__ uint32_t h[1024];
   __shared__ uint32_t lds[8];
   const int b = blockIdx.y;
-  if (a.skip != nullptr && a.skip[b] != 0) return;
+  if (a.skip != nullptr && a.skip[b / a.heads] != 0) return;
   const int LO = ranked_lo(a, b), N = ranked_hi(a, b, LO);
   const int base = blockIdx.x * kTopkChunk;
   if (base >= N && blockIdx.x != 0) return;
@@ -173,7 +174,7 @@ __global__ __launch_bounds__(256) void topk_count_kernel(TopkArgs a) {
   __shared__ uint32_t lds[8];
   __shared__ uint32_t red[4];
   const int b = blockIdx.y;
-  if (a.skip != nullptr && a.skip[b] != 0) return;
+  if (a.skip != nullptr && a.skip[b / a.heads] != 0) return;
   const int LO = ranked_lo(a, b), N = ranked_hi(a, b, LO);
   const int base = blockIdx.x * kTopkChunk;
   uint32_t key[kTopkChunk / 256]; bool valid[kTopkChunk / 256];
@@ -210,16 +211,20 @@ __global__ __launch_bounds__(256) void topk_emit_kernel(TopkArgs a) {
   __shared__ uint32_t scan_lds[8];
   __shared__ uint32_t red[2][4];
   const int b = blockIdx.y;
-  if (a.skip != nullptr && a.skip[b] != 0) return;
+  if (a.skip != nullptr && a.skip[b / a.heads] != 0) return;
   const int LO = ranked_lo(a, b), N = ranked_hi(a, b, LO);
   const uint32_t thr = a.state[b * 8 + ST_THR];
   const uint32_t need_eq = a.state[b * 8 + ST_NEED_EQ];
   const bool none = a.state[b * 8 + ST_NONE] != 0;
   const int k_eff = (int)a.state[b * 8 + ST_KEFF];
-  int32_t* out = a.idx + (size_t)b * a.k;
+  const bool as_votes = a.vote_acc != nullptr;      // Eq. 4: winners are counted per token, not listed
+  int32_t* out = as_votes ? nullptr : a.idx + (size_t)b * a.k;
+  float* acc = as_votes ? a.vote_acc + (size_t)(b / a.heads) * a.max_seq_len : nullptr;
   if (blockIdx.x == 0) {
-    for (int i = k_eff + threadIdx.x; i < a.k; i += 256) out[i] = -1;
-    if (threadIdx.x == 0) a.count[b] = k_eff;
+    if (!as_votes) {
+      for (int i = k_eff + threadIdx.x; i < a.k; i += 256) out[i] = -1;
+      if (threadIdx.x == 0) a.count[b] = k_eff;
+    }
     uint32_t* g2 = a.hist + ((size_t)b * 3 + 2) * kTopkBins;
     for (int i = threadIdx.x; i < 1024; i += 256) g2[i] = 0u;
   }
@@ -254,10 +259,14 @@ __global__ __launch_bounds__(256) void topk_emit_kernel(TopkArgs a) {
     const int t = t0 + e;
     if (t >= LO && t < N) {
       if (key[e] > thr) {
-        out[gt_before + min(eq_before, need_eq)] = t;
+        if (as_votes) atomicAdd(&acc[t], 1.0f);      // small integers: exact and order-independent in float
+        else out[gt_before + min(eq_before, need_eq)] = t;
         ++gt_before;
       } else if (key[e] == thr) {
-        if (eq_before < need_eq) out[gt_before + eq_before] = t;
+        if (eq_before < need_eq) {
+          if (as_votes) atomicAdd(&acc[t], 1.0f);
+          else out[gt_before + eq_before] = t;
+        }
         ++eq_before;
       }
     }

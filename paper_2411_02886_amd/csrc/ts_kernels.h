@@ -48,6 +48,8 @@ struct TopkArgs {
   uint32_t* state;      // [B][8]
   uint32_t* blk;        // [B][nblk]
   int k, max_seq_len, nblk;
+  int heads;            // virtual sequences per real one (Eq. 4: one per head over transposed scores); 1 = plain
+  float* vote_acc;      // Eq. 4: the emit pass adds 1 to vote_acc[real sequence][t] for every winner instead of writing idx
 };
 
 struct SelcacheArgs {
@@ -124,5 +126,9 @@ hipError_t launch_topk(const TopkArgs& a, int B, hipStream_t s);
 hipError_t launch_selcache(const SelcacheArgs& a, int B, hipStream_t s);
 hipError_t launch_sparse_attn_decode(int dtype, int D, int G, const AttnArgs& a, int B, hipStream_t s);
 hipError_t launch_chunk_mean_query(const void* q, void* out, int B, int C, int n, hipStream_t s);
+hipError_t launch_sum_vote(const VoteArgs& a, int B, hipStream_t s);
+hipError_t launch_transpose_scores(const VoteArgs& a, float* st, int B, hipStream_t s);
+hipError_t launch_zero_votes(const VoteArgs& a, int B, hipStream_t s);
+hipError_t launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t s);
 
 }  // namespace ts

@@ -80,9 +80,20 @@ class DecodeLayer:
     def selcache_check(self, q, theta):
         ts.ts_selcache_check(self.problem, q, self.cached_q, self.first, theta, self.reuse)
 
-    def select(self, q, score_scale=1.0, skip=None):
+    def select(self, q, score_scale=1.0, skip=None, kind="soft"):
+        """kind: "soft" = Eq. 5 (the method), "sum" = Eq. 3, "head" = Eq. 4 (the paper's ablation baselines)."""
         ts.ts_paged_qk_scores(self.problem, q, self.scores, score_scale, skip, self.ws)
-        ts.ts_soft_vote(self.problem, self.scores, score_scale, self.row_stats, self.votes, skip, self.ws)
+        if kind == "soft":
+            ts.ts_soft_vote(self.problem, self.scores, score_scale, self.row_stats, self.votes, skip, self.ws)
+        elif kind == "sum":
+            ts.ts_sum_vote(self.problem, self.scores, self.votes, skip)
+        elif kind == "head":
+            if getattr(self, "_hv_scratch", None) is None:
+                nb = ts.ts_head_vote_scratch_bytes(self.problem)
+                self._hv_scratch = torch.empty((nb + 255) // 256 * 64, dtype=torch.int32, device=self.device)
+            ts.ts_head_vote(self.problem, self.scores, self.k, self.votes, skip, self._hv_scratch)
+        else:
+            raise ValueError(kind)
         ts.ts_topk(self.problem, self.votes, self.k, self.idx, self.count, skip, self.ws)
 
     def attend(self, q, sm_scale):

@@ -1,0 +1,118 @@
+"""GPU parity of the ablation selection functions of Sec. 5.1 -- Eq. 3 (dot products summed over heads) and
+Eq. 4 (every head takes its own top-k, tokens are ranked by the number of heads that took them) -- against the
+CPU oracle.  Both decide integers from floating point, so the strict comparison is made on the GPU's own score
+matrix (itself checked against the oracle's to a few ulp): there the votes and the index set must match bit for
+bit.  End to end against the oracle's own scores the sets must be identical whenever no decision boundary is
+closer than the score rounding error, and overlap almost completely otherwise."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads as W
+from parity_util import ulp32
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2411_02886_amd as ts
+    ts.load()
+    return ts
+
+
+def boundary_gap(values, k):
+    """Distance between the k-th and (k+1)-th largest value (inf when k >= len)."""
+    if k >= len(values):
+        return float("inf")
+    s = np.sort(values)[::-1]
+    return float(s[k - 1] - s[k])
+
+
+def check_variant(w, kind, n_init=0, n_local=0, label=""):
+    from paper_2411_02886_amd.runtime import DecodeLayer, to_device, to_host
+    layer = DecodeLayer.from_workload(w, num_initial=n_init, num_local=n_local)
+    q = to_device(w.q)
+    layer.select(q, 1.0, None, kind=kind)
+    layer.attend(q, 1.0 / math.sqrt(w.D))
+    torch.cuda.synchronize()
+    S_g = to_host(layer.scores); v_g = to_host(layer.votes); idx_g = to_host(layer.idx); cnt_g = to_host(layer.count)
+    out_g = to_host(layer.out, bits16=(w.dtype == W.BF16))
+    strict = 0
+    for b in range(w.B):
+        N = int(w.seq_lens[b])
+        lab = "%s %s b=%d N=%d" % (label, kind, b, N)
+        lo, hi = oracle.ranked_range(N, n_init, n_local)
+        if N == 0:
+            assert cnt_g[b] == 0, lab
+            continue
+        Sg = np.ascontiguousarray(S_g[b, :N, :].T).astype(np.float64)
+        So = oracle.paged_qk_scores(np.ascontiguousarray(w.q[b, 0]), w.k_pool, w.dtype, w.H_kv, w.P, w.pages_of(b), N)
+        assert np.abs(Sg - So).max() <= 6 * ulp32(np.abs(So).max()), (lab, "scores")
+        Sr = np.ascontiguousarray(Sg[:, lo:hi])
+        # votes from the GPU's own scores: bit for bit
+        ref = oracle.sum_vote(Sr).astype(np.float32) if kind == "sum" else oracle.head_vote(Sr, layer.k).astype(np.float32)
+        assert np.array_equal(v_g[b, lo:hi], ref), (lab, "votes")
+        assert not v_g[b, :lo].any() and not v_g[b, hi:N].any(), lab
+        if kind == "head":
+            assert v_g[b, lo:hi].sum() == w.H * min(layer.k, hi - lo), lab
+        i_iso, c_iso = oracle.topk(v_g[b, lo:hi].astype(np.float64), layer.k)
+        i_iso = i_iso.copy(); i_iso[:c_iso] += lo
+        assert cnt_g[b] == c_iso and np.array_equal(idx_g[b], i_iso), (lab, "radix select")
+        # end to end against the oracle's own scores
+        Sor = np.ascontiguousarray(So[:, lo:hi])
+        vo = oracle.sum_vote(Sor) if kind == "sum" else oracle.head_vote(Sor, layer.k)
+        i_o, c_o = oracle.topk(oracle.decision_votes(vo), layer.k)
+        i_o = i_o.copy(); i_o[:c_o] += lo
+        eps = 64 * ulp32(np.abs(So).max())
+        if kind == "sum":
+            unambiguous = boundary_gap(vo, layer.k) > w.H * eps
+        else:
+            unambiguous = all(boundary_gap(Sor[h], layer.k) > eps for h in range(w.H))
+        if unambiguous:
+            assert cnt_g[b] == c_o and np.array_equal(idx_g[b], i_o), (lab, "end to end")
+            strict += 1
+        else:
+            ov = len(set(idx_g[b, :c_o].tolist()) & set(i_o[:c_o].tolist())) / max(1, c_o)
+            print(lab, "a decision boundary lies within the score rounding error; overlap %.4f" % ov)
+            assert ov >= 0.98, lab
+        att = oracle.attended_tokens(idx_g[b], int(cnt_g[b]), N, n_init, n_local)
+        o_ref = oracle.sparse_attn(np.ascontiguousarray(w.q[b, 0]), w.k_pool, w.v_pool, w.dtype, w.H_kv, w.P, w.pages_of(b),
+                                   att, len(att), float(np.float32(1.0 / math.sqrt(w.D))))
+        tol = 2e-2 if w.dtype == W.BF16 else 1e-4
+        assert np.abs(W.as_f32(out_g[b, 0], w.dtype).astype(np.float64) - o_ref).max() <= tol, (lab, "attention")
+    return strict
+
+
+SHAPES = [
+    (W.F32, 8, 2, 64, 16, [4096], 256),                 # config 1's shape
+    (W.BF16, 32, 8, 128, 16, [5000], 300),              # config 2's head shapes
+    (W.BF16, 28, 4, 128, 16, [2500], 128),              # group of seven
+    (W.BF16, 8, 2, 128, 16, [0, 1, 31, 2049, 700, 15, 4100], 40),   # ragged batch, several 2048-token chunks
+    (W.BF16, 6, 2, 64, 4, [450], 600),                  # k larger than the sequence
+]
+
+
+@pytest.mark.parametrize("kind", ["sum", "head"])
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "dt%d_H%d_%d_D%d_P%d_k%d" % (s[0], s[1], s[2], s[3], s[4], s[6]))
+def test_selection_variants(gpu, kind, shape):
+    dtype, H, H_kv, D, P, lens, k = shape
+    print("variant", kind, shape, flush=True)
+    w = W.make_workload("var", dtype=dtype, B=len(lens), H=H, H_kv=H_kv, D=D, P=P, seq_lens=lens, k=k, beta=3.0,
+                        planted_per_head=0, seed=sum(lens) + H)
+    check_variant(w, kind, label=str(shape))
+
+
+@pytest.mark.parametrize("kind", ["sum", "head"])
+def test_selection_variants_with_forced_tokens_and_ties(gpu, kind):
+    w = W.make_workload("varf", dtype=W.BF16, B=3, H=8, H_kv=2, D=128, P=16, seq_lens=[3000, 200, 700], k=64, seed=77)
+    check_variant(w, kind, n_init=16, n_local=100, label="forced")
+    # a zero query: all scores equal -> every head takes the first k tokens (lower index wins), votes = H there
+    w0 = W.make_workload("var0", dtype=W.F32, H=4, H_kv=2, D=64, P=16, seq_lens=[500], k=20, seed=78)
+    w0.q[:] = 0
+    check_variant(w0, kind, label="zero query")
