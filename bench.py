@@ -44,12 +44,14 @@ def parse():
     ap.add_argument("--score-wg", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tokens", type=int, default=0, help="override the number of cached tokens (profiling only)")
+    ap.add_argument("--selection", choices=["soft", "sum", "head"], default="soft",
+                    help="selection function: soft = Eq. 5 (the method, default), sum = Eq. 3, head = Eq. 4 (ablation baselines)")
     ap.add_argument("--n-init", type=int, default=0, help="forced initial tokens (the paper's runs use 128); default 0 as in the configurations")
     ap.add_argument("--n-local", type=int, default=0, help="forced most recent tokens (the paper's runs use 512); default 0")
     return ap.parse_args()
 
 
-def cpu_baseline(w, budget_s=12.0):
+def cpu_baseline(w, budget_s=12.0, n_init=0, n_local=0):
     """The oracle as it stands, timed on this host for whole decode steps of the same workload."""
     import oracle
     N = int(w.seq_lens[0])
@@ -59,8 +61,9 @@ def cpu_baseline(w, budget_s=12.0):
     t_all = time.perf_counter()
     while True:
         t0 = time.perf_counter()
-        idx, cnt = oracle.select(qb, w.k_pool, w.dtype, w.H_kv, w.P, w.pages_of(0), N, w.k)
-        oracle.sparse_attn(qb, w.k_pool, w.v_pool, w.dtype, w.H_kv, w.P, w.pages_of(0), idx, cnt, sm)
+        idx, cnt = oracle.select(qb, w.k_pool, w.dtype, w.H_kv, w.P, w.pages_of(0), N, w.k, n_init=n_init, n_local=n_local)
+        att = oracle.attended_tokens(idx, cnt, N, n_init, n_local)
+        oracle.sparse_attn(qb, w.k_pool, w.v_pool, w.dtype, w.H_kv, w.P, w.pages_of(0), att, len(att), sm)
         times.append(time.perf_counter() - t0)
         if time.perf_counter() - t_all > budget_s or len(times) >= 50:
             break
@@ -246,6 +249,10 @@ def main():
         layer.swap_pool(kp, vp, pi)
         problems.append(layer.problem)
     stream = torch.cuda.current_stream()
+    hv_scratch = None
+    if args.selection == "head":
+        nb = ts.ts_head_vote_scratch_bytes(layer.problem)
+        hv_scratch = torch.empty((nb + 255) // 256 * 64, dtype=torch.int32, device=dev)
 
     def step(i, ev=None):
         p = problems[i % R]
@@ -256,7 +263,12 @@ def main():
         ts.ts_paged_qk_scores(p, q, layer.scores, scale, layer.reuse, layer.ws, stream)
         if ev is not None:
             ev[1].record(stream)
-        ts.ts_soft_vote(p, layer.scores, scale, layer.row_stats, layer.votes, layer.reuse, layer.ws, stream)
+        if args.selection == "soft":
+            ts.ts_soft_vote(p, layer.scores, scale, layer.row_stats, layer.votes, layer.reuse, layer.ws, stream)
+        elif args.selection == "sum":
+            ts.ts_sum_vote(p, layer.scores, layer.votes, layer.reuse, stream)
+        else:
+            ts.ts_head_vote(p, layer.scores, layer.k, layer.votes, layer.reuse, hv_scratch, stream)
         ts.ts_topk(p, layer.votes, layer.k, layer.idx, layer.count, layer.reuse, layer.ws, stream)
         ts.ts_sparse_paged_attn(p, q, layer.idx, layer.k, layer.count, sm, layer.out, layer.lse, layer.ws, stream)
 
@@ -266,13 +278,19 @@ def main():
         kp, vp, pi = pools[r]
         layer.swap_pool(kp, vp, pi)
         layer.first.fill_(1)
-        layer.step(qs[0], theta=theta, score_scale=scale, sm_scale=sm)
+        layer.select(qs[0], scale, None, kind=args.selection)
         torch.cuda.synchronize()
         got = to_host(layer.idx).copy()
         if ref_idx is None:
             ref_idx = got
         assert np.array_equal(got, ref_idx), "selection changed with the physical page layout"
     layer.first.fill_(1)
+    # planted critical tokens among the selected ones (the workload's own query, first pool copy)
+    planted = set(np.concatenate(list(w.planted[0])).tolist()) if len(w.planted) and w.planted[0].size else set()
+    sel_set = set(ref_idx[0][ref_idx[0] >= 0].tolist())
+    quality = {"planted_tokens": len(planted), "selected": len(sel_set),
+               "precision": len(sel_set & planted) / max(1, len(sel_set)),
+               "recall": len(sel_set & planted) / max(1, len(planted))}
 
     for i in range(args.warmup):
         step(i)
@@ -301,7 +319,10 @@ def main():
         "config": {"workload": w.name, "batch": w.B, "cached_tokens": N, "num_q_heads": w.H, "num_kv_heads": w.H_kv,
                    "head_dim": w.D, "page_size": w.P, "k": w.k, "score_scale": scale, "theta": theta,
                    "pool_copies_rotated": R, "selection_cache": "every step is a miss",
-                   "forced_initial_tokens": args.n_init, "forced_recent_tokens": args.n_local},
+                   "forced_initial_tokens": args.n_init, "forced_recent_tokens": args.n_local,
+                   "selection_function": {"soft": "Eq. 5 head soft vote", "sum": "Eq. 3 summed dot products",
+                                          "head": "Eq. 4 head vote"}[args.selection]},
+        "planted_token_quality": quality,
         "decode_steps_per_s": 1e3 / ms_step,
         "roofline": {"bound": "hbm", "kernel": "ts::score_decode_kernel (the one launch of ts_paged_qk_scores)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
@@ -312,7 +333,7 @@ def main():
                      "score_pass_tokens_per_s": N / (score_avg_ms * 1e-3)},
     }
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(w)
+        res["cpu_baseline"] = cpu_baseline(w, n_init=args.n_init, n_local=args.n_local)
     print(json.dumps(res))
 
 
