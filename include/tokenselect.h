@@ -193,6 +193,12 @@ int32_t ts_chunk_mean_query(const ts_problem* p, const void* q, void* q_mean, vo
  * Host only. */
 int32_t ts_debug_set_score_variant(int32_t variant, int32_t wg, int32_t run_tiles);
 
+/* Tuning knob (process-wide, tests and benchmarks): five_pass = 1 makes ts_topk / ts_head_vote use the
+ * five-pass radix select (three global histogram passes, count, emit) that otherwise only serves sequences
+ * beyond 16 Mi tokens; 0 (default) = histogram pass, compaction of the candidates, one finishing workgroup
+ * per sequence.  Both give the same result.  Host only. */
+int32_t ts_debug_set_topk_path(int32_t five_pass);
+
 #ifdef __cplusplus
 }
 #endif

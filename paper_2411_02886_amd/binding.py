@@ -76,10 +76,11 @@ def load():
         L.ts_head_vote_scratch_bytes.argtypes = [pp, ctypes.POINTER(sz)]
         L.ts_head_vote.argtypes = [pp, vp, i32, vp, vp, vp, sz, vp]
         L.ts_debug_set_score_variant.argtypes = [i32, i32, i32]
+        L.ts_debug_set_topk_path.argtypes = [i32]
         for name in ("ts_workspace_bytes", "ts_workspace_init", "ts_paged_qk_scores", "ts_soft_vote", "ts_topk",
                      "ts_selcache_check", "ts_sparse_paged_attn", "ts_debug_set_score_variant", "ts_chunk_row_stats",
                      "ts_chunk_soft_vote", "ts_chunk_mean_query", "ts_sum_vote", "ts_head_vote_scratch_bytes",
-                     "ts_head_vote"):
+                     "ts_head_vote", "ts_debug_set_topk_path"):
             getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -135,6 +136,10 @@ def ts_workspace_init(ws, stream=None) -> None:
 
 def ts_debug_set_score_variant(variant: int, wg: int = 0, run_tiles: int = 0) -> None:
     _ok(load().ts_debug_set_score_variant(int(variant), int(wg), int(run_tiles)), "ts_debug_set_score_variant")
+
+
+def ts_debug_set_topk_path(five_pass: int) -> None:
+    _ok(load().ts_debug_set_topk_path(int(five_pass)), "ts_debug_set_topk_path")
 
 
 def _nbytes(ws) -> int:

@@ -10,6 +10,7 @@ __global__ void fill_zero_kernel(uint32_t* p, size_t n) {
 static int g_score_variant = 1;   // 0 = fma, 1 = packed bf16 dot2 (tuning knob, see ts_debug_set_score_variant)
 static int g_score_wg = 0;        // 0 = automatic
 static int g_score_rr = 0;        // tiles per staged run; 0 = automatic
+static int g_topk_five_pass = 0;  // 1 = force the five-pass radix select (tuning knob)
 
 // workgroups per sequence of the score pass (also the number of statistics partials it leaves)
 // Tiles a wave of the score pass stages before writing them out: longer runs make the score stores
@@ -121,6 +122,12 @@ int32_t ts_debug_set_score_variant(int32_t variant, int32_t wg, int32_t run_tile
   return TS_OK;
 }
 
+int32_t ts_debug_set_topk_path(int32_t five_pass) {
+  if (five_pass != 0 && five_pass != 1) return TS_ERR_INVALID_ARG;
+  g_topk_five_pass = five_pass;
+  return TS_OK;
+}
+
 int32_t ts_paged_qk_scores(const ts_problem* p, const void* q, float* scores, float score_scale,
                            const uint8_t* skip, void* ws, size_t ws_bytes, void* stream) {
   int32_t st = check_problem(p);
@@ -183,6 +190,7 @@ int32_t ts_topk(const ts_problem* p, const float* votes, int32_t k, int32_t* idx
   a.hist = (uint32_t*)((uint8_t*)ws + w.topk_hist);
   a.state = (uint32_t*)((uint8_t*)ws + w.topk_state);
   a.blk = (uint32_t*)((uint8_t*)ws + w.topk_blk);
+  a.list = g_topk_five_pass ? nullptr : (uint2*)((uint8_t*)ws + w.topk_list);
   a.k = k; a.max_seq_len = p->max_seq_len; a.nblk = w.topk_nblk; a.heads = 1;
   return launch_topk(a, p->batch, (hipStream_t)stream) == hipSuccess ? TS_OK : TS_ERR_HIP;
 }
@@ -201,7 +209,7 @@ int32_t ts_sum_vote(const ts_problem* p, const float* scores, float* votes, cons
 }
 
 // scratch of ts_head_vote: transposed scores, then histograms / state / chunk counts of B * H radix selects
-struct HeadVoteLayout { size_t st, hist, state, blk, total; int nblk; };
+struct HeadVoteLayout { size_t st, hist, state, blk, list, total; int nblk; };
 static HeadVoteLayout head_vote_layout(const ts_problem* p) {
   HeadVoteLayout l{};
   const size_t V = (size_t)p->batch * p->num_q_heads;
@@ -212,6 +220,7 @@ static HeadVoteLayout head_vote_layout(const ts_problem* p) {
   l.hist = take(V * 3 * kTopkBins * 4);
   l.state = take(V * 8 * 4);
   l.blk = take(V * (size_t)l.nblk * 4);
+  l.list = take(V * (size_t)l.nblk * kTopkChunk * 8);
   l.total = off;
   return l;
 }
@@ -250,6 +259,7 @@ int32_t ts_head_vote(const ts_problem* p, const float* scores, int32_t k_head, f
   a.head = p->num_initial; a.tail = p->num_local;
   a.votes = (const float*)(base + l.st); a.seq_lens = p->seq_lens; a.skip = skip;
   a.hist = (uint32_t*)(base + l.hist); a.state = (uint32_t*)(base + l.state); a.blk = (uint32_t*)(base + l.blk);
+  a.list = g_topk_five_pass ? nullptr : (uint2*)(base + l.list);
   a.k = k_head; a.max_seq_len = p->max_seq_len; a.nblk = l.nblk; a.heads = p->num_q_heads; a.vote_acc = votes;
   return launch_topk(a, p->batch * p->num_q_heads, s) == hipSuccess ? TS_OK : TS_ERR_HIP;
 }

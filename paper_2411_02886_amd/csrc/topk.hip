@@ -273,9 +273,232 @@ __global__ __launch_bounds__(256) void topk_emit_kernel(TopkArgs a) {
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Short path (3 launches): after pass 0 every chunk compacts, in token order, the keys that fall in or above
+// the bin of the k-th key (the winners for sure plus the few candidates that share its bin; typically k plus a
+// few hundred entries in all), and one workgroup per sequence finishes the job on that list: two more radix
+// digits over the candidates in LDS histograms, then the ordered emit.  Same result as the five-pass form.
+
+constexpr int kFinalThreads = 1024;
+constexpr int kFinalPer = 8;               // consecutive list entries per thread and batch
+constexpr int kFinalMaxBlk = 8192;         // chunks per sequence the short path handles (16 Mi tokens)
+
+// pass 1 of the short path: fix digit 0, compact the entries with (key >> 21) >= digit 0
+__global__ __launch_bounds__(256) void topk_compact_kernel(TopkArgs a) {
+  __shared__ uint32_t lds[8];
+  __shared__ uint32_t scan_lds[8];
+  const int b = blockIdx.y;
+  if (a.skip != nullptr && a.skip[b / a.heads] != 0) return;
+  const int LO = ranked_lo(a, b), N = ranked_hi(a, b, LO);
+  const uint32_t k_eff = (uint32_t)min(a.k, N - LO);
+  uint32_t d0, krem0;
+  find_digit<kTopkBins>(a.hist + ((size_t)b * 3 + 0) * kTopkBins, k_eff, &d0, &krem0, lds);
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    a.state[b * 8 + ST_PREFIX0] = d0 << 21; a.state[b * 8 + ST_KREM0] = krem0; a.state[b * 8 + ST_KEFF] = k_eff;
+  }
+  constexpr int PER = kTopkChunk / 256;
+  const int base = blockIdx.x * kTopkChunk;
+  const int t0 = base + threadIdx.x * PER;   // PER consecutive tokens per thread: order is preserved
+  const float* v = a.votes + (size_t)b * a.max_seq_len;
+  uint32_t key[PER];
+  uint32_t n = 0;
+#pragma unroll
+  for (int e = 0; e < PER; ++e) {
+    const bool valid = (t0 + e) >= LO && (t0 + e) < N;
+    key[e] = valid ? float_key(v[t0 + e]) : 0u;
+    n += valid && (key[e] >> 21) >= d0;      // d0 == kTopkBins (empty selection) matches nothing
+  }
+  uint32_t total;
+  uint32_t pos = block_exclusive_scan(n, &total, scan_lds);
+  uint2* list = a.list + ((size_t)b * a.nblk + blockIdx.x) * kTopkChunk;
+#pragma unroll
+  for (int e = 0; e < PER; ++e) {
+    const bool valid = (t0 + e) >= LO && (t0 + e) < N;
+    if (valid && (key[e] >> 21) >= d0) list[pos++] = make_uint2(key[e], (uint32_t)(t0 + e));
+  }
+  if (threadIdx.x == 0) a.blk[(size_t)b * a.nblk + blockIdx.x] = total;
+}
+
+// exclusive prefix sum over the kFinalThreads threads of the final workgroup
+__device__ __forceinline__ uint32_t final_exclusive_scan(uint32_t v, uint32_t* total, uint32_t* lds /* >= 16 words */) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint32_t incl = v;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t o = __shfl_up(incl, off);
+    if (lane >= off) incl += o;
+  }
+  __syncthreads();
+  if (lane == 63) lds[wave] = incl;
+  __syncthreads();
+  uint32_t base = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < kFinalThreads / 64; ++w) {
+    const uint32_t x = lds[w];
+    if (w < wave) base += x;
+    tot += x;
+  }
+  *total = tot;
+  return base + incl - v;
+}
+
+// digit of the k_rem-th largest key in an LDS histogram of NB bins (all threads get the result)
+template <int NB>
+__device__ __forceinline__ void final_find_digit(const uint32_t* h, uint32_t k_rem, uint32_t* digit, uint32_t* k_next,
+                                                 uint32_t* scan_lds, uint32_t* res /* 2 words */) {
+  constexpr int PER = NB / kFinalThreads;   // 2 or 1
+  uint32_t c[PER];
+  uint32_t sum = 0;
+#pragma unroll
+  for (int e = 0; e < PER; ++e) { c[e] = h[NB - 1 - (threadIdx.x * PER + e)]; sum += c[e]; }
+  uint32_t total;
+  uint32_t above = final_exclusive_scan(sum, &total, scan_lds);
+  if (threadIdx.x == 0) { res[0] = NB; res[1] = 0u; }
+  __syncthreads();
+  if (k_rem != 0) {
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+      if (above < k_rem && k_rem <= above + c[e]) { res[0] = NB - 1 - (threadIdx.x * PER + e); res[1] = k_rem - above; }
+      above += c[e];
+    }
+  }
+  __syncthreads();
+  *digit = res[0];
+  *k_next = res[1];
+  __syncthreads();
+}
+
+// passes 2, 3 and the emit of the short path: one workgroup per (virtual) sequence
+__global__ __launch_bounds__(kFinalThreads) void topk_final_kernel(TopkArgs a) {
+  __shared__ uint32_t off[kFinalMaxBlk + 1];   // exclusive prefix of the chunks' entry counts
+  __shared__ uint32_t h[kTopkBins];
+  __shared__ uint32_t scan_lds[16];
+  __shared__ uint32_t res[2];
+  const int b = blockIdx.x;
+  if (a.skip != nullptr && a.skip[b / a.heads] != 0) return;
+  const int tid = threadIdx.x;
+  const uint32_t d0 = a.state[b * 8 + ST_PREFIX0] >> 21, krem0 = a.state[b * 8 + ST_KREM0];
+  const int k_eff = (int)a.state[b * 8 + ST_KEFF];
+  const bool as_votes = a.vote_acc != nullptr;
+  int32_t* out = as_votes ? nullptr : a.idx + (size_t)b * a.k;
+  float* acc = as_votes ? a.vote_acc + (size_t)(b / a.heads) * a.max_seq_len : nullptr;
+  if (!as_votes) {
+    for (int i = k_eff + tid; i < a.k; i += kFinalThreads) out[i] = -1;
+    if (tid == 0) a.count[b] = k_eff;
+  }
+  {  // histogram 0 has been consumed by the compact pass: leave it zeroed for the next call
+    uint32_t* g0 = a.hist + ((size_t)b * 3 + 0) * kTopkBins;
+    for (int i = tid; i < kTopkBins; i += kFinalThreads) g0[i] = 0u;
+  }
+  // ---- chunk offsets
+  uint32_t carry = 0;
+  for (int c0 = 0; c0 < a.nblk; c0 += kFinalThreads) {
+    const int c = c0 + tid;
+    const uint32_t n = c < a.nblk ? a.blk[(size_t)b * a.nblk + c] : 0u;
+    uint32_t tot;
+    const uint32_t ex = final_exclusive_scan(n, &tot, scan_lds);
+    if (c < a.nblk) off[c] = carry + ex;
+    carry += tot;
+    __syncthreads();
+  }
+  const uint32_t total = carry;
+  if (tid == 0) off[a.nblk] = total;
+  __syncthreads();
+  if (total == 0 || k_eff == 0) return;
+  const uint2* list = a.list + (size_t)b * a.nblk * kTopkChunk;
+
+  // entries of a batch: thread tid owns the kFinalPer consecutive positions from p0
+  auto load_batch = [&](uint32_t base, uint2 (&e)[kFinalPer]) {
+    const uint32_t p0 = base + (uint32_t)tid * kFinalPer;
+    int c = 0;
+    if (p0 < total) {                         // chunk with off[c] <= p0 < off[c + 1]
+      int lo = 0, hi = a.nblk;                // invariant: off[lo] <= p0 < off[hi]
+      while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if (off[mid] <= p0) lo = mid; else hi = mid; }
+      c = lo;
+    }
+#pragma unroll
+    for (int i = 0; i < kFinalPer; ++i) {
+      const uint32_t p = p0 + i;
+      e[i] = make_uint2(0u, 0xffffffffu);
+      if (p < total) {
+        while (p >= off[c + 1]) ++c;          // ends: p < total = off[nblk]
+        e[i] = list[(size_t)c * kTopkChunk + (p - off[c])];
+      }
+    }
+  };
+  const bool single = total <= (uint32_t)kFinalThreads * kFinalPer;   // the usual case: the list sits in registers
+  uint2 e[kFinalPer];
+  if (single) load_batch(0, e);
+
+  // ---- digit 1: bits 20..10 of the candidates (entries of bin d0)
+  for (int i = tid; i < kTopkBins; i += kFinalThreads) h[i] = 0u;
+  __syncthreads();
+  for (uint32_t base = 0; base < total; base += kFinalThreads * kFinalPer) {
+    if (!single) load_batch(base, e);
+#pragma unroll
+    for (int i = 0; i < kFinalPer; ++i)
+      if (e[i].y != 0xffffffffu && (e[i].x >> 21) == d0) atomicAdd(&h[(e[i].x >> 10) & 2047u], 1u);
+  }
+  __syncthreads();
+  uint32_t d1, krem1;
+  final_find_digit<kTopkBins>(h, krem0, &d1, &krem1, scan_lds, res);
+  const uint32_t prefix1 = (d0 << 21) | ((d1 & 2047u) << 10);
+  // ---- digit 2: the last 10 bits
+  for (int i = tid; i < 1024; i += kFinalThreads) h[i] = 0u;
+  __syncthreads();
+  for (uint32_t base = 0; base < total; base += kFinalThreads * kFinalPer) {
+    if (!single) load_batch(base, e);
+#pragma unroll
+    for (int i = 0; i < kFinalPer; ++i)
+      if (e[i].y != 0xffffffffu && (e[i].x >> 10) == (prefix1 >> 10)) atomicAdd(&h[e[i].x & 1023u], 1u);
+  }
+  __syncthreads();
+  uint32_t d2, need_eq;
+  final_find_digit<1024>(h, krem1, &d2, &need_eq, scan_lds, res);
+  const uint32_t thr = prefix1 | (d2 & 1023u);
+  // ---- emit in token order: every key above the threshold, and the first need_eq keys equal to it
+  uint32_t gt_done = 0, eq_done = 0;
+  for (uint32_t base = 0; base < total; base += kFinalThreads * kFinalPer) {
+    if (!single) load_batch(base, e);
+    uint32_t gt = 0, eq = 0;
+#pragma unroll
+    for (int i = 0; i < kFinalPer; ++i) {
+      const bool valid = e[i].y != 0xffffffffu;
+      gt += valid && e[i].x > thr;
+      eq += valid && e[i].x == thr;
+    }
+    uint32_t tot;
+    const uint32_t ex = final_exclusive_scan(gt | (eq << 16), &tot, scan_lds);   // a batch holds 8192 entries: 14 bits each
+    uint32_t gt_before = gt_done + (ex & 0xffffu), eq_before = eq_done + (ex >> 16);
+#pragma unroll
+    for (int i = 0; i < kFinalPer; ++i) {
+      if (e[i].y == 0xffffffffu) continue;
+      const int t = (int)e[i].y;
+      if (e[i].x > thr) {
+        if (as_votes) atomicAdd(&acc[t], 1.0f);
+        else out[gt_before + min(eq_before, need_eq)] = t;
+        ++gt_before;
+      } else if (e[i].x == thr) {
+        if (eq_before < need_eq) {
+          if (as_votes) atomicAdd(&acc[t], 1.0f);
+          else out[gt_before + eq_before] = t;
+        }
+        ++eq_before;
+      }
+    }
+    gt_done += tot & 0xffffu; eq_done += tot >> 16;
+    __syncthreads();
+  }
+}
+
 hipError_t launch_topk(const TopkArgs& a, int B, hipStream_t s) {
   dim3 grid(a.nblk, B);
   hipLaunchKernelGGL(topk_hist0_kernel, grid, dim3(256), 0, s, a);
+  if (a.list != nullptr && a.nblk <= kFinalMaxBlk) {
+    hipLaunchKernelGGL(topk_compact_kernel, grid, dim3(256), 0, s, a);
+    hipLaunchKernelGGL(topk_final_kernel, dim3(B), dim3(kFinalThreads), 0, s, a);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(topk_hist1_kernel, grid, dim3(256), 0, s, a);
   hipLaunchKernelGGL(topk_hist2_kernel, grid, dim3(256), 0, s, a);
   hipLaunchKernelGGL(topk_count_kernel, grid, dim3(256), 0, s, a);

@@ -21,7 +21,8 @@ struct WsLayout {
   size_t topk_hist;        // uint32 [B][3][kTopkBins] : one histogram per radix pass (must start zeroed)
   size_t topk_state;       // uint32 [B][8] : digits and remaining ranks fixed so far
   size_t score_partials;   // float [B][kScoreMaxWg][H][2]
-  size_t topk_blk;         // uint32 [B][nblk] : per-chunk (above | equal << 16) counts
+  size_t topk_blk;         // uint32 [B][nblk] : per-chunk counts
+  size_t topk_list;        // uint2 [B][nblk][kTopkChunk] : compacted (key, token) entries of the short top-k path
   size_t attn_out;         // float [B][H][nsplit][D]
   size_t attn_ml;          // float [B][H][nsplit][2]
   size_t pf_stat_part;     // float [B][TS][C][H][2]            (chunk > 1 only)
@@ -49,6 +50,7 @@ inline WsLayout ws_layout(const ts_problem* p, int k) {
   w.topk_state = take(B * 8 * 4);
   w.score_partials = take(B * kScoreMaxWg * H * 2 * 4);
   w.topk_blk = take(B * (size_t)w.topk_nblk * 4);
+  w.topk_list = take(B * (size_t)w.topk_nblk * kTopkChunk * 8);
   if (p->chunk > 1) {
     const int G = p->num_q_heads / p->num_kv_heads;
     w.pf_rb = (p->chunk * G + 255) / 256;

@@ -47,6 +47,7 @@ struct TopkArgs {
   uint32_t* hist;       // [B][3][kTopkBins]
   uint32_t* state;      // [B][8]
   uint32_t* blk;        // [B][nblk]
+  uint2* list;          // [B][nblk][kTopkChunk] (key, token) entries of the short path; nullptr = five-pass form
   int k, max_seq_len, nblk;
   int heads;            // virtual sequences per real one (Eq. 4: one per head over transposed scores); 1 = plain
   float* vote_acc;      // Eq. 4: the emit pass adds 1 to vote_acc[real sequence][t] for every winner instead of writing idx

@@ -151,6 +151,43 @@ def test_ties_go_to_lower_index_and_zero_query(gpu):
     assert to_host(layer.idx)[0].tolist() == list(range(10))
 
 
+def test_topk_with_more_tied_candidates_than_one_batch(gpu):
+    # a zero query over 20000 tokens: every vote is equal, all tokens share the k-th key's bin, so the finishing
+    # workgroup of the short top-k path walks its list in several batches; the first k tokens must win
+    from paper_2411_02886_amd.runtime import to_host
+    w = W.make_workload("ties20k", dtype=W.BF16, B=2, H=8, H_kv=2, D=128, P=16, seq_lens=[20000, 9000], k=300, seed=33)
+    w.q[:] = 0
+    layer, q = make_layer(w)
+    check_decode_against_oracle(w, layer, q, score_scale=1.0, label="zero query 20k")
+    assert to_host(layer.idx)[0].tolist() == list(range(300)) and to_host(layer.idx)[1].tolist() == list(range(300))
+    # half of the tokens get one duplicated K row: thousands of exact ties around the threshold
+    w = W.make_workload("ties20k2", dtype=W.BF16, H=8, H_kv=2, D=128, P=16, seq_lens=[20000], k=6000, seed=34)
+    kl = w.k_pool.reshape(-1, w.H_kv, w.D); slots = w.slots_of(0)
+    kl[slots[1::2]] = kl[slots[1]]
+    layer, q = make_layer(w)
+    check_decode_against_oracle(w, layer, q, score_scale=0.05, label="many ties 20k")
+
+
+def test_five_pass_topk_path_gives_the_same_result(gpu):
+    # the five-pass radix select (kept for sequences beyond 16 Mi tokens) forced on small inputs
+    from paper_2411_02886_amd.runtime import to_host
+    gpu.ts_debug_set_topk_path(1)
+    try:
+        for shape in [(W.BF16, 32, 8, 128, 16, [5000], 300), (W.F32, 8, 2, 64, 4, [0, 1, 31, 2049, 700, 4100], 33)]:
+            dtype, H, H_kv, D, P, lens, k = shape
+            print("five-pass", shape, flush=True)
+            w = W.make_workload("fp", dtype=dtype, B=len(lens), H=H, H_kv=H_kv, D=D, P=P, seq_lens=lens, k=k, seed=sum(lens))
+            layer, q = make_layer(w)
+            check_decode_against_oracle(w, layer, q, score_scale=1.0 / math.sqrt(D), label="five-pass %s" % (shape,))
+        w = W.make_workload("fp0", dtype=W.F32, H=4, H_kv=2, D=64, P=16, seq_lens=[5000], k=10, seed=35)
+        w.q[:] = 0
+        layer, q = make_layer(w)
+        check_decode_against_oracle(w, layer, q, score_scale=1.0, label="five-pass zero query")
+        assert to_host(layer.idx)[0].tolist() == list(range(10))
+    finally:
+        gpu.ts_debug_set_topk_path(0)
+
+
 def test_k_larger_than_n_equals_full_attention(gpu):
     w = W.make_workload("full", dtype=W.F32, H=8, H_kv=2, D=64, P=16, seq_lens=[150], k=256, seed=41)
     layer, q = make_layer(w)
