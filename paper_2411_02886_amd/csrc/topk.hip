@@ -279,8 +279,8 @@ __global__ __launch_bounds__(256) void topk_emit_kernel(TopkArgs a) {
 // few hundred entries in all), and one workgroup per sequence finishes the job on that list: two more radix
 // digits over the candidates in LDS histograms, then the ordered emit.  Same result as the five-pass form.
 
-constexpr int kFinalThreads = 1024;
-constexpr int kFinalPer = 8;               // consecutive list entries per thread and batch
+constexpr int kFinalThreads = 1024;        // many threads, few entries each: the per-entry chain of a thread is the latency
+                                           // that counts (256 threads x 32 entries measured 1.7x slower)
 constexpr int kFinalMaxBlk = 8192;         // chunks per sequence the short path handles (16 Mi tokens)
 
 // pass 1 of the short path: fix digit 0, compact the entries with (key >> 21) >= digit 0
@@ -346,7 +346,7 @@ __device__ __forceinline__ uint32_t final_exclusive_scan(uint32_t v, uint32_t* t
 template <int NB>
 __device__ __forceinline__ void final_find_digit(const uint32_t* h, uint32_t k_rem, uint32_t* digit, uint32_t* k_next,
                                                  uint32_t* scan_lds, uint32_t* res /* 2 words */) {
-  constexpr int PER = NB / kFinalThreads;   // 2 or 1
+  constexpr int PER = NB / kFinalThreads;
   uint32_t c[PER];
   uint32_t sum = 0;
 #pragma unroll
@@ -369,6 +369,7 @@ __device__ __forceinline__ void final_find_digit(const uint32_t* h, uint32_t k_r
 }
 
 // passes 2, 3 and the emit of the short path: one workgroup per (virtual) sequence
+template <int kFinalPer>                   // consecutive list entries per thread and batch
 __global__ __launch_bounds__(kFinalThreads) void topk_final_kernel(TopkArgs a) {
   __shared__ uint32_t off[kFinalMaxBlk + 1];   // exclusive prefix of the chunks' entry counts
   __shared__ uint32_t h[kTopkBins];
@@ -416,13 +417,14 @@ __global__ __launch_bounds__(kFinalThreads) void topk_final_kernel(TopkArgs a) {
       while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if (off[mid] <= p0) lo = mid; else hi = mid; }
       c = lo;
     }
+    uint32_t cur = off[c], next = off[c + 1];
 #pragma unroll
     for (int i = 0; i < kFinalPer; ++i) {
       const uint32_t p = p0 + i;
       e[i] = make_uint2(0u, 0xffffffffu);
       if (p < total) {
-        while (p >= off[c + 1]) ++c;          // ends: p < total = off[nblk]
-        e[i] = list[(size_t)c * kTopkChunk + (p - off[c])];
+        while (p >= next) { ++c; cur = next; next = off[c + 1]; }   // ends: p < total = off[nblk]
+        e[i] = list[(size_t)c * kTopkChunk + (p - cur)];
       }
     }
   };
@@ -468,7 +470,7 @@ __global__ __launch_bounds__(kFinalThreads) void topk_final_kernel(TopkArgs a) {
       eq += valid && e[i].x == thr;
     }
     uint32_t tot;
-    const uint32_t ex = final_exclusive_scan(gt | (eq << 16), &tot, scan_lds);   // a batch holds 8192 entries: 14 bits each
+    const uint32_t ex = final_exclusive_scan(gt | (eq << 16), &tot, scan_lds);   // a batch holds at most 8192 entries: 14 bits each half
     uint32_t gt_before = gt_done + (ex & 0xffffu), eq_before = eq_done + (ex >> 16);
 #pragma unroll
     for (int i = 0; i < kFinalPer; ++i) {
@@ -496,7 +498,9 @@ hipError_t launch_topk(const TopkArgs& a, int B, hipStream_t s) {
   hipLaunchKernelGGL(topk_hist0_kernel, grid, dim3(256), 0, s, a);
   if (a.list != nullptr && a.nblk <= kFinalMaxBlk) {
     hipLaunchKernelGGL(topk_compact_kernel, grid, dim3(256), 0, s, a);
-    hipLaunchKernelGGL(topk_final_kernel, dim3(B), dim3(kFinalThreads), 0, s, a);
+    // the list holds about k entries plus the few that share the k-th key's bin: one batch in the usual case
+    if (a.k <= 3072) hipLaunchKernelGGL(topk_final_kernel<4>, dim3(B), dim3(kFinalThreads), 0, s, a);
+    else hipLaunchKernelGGL(topk_final_kernel<8>, dim3(B), dim3(kFinalThreads), 0, s, a);
     return hipGetLastError();
   }
   hipLaunchKernelGGL(topk_hist1_kernel, grid, dim3(256), 0, s, a);
