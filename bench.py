@@ -44,6 +44,10 @@ def parse():
     ap.add_argument("--score-wg", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tokens", type=int, default=0, help="override the number of cached tokens (profiling only)")
+    ap.add_argument("--theta", type=float, default=0.9, help="Selection Cache threshold of the config-3 run")
+    ap.add_argument("--theta-sweep", action="store_true",
+                    help="config 3: also run the thresholds of the paper's theta study (0.5 ... 1.0) and report reuse rate and steps/s for each")
+    ap.add_argument("--page-size", type=int, default=16, help="tokens per page (16 in the configurations; 1 is the paper's own setting)")
     ap.add_argument("--selection", choices=["soft", "sum", "head"], default="soft",
                     help="selection function: soft = Eq. 5 (the method, default), sum = Eq. 3, head = Eq. 4 (ablation baselines)")
     ap.add_argument("--n-init", type=int, default=0, help="forced initial tokens (the paper's runs use 128); default 0 as in the configurations")
@@ -97,10 +101,10 @@ def selection_cache_run(args):
     slots_d = torch.from_numpy(slots).to(dev)
     kflat = layer.k_pool.view(-1, w.H_kv, w.D); vflat = layer.v_pool.view(-1, w.H_kv, w.D)
     len0 = layer.seq_lens.clone()
-    sm, theta, scale = 1.0 / math.sqrt(w.D), 0.9, 1.0
+    sm, theta, scale = 1.0 / math.sqrt(w.D), args.theta, 1.0
     reuse_log = torch.zeros((steps, w.B), dtype=torch.uint8, device=dev)
 
-    def run():
+    def run(theta=theta):
         layer.seq_lens.copy_(len0); layer.first.fill_(1)
         for t in range(steps):
             kflat.index_copy_(0, slots_d[t], ksd[t]); vflat.index_copy_(0, slots_d[t], vsd[t])   # append this step's K/V rows
@@ -128,7 +132,17 @@ def selection_cache_run(args):
                       "forced_initial_tokens": args.n_init, "forced_recent_tokens": args.n_local},
            "reuse_rate": float(reuse.mean()), "sequence_steps_per_s": steps * w.B / dt,
            "tokens_scanned_per_s": scanned / dt,
-           "note": "host-driven loop: 12 library launches + 4 torch launches per step, no graph capture"}
+           "note": "host-driven loop: 10 library launches + 4 torch launches per step, no graph capture"}
+    if args.theta_sweep:
+        sweep = []
+        for th in (0.5, 0.6, 0.7, 0.8, 0.85, 0.9, 0.95, 1.0):       # the thresholds of the paper's theta study
+            run(th); torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            run(th); torch.cuda.synchronize()
+            d = time.perf_counter() - t0
+            sweep.append({"theta": th, "reuse_rate": float(to_host(reuse_log).astype(bool).mean()),
+                          "batch_steps_per_s": steps / d})
+        res["theta_sweep"] = sweep
     print(json.dumps(res))
 
 
@@ -215,6 +229,8 @@ def main():
     ts.load()
     dev = "cuda:0"
     kw = {"N": args.tokens} if args.tokens else {}
+    if args.page_size != 16:
+        kw["P"] = args.page_size
     w = W.CONFIGS[args.config](**kw)
     N = int(w.seq_lens[0])
     if args.variant >= 0 or args.score_wg:
