@@ -29,7 +29,7 @@ import numpy as np  # noqa: E402
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the score kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what
 # the same counters read for plain copy kernels of known size (profiles/decode_step_cfg2_hbm_traffic.md)
-MEASURED_TRAFFIC_BYTES = {2: int((128.17 * 1.98 + 16.25 * 1.00) * 2**20)}
+MEASURED_TRAFFIC_BYTES = {2: int((128.15 * 1.98 + 16.25 * 1.00) * 2**20)}
 
 
 def parse():

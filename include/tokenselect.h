@@ -115,9 +115,14 @@ int32_t ts_soft_vote(const ts_problem* p, const float* scores, float score_scale
 /* TopK of Eq. 3-5 over votes[b][0..N_b): the min(k, N_b) largest values, equal values taken in
  * order of increasing token index, written as ascending logical token ids.
  * idx [device] int32 [B][k] (slots past the count are set to -1); count [device] int32 [B].
- * -0.0 compares equal to +0.0. */
+ * -0.0 compares equal to +0.0.
+ * flags: 0, or TS_TOPK_FLAT_VOTES.  By default (decode) the radix select runs as three launches whose last one
+ * finishes each sequence on one workgroup: fast when few votes lie within a quarter octave of the k-th vote, as
+ * with the peaked votes of Eq. 5, and slow (still exact) when most do.  TS_TOPK_FLAT_VOTES selects the five-launch
+ * form whose time does not depend on the distribution; chunk problems (chunk > 1) always use it. */
+#define TS_TOPK_FLAT_VOTES 1
 int32_t ts_topk(const ts_problem* p, const float* votes, int32_t k, int32_t* idx, int32_t* count,
-                const uint8_t* skip, void* ws, size_t ws_bytes, void* stream);
+                const uint8_t* skip, int32_t flags, void* ws, size_t ws_bytes, void* stream);
 
 /* The two selection functions the paper ablates against Eq. 5 (Sec. 5.1), as other ways to fill `votes`
  * from the scores of ts_paged_qk_scores; ts_topk then ranks them as usual (decode only, chunk == 1).

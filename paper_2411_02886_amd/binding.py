@@ -16,6 +16,7 @@ _LIB_PATH = os.path.join(_HERE, "libtokenselect.so")
 _HEADER = os.path.join(os.path.dirname(_HERE), "include", "tokenselect.h")
 
 TS_F32, TS_BF16 = 0, 1
+TS_TOPK_FLAT_VOTES = 1
 
 
 class TokenSelectError(RuntimeError):
@@ -66,7 +67,7 @@ def load():
         L.ts_workspace_init.argtypes = [vp, sz, vp]
         L.ts_paged_qk_scores.argtypes = [pp, vp, vp, f32, vp, vp, sz, vp]
         L.ts_soft_vote.argtypes = [pp, vp, f32, vp, vp, vp, vp, sz, vp]
-        L.ts_topk.argtypes = [pp, vp, i32, vp, vp, vp, vp, sz, vp]
+        L.ts_topk.argtypes = [pp, vp, i32, vp, vp, vp, i32, vp, sz, vp]
         L.ts_selcache_check.argtypes = [pp, vp, vp, vp, f32, vp, vp]
         L.ts_sparse_paged_attn.argtypes = [pp, vp, vp, i32, vp, f32, vp, vp, vp, sz, vp]
         L.ts_chunk_row_stats.argtypes = [pp, vp, f32, vp, vp, sz, vp]
@@ -185,9 +186,9 @@ def ts_chunk_mean_query(p: Problem, q, q_mean, stream=None) -> None:
     _ok(load().ts_chunk_mean_query(p.ref(), _ptr(q), _ptr(q_mean), _stream(stream)), "ts_chunk_mean_query")
 
 
-def ts_topk(p: Problem, votes, k: int, idx, count, skip, ws, stream=None) -> None:
-    _ok(load().ts_topk(p.ref(), _ptr(votes), int(k), _ptr(idx), _ptr(count), _ptr(skip), _ptr(ws),
-                       ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)), "ts_topk")
+def ts_topk(p: Problem, votes, k: int, idx, count, skip, ws, stream=None, flags: int = 0) -> None:
+    _ok(load().ts_topk(p.ref(), _ptr(votes), int(k), _ptr(idx), _ptr(count), _ptr(skip), int(flags), _ptr(ws), _nbytes(ws),
+                       _stream(stream)), "ts_topk")
 
 
 def ts_selcache_check(p: Problem, q, cached_q, first, theta: float, reuse, stream=None) -> None:

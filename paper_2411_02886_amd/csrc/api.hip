@@ -177,10 +177,11 @@ int32_t ts_soft_vote(const ts_problem* p, const float* scores, float score_scale
 }
 
 int32_t ts_topk(const ts_problem* p, const float* votes, int32_t k, int32_t* idx, int32_t* count,
-                const uint8_t* skip, void* ws, size_t ws_bytes, void* stream) {
+                const uint8_t* skip, int32_t flags, void* ws, size_t ws_bytes, void* stream) {
   int32_t st = check_problem(p);
   if (st != TS_OK) return st;
   if (votes == nullptr || idx == nullptr || count == nullptr || k < 1) return TS_ERR_INVALID_ARG;
+  if ((flags & ~TS_TOPK_FLAT_VOTES) != 0) return TS_ERR_INVALID_ARG;
   const WsLayout w = ws_layout(p, k);
   if (ws == nullptr || ((uintptr_t)ws & 255) != 0 || ws_bytes < w.attn_out) return TS_ERR_WORKSPACE;
   TopkArgs a{};
@@ -190,7 +191,11 @@ int32_t ts_topk(const ts_problem* p, const float* votes, int32_t k, int32_t* idx
   a.hist = (uint32_t*)((uint8_t*)ws + w.topk_hist);
   a.state = (uint32_t*)((uint8_t*)ws + w.topk_state);
   a.blk = (uint32_t*)((uint8_t*)ws + w.topk_blk);
-  a.list = g_topk_five_pass ? nullptr : (uint2*)((uint8_t*)ws + w.topk_list);
+  // The short path finishes on one workgroup per sequence: right when few votes share the k-th vote's
+  // quarter-octave (decode votes are peaked), slow when most do.  Votes summed over a chunk's queries are flat,
+  // so chunk problems (and callers that say so) take the five-pass form, whose cost does not depend on the
+  // distribution.
+  a.list = (g_topk_five_pass || p->chunk > 1 || (flags & TS_TOPK_FLAT_VOTES)) ? nullptr : (uint2*)((uint8_t*)ws + w.topk_list);
   a.k = k; a.max_seq_len = p->max_seq_len; a.nblk = w.topk_nblk; a.heads = 1;
   return launch_topk(a, p->batch, (hipStream_t)stream) == hipSuccess ? TS_OK : TS_ERR_HIP;
 }

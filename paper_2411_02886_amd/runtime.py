@@ -179,4 +179,5 @@ class ChunkSelector:
         ts.ts_chunk_mean_query(self.problem, q, m["q_mean"])
         ts.ts_paged_qk_scores(m["problem"], m["q_mean"], m["scores"], score_scale, None, m["ws"])
         ts.ts_soft_vote(m["problem"], m["scores"], score_scale, m["row_stats"], self.votes, None, m["ws"])
-        ts.ts_topk(m["problem"], self.votes, self.k, self.idx, self.count, None, m["ws"])
+        # the mean of many queries can be short, its votes flat: take the distribution-independent select
+        ts.ts_topk(m["problem"], self.votes, self.k, self.idx, self.count, None, m["ws"], flags=ts.TS_TOPK_FLAT_VOTES)

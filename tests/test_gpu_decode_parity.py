@@ -186,6 +186,16 @@ def test_five_pass_topk_path_gives_the_same_result(gpu):
         assert to_host(layer.idx)[0].tolist() == list(range(10))
     finally:
         gpu.ts_debug_set_topk_path(0)
+    # the same form chosen per call
+    w = W.make_workload("flat", dtype=W.BF16, B=2, H=8, H_kv=2, D=128, P=16, seq_lens=[5000, 2100], k=100, seed=37)
+    layer, q = make_layer(w)
+    layer.select(q, 0.01, None)                      # a small scale: nearly uniform votes
+    torch.cuda.synchronize()
+    idx_a, cnt_a = to_host(layer.idx).copy(), to_host(layer.count).copy()
+    layer.idx.fill_(-7); layer.count.fill_(-7)
+    gpu.ts_topk(layer.problem, layer.votes, layer.k, layer.idx, layer.count, None, layer.ws, flags=gpu.TS_TOPK_FLAT_VOTES)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host(layer.idx), idx_a) and np.array_equal(to_host(layer.count), cnt_a)
 
 
 def test_k_larger_than_n_equals_full_attention(gpu):
