@@ -204,6 +204,16 @@ int32_t ts_debug_set_score_variant(int32_t variant, int32_t wg, int32_t run_tile
  * per sequence.  Both give the same result.  Host only. */
 int32_t ts_debug_set_topk_path(int32_t five_pass);
 
+/* Benchmark helpers (host only; process-wide, not thread-safe).  ts_debug_set_score_timing_events(start, stop)
+ * makes every following ts_paged_qk_scores launch record `start` when its kernel begins and `stop` when it ends
+ * (events bound to the dispatch itself, so their difference is the kernel's duration without what stream-ordered
+ * event records add around a launch); (NULL, NULL) switches it off.  The events are hipEvent_t handles made by
+ * ts_debug_event_create; read them with ts_debug_event_elapsed_ms after the stream has been synchronised. */
+int32_t ts_debug_event_create(void** event);
+int32_t ts_debug_event_destroy(void* event);
+int32_t ts_debug_event_elapsed_ms(void* start, void* stop, float* ms);
+int32_t ts_debug_set_score_timing_events(void* start, void* stop);
+
 #ifdef __cplusplus
 }
 #endif

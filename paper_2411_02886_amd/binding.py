@@ -78,10 +78,15 @@ def load():
         L.ts_head_vote.argtypes = [pp, vp, i32, vp, vp, vp, sz, vp]
         L.ts_debug_set_score_variant.argtypes = [i32, i32, i32]
         L.ts_debug_set_topk_path.argtypes = [i32]
+        L.ts_debug_event_create.argtypes = [ctypes.POINTER(vp)]
+        L.ts_debug_event_destroy.argtypes = [vp]
+        L.ts_debug_event_elapsed_ms.argtypes = [vp, vp, ctypes.POINTER(f32)]
+        L.ts_debug_set_score_timing_events.argtypes = [vp, vp]
         for name in ("ts_workspace_bytes", "ts_workspace_init", "ts_paged_qk_scores", "ts_soft_vote", "ts_topk",
                      "ts_selcache_check", "ts_sparse_paged_attn", "ts_debug_set_score_variant", "ts_chunk_row_stats",
                      "ts_chunk_soft_vote", "ts_chunk_mean_query", "ts_sum_vote", "ts_head_vote_scratch_bytes",
-                     "ts_head_vote", "ts_debug_set_topk_path"):
+                     "ts_head_vote", "ts_debug_set_topk_path", "ts_debug_event_create", "ts_debug_event_destroy",
+                     "ts_debug_event_elapsed_ms", "ts_debug_set_score_timing_events"):
             getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -141,6 +146,29 @@ def ts_debug_set_score_variant(variant: int, wg: int = 0, run_tiles: int = 0) ->
 
 def ts_debug_set_topk_path(five_pass: int) -> None:
     _ok(load().ts_debug_set_topk_path(int(five_pass)), "ts_debug_set_topk_path")
+
+
+def ts_debug_event_create() -> int:
+    ev = ctypes.c_void_p(0)
+    _ok(load().ts_debug_event_create(ctypes.byref(ev)), "ts_debug_event_create")
+    return int(ev.value)
+
+
+def ts_debug_event_destroy(ev: int) -> None:
+    _ok(load().ts_debug_event_destroy(ctypes.c_void_p(ev)), "ts_debug_event_destroy")
+
+
+def ts_debug_event_elapsed_ms(start: int, stop: int) -> float:
+    ms = ctypes.c_float(0.0)
+    _ok(load().ts_debug_event_elapsed_ms(ctypes.c_void_p(start), ctypes.c_void_p(stop), ctypes.byref(ms)),
+        "ts_debug_event_elapsed_ms")
+    return float(ms.value)
+
+
+def ts_debug_set_score_timing_events(start, stop) -> None:
+    _ok(load().ts_debug_set_score_timing_events(ctypes.c_void_p(start) if start else None,
+                                                ctypes.c_void_p(stop) if stop else None),
+        "ts_debug_set_score_timing_events")
 
 
 def _nbytes(ws) -> int:

@@ -122,6 +122,30 @@ int32_t ts_debug_set_score_variant(int32_t variant, int32_t wg, int32_t run_tile
   return TS_OK;
 }
 
+int32_t ts_debug_event_create(void** event) {
+  if (event == nullptr) return TS_ERR_INVALID_ARG;
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return TS_ERR_HIP;
+  *event = (void*)e;
+  return TS_OK;
+}
+
+int32_t ts_debug_event_destroy(void* event) {
+  if (event == nullptr) return TS_ERR_INVALID_ARG;
+  return hipEventDestroy((hipEvent_t)event) == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
+int32_t ts_debug_event_elapsed_ms(void* start, void* stop, float* ms) {
+  if (start == nullptr || stop == nullptr || ms == nullptr) return TS_ERR_INVALID_ARG;
+  return hipEventElapsedTime(ms, (hipEvent_t)start, (hipEvent_t)stop) == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
+int32_t ts_debug_set_score_timing_events(void* start, void* stop) {
+  if ((start == nullptr) != (stop == nullptr)) return TS_ERR_INVALID_ARG;
+  set_score_timing_events((hipEvent_t)start, (hipEvent_t)stop);
+  return TS_OK;
+}
+
 int32_t ts_debug_set_topk_path(int32_t five_pass) {
   if (five_pass != 0 && five_pass != 1) return TS_ERR_INVALID_ARG;
   g_topk_five_pass = five_pass;

@@ -13,6 +13,7 @@
 // longer sequences: on this memory system a write stream mixed into the read stream costs about three
 // times its bytes, and fewer, larger bursts reduce that.
 #include "ts_kernels.h"
+#include <hip/hip_ext.h>
 
 namespace ts {
 
@@ -294,9 +295,17 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
+// Optional pair of events that the next launches bind to the kernel's own start and end (benchmarks: the
+// duration then excludes what stream-ordered event records add around a launch).
+static hipEvent_t g_time_start = nullptr, g_time_stop = nullptr;
+void set_score_timing_events(hipEvent_t start, hipEvent_t stop) { g_time_start = start; g_time_stop = stop; }
+
 template <int DT, int D, int G, bool DOT2>
 static hipError_t launch_one(const ScoreArgs& a, dim3 grid, size_t lds, hipStream_t s) {
-  hipLaunchKernelGGL((score_decode_kernel<DT, D, G, DOT2>), grid, dim3(256), lds, s, a);
+  if (g_time_start != nullptr && g_time_stop != nullptr)
+    hipExtLaunchKernelGGL((score_decode_kernel<DT, D, G, DOT2>), grid, dim3(256), (uint32_t)lds, s, g_time_start, g_time_stop, 0u, a);
+  else
+    hipLaunchKernelGGL((score_decode_kernel<DT, D, G, DOT2>), grid, dim3(256), lds, s, a);
   return hipGetLastError();
 }
 

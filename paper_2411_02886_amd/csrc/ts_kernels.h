@@ -131,5 +131,6 @@ hipError_t launch_sum_vote(const VoteArgs& a, int B, hipStream_t s);
 hipError_t launch_transpose_scores(const VoteArgs& a, float* st, int B, hipStream_t s);
 hipError_t launch_zero_votes(const VoteArgs& a, int B, hipStream_t s);
 hipError_t launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t s);
+void set_score_timing_events(hipEvent_t start, hipEvent_t stop);
 
 }  // namespace ts
