@@ -1,10 +1,10 @@
 // Eq. 5 (head soft vote): votes[t] = sum_h exp(c * (S[h][t] - max_h)) / sumexp_h.
 //
 // Up to eight lanes share one token; its H scores are one contiguous row, read as 16-byte pieces
-// (a wave load covers whole consecutive rows).  All arithmetic after the load is
-// double precision (the subtraction of the row maximum is then exact and the exponential is good to
-// ~1e-11), so the float scores are the only source of error in a vote; the sum over heads is rounded
-// to float once.
+// (a wave load covers whole consecutive rows).  The subtraction of the row maximum, the scaling and the
+// argument reduction are double precision (exact difference, no loss to a large argument), the fractional
+// power of two is the hardware float exponential, the weighted sum over heads is double again and is rounded
+// to float once: a vote carries about 1e-7 relative error on top of what the float scores' own rounding gives.
 #include "ts_kernels.h"
 
 namespace ts {
@@ -54,8 +54,21 @@ __global__ __launch_bounds__(256) void score_stats_merge_kernel(VoteArgs a) {
   }
 }
 
+// exp(c * d) for the vote, d = score - row maximum (exact in double), c2 = c * log2(e): the argument is reduced in
+// double (t = n + f, |f| <= 1/2, so nothing of the float scores' precision is lost to a large argument), 2^f comes
+// from the hardware float exponential (1 ulp) and is scaled by 2^n.  Relative error about 1e-7, the size of the
+// rounding of the float vote itself and well below what the float scores' own rounding does to a vote.
+__device__ __forceinline__ float vote_exp(double d, double c2) {
+  const double t = fmax(d * c2, -1000.0);
+  const double n = rint(t);
+  const float f = (float)(t - n);
+  return ldexpf(__builtin_amdgcn_exp2f(f), (int)n);
+}
+
 // LPT lanes share one token row of H scores (stored [token][head]); a lane owns CPL 16-byte chunks.
-template <int CPL, bool VEC>
+// A workgroup takes NP passes of 256 / LPT tokens, all score loads issued up front (NP > 1 for long sequences:
+// fewer, fatter workgroups, as the dispatch rate of tiny workgroups is what limits the kernel there).
+template <int CPL, bool VEC, int NP>
 __global__ __launch_bounds__(256) void soft_vote_kernel(VoteArgs a, int lpt_shift) {
   __shared__ double s_m[128];
   __shared__ double s_inv[128];
@@ -63,44 +76,51 @@ __global__ __launch_bounds__(256) void soft_vote_kernel(VoteArgs a, int lpt_shif
   if (a.skip != nullptr && a.skip[b] != 0) return;
   const int N = min(max(a.seq_lens[b], 0), a.max_seq_len);
   const int LPT = 1 << lpt_shift;
-  const int tpb = 256 >> lpt_shift;                 // tokens per workgroup
-  if (blockIdx.x * tpb >= N) return;
+  const int tpp = 256 >> lpt_shift;                 // tokens per pass
+  const int tok0 = blockIdx.x * (tpp * NP);
+  if (tok0 >= N) return;
   const int jv = threadIdx.x & (LPT - 1);
-  const int t = blockIdx.x * tpb + (threadIdx.x >> lpt_shift);
-  const int tc = min(t, N - 1);                     // out-of-range threads shadow the last token
-  const double c = (double)a.scale;
+  const double c2 = (double)a.scale * 1.44269504088896340736;
   const int H = a.H;
-  const float* sp = a.scores + ((size_t)b * a.max_seq_len + tc) * H;
   // statistics of every head: issued together with the score loads
   const float2 stv = *reinterpret_cast<const float2*>(a.row_stats + ((size_t)b * H + min((int)threadIdx.x, H - 1)) * 2);
-  float s[CPL][4];
+  float s[NP][CPL][4];
 #pragma unroll
-  for (int i = 0; i < CPL; ++i) {
-    const int h0 = (jv + i * LPT) * 4;
-    if (VEC) {
-      const float4 v = *reinterpret_cast<const float4*>(sp + min(h0, H - 4));   // clamped: no branch between loads
-      s[i][0] = v.x; s[i][1] = v.y; s[i][2] = v.z; s[i][3] = v.w;
-    } else {
+  for (int p = 0; p < NP; ++p) {
+    const int tc = min(tok0 + p * tpp + (int)(threadIdx.x >> lpt_shift), N - 1);   // out-of-range threads shadow the last token
+    const float* sp = a.scores + ((size_t)b * a.max_seq_len + tc) * H;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) s[i][e] = sp[min(h0 + e, H - 1)];
+    for (int i = 0; i < CPL; ++i) {
+      const int h0 = (jv + i * LPT) * 4;
+      if (VEC) {
+        const float4 v = *reinterpret_cast<const float4*>(sp + min(h0, H - 4));   // clamped: no branch between loads
+        s[p][i][0] = v.x; s[p][i][1] = v.y; s[p][i][2] = v.z; s[p][i][3] = v.w;
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) s[p][i][e] = sp[min(h0 + e, H - 1)];
+      }
     }
   }
   if (threadIdx.x < H) { s_m[threadIdx.x] = (double)stv.x; s_inv[threadIdx.x] = 1.0 / (double)stv.y; }
   __syncthreads();
-  double vote = 0.0;
-#pragma unroll
-  for (int i = 0; i < CPL; ++i) {
-    const int h0 = (jv + i * LPT) * 4;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int hh = min(h0 + e, H - 1);
-      const double w = (h0 + e < H) ? s_inv[hh] : 0.0;
-      vote = fma(exp_f64(c * ((double)s[i][e] - s_m[hh])), w, vote);
-    }
-  }
-  for (int off = 1; off < LPT; off <<= 1) vote += __shfl_xor(vote, off);
   const int r_lo = min(a.n_init, N), r_hi = max(r_lo, N - a.n_local);
-  if (t < N && jv == 0) a.votes[(size_t)b * a.max_seq_len + t] = (t >= r_lo && t < r_hi) ? (float)vote : 0.f;
+#pragma unroll
+  for (int p = 0; p < NP; ++p) {
+    const int t = tok0 + p * tpp + (int)(threadIdx.x >> lpt_shift);
+    double vote = 0.0;
+#pragma unroll
+    for (int i = 0; i < CPL; ++i) {
+      const int h0 = (jv + i * LPT) * 4;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int hh = min(h0 + e, H - 1);
+        const double w = (h0 + e < H) ? s_inv[hh] : 0.0;
+        vote = fma((double)vote_exp((double)s[p][i][e] - s_m[hh], c2), w, vote);
+      }
+    }
+    for (int off = 1; off < LPT; off <<= 1) vote += __shfl_xor(vote, off);
+    if (t < N && jv == 0) a.votes[(size_t)b * a.max_seq_len + t] = (t >= r_lo && t < r_hi) ? (float)vote : 0.f;
+  }
 }
 
 hipError_t launch_soft_vote(const VoteArgs& a, int B, hipStream_t s) {
@@ -110,8 +130,13 @@ hipError_t launch_soft_vote(const VoteArgs& a, int B, hipStream_t s) {
   const int cpl = (hq + (1 << lpt_shift) - 1) >> lpt_shift;   // 1, 2 or 4 for H <= 128
   const bool vec = (a.H % 4 == 0) && (((uintptr_t)a.scores & 15) == 0);
   hipLaunchKernelGGL(score_stats_merge_kernel, dim3(a.H, B), dim3(256), 0, s, a);
-  dim3 grid((a.max_seq_len + (256 >> lpt_shift) - 1) / (256 >> lpt_shift), B);
-#define TS_VOTE(C, V) hipLaunchKernelGGL((soft_vote_kernel<C, V>), grid, dim3(256), 0, s, a, lpt_shift)
+  const int tpp = 256 >> lpt_shift;
+  const long nwg1 = ((long)a.max_seq_len * B + tpp - 1) / tpp;
+  const int np = nwg1 >= 16384 ? 4 : (nwg1 >= 2048 ? 2 : 1);   // passes per workgroup (measured: 1 M tokens 42 -> 32 us with 4)
+  dim3 grid((a.max_seq_len + tpp * np - 1) / (tpp * np), B);
+#define TS_VOTE(C, V) do { if (np == 4) hipLaunchKernelGGL((soft_vote_kernel<C, V, 4>), grid, dim3(256), 0, s, a, lpt_shift); \
+    else if (np == 2) hipLaunchKernelGGL((soft_vote_kernel<C, V, 2>), grid, dim3(256), 0, s, a, lpt_shift); \
+    else hipLaunchKernelGGL((soft_vote_kernel<C, V, 1>), grid, dim3(256), 0, s, a, lpt_shift); } while (0)
   if (cpl <= 1) { if (vec) TS_VOTE(1, true); else TS_VOTE(1, false); }
   else if (cpl <= 2) { if (vec) TS_VOTE(2, true); else TS_VOTE(2, false); }
   else { if (vec) TS_VOTE(4, true); else TS_VOTE(4, false); }

@@ -95,21 +95,23 @@ __device__ __forceinline__ void flush_hist(const uint32_t* h, uint32_t* gh, int 
     if (h[i] != 0) atomicAdd(&gh[i], h[i]);
 }
 
-// pass 0: histogram of the top 11 key bits
+// pass 0: histogram of the top 11 key bits.  A workgroup walks every gridDim.x-th chunk and flushes its LDS
+// histogram once: the flush is atomics on a few hundred hot bins, so fewer, fatter workgroups contend less.
 __global__ __launch_bounds__(256) void topk_hist0_kernel(TopkArgs a) {
   __shared__ uint32_t h[kTopkBins];
   const int b = blockIdx.y;
   if (a.skip != nullptr && a.skip[b / a.heads] != 0) return;
   const int LO = ranked_lo(a, b), N = ranked_hi(a, b, LO);
-  const int base = blockIdx.x * kTopkChunk;
-  if (base >= N) return;
-  uint32_t key[kTopkChunk / 256]; bool valid[kTopkChunk / 256];
-  load_keys(a.votes + (size_t)b * a.max_seq_len, base, LO, N, key, valid);
+  if ((int)blockIdx.x * kTopkChunk >= N) return;
   for (int i = threadIdx.x; i < kTopkBins; i += 256) h[i] = 0;
   __syncthreads();
+  for (int base = blockIdx.x * kTopkChunk; base < N; base += gridDim.x * kTopkChunk) {
+    uint32_t key[kTopkChunk / 256]; bool valid[kTopkChunk / 256];
+    load_keys(a.votes + (size_t)b * a.max_seq_len, base, LO, N, key, valid);
 #pragma unroll
-  for (int i = 0; i < kTopkChunk / 256; ++i)
-    if (valid[i]) atomicAdd(&h[key[i] >> 21], 1u);
+    for (int i = 0; i < kTopkChunk / 256; ++i)
+      if (valid[i]) atomicAdd(&h[key[i] >> 21], 1u);
+  }
   __syncthreads();
   flush_hist(h, a.hist + ((size_t)b * 3 + 0) * kTopkBins, kTopkBins);
 }
@@ -495,7 +497,7 @@ __global__ __launch_bounds__(kFinalThreads) void topk_final_kernel(TopkArgs a) {
 
 hipError_t launch_topk(const TopkArgs& a, int B, hipStream_t s) {
   dim3 grid(a.nblk, B);
-  hipLaunchKernelGGL(topk_hist0_kernel, grid, dim3(256), 0, s, a);
+  hipLaunchKernelGGL(topk_hist0_kernel, dim3(a.nblk < 128 ? a.nblk : 128, B), dim3(256), 0, s, a);
   if (a.list != nullptr && a.nblk <= kFinalMaxBlk) {
     hipLaunchKernelGGL(topk_compact_kernel, grid, dim3(256), 0, s, a);
     // the list holds about k entries plus the few that share the k-th key's bin: one batch in the usual case
