@@ -47,6 +47,7 @@ def parse():
     ap.add_argument("--theta", type=float, default=0.9, help="Selection Cache threshold of the config-3 run")
     ap.add_argument("--theta-sweep", action="store_true",
                     help="config 3: also run the thresholds of the paper's theta study (0.5 ... 1.0) and report reuse rate and steps/s for each")
+    ap.add_argument("--no-graph", action="store_true", help="config 3: time the host-driven loop only (no HIP-graph replay)")
     ap.add_argument("--page-size", type=int, default=16, help="tokens per page (16 in the configurations; 1 is the paper's own setting)")
     ap.add_argument("--selection", choices=["soft", "sum", "head"], default="soft",
                     help="selection function: soft = Eq. 5 (the method, default), sum = Eq. 3, head = Eq. 4 (ablation baselines)")
@@ -118,8 +119,38 @@ def selection_cache_run(args):
     for _ in range(reps):
         run()
     torch.cuda.synchronize()
-    dt = (time.perf_counter() - t0) / reps
-    reuse = to_host(reuse_log).astype(bool)
+    dt_eager = (time.perf_counter() - t0) / reps
+    reuse_eager = to_host(reuse_log).copy(); idx_eager = to_host(layer.idx).copy(); out_eager = to_host(layer.out).copy()
+    # The 64-step run is launch-bound on the host (14 launches per step), so it is also captured once as a HIP
+    # graph (every hit/miss decision is taken on the device, nothing in it depends on the host) and replayed.
+    dt, mode = dt_eager, "eager"
+    if not args.no_graph:
+        try:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                run()                                            # warm-up on the capture stream
+            torch.cuda.current_stream().wait_stream(side); torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                run()
+            ok = True
+            for _ in range(3):                                   # replays, eager work and synchronisations in between
+                reuse_log.zero_(); layer.idx.fill_(-5); torch.cuda.synchronize()
+                g.replay(); torch.cuda.synchronize()
+                ok = ok and np.array_equal(to_host(reuse_log), reuse_eager) and np.array_equal(to_host(layer.idx), idx_eager) \
+                    and np.array_equal(to_host(layer.out), out_eager)
+            if ok:
+                t0 = time.perf_counter()
+                for _ in range(reps):
+                    g.replay()
+                torch.cuda.synchronize()
+                dt, mode = (time.perf_counter() - t0) / reps, "graph"
+            else:
+                print("bench.py: graph replays did not reproduce the eager run; reporting the eager loop", file=sys.stderr)
+        except Exception as e:                                   # capture not possible: the eager figure stands
+            print("bench.py: graph capture failed (%s); reporting the eager loop" % e, file=sys.stderr)
+    reuse = reuse_eager.astype(bool)
     lens = w.seq_lens.astype(np.int64)[None, :] + 1 + np.arange(steps)[:, None]
     scanned = int((lens * (~reuse)).sum())
     res = {"metric": "decode steps/s over the Selection Cache run (batch of 8 sequences per step)",
@@ -132,7 +163,9 @@ def selection_cache_run(args):
                       "forced_initial_tokens": args.n_init, "forced_recent_tokens": args.n_local},
            "reuse_rate": float(reuse.mean()), "sequence_steps_per_s": steps * w.B / dt,
            "tokens_scanned_per_s": scanned / dt,
-           "note": "host-driven loop: 10 library launches + 4 torch launches per step, no graph capture"}
+           "execution": mode, "eager_batch_steps_per_s": steps / dt_eager,
+           "note": "10 library launches + 4 torch launches per step; 'graph' = the whole 64-step run captured once as a HIP graph "
+                   "and replayed (replays checked against the eager run), 'eager' = host-driven loop"}
     if args.theta_sweep:
         sweep = []
         for th in (0.5, 0.6, 0.7, 0.8, 0.85, 0.9, 0.95, 1.0):       # the thresholds of the paper's theta study

@@ -22,7 +22,7 @@ static int score_run_tiles(const ts_problem* p) {
   const int hs = (hb * (p->num_q_heads / p->num_kv_heads) + 3) & ~3;
   const long ntiles = (long)(p->max_seq_len + kScoreTileTokens - 1) / kScoreTileTokens;
   for (int rr = 4; rr > 1; rr >>= 1) {
-    const long runs = (ntiles + rr - 1) / rr * nu * p->batch;
+    const long runs = (ntiles + rr - 1) / rr * nu;   // per sequence: others of the batch may be skipped
     if (runs >= 4096 && (size_t)4 * rr * kScoreTileTokens * hs * sizeof(float) <= 65536) return rr;
   }
   return 1;
@@ -44,10 +44,9 @@ static int score_workgroups(const ts_problem* p) {
   const int rr = score_run_tiles_eff(p);
   const int ntiles = (p->max_seq_len + kScoreTileTokens - 1) / kScoreTileTokens;
   const int nruns = (ntiles + rr - 1) / rr * nu;
+  // per sequence, whatever the batch: with a Selection Cache most sequences of a step may be skipped, and the
+  // ones that are scanned must still fill the machine
   int wg = g_score_wg > 0 ? g_score_wg : (nruns + 3) / 4;
-  int cap = kScoreMaxWg / (p->batch < 1 ? 1 : p->batch);
-  if (cap < 64) cap = 64;
-  if (g_score_wg == 0 && wg > cap) wg = cap;
   if (wg > kScoreMaxWg) wg = kScoreMaxWg;
   if (wg < 1) wg = 1;
   return wg;

@@ -344,3 +344,44 @@ def test_kernels_are_deterministic(gpu):
         outs.append([to_host(x).copy() for x in (layer.scores, layer.row_stats, layer.votes, layer.idx, layer.out)])
     for a, b in zip(*outs):
         assert np.array_equal(a, b)
+
+
+def test_decode_steps_captured_in_a_hip_graph_replay_identically(gpu):
+    # Every hit/miss decision is taken on the device and the library neither allocates nor synchronises, so a
+    # run of decode steps can be captured once and replayed.  Several replays, with eager work and
+    # synchronisations in between, must each reproduce the eager run (indices, reuse flags, outputs).
+    from paper_2411_02886_amd.runtime import to_device, to_host
+    steps, theta = 6, 0.9
+    w = W.make_workload("graph", dtype=W.BF16, B=3, H=8, H_kv=2, D=128, P=16, seq_lens=[900, 2500, 70], k=48, seed=51,
+                        beta=3.0, planted_per_head=1)
+    qs = [to_device(q) for q in W.ar1_queries(w, steps, rho=0.95)]
+    layer, _ = make_layer(w, num_initial=4, num_local=16)
+    reuse_log = torch.zeros((steps, w.B), dtype=torch.uint8, device=layer.device)
+    idx_log = torch.zeros((steps, w.B, w.k), dtype=torch.int32, device=layer.device)
+    out_log = torch.zeros((steps,) + tuple(layer.out.shape), dtype=layer.out.dtype, device=layer.device)
+
+    def run():
+        layer.first.fill_(1)
+        for t in range(steps):
+            layer.step(qs[t], theta=theta, score_scale=0.1)
+            reuse_log[t].copy_(layer.reuse); idx_log[t].copy_(layer.idx); out_log[t].copy_(layer.out)
+
+    run(); torch.cuda.synchronize()
+    ref = (to_host(reuse_log).copy(), to_host(idx_log).copy(), to_host(out_log).copy())
+    assert 0 < ref[0].sum() < ref[0].size                      # hits and misses both occur
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run()
+    torch.cuda.current_stream().wait_stream(side); torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        run()
+    for rep in range(4):
+        reuse_log.zero_(); idx_log.fill_(-9); out_log.zero_()
+        layer.idx.fill_(-9); layer.cached_q.zero_()             # eager work between the replays
+        torch.cuda.synchronize()
+        g.replay(); torch.cuda.synchronize()
+        got = (to_host(reuse_log), to_host(idx_log), to_host(out_log))
+        for a, b in zip(got, ref):
+            assert np.array_equal(a, b), rep
