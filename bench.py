@@ -297,7 +297,6 @@ def main():
     for kp, vp, pi in pools:
         layer.swap_pool(kp, vp, pi)
         problems.append(layer.problem)
-    stream = torch.cuda.current_stream()
     hv_scratch = None
     if args.selection == "head":
         nb = ts.ts_head_vote_scratch_bytes(layer.problem)
@@ -306,6 +305,7 @@ def main():
     def step(i, ev=None, kev=None):
         p = problems[i % R]
         q = qs[i % R]
+        stream = torch.cuda.current_stream()      # the capture stream while a graph is being recorded
         ts.ts_selcache_check(p, q, layer.cached_q, layer.first, theta, layer.reuse, stream)
         if ev is not None:
             ev[0].record(stream)
@@ -372,6 +372,42 @@ def main():
     score_avg_ms = float(score_ms.mean())
     achieved = k_bytes / (score_avg_ms * 1e-3) / 1e9
 
+    # The same steps as one HIP graph (R consecutive steps, one per pool copy), replayed: what the step costs
+    # without the host in the loop.  Informational; `value` is the host-driven loop above.
+    graph_info = None
+    if not args.no_graph:
+        try:
+            idx_ref = []
+            for i in range(R):
+                step(i); torch.cuda.synchronize(); idx_ref.append(to_host(layer.idx).copy())
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            idx_log = torch.zeros((R,) + tuple(layer.idx.shape), dtype=torch.int32, device=dev)
+
+            def steps_r():
+                for i in range(R):
+                    step(i); idx_log[i].copy_(layer.idx)
+            with torch.cuda.stream(side):
+                steps_r()
+            torch.cuda.current_stream().wait_stream(side); torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                steps_r()
+            ok = True
+            for _ in range(3):
+                idx_log.fill_(-3); layer.idx.fill_(-3); torch.cuda.synchronize()
+                g.replay(); torch.cuda.synchronize()
+                ok = ok and all(np.array_equal(to_host(idx_log[i]), idx_ref[i]) for i in range(R))
+            nrep = max(1, args.steps // R)
+            tg = time.perf_counter()
+            for _ in range(nrep):
+                g.replay()
+            torch.cuda.synchronize()
+            graph_info = {"ms_per_step": (time.perf_counter() - tg) * 1e3 / (nrep * R), "steps": nrep * R,
+                          "replays_match_eager": bool(ok)}
+        except Exception as e:
+            graph_info = {"error": str(e)[:200]}
+
     res = {
         "metric": "KV tokens scanned/s (whole decode step: Selection Cache check + score pass + soft vote + top-k + sparse attention)",
         "value": N / (ms_step * 1e-3),
@@ -387,6 +423,7 @@ def main():
                                           "head": "Eq. 4 head vote"}[args.selection]},
         "planted_token_quality": quality,
         "decode_steps_per_s": 1e3 / ms_step,
+        "hip_graph_replay": graph_info,
         "roofline": {"bound": "hbm", "kernel": "ts::score_decode_kernel (the one launch of ts_paged_qk_scores)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(args.config) if not args.tokens else None,
