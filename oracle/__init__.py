@@ -3,7 +3,8 @@
 A plain double-precision implementation (C, oracle/tokenselect_oracle.c, driven from numpy) of
 what the GPU library computes: Algorithm 2 (paged dot product), Eq. 5 (head soft vote), the TopK
 of Eq. 3-5, Algorithm 1 (Selection Cache), Eq. 2 (selective sparse attention) and Eq. 1 (full
-attention, brute force).  It imports nothing from the HIP package and the HIP package imports
+attention, brute force); composed in numpy from these: Eq. 3 and Eq. 4 (the ablation selection
+functions), forced initial / recent tokens (Sec. 6.1) and the mean-query chunk selection (Sec. 5.2).  It imports nothing from the HIP package and the HIP package imports
 nothing from here; only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg use it.
 
 Readings of the paper taken here (each is an explicit argument or a named constant):
@@ -17,6 +18,8 @@ Readings of the paper taken here (each is an explicit argument or a named consta
   * Decode: the cached tokens already contain the current token; nothing is appended in Eq. 2.
   * Eq. 3 is read as the top-k of the dot products summed over the heads (the form whose weakness the
     paper describes: heads with large logits dominate); Eq. 4 lets every head vote for k tokens.
+  * Forced tokens: the first n_init and last n_local cached tokens are attended in addition to the k
+    selected ones; the selection function sees only the tokens between them (`ranked_range`).
   * Chunked prefill (`select_chunk`): votes are summed over heads and over the chunk's queries;
     `select_chunk_mean_query` is the paper's Sec. 5.2 form (mean query fed to the decode selection).
 """

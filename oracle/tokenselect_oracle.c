@@ -15,8 +15,9 @@
  * Pins (tests/test_oracle_pins.py): numpy einsum on un-paged arrays, paging invariance, softmax
  * rows summing to one / votes summing to H, H = 1 reducing to an argsort of raw logits, brute
  * force top-k on tiny inputs, constructed ties, k >= N equal to brute-force full attention,
- * Algorithm 1 traced by hand, scipy's softmax, planted tokens recovered.  The paper prints no
- * worked numerical example of this path, so absolute values are pinned by these only.
+ * Algorithm 1 traced by hand, scipy's softmax, planted tokens recovered; the chunk's mean query against numpy
+ * and constructed halfway cases of the bfloat16 rounding.  The paper prints no worked numerical example of
+ * this path, so absolute values are pinned by these only.
  */
 #include <math.h>
 #include <stdint.h>
