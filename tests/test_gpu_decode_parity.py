@@ -265,6 +265,15 @@ def test_config2_full_size(gpu):
         assert (rg, pg) == (ro, po)
 
 
+@pytest.mark.timeout(600)
+def test_config2_full_size_with_the_papers_forced_tokens(gpu):
+    # configuration 2 with the 128 initial + 512 most recent tokens that the paper's runs always attend
+    w = W.config2()
+    layer, q = make_layer(w, num_initial=128, num_local=512)
+    print("cfg2 full size, forced 128 + 512", flush=True)
+    check_decode_against_oracle(w, layer, q, score_scale=1.0, label="cfg2 full forced")
+
+
 @pytest.mark.timeout(900)
 def test_config4_full_size(gpu):
     # configuration 4: 1048576 tokens, 28 query heads over 4 KV heads, k = 4096
@@ -331,6 +340,67 @@ def test_config3_shape_decode_run_with_appended_tokens(gpu, forced):
     rate = reuse_total / (steps * w.B)
     print("cfg3 reuse rate %.3f" % rate)
     assert 0.2 < rate < 0.9
+
+
+@pytest.mark.timeout(1500)
+def test_config3_full_size_selection_cache_run(gpu):
+    # configuration 3 as bench.py runs it: 8 sequences of 16384..65536 cached tokens, 64 steps, AR(1) queries, one
+    # K/V row appended per sequence per step, theta = 0.9.  Reuse flags and index sets of every step and sequence
+    # against Algorithm 1 on the oracle (band rule for the sets); attention on a sample of (step, sequence) pairs.
+    from paper_2411_02886_amd.runtime import to_device, to_host
+    theta, scale = 0.9, 1.0
+    w = W.config3()
+    steps = int(w.extra["steps"])
+    qs = W.ar1_queries(w, steps, rho=0.95)
+    ks, vs = W.appended_kv(w, steps)
+    layer, _ = make_layer(w, max_seq_len=int(w.seq_lens.max()) + steps)
+    lens = w.seq_lens.copy()
+    cq = [np.zeros((w.H, w.D), np.uint16) for _ in range(w.B)]
+    first = [np.ones(1, np.uint8) for _ in range(w.B)]
+    cidx = [np.full(w.k, -1, np.int32) for _ in range(w.B)]
+    ccnt = [np.zeros(1, np.int32) for _ in range(w.B)]
+    kflat = w.k_pool.reshape(-1, w.H_kv, w.D); vflat = w.v_pool.reshape(-1, w.H_kv, w.D)
+    kdev = layer.k_pool.view(-1, w.H_kv, w.D); vdev = layer.v_pool.view(-1, w.H_kv, w.D)
+    reuse_total, exceptions = 0, 0
+    sm = float(np.float32(1 / math.sqrt(w.D)))
+    for t in range(steps):
+        slots = np.array([int(w.pages_of(b)[int(lens[b]) // w.P]) * w.P + int(lens[b]) % w.P for b in range(w.B)])
+        kflat[slots] = ks[t]; vflat[slots] = vs[t]
+        sd = torch.from_numpy(slots).to(layer.device)
+        kdev.index_copy_(0, sd, to_device(ks[t])); vdev.index_copy_(0, sd, to_device(vs[t]))
+        lens += 1
+        layer.seq_lens.copy_(to_device(lens))
+        layer.step(to_device(qs[t]), theta=theta, score_scale=scale)
+        torch.cuda.synchronize()
+        reuse_g = to_host(layer.reuse); idx_g = to_host(layer.idx); cnt_g = to_host(layer.count)
+        out_g = to_host(layer.out, bits16=True)
+        for b in range(w.B):
+            qb = np.ascontiguousarray(qs[t][b, 0])
+            holder = {}
+
+            def sel(qq, b=b):
+                i, c, v, _ = oracle.select(qq, w.k_pool, w.dtype, w.H_kv, w.P, w.pages_of(b), int(lens[b]), w.k,
+                                           score_scale=float(np.float32(scale)), details=True)
+                holder["votes"] = v
+                return i, c
+            i_o, c_o, r_o = oracle.selcache_step(qb, cq[b], cidx[b], ccnt[b], first[b], float(np.float32(theta)), sel)
+            assert bool(reuse_g[b]) == r_o, (t, b)
+            reuse_total += r_o
+            if not r_o:     # a fresh selection: compare with the band rule, then adopt the GPU's set as the cached one
+                exc = compare_index_sets(idx_g[b], int(cnt_g[b]), dict(idx=i_o, count=c_o, votes=holder["votes"]),
+                                         "cfg3 t=%d b=%d" % (t, b))
+                exceptions += len(exc)
+                cidx[b][:] = idx_g[b]
+            else:
+                assert cnt_g[b] == c_o and np.array_equal(idx_g[b], cidx[b]), (t, b)
+            if (t * w.B + b) % 37 == 0:
+                o_ref = oracle.sparse_attn(qb, w.k_pool, w.v_pool, w.dtype, w.H_kv, w.P, w.pages_of(b), idx_g[b], int(cnt_g[b]), sm)
+                assert np.abs(W.as_f32(out_g[b, 0], w.dtype) - o_ref).max() <= 2e-2, (t, b)
+        if t % 16 == 0:
+            print("cfg3 full step", t, "reuse so far", reuse_total, flush=True)
+    rate = reuse_total / (steps * w.B)
+    print("cfg3 full size: reuse rate %.4f, tolerated near-tie exceptions %d" % (rate, exceptions))
+    assert 0.5 < rate < 0.75
 
 
 def test_kernels_are_deterministic(gpu):
