@@ -89,8 +89,10 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int j = lane & 7, r = lane >> 3;
   const int b = blockIdx.y;
-  if (a.skip != nullptr && a.skip[b] != 0) return;
+  const int skip_flag = a.skip != nullptr ? (int)a.skip[b] : 0;   // issued together with the length
   const int N = min(max(a.seq_lens[b], 0), a.max_seq_len);
+  const int indptr = a.page_indptr[b];
+  if (skip_flag != 0) return;
   const int H = a.H, HB = a.HB, HBG = HB * G;
   const int HS = (HBG + 3) & ~3;             // floats per token row of the staged tile
   const int RR = a.RR;                        // tiles a wave stages before it writes them out as one run
@@ -105,7 +107,6 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
   const int h_base = u * HBG;
   const int ntt = (N + TT - 1) / TT;
   const int tt_step = (gridDim.x * 4) / a.NU;
-  const int indptr = a.page_indptr[b];
   const int npages = (N + a.P - 1) >> a.p_shift;
   const float c2 = a.c2;
   const int r_lo = min(a.n_init, N), r_hi = max(r_lo, N - a.n_local);   // ranked range: the statistics cover it only

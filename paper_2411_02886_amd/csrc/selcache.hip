@@ -40,6 +40,7 @@ __global__ __launch_bounds__(256) void selcache_kernel(SelcacheArgs a) {
   const uint4* q = reinterpret_cast<const uint4*>(a.q + (size_t)b * a.n * ES);
   uint4* cq = reinterpret_cast<uint4*>(a.cached_q + (size_t)b * a.n * ES);
   const int npieces = a.n * ES / 16;            // H * D is a multiple of 64, so this is exact
+  const int first0 = a.first[b];                // read with the vectors, not after the reduction
   double ab = 0.0, aa = 0.0, bb = 0.0;
   uint4 qkeep[KEEP];
   for (int p0 = 0; p0 < npieces; p0 += 256 * KEEP) {
@@ -66,7 +67,7 @@ __global__ __launch_bounds__(256) void selcache_kernel(SelcacheArgs a) {
     aa = red[1][0] + red[1][1] + red[1][2] + red[1][3];
     bb = red[2][0] + red[2][1] + red[2][2] + red[2][3];
     const double c = (aa == 0.0 || bb == 0.0) ? 0.0 : ab / (sqrt(aa) * sqrt(bb));
-    const int reselect = (a.first[b] != 0) || (c < (double)a.theta);
+    const int reselect = (first0 != 0) || (c < (double)a.theta);
     s_reuse = !reselect;
     a.reuse[b] = (uint8_t)(!reselect);
     if (reselect) a.first[b] = 0;

@@ -12,8 +12,9 @@ namespace ts {
 // Eq. 3: one thread per token, the H scores of its row summed in double in head order, rounded once
 __global__ __launch_bounds__(256) void sum_vote_kernel(VoteArgs a) {
   const int b = blockIdx.y;
-  if (a.skip != nullptr && a.skip[b] != 0) return;
+  const int skip_flag = a.skip != nullptr ? (int)a.skip[b] : 0;   // issued together with the length
   const int N = min(max(a.seq_lens[b], 0), a.max_seq_len);
+  if (skip_flag != 0) return;
   const int t = blockIdx.x * 256 + threadIdx.x;
   if (t >= N) return;
   const int r_lo = min(a.n_init, N), r_hi = max(r_lo, N - a.n_local);
@@ -27,8 +28,9 @@ __global__ __launch_bounds__(256) void sum_vote_kernel(VoteArgs a) {
 __global__ __launch_bounds__(256) void transpose_scores_kernel(VoteArgs a, float* __restrict__ st) {
   __shared__ float tile[64][129];
   const int b = blockIdx.y;
-  if (a.skip != nullptr && a.skip[b] != 0) return;
+  const int skip_flag = a.skip != nullptr ? (int)a.skip[b] : 0;   // issued together with the length
   const int N = min(max(a.seq_lens[b], 0), a.max_seq_len);
+  if (skip_flag != 0) return;
   const int t0 = blockIdx.x * 64;
   if (t0 >= N) return;
   const int H = a.H, nt = min(64, N - t0);
@@ -47,8 +49,9 @@ __global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t* p, size_t n, ui
 // votes[b][0..N_b) = 0 for the sequences that are not skipped
 __global__ __launch_bounds__(256) void zero_votes_kernel(VoteArgs a) {
   const int b = blockIdx.y;
-  if (a.skip != nullptr && a.skip[b] != 0) return;
+  const int skip_flag = a.skip != nullptr ? (int)a.skip[b] : 0;   // issued together with the length
   const int N = min(max(a.seq_lens[b], 0), a.max_seq_len);
+  if (skip_flag != 0) return;
   const int t = blockIdx.x * 256 + threadIdx.x;
   if (t < N) a.votes[(size_t)b * a.max_seq_len + t] = 0.f;
 }

@@ -18,7 +18,7 @@ __global__ __launch_bounds__(256) void score_stats_merge_kernel(VoteArgs a) {
   __shared__ float s_m[4];
   __shared__ double s_l[4];
   const int h = blockIdx.x, b = blockIdx.y;
-  if (a.skip != nullptr && a.skip[b] != 0) return;
+  const int skip_flag = a.skip != nullptr ? (int)a.skip[b] : 0;   // checked after the partials' loads have been issued
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   constexpr int PER = kScoreMaxWg / 256;
   float mp[PER], lp[PER];
@@ -31,6 +31,7 @@ __global__ __launch_bounds__(256) void score_stats_merge_kernel(VoteArgs a) {
       mp[i] = v.x; lp[i] = v.y;
     }
   }
+  if (skip_flag != 0) return;
   float m = mp[0];
 #pragma unroll
   for (int i = 1; i < PER; ++i) m = fmaxf(m, mp[i]);
@@ -73,8 +74,9 @@ __global__ __launch_bounds__(256) void soft_vote_kernel(VoteArgs a, int lpt_shif
   __shared__ double s_m[128];
   __shared__ double s_inv[128];
   const int b = blockIdx.y;
-  if (a.skip != nullptr && a.skip[b] != 0) return;
+  const int skip_flag = a.skip != nullptr ? (int)a.skip[b] : 0;   // issued together with the length
   const int N = min(max(a.seq_lens[b], 0), a.max_seq_len);
+  if (skip_flag != 0) return;
   const int LPT = 1 << lpt_shift;
   const int tpp = 256 >> lpt_shift;                 // tokens per pass
   const int tok0 = blockIdx.x * (tpp * NP);

@@ -100,8 +100,9 @@ __device__ __forceinline__ void flush_hist(const uint32_t* h, uint32_t* gh, int 
 __global__ __launch_bounds__(256) void topk_hist0_kernel(TopkArgs a) {
   __shared__ uint32_t h[kTopkBins];
   const int b = blockIdx.y;
-  if (a.skip != nullptr && a.skip[b / a.heads] != 0) return;
+  const int skip_flag = a.skip != nullptr ? (int)a.skip[b / a.heads] : 0;   // issued together with the length
   const int LO = ranked_lo(a, b), N = ranked_hi(a, b, LO);
+  if (skip_flag != 0) return;
   if ((int)blockIdx.x * kTopkChunk >= N) return;
   for (int i = threadIdx.x; i < kTopkBins; i += 256) h[i] = 0;
   __syncthreads();
@@ -121,8 +122,9 @@ __global__ __launch_bounds__(256) void topk_hist1_kernel(TopkArgs a) {
   __shared__ uint32_t h[kTopkBins];
   __shared__ uint32_t lds[8];
   const int b = blockIdx.y;
-  if (a.skip != nullptr && a.skip[b / a.heads] != 0) return;
+  const int skip_flag = a.skip != nullptr ? (int)a.skip[b / a.heads] : 0;   // issued together with the length
   const int LO = ranked_lo(a, b), N = ranked_hi(a, b, LO);
+  if (skip_flag != 0) return;
   const int base = blockIdx.x * kTopkChunk;
   if (base >= N && blockIdx.x != 0) return;
   uint32_t key[kTopkChunk / 256]; bool valid[kTopkChunk / 256];
@@ -146,8 +148,9 @@ __global__ __launch_bounds__(256) void topk_hist2_kernel(TopkArgs a) {
   __shared__ uint32_t h[1024];
   __shared__ uint32_t lds[8];
   const int b = blockIdx.y;
-  if (a.skip != nullptr && a.skip[b / a.heads] != 0) return;
+  const int skip_flag = a.skip != nullptr ? (int)a.skip[b / a.heads] : 0;   // issued together with the length
   const int LO = ranked_lo(a, b), N = ranked_hi(a, b, LO);
+  if (skip_flag != 0) return;
   const int base = blockIdx.x * kTopkChunk;
   if (base >= N && blockIdx.x != 0) return;
   uint32_t key[kTopkChunk / 256]; bool valid[kTopkChunk / 256];
@@ -176,8 +179,9 @@ __global__ __launch_bounds__(256) void topk_count_kernel(TopkArgs a) {
   __shared__ uint32_t lds[8];
   __shared__ uint32_t red[4];
   const int b = blockIdx.y;
-  if (a.skip != nullptr && a.skip[b / a.heads] != 0) return;
+  const int skip_flag = a.skip != nullptr ? (int)a.skip[b / a.heads] : 0;   // issued together with the length
   const int LO = ranked_lo(a, b), N = ranked_hi(a, b, LO);
+  if (skip_flag != 0) return;
   const int base = blockIdx.x * kTopkChunk;
   uint32_t key[kTopkChunk / 256]; bool valid[kTopkChunk / 256];
   load_keys(a.votes + (size_t)b * a.max_seq_len, base, LO, N, key, valid);
@@ -213,8 +217,9 @@ __global__ __launch_bounds__(256) void topk_emit_kernel(TopkArgs a) {
   __shared__ uint32_t scan_lds[8];
   __shared__ uint32_t red[2][4];
   const int b = blockIdx.y;
-  if (a.skip != nullptr && a.skip[b / a.heads] != 0) return;
+  const int skip_flag = a.skip != nullptr ? (int)a.skip[b / a.heads] : 0;   // issued together with the length
   const int LO = ranked_lo(a, b), N = ranked_hi(a, b, LO);
+  if (skip_flag != 0) return;
   const uint32_t thr = a.state[b * 8 + ST_THR];
   const uint32_t need_eq = a.state[b * 8 + ST_NEED_EQ];
   const bool none = a.state[b * 8 + ST_NONE] != 0;
@@ -290,34 +295,36 @@ __global__ __launch_bounds__(256) void topk_compact_kernel(TopkArgs a) {
   __shared__ uint32_t lds[8];
   __shared__ uint32_t scan_lds[8];
   const int b = blockIdx.y;
-  if (a.skip != nullptr && a.skip[b / a.heads] != 0) return;
+  const int skip_flag = a.skip != nullptr ? (int)a.skip[b / a.heads] : 0;   // issued together with the length
   const int LO = ranked_lo(a, b), N = ranked_hi(a, b, LO);
+  if (skip_flag != 0) return;
   const uint32_t k_eff = (uint32_t)min(a.k, N - LO);
+  constexpr int PER = kTopkChunk / 256;
+  const int base = blockIdx.x * kTopkChunk;
+  const int t0 = base + threadIdx.x * PER;   // PER consecutive tokens per thread: order is preserved
+  const float* v = a.votes + (size_t)b * a.max_seq_len;
+  // the votes are loaded before the histogram is walked: the two round trips overlap
+  uint32_t key[PER];
+  bool valid[PER];
+#pragma unroll
+  for (int e = 0; e < PER; ++e) {
+    valid[e] = (t0 + e) >= LO && (t0 + e) < N;
+    key[e] = valid[e] ? float_key(v[t0 + e]) : 0u;
+  }
   uint32_t d0, krem0;
   find_digit<kTopkBins>(a.hist + ((size_t)b * 3 + 0) * kTopkBins, k_eff, &d0, &krem0, lds);
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     a.state[b * 8 + ST_PREFIX0] = d0 << 21; a.state[b * 8 + ST_KREM0] = krem0; a.state[b * 8 + ST_KEFF] = k_eff;
   }
-  constexpr int PER = kTopkChunk / 256;
-  const int base = blockIdx.x * kTopkChunk;
-  const int t0 = base + threadIdx.x * PER;   // PER consecutive tokens per thread: order is preserved
-  const float* v = a.votes + (size_t)b * a.max_seq_len;
-  uint32_t key[PER];
   uint32_t n = 0;
 #pragma unroll
-  for (int e = 0; e < PER; ++e) {
-    const bool valid = (t0 + e) >= LO && (t0 + e) < N;
-    key[e] = valid ? float_key(v[t0 + e]) : 0u;
-    n += valid && (key[e] >> 21) >= d0;      // d0 == kTopkBins (empty selection) matches nothing
-  }
+  for (int e = 0; e < PER; ++e) n += valid[e] && (key[e] >> 21) >= d0;      // d0 == kTopkBins (empty selection) matches nothing
   uint32_t total;
   uint32_t pos = block_exclusive_scan(n, &total, scan_lds);
   uint2* list = a.list + ((size_t)b * a.nblk + blockIdx.x) * kTopkChunk;
 #pragma unroll
-  for (int e = 0; e < PER; ++e) {
-    const bool valid = (t0 + e) >= LO && (t0 + e) < N;
-    if (valid && (key[e] >> 21) >= d0) list[pos++] = make_uint2(key[e], (uint32_t)(t0 + e));
-  }
+  for (int e = 0; e < PER; ++e)
+    if (valid[e] && (key[e] >> 21) >= d0) list[pos++] = make_uint2(key[e], (uint32_t)(t0 + e));
   if (threadIdx.x == 0) a.blk[(size_t)b * a.nblk + blockIdx.x] = total;
 }
 
@@ -378,10 +385,11 @@ __global__ __launch_bounds__(kFinalThreads) void topk_final_kernel(TopkArgs a) {
   __shared__ uint32_t scan_lds[16];
   __shared__ uint32_t res[2];
   const int b = blockIdx.x;
-  if (a.skip != nullptr && a.skip[b / a.heads] != 0) return;
+  const int skip_flag = a.skip != nullptr ? (int)a.skip[b / a.heads] : 0;   // issued together with the state words
   const int tid = threadIdx.x;
   const uint32_t d0 = a.state[b * 8 + ST_PREFIX0] >> 21, krem0 = a.state[b * 8 + ST_KREM0];
   const int k_eff = (int)a.state[b * 8 + ST_KEFF];
+  if (skip_flag != 0) return;
   const bool as_votes = a.vote_acc != nullptr;
   int32_t* out = as_votes ? nullptr : a.idx + (size_t)b * a.k;
   float* acc = as_votes ? a.vote_acc + (size_t)(b / a.heads) * a.max_seq_len : nullptr;
