@@ -157,32 +157,34 @@ __global__ __launch_bounds__(256, 2) void prefill_qk_kernel(PrefillArgs a) {
   auto softmax_block = [&](const f32x16_t (&acc)[2], int tile, int nb, int cbuf) {
     const bool cvalid = (tile * kPfTile + nb * 32 + col) < Nc;
     if (SWEEP == 1) {
-      float ar[2][16];
-      float amax = -INFINITY;
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const float v = cvalid ? fmaf(c2, acc[mb][e], -off[mb][e]) : -INFINITY;   // +inf while off is unset
-          ar[mb][e] = v;
-          amax = fmaxf(amax, v);
-        }
-      if (__builtin_amdgcn_ballot_w64(amax > 64.f) != 0) {   // first column of a lane, or a score far above the reference
+      if (cvalid) {   // lane predication (one exec-mask update per block): columns past the end take no part
+        float ar[2][16];
+        float amax = -INFINITY;
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-          for (int e = 0; e < 16; ++e)
-            if (ar[mb][e] > 64.f) {
-              const float noff = c2 * acc[mb][e];
-              aux[mb][e] = (off[mb][e] == -INFINITY) ? 0.f : aux[mb][e] * __builtin_amdgcn_exp2f(off[mb][e] - noff);
-              off[mb][e] = noff;
-              ar[mb][e] = 0.f;
-            }
+          for (int e = 0; e < 16; ++e) {
+            const float v = fmaf(c2, acc[mb][e], -off[mb][e]);   // +inf while off is unset
+            ar[mb][e] = v;
+            amax = fmaxf(amax, v);
+          }
+        if (__builtin_amdgcn_ballot_w64(amax > 64.f) != 0) {   // first column of a lane, or a score far above the reference
+#pragma unroll
+          for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+              if (ar[mb][e] > 64.f) {
+                const float noff = c2 * acc[mb][e];
+                aux[mb][e] = (off[mb][e] == -INFINITY) ? 0.f : aux[mb][e] * __builtin_amdgcn_exp2f(off[mb][e] - noff);
+                off[mb][e] = noff;
+                ar[mb][e] = 0.f;
+              }
+        }
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) aux[mb][e] += __builtin_amdgcn_exp2f(ar[mb][e]);
       }
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) aux[mb][e] += __builtin_amdgcn_exp2f(ar[mb][e]);
     } else {
       float cs = 0.f;
 #pragma unroll
