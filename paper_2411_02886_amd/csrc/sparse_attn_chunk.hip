@@ -100,13 +100,20 @@ __global__ __launch_bounds__(256) void chunk_attn_kernel(ChunkAttnArgs a) {
   const int st_key = threadIdx.x / PPR, st_piece = threadIdx.x % PPR;
   constexpr int KPP = 256 / PPR;                 // keys per pass
   struct Rows { uint4 k[NLD]; uint4 v[NLD]; };
-  auto fetch = [&](int tile) -> Rows {
+  struct Slots { int v[NLD]; };
+  // the slots of a tile are read one tile earlier than its rows: the slot list and the pools are two dependent
+  // round trips, and a tile's arithmetic is too short to hide both
+  auto fetch_slots = [&](int tile) -> Slots {
+    Slots r;
+#pragma unroll
+    for (int it = 0; it < NLD; ++it) r.v[it] = slots[min(tile * kCaTile + st_key + it * KPP, nkeys - 1)];   // ragged last tile: shadow the last key
+    return r;
+  };
+  auto fetch = [&](const Slots& sl) -> Rows {
     Rows r;
 #pragma unroll
     for (int it = 0; it < NLD; ++it) {
-      const int j = min(tile * kCaTile + st_key + it * KPP, nkeys - 1);   // ragged last tile: shadow the last key
-      const size_t slot = (size_t)slots[j];
-      const size_t o = (slot * a.H_kv + kvh) * RBYTES + st_piece * 16;
+      const size_t o = ((size_t)sl.v[it] * a.H_kv + kvh) * RBYTES + st_piece * 16;
       r.k[it] = *reinterpret_cast<const uint4*>(a.k_pool + o);
       r.v[it] = *reinterpret_cast<const uint4*>(a.v_pool + o);
     }
@@ -129,14 +136,19 @@ __global__ __launch_bounds__(256) void chunk_attn_kernel(ChunkAttnArgs a) {
   Rows pre;
 #pragma unroll
   for (int it = 0; it < NLD; ++it) { pre.k[it] = make_uint4(0, 0, 0, 0); pre.v[it] = make_uint4(0, 0, 0, 0); }
-  stage(0, fetch(0));
-  if (ntile > 1) pre = fetch(1);
+  Slots spre;
+#pragma unroll
+  for (int it = 0; it < NLD; ++it) spre.v[it] = 0;
+  stage(0, fetch(fetch_slots(0)));
+  if (ntile > 1) pre = fetch(fetch_slots(1));
+  if (ntile > 2) spre = fetch_slots(2);
   __syncthreads();
 
   for (int tile = 0; tile < ntile; ++tile) {
     const int buf = tile & 1;
     if (tile + 1 < ntile) stage(buf ^ 1, pre);
-    if (tile + 2 < ntile) pre = fetch(tile + 2);
+    if (tile + 2 < ntile) pre = fetch(spre);
+    if (tile + 3 < ntile) spre = fetch_slots(tile + 3);
 
     // ---- S = Q K^T for 32 rows x 32 keys
     f32x16_t sacc;
