@@ -374,6 +374,8 @@ int32_t ts_sparse_paged_attn(const ts_problem* p, const void* q, const int32_t* 
     c.C = p->chunk; c.H = p->num_q_heads; c.H_kv = p->num_kv_heads; c.G = p->num_q_heads / p->num_kv_heads;
     c.D = p->head_dim; c.P = p->page_size; c.p_shift = ilog2(p->page_size); c.idx_stride = idx_stride;
     c.max_seq_len = p->max_seq_len; c.sm_scale = sm_scale;
+    c.nsplit = w.attn_chunk_nsplit;
+    c.part_o = (float*)((uint8_t*)ws + w.attn_chunk_o); c.part_ml = (float*)((uint8_t*)ws + w.attn_chunk_ml);
     return launch_sparse_attn_chunk(c, p->batch, (hipStream_t)stream) == hipSuccess ? TS_OK : TS_ERR_HIP;
   }
   if (w.attn_nsplit > kAttnMaxSplit) return TS_ERR_UNSUPPORTED;

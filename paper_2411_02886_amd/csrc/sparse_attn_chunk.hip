@@ -54,7 +54,7 @@ __global__ __launch_bounds__(256) void chunk_attn_kernel(ChunkAttnArgs a) {
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int half = lane >> 5, col = lane & 31;
-  const int rb = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  const int rb = blockIdx.x / a.nsplit, split = blockIdx.x % a.nsplit, kvh = blockIdx.y, b = blockIdx.z;
   const int C = a.C, G = a.G, H = a.H;
   const int nrows = C * G;
   const int cnt = min(max(a.count[b], 0), a.idx_stride);
@@ -62,7 +62,11 @@ __global__ __launch_bounds__(256) void chunk_attn_kernel(ChunkAttnArgs a) {
   if (r0 >= nrows) return;
   const int c_last = min(C - 1, (r0 + kCaRows - 1) / G);      // last query of this row block
   const int nkeys = cnt + c_last + 1;                          // keys any row of the block may see
-  const int ntile = (nkeys + kCaTile - 1) / kCaTile;
+  const int ntile_all = (nkeys + kCaTile - 1) / kCaTile;
+  // this workgroup's share of the key list (tiles [tile0, tile0 + ntile)); may be empty
+  const int tps = (ntile_all + a.nsplit - 1) / a.nsplit;
+  const int tile0 = min(split * tps, ntile_all);
+  const int ntile = min(tps, ntile_all - tile0);
   const int* slots = a.slots + (size_t)b * (a.idx_stride + C);
   const float c2 = a.sm_scale * 1.44269504088896340736f;
 
@@ -106,7 +110,7 @@ __global__ __launch_bounds__(256) void chunk_attn_kernel(ChunkAttnArgs a) {
   auto fetch_slots = [&](int tile) -> Slots {
     Slots r;
 #pragma unroll
-    for (int it = 0; it < NLD; ++it) r.v[it] = slots[min(tile * kCaTile + st_key + it * KPP, nkeys - 1)];   // ragged last tile: shadow the last key
+    for (int it = 0; it < NLD; ++it) r.v[it] = slots[min((tile0 + tile) * kCaTile + st_key + it * KPP, nkeys - 1)];   // ragged last tile: shadow the last key
     return r;
   };
   auto fetch = [&](const Slots& sl) -> Rows {
@@ -160,7 +164,7 @@ __global__ __launch_bounds__(256) void chunk_attn_kernel(ChunkAttnArgs a) {
       sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qfrag[ks], __builtin_bit_cast(bf16x8_t, bv), sacc, 0, 0, 0);
     }
     // ---- mask and exponent arguments; key j of this lane's column
-    const int j = tile * kCaTile + col;
+    const int j = (tile0 + tile) * kCaTile + col;
     const int cq = j - cnt;                                    // >= 0: the chunk's token cq
     float raw[16], ar[16];
     float amax = -INFINITY;
@@ -215,7 +219,7 @@ __global__ __launch_bounds__(256) void chunk_attn_kernel(ChunkAttnArgs a) {
     __syncthreads();
   }
 
-  // ---- finish: row sums over the 32 columns, normalise, write
+  // ---- finish: row sums over the 32 columns; normalise and write, or hand the partial to the merge kernel
 #pragma unroll
   for (int e = 0; e < 16; ++e) {
     float l = lsum[e];
@@ -225,20 +229,53 @@ __global__ __launch_bounds__(256) void chunk_attn_kernel(ChunkAttnArgs a) {
     if (row < nrows) {
       const int c = row / G, g = row % G;
       const size_t hb = ((size_t)b * C + c) * H + kvh * G + g;
-      const float inv = l > 0.f ? 1.f / l : 0.f;
+      if (a.nsplit == 1) {
+        const float inv = l > 0.f ? 1.f / l : 0.f;
 #pragma unroll
-      for (int nb = 0; nb < NBO; ++nb)
-        reinterpret_cast<uint16_t*>(a.out)[hb * D + nb * 32 + col] = (uint16_t)f32_to_bf16_bits(oacc[nb][e] * inv);
-      if (a.lse != nullptr && col == 0) a.lse[hb] = l > 0.f ? (ref[e] + __builtin_amdgcn_logf(l)) * 0.69314718055994530942f : -INFINITY;
+        for (int nb = 0; nb < NBO; ++nb)
+          reinterpret_cast<uint16_t*>(a.out)[hb * D + nb * 32 + col] = (uint16_t)f32_to_bf16_bits(oacc[nb][e] * inv);
+        if (a.lse != nullptr && col == 0) a.lse[hb] = l > 0.f ? (ref[e] + __builtin_amdgcn_logf(l)) * 0.69314718055994530942f : -INFINITY;
+      } else {
+        float* po = a.part_o + (hb * a.nsplit + split) * D;
+#pragma unroll
+        for (int nb = 0; nb < NBO; ++nb) po[nb * 32 + col] = oacc[nb][e];
+        if (col == 0) { float* pm = a.part_ml + (hb * a.nsplit + split) * 2; pm[0] = ref[e]; pm[1] = l; }
+      }
     }
   }
+}
+
+// Merges the key-list splits of one row: with M = max_s ref_s (base-2 exponents),
+// out = sum_s 2^(ref_s - M) O_s / sum_s 2^(ref_s - M) l_s.  One workgroup of D threads per row.
+template <int D>
+__global__ __launch_bounds__(D) void chunk_attn_merge_kernel(ChunkAttnArgs a) {
+  const size_t hb = blockIdx.x;
+  const int d = threadIdx.x;
+  const float* pm = a.part_ml + hb * a.nsplit * 2;
+  float M = -INFINITY;
+  for (int s = 0; s < a.nsplit; ++s) M = fmaxf(M, pm[2 * s]);
+  float L = 0.f, o = 0.f;
+  for (int s = 0; s < a.nsplit; ++s) {
+    const float r = pm[2 * s];
+    const float w = (r == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(r - M);
+    L = fmaf(w, pm[2 * s + 1], L);
+    o = fmaf(w, a.part_o[(hb * a.nsplit + s) * D + d], o);
+  }
+  reinterpret_cast<uint16_t*>(a.out)[hb * D + d] = (uint16_t)f32_to_bf16_bits(L > 0.f ? o / L : 0.f);
+  if (a.lse != nullptr && d == 0) a.lse[hb] = L > 0.f ? (M + __builtin_amdgcn_logf(L)) * 0.69314718055994530942f : -INFINITY;
 }
 
 hipError_t launch_sparse_attn_chunk(const ChunkAttnArgs& a, int B, hipStream_t s) {
   hipLaunchKernelGGL(chunk_slots_kernel, dim3((a.idx_stride + a.C + 255) / 256, B), dim3(256), 0, s, a);
   const int nrb = (a.C * a.G + kCaRows - 1) / kCaRows;
-  if (a.D == 128) hipLaunchKernelGGL(chunk_attn_kernel<128>, dim3(nrb, a.H_kv, B), dim3(256), 0, s, a);
-  else hipLaunchKernelGGL(chunk_attn_kernel<64>, dim3(nrb, a.H_kv, B), dim3(256), 0, s, a);
+  const dim3 grid(nrb * a.nsplit, a.H_kv, B);
+  if (a.D == 128) hipLaunchKernelGGL(chunk_attn_kernel<128>, grid, dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(chunk_attn_kernel<64>, grid, dim3(256), 0, s, a);
+  if (a.nsplit > 1) {
+    const int rows = B * a.C * a.H;
+    if (a.D == 128) hipLaunchKernelGGL(chunk_attn_merge_kernel<128>, dim3(rows), dim3(128), 0, s, a);
+    else hipLaunchKernelGGL(chunk_attn_merge_kernel<64>, dim3(rows), dim3(64), 0, s, a);
+  }
   return hipGetLastError();
 }
 

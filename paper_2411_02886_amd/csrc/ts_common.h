@@ -28,6 +28,9 @@ struct WsLayout {
   size_t pf_stat_part;     // float [B][TS][C][H][2]            (chunk > 1 only)
   size_t pf_vote_part;     // float [B][RB * H_kv][max_seq_len] (chunk > 1 only)
   size_t attn_slots;       // int32 [B][k + C]                  (chunk > 1 only)
+  size_t attn_chunk_o;     // float [B][C][H][nsplit][D]        (chunk > 1 with key-list splits)
+  size_t attn_chunk_ml;    // float [B][C][H][nsplit][2]
+  int attn_chunk_nsplit;
   size_t total;
   int pf_rb, pf_ts;
   int topk_nblk;
@@ -35,6 +38,19 @@ struct WsLayout {
 };
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Key-list splits of the chunk-form attention: its rows alone give few waves (config 5: 512 on 1024 SIMDs), so the
+// key list is split until about two waves per SIMD are in flight; every split keeps at least four 32-key tiles.
+inline int chunk_attn_splits(const ts_problem* p, int k) {
+  const int G = p->num_q_heads / p->num_kv_heads;
+  const long waves = (long)((p->chunk * G + 127) / 128) * 4 * p->num_kv_heads * p->batch;
+  const int ntile = (k + p->chunk + 31) / 32;
+  int s = (int)((2048 + waves - 1) / waves);
+  if (s > 8) s = 8;
+  if (s > ntile / 4) s = ntile / 4;
+  if (s < 1) s = 1;
+  return s;
+}
 
 inline WsLayout ws_layout(const ts_problem* p, int k) {
   WsLayout w{};
@@ -66,7 +82,14 @@ inline WsLayout ws_layout(const ts_problem* p, int k) {
   // the sections that depend on k come last, so that every other offset is the same for any k
   w.attn_out = take(B * H * (size_t)w.attn_nsplit * D * 4);
   w.attn_ml = take(B * H * (size_t)w.attn_nsplit * 2 * 4);
-  if (p->chunk > 1) w.attn_slots = take(B * ((size_t)k + p->chunk) * 4);
+  if (p->chunk > 1) {
+    w.attn_slots = take(B * ((size_t)k + p->chunk) * 4);
+    w.attn_chunk_nsplit = chunk_attn_splits(p, k);
+    if (w.attn_chunk_nsplit > 1) {
+      w.attn_chunk_o = take(B * p->chunk * H * (size_t)w.attn_chunk_nsplit * D * 4);
+      w.attn_chunk_ml = take(B * p->chunk * H * (size_t)w.attn_chunk_nsplit * 2 * 4);
+    }
+  }
   w.total = off;
   return w;
 }

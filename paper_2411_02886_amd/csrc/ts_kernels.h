@@ -116,6 +116,9 @@ struct ChunkAttnArgs {
   uint8_t* out;              // [B][C][H][D] bf16
   float* lse;                // [B][C][H] or null
   int C, H, H_kv, G, D, P, p_shift, idx_stride, max_seq_len;
+  int nsplit;                // key-list splits per row block (1 = the kernel writes the result itself)
+  float* part_o;             // [B][C][H][nsplit][D] un-normalised partial outputs (nsplit > 1)
+  float* part_ml;            // [B][C][H][nsplit][2] (reference exponent, row sum) of each partial
   float sm_scale;
 };
 hipError_t launch_sparse_attn_chunk(const ChunkAttnArgs& a, int B, hipStream_t s);
