@@ -22,6 +22,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 
 constexpr int kPfRowsPerWg = 256;
 constexpr int kPfTile = 64;            // tokens per tile
+constexpr float kRefHead = 32.f;       // head room (log2 units) a raised reference exponent gets in sweep 1
 
 // XCD-aware decode of the linear workgroup id: (row block, group) with group = (sequence, KV head, split)
 __device__ __forceinline__ bool pf_decode_block(const PrefillArgs& a, int* rb, int* b, int* kvh, int* split) {
@@ -85,7 +86,7 @@ __global__ __launch_bounds__(256, 2) void prefill_qk_kernel(PrefillArgs a) {
   // 8 * i + 4 * half + j (i, j < 4) of each 32-row block: 32 rows per lane.
   // Sweep 1 keeps, per lane and row, a reference exponent `off` (log2 units) and the sum of
   // exp2(c2 * s - off) over the lane's columns; the reference is raised only when an argument would
-  // exceed 2^64 (rare), so the common path is one fma, one exp2 and one add per score.
+  // exceed 2^64 (rare: a raised reference gets 2^32 of head room), so the common path is one fma, one exp2 and one add per score.
   // Sweep 2 holds the row's log2-sum-exp: the high float as the exponent offset, 2^-low as a weight.
   float off[2][16], aux[2][16];
 #pragma unroll
@@ -174,10 +175,12 @@ __global__ __launch_bounds__(256, 2) void prefill_qk_kernel(PrefillArgs a) {
 #pragma unroll
             for (int e = 0; e < 16; ++e)
               if (ar[mb][e] > 64.f) {
-                const float noff = c2 * acc[mb][e];
+                // the new reference sits kRefHead above the value that forced it: a lane's first score is a typical
+                // one, not a large one, and without head room nearly every block would raise some reference again
+                const float noff = c2 * acc[mb][e] + kRefHead;
                 aux[mb][e] = (off[mb][e] == -INFINITY) ? 0.f : aux[mb][e] * __builtin_amdgcn_exp2f(off[mb][e] - noff);
                 off[mb][e] = noff;
-                ar[mb][e] = 0.f;
+                ar[mb][e] = -kRefHead;
               }
         }
 #pragma unroll
