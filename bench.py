@@ -9,7 +9,8 @@ last-level cache warm, the steps rotate over R physical copies of the pool (same
 different random page permutation each) and over R different queries, so that every step is a
 Selection Cache miss (cosine of independent queries ~ 0 < theta = 0.9) and scans all cached tokens.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric, value (tokens scanned per second over whole steps), ms_per_step, the score
+kernel's roofline (achieved GB/s from HIP events bound to its dispatch), and the CPU oracle timed on the same workload.
 """
 from __future__ import annotations
 
@@ -246,7 +247,7 @@ def chunked_prefill_run(args):
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only; --gpus %d is not supported (see DESIGN.md, 'More than one GPU')"
+        print("bench.py: this build runs on one GPU only; --gpus %d is not supported"
               % args.gpus, file=sys.stderr)
         sys.exit(2)
     if args.config == 3:
