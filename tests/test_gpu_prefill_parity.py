@@ -199,3 +199,29 @@ def test_mean_query_selection_ragged_batch(gpu):
     w = W.make_workload("chunkmqb", dtype=W.BF16, B=len(lens), C=C, H=8, H_kv=2, D=128, P=16, seq_lens=lens, k=40, seed=4)
     print("mean-query ragged batch", lens, flush=True)
     check_mean_query(gpu, w, 40, 0.0884, "mq ragged")
+
+
+@pytest.mark.parametrize("direction", ["rising", "falling", "spikes"])
+def test_chunk_selection_with_scores_that_keep_outgrowing_the_reference(gpu, direction):
+    # Sweep 1 keeps lazy per-lane reference exponents; here every row's scores drift by hundreds of units along
+    # the sequence (or jump in isolated spikes), so references are raised again and again and far apart.
+    C, H, H_kv, D, P, L, k = 40, 8, 2, 128, 16, 2600, 64
+    w = W.make_workload("drift", dtype=W.BF16, C=C, H=H, H_kv=H_kv, D=D, P=P, seq_lens=[L], k=k, seed=61)
+    Nc = L - C
+    rng = np.random.Generator(np.random.PCG64(62))
+    kf = W.as_f32(w.k_pool, w.dtype).reshape(-1, H_kv, D).copy()
+    qf = W.as_f32(w.q, w.dtype)[0]                          # [C][H][D]
+    slots = w.slots_of(0)
+    dirs = qf.mean(axis=0).reshape(H_kv, H // H_kv, D).mean(axis=1)      # one direction per KV head
+    dirs /= np.linalg.norm(dirs, axis=1, keepdims=True)
+    t = np.arange(Nc, dtype=np.float32)
+    if direction == "rising":
+        amp = -12.0 + 24.0 * t / Nc
+    elif direction == "falling":
+        amp = 12.0 - 24.0 * t / Nc
+    else:
+        amp = np.zeros(Nc, np.float32); amp[rng.choice(Nc, size=12, replace=False)] = rng.uniform(8.0, 20.0, size=12)
+    kf[slots[:Nc]] += amp[:, None, None] * dirs[None, :, :] * 3.0
+    w.k_pool[:] = W.store(kf.reshape(w.k_pool.shape), w.dtype)
+    check_chunk(gpu, w, k, 1.0, "drift " + direction)
+    check_chunk(gpu, w, k, 0.0884, "drift " + direction + " scaled")
