@@ -71,3 +71,18 @@ def test_calls_reject_bad_arguments_without_launching():
     assert L.ts_debug_set_score_variant(1, 0, 3) == -1
     assert L.ts_debug_set_score_variant(1, 0, 0) == 0
     assert L.ts_debug_set_topk_path(2) == -1 and L.ts_debug_set_topk_path(0) == 0
+
+
+def test_header_is_plain_c_and_host_calls_link(tmp_path):
+    import os, shutil, subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    libdir = os.path.dirname(ts.lib_path())
+    exe = str(tmp_path / "c_abi_check")
+    subprocess.check_call([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(root, "include"),
+                           os.path.join(root, "tests", "c_abi_check.c"), "-o", exe, "-L", libdir, "-ltokenselect",
+                           "-Wl,-rpath," + libdir])
+    r = subprocess.run([exe], capture_output=True, text=True)
+    assert r.returncode == 0 and "c abi ok" in r.stdout, (r.returncode, r.stdout, r.stderr)
