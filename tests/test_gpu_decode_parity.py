@@ -126,6 +126,15 @@ def test_ragged_batch_with_empty_and_short_sequences(gpu):
     check_decode_against_oracle(w, layer, q, score_scale=0.1, label="ragged")
 
 
+def test_large_batch_of_short_sequences(gpu):
+    rng = np.random.Generator(np.random.PCG64(71))
+    lens = [int(x) for x in rng.integers(0, 1500, size=40)]
+    w = W.make_workload("batch40", dtype=W.BF16, B=40, H=28, H_kv=4, D=128, P=16, seq_lens=lens, k=48, seed=72)
+    layer, q = make_layer(w, num_initial=4, num_local=16)
+    print("batch of 40", flush=True)
+    check_decode_against_oracle(w, layer, q, score_scale=0.2, label="batch40")
+
+
 def test_max_seq_len_larger_than_every_sequence(gpu):
     w = W.make_workload("odd", dtype=W.F32, H=4, H_kv=2, D=64, P=16, seq_lens=[203], k=20, seed=12)
     layer, q = make_layer(w, max_seq_len=205)
