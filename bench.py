@@ -322,6 +322,8 @@ def main():
         else:
             ts.ts_head_vote(p, layer.scores, layer.k, layer.votes, layer.reuse, hv_scratch, stream)
         ts.ts_topk(p, layer.votes, layer.k, layer.idx, layer.count, layer.reuse, layer.ws, stream)
+        if ev is not None:
+            ev[2].record(stream)
         ts.ts_sparse_paged_attn(p, q, layer.idx, layer.k, layer.count, sm, layer.out, layer.lse, layer.ws, stream)
 
     # sanity before timing: paging invariance across the pool copies (same query -> same selection)
@@ -351,14 +353,18 @@ def main():
     # dispatch (a launch that carries such events costs the step a few microseconds, so not on every step).
     every = 4 if args.steps >= 16 else 1
     sampled = [i for i in range(args.steps) if i % every == 0]
-    events = {i: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for i in sampled}
+    events = {i: tuple(torch.cuda.Event(enable_timing=True) for _ in range(3)) for i in sampled}
     kevents = {i: (ts.ts_debug_event_create(), ts.ts_debug_event_create()) for i in sampled}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    sel_events = {i: tuple(torch.cuda.Event(enable_timing=True) for _ in range(3)) for i in range(args.steps)
+                  if every == 4 and i % 16 == 2}
     for i in range(args.steps):
         if i in kevents:
             step(args.warmup + i, events[i], kevents[i])
             ts.ts_debug_set_score_timing_events(None, None)
+        elif i in sel_events:
+            step(args.warmup + i, sel_events[i])          # stream-ordered records only: score pass .. top-k
         else:
             step(args.warmup + i)
     torch.cuda.synchronize()
@@ -366,7 +372,8 @@ def main():
     misses = int((to_host(layer.reuse) == 0).sum())
     assert misses == w.B, "the benchmark step must be a Selection Cache miss"
     ms_step = (t1 - t0) * 1e3 / args.steps
-    stream_ms = np.array([a.elapsed_time(b) for a, b in events.values()], dtype=np.float64)   # stream-ordered records around the call
+    stream_ms = np.array([e[0].elapsed_time(e[1]) for e in events.values()], dtype=np.float64)   # stream-ordered records around the call
+    select_ms = np.array([e[0].elapsed_time(e[2]) for e in (sel_events or events).values()], dtype=np.float64)   # score pass + vote + top-k
     score_ms = np.array([ts.ts_debug_event_elapsed_ms(a, b) for a, b in kevents.values()], dtype=np.float64)   # the kernel itself
     for a, b in kevents.values():
         ts.ts_debug_event_destroy(a); ts.ts_debug_event_destroy(b)
@@ -425,6 +432,8 @@ def main():
         "planted_token_quality": quality,
         "decode_steps_per_s": 1e3 / ms_step,
         "hip_graph_replay": graph_info,
+        "selection_ms": {"what": "score pass + vote + top-k (the selection of Eq. 5), stream-ordered events on every 16th timed step",
+                         "avg": float(select_ms.mean()), "median": float(np.median(select_ms)), "min": float(select_ms.min())},
         "roofline": {"bound": "hbm", "kernel": "ts::score_decode_kernel (the one launch of ts_paged_qk_scores)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(args.config) if not args.tokens else None,
