@@ -225,14 +225,20 @@ def attended_tokens(idx, count, N, n_init=0, n_local=0) -> np.ndarray:
                            np.arange(hi, N, dtype=np.int32)])
 
 
-def select_chunk(qc, k_pool, dtype, H_kv, P, page_indices, N, k, score_scale=1.0, details=False):
+def select_chunk(qc, k_pool, dtype, H_kv, P, page_indices, N, k, score_scale=1.0, details=False, n_init=0, n_local=0):
     """Chunked-prefill selection with per-query votes: votes[t] = sum_c sum_h softmax_t(c*S[c][h][:])[t]
-    over the N cached tokens; one top-k shared by the chunk.  qc: [C][H][D]."""
+    over the N cached tokens; one top-k shared by the chunk.  qc: [C][H][D].  With forced tokens the first n_init
+    and the last n_local *cached* tokens (the ones just before the chunk) are attended by every query of the chunk
+    and only the tokens between them are ranked (the softmax of every query runs over that range)."""
+    lo, hi = ranked_range(N, n_init, n_local)
     votes = np.zeros(N, dtype=np.float64)
-    for c in range(qc.shape[0]):
-        S = paged_qk_scores(np.ascontiguousarray(qc[c]), k_pool, dtype, H_kv, P, page_indices, N)
-        votes += soft_vote(S, score_scale)
-    idx, cnt = topk(decision_votes(votes), k)
+    if hi > lo:
+        for c in range(qc.shape[0]):
+            S = paged_qk_scores(np.ascontiguousarray(qc[c]), k_pool, dtype, H_kv, P, page_indices, N)
+            votes[lo:hi] += soft_vote(np.ascontiguousarray(S[:, lo:hi]), score_scale)
+    idx, cnt = topk(decision_votes(votes[lo:hi]), k)
+    idx = idx.copy()
+    idx[:cnt] += lo
     return (idx, cnt, votes) if details else (idx, cnt)
 
 
@@ -244,9 +250,11 @@ def mean_query(qc: np.ndarray, dtype: int) -> np.ndarray:
     return out
 
 
-def select_chunk_mean_query(qc, k_pool, dtype, H_kv, P, page_indices, N, k, score_scale=1.0, details=False):
+def select_chunk_mean_query(qc, k_pool, dtype, H_kv, P, page_indices, N, k, score_scale=1.0, details=False,
+                            n_init=0, n_local=0):
     """Sec. 5.2 as printed: one selection per chunk, S applied to the mean query over the N cached tokens."""
-    return select(mean_query(qc, dtype), k_pool, dtype, H_kv, P, page_indices, N, k, score_scale, details)
+    return select(mean_query(qc, dtype), k_pool, dtype, H_kv, P, page_indices, N, k, score_scale, details,
+                  n_init=n_init, n_local=n_local)
 
 
 def selcache_step(q, cached_q, cached_idx, cached_cnt, first, theta, select_fn):

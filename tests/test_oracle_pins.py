@@ -486,3 +486,29 @@ def test_sum_vote_is_dominated_by_a_head_with_large_logits_while_votes_are_not()
     assert len(top_h0 & set(i_sum.tolist())) >= 9
     hv = oracle.head_vote(S, 10)
     assert hv.max() <= 4 and hv.sum() == 40
+
+
+def test_chunk_selection_with_forced_tokens_is_plain_chunk_selection_on_the_middle():
+    C, N, k, ni, nl = 3, 90, 10, 6, 13
+    w = W.make_workload("cf", dtype=W.F32, C=C, H=4, H_kv=2, D=16, P=1, seq_lens=[N + C], k=k, seed=23)
+    qc = w.q[0]
+    idx, cnt, votes = oracle.select_chunk(qc, w.k_pool, w.dtype, w.H_kv, w.P, w.pages_of(0), N, k, details=True,
+                                          n_init=ni, n_local=nl)
+    lo, hi = ni, N - nl
+    idx2, cnt2, votes2 = oracle.select_chunk(qc, w.k_pool, w.dtype, w.H_kv, w.P, w.pages_of(0)[lo:hi], hi - lo, k, details=True)
+    assert cnt == cnt2 == k and (idx[:cnt] - lo).tolist() == idx2[:cnt2].tolist()
+    np.testing.assert_array_equal(votes[lo:hi], votes2)
+    assert not votes[:lo].any() and not votes[hi:].any() and abs(votes.sum() - C * w.H) < 1e-12
+    # the attended list of query c: initial block, selection, the cached tokens just before the chunk, chunk tokens 0..c
+    att = oracle.attended_tokens(idx, cnt, N, ni, nl)
+    assert att.tolist() == list(range(ni)) + idx[:cnt].tolist() + list(range(N - nl, N))
+    # forced blocks covering the cache: every query sees the whole cache plus its causal part of the chunk = full
+    # causal attention over the sequence up to itself (bitwise: same order of terms)
+    idx0, cnt0 = oracle.select_chunk(qc, w.k_pool, w.dtype, w.H_kv, w.P, w.pages_of(0), N, k, n_init=50, n_local=60)
+    assert cnt0 == 0
+    att0 = oracle.attended_tokens(idx0, cnt0, N, 50, 60)
+    for c in range(C):
+        a = oracle.sparse_attn(np.ascontiguousarray(qc[c]), w.k_pool, w.v_pool, w.dtype, w.H_kv, w.P, w.pages_of(0), att0, N, 0.25,
+                               extra_first=N, n_extra=c + 1)
+        b = oracle.full_attn(np.ascontiguousarray(qc[c]), w.k_pool, w.v_pool, w.dtype, w.H_kv, w.P, w.pages_of(0), N + c + 1, 0.25)
+        assert np.array_equal(a, b), c
