@@ -189,7 +189,7 @@ def chunked_prefill_run(args):
     from paper_2411_02886_amd.runtime import ChunkSelector, to_device
     w = W.config5()
     N = int(w.extra["n_cached"])
-    sel = ChunkSelector.from_workload(w)
+    sel = ChunkSelector.from_workload(w, num_initial=args.n_init, num_local=args.n_local)
     q = to_device(w.q)
     names = ["row_stats", "soft_vote", "topk", "attention"]
     calls = [lambda: ts.ts_chunk_row_stats(sel.problem, q, 1.0, sel.row_stats, sel.ws),
@@ -217,7 +217,8 @@ def chunked_prefill_run(args):
            "value": w.C * N / dt, "unit": "pairs/s", "n_gpus": 1, "steps": steps, "warmup": warm, "ms_per_step": dt * 1e3,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
            "config": {"workload": w.name, "chunk": w.C, "cached_tokens": N, "num_q_heads": w.H, "num_kv_heads": w.H_kv,
-                      "head_dim": w.D, "k": w.k, "score_scale": 1.0},
+                      "head_dim": w.D, "k": w.k, "score_scale": 1.0,
+                      "forced_initial_tokens": args.n_init, "forced_recent_tokens": args.n_local},
            "ms_per_call": dict(zip(names, [float(x) for x in per])),
            "roofline": {"bound": "mfma", "kernel": "ts::prefill_qk_kernel<128, 2> (vote sweep of ts_chunk_soft_vote)",
                         "achieved": tf, "peak": peak, "unit": "TFLOP/s", "frac": tf / peak, "traffic": None,

@@ -70,7 +70,10 @@ typedef struct ts_problem {
    * [lo_b, hi_b) only: the softmax statistics of ts_paged_qk_scores / ts_soft_vote cover that range,
    * votes outside it are 0, ts_topk returns min(k, hi_b - lo_b) tokens of it, and ts_sparse_paged_attn
    * attends over tokens [0, lo_b), the selected ones, and [hi_b, N_b) of the *current* N_b (a cached
-   * selection made at a smaller N_b stays valid).  Both 0 = no forced tokens.  Decode only (chunk == 1). */
+   * selection made at a smaller N_b stays valid).  Both 0 = no forced tokens.
+   * Chunk form (chunk = C > 1): the blocks are taken from the N_b - C cached tokens before the chunk -- the first
+   * num_initial of them and the num_local just before the chunk -- and are attended by every query of the chunk;
+   * ts_chunk_row_stats / ts_chunk_soft_vote / ts_topk rank the cached tokens between them. */
   int32_t num_initial;
   int32_t num_local;
 } ts_problem;

@@ -74,7 +74,6 @@ static int32_t check_problem(const ts_problem* p) {
   if ((int64_t)p->batch * p->num_q_heads * (int64_t)p->max_seq_len > ((int64_t)1 << 40)) return TS_ERR_UNSUPPORTED;
   if (p->num_initial < 0 || p->num_local < 0) return TS_ERR_INVALID_ARG;
   if (p->num_initial > (1 << 20) || p->num_local > (1 << 20)) return TS_ERR_UNSUPPORTED;
-  if ((p->num_initial != 0 || p->num_local != 0) && p->chunk != 1) return TS_ERR_UNSUPPORTED;   // forced tokens: decode only
   return TS_OK;
 }
 
@@ -209,7 +208,7 @@ int32_t ts_topk(const ts_problem* p, const float* votes, int32_t k, int32_t* idx
   if (ws == nullptr || ((uintptr_t)ws & 255) != 0 || ws_bytes < w.attn_out) return TS_ERR_WORKSPACE;
   TopkArgs a{};
   a.head = p->num_initial;
-  a.tail = p->chunk > 1 ? p->chunk : p->num_local;
+  a.tail = (p->chunk > 1 ? p->chunk : 0) + p->num_local;   // the chunk's own tokens and the forced recent block
   a.votes = votes; a.seq_lens = p->seq_lens; a.skip = skip; a.idx = idx; a.count = count;
   a.hist = (uint32_t*)((uint8_t*)ws + w.topk_hist);
   a.state = (uint32_t*)((uint8_t*)ws + w.topk_state);
@@ -308,6 +307,7 @@ static int32_t fill_prefill_args(const ts_problem* p, const void* q, float score
   a->B = p->batch; a->C = p->chunk; a->H = p->num_q_heads; a->H_kv = p->num_kv_heads;
   a->G = p->num_q_heads / p->num_kv_heads; a->D = p->head_dim; a->P = p->page_size; a->p_shift = ilog2(p->page_size);
   a->max_seq_len = p->max_seq_len; a->RB = w.pf_rb; a->TS = w.pf_ts;
+  a->n_init = p->num_initial; a->n_local = p->num_local;
   a->scale = score_scale; a->c2 = score_scale * 1.44269504088896340736f;
   return TS_OK;
 }
@@ -375,6 +375,8 @@ int32_t ts_sparse_paged_attn(const ts_problem* p, const void* q, const int32_t* 
     c.D = p->head_dim; c.P = p->page_size; c.p_shift = ilog2(p->page_size); c.idx_stride = idx_stride;
     c.max_seq_len = p->max_seq_len; c.sm_scale = sm_scale;
     c.nsplit = w.attn_chunk_nsplit;
+    c.n_init = p->num_initial; c.n_local = p->num_local;
+    c.slot_stride = idx_stride + p->num_initial + p->num_local + p->chunk;
     c.part_o = (float*)((uint8_t*)ws + w.attn_chunk_o); c.part_ml = (float*)((uint8_t*)ws + w.attn_chunk_ml);
     return launch_sparse_attn_chunk(c, p->batch, (hipStream_t)stream) == hipSuccess ? TS_OK : TS_ERR_HIP;
   }

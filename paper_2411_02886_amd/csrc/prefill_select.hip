@@ -55,9 +55,11 @@ __global__ __launch_bounds__(256, 2) void prefill_qk_kernel(PrefillArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int C = a.C, G = a.G, H = a.H;
   const int Nc = min(max(a.seq_lens[b] - C, 0), a.max_seq_len);     // cached tokens the selection looks at
-  const int ntile = (Nc + kPfTile - 1) / kPfTile;
-  const int tps = (ntile + a.TS - 1) / a.TS;
-  const int tile_begin = split * tps, tile_end = min(ntile, tile_begin + tps);
+  // forced tokens: only the cached tokens [r_lo, r_hi) are ranked; the tiles that hold them are split over TS
+  const int r_lo = min(a.n_init, Nc), r_hi = max(r_lo, Nc - a.n_local);
+  const int tile_lo = r_lo / kPfTile, tile_hi = (r_hi > r_lo) ? (r_hi + kPfTile - 1) / kPfTile : tile_lo;
+  const int tps = (tile_hi - tile_lo + a.TS - 1) / a.TS;
+  const int tile_begin = min(tile_hi, tile_lo + split * tps), tile_end = min(tile_hi, tile_begin + tps);
   const int indptr = a.page_indptr[b];
   const int nrows = C * G;
   const float c2 = a.c2;
@@ -156,7 +158,8 @@ __global__ __launch_bounds__(256, 2) void prefill_qk_kernel(PrefillArgs a) {
   };
   // the softmax arithmetic of one block on the vector ALU
   auto softmax_block = [&](const f32x16_t (&acc)[2], int tile, int nb, int cbuf) {
-    const bool cvalid = (tile * kPfTile + nb * 32 + col) < Nc;
+    const int tcol = tile * kPfTile + nb * 32 + col;
+    const bool cvalid = tcol >= r_lo && tcol < r_hi;
     if (SWEEP == 1) {
       if (cvalid) {   // lane predication (one exec-mask update per block): columns past the end take no part
         float ar[2][16];
@@ -201,7 +204,7 @@ __global__ __launch_bounds__(256, 2) void prefill_qk_kernel(PrefillArgs a) {
   auto write_votes = [&](int tile, int cbuf) {
     if (SWEEP == 2 && threadIdx.x < kPfTile) {
       const int t = tile * kPfTile + threadIdx.x;
-      if (t < Nc) vout[t] = (s_col[cbuf][0][threadIdx.x] + s_col[cbuf][1][threadIdx.x]) + (s_col[cbuf][2][threadIdx.x] + s_col[cbuf][3][threadIdx.x]);
+      if (t >= r_lo && t < r_hi) vout[t] = (s_col[cbuf][0][threadIdx.x] + s_col[cbuf][1][threadIdx.x]) + (s_col[cbuf][2][threadIdx.x] + s_col[cbuf][3][threadIdx.x]);
     }
   };
 
@@ -277,6 +280,8 @@ __global__ __launch_bounds__(256) void prefill_vote_reduce_kernel(PrefillArgs a)
   const int t = blockIdx.x * 256 + threadIdx.x;
   const int Nc = min(max(a.seq_lens[b] - a.C, 0), a.max_seq_len);
   if (t >= Nc) return;
+  const int r_lo = min(a.n_init, Nc), r_hi = max(r_lo, Nc - a.n_local);
+  if (t < r_lo || t >= r_hi) { a.votes[(size_t)b * a.max_seq_len + t] = 0.f; return; }   // forced tokens are not ranked
   const int np = a.RB * a.H_kv;
   const float* p = a.vote_part + (size_t)b * np * a.max_seq_len + t;
   double v = 0.0;

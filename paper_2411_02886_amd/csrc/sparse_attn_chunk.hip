@@ -22,19 +22,25 @@ constexpr int kCaRows = 128;   // rows per workgroup
 constexpr int kCaTile = 32;    // keys per tile
 
 // slots[b][j]: physical slot of the j-th key of sequence b: the count[b] selected tokens, then the
-// chunk's C tokens (logical positions N_b - C ...)
+// chunk's C tokens (logical positions N_b - C ...); with forced tokens the selected ones are preceded by the initial
+// block and followed by the cached tokens just before the chunk
 __global__ __launch_bounds__(256) void chunk_slots_kernel(ChunkAttnArgs a) {
   const int b = blockIdx.y;
   const int j = blockIdx.x * 256 + threadIdx.x;
   const int cnt = min(max(a.count[b], 0), a.idx_stride);
   const int N = min(max(a.seq_lens[b], 0), a.max_seq_len);
-  if (j >= cnt + a.C) return;
+  const int Nc = max(N - a.C, 0);                               // cached tokens before the chunk
+  const int f_lo = min(a.n_init, Nc), f_hi = max(f_lo, Nc - a.n_local);   // forced blocks [0, f_lo) and [f_hi, Nc)
+  const int nsel = f_lo + cnt + (Nc - f_hi);                    // keys every query of the chunk sees
+  if (j >= nsel + a.C) return;
   int t;
-  if (j < cnt) t = a.idx[(size_t)b * a.idx_stride + j];
-  else t = N - a.C + (j - cnt);
+  if (j < f_lo) t = j;
+  else if (j < f_lo + cnt) t = a.idx[(size_t)b * a.idx_stride + (j - f_lo)];
+  else if (j < nsel) t = f_hi + (j - f_lo - cnt);
+  else t = N - a.C + (j - nsel);
   t = min(max(t, 0), max(N, 1) - 1);             // a stale or corrupt index must not leave the page table
   const int page = a.page_indices[a.page_indptr[b] + (t >> a.p_shift)];
-  a.slots[(size_t)b * (a.idx_stride + a.C) + j] = (page << a.p_shift) + (t & (a.P - 1));
+  a.slots[(size_t)b * a.slot_stride + j] = (page << a.p_shift) + (t & (a.P - 1));
 }
 
 template <int D>
@@ -57,7 +63,10 @@ __global__ __launch_bounds__(256) void chunk_attn_kernel(ChunkAttnArgs a) {
   const int rb = blockIdx.x / a.nsplit, split = blockIdx.x % a.nsplit, kvh = blockIdx.y, b = blockIdx.z;
   const int C = a.C, G = a.G, H = a.H;
   const int nrows = C * G;
-  const int cnt = min(max(a.count[b], 0), a.idx_stride);
+  // keys every query sees: forced initial block, selected tokens, forced block before the chunk (see chunk_slots_kernel)
+  const int Nc_ = max(min(max(a.seq_lens[b], 0), a.max_seq_len) - C, 0);
+  const int f_lo_ = min(a.n_init, Nc_), f_hi_ = max(f_lo_, Nc_ - a.n_local);
+  const int cnt = f_lo_ + min(max(a.count[b], 0), a.idx_stride) + (Nc_ - f_hi_);
   const int r0 = rb * kCaRows;
   if (r0 >= nrows) return;
   const int c_last = min(C - 1, (r0 + kCaRows - 1) / G);      // last query of this row block
@@ -67,7 +76,7 @@ __global__ __launch_bounds__(256) void chunk_attn_kernel(ChunkAttnArgs a) {
   const int tps = (ntile_all + a.nsplit - 1) / a.nsplit;
   const int tile0 = min(split * tps, ntile_all);
   const int ntile = min(tps, ntile_all - tile0);
-  const int* slots = a.slots + (size_t)b * (a.idx_stride + C);
+  const int* slots = a.slots + (size_t)b * a.slot_stride;
   const float c2 = a.sm_scale * 1.44269504088896340736f;
 
   // ---- query fragments (A operand of Q K^T): lane holds row = col, k = 16 * ks + 8 * half .. + 8
@@ -266,7 +275,7 @@ __global__ __launch_bounds__(D) void chunk_attn_merge_kernel(ChunkAttnArgs a) {
 }
 
 hipError_t launch_sparse_attn_chunk(const ChunkAttnArgs& a, int B, hipStream_t s) {
-  hipLaunchKernelGGL(chunk_slots_kernel, dim3((a.idx_stride + a.C + 255) / 256, B), dim3(256), 0, s, a);
+  hipLaunchKernelGGL(chunk_slots_kernel, dim3((a.slot_stride + 255) / 256, B), dim3(256), 0, s, a);
   const int nrb = (a.C * a.G + kCaRows - 1) / kCaRows;
   const dim3 grid(nrb * a.nsplit, a.H_kv, B);
   if (a.D == 128) hipLaunchKernelGGL(chunk_attn_kernel<128>, grid, dim3(256), 0, s, a);

@@ -44,7 +44,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int chunk_attn_splits(const ts_problem* p, int k) {
   const int G = p->num_q_heads / p->num_kv_heads;
   const long waves = (long)((p->chunk * G + 127) / 128) * 4 * p->num_kv_heads * p->batch;
-  const int ntile = (k + p->chunk + 31) / 32;
+  const int ntile = (k + p->num_initial + p->num_local + p->chunk + 31) / 32;
   int s = (int)((2048 + waves - 1) / waves);
   if (s > 8) s = 8;
   if (s > ntile / 4) s = ntile / 4;
@@ -83,7 +83,7 @@ inline WsLayout ws_layout(const ts_problem* p, int k) {
   w.attn_out = take(B * H * (size_t)w.attn_nsplit * D * 4);
   w.attn_ml = take(B * H * (size_t)w.attn_nsplit * 2 * 4);
   if (p->chunk > 1) {
-    w.attn_slots = take(B * ((size_t)k + p->chunk) * 4);
+    w.attn_slots = take(B * ((size_t)k + p->num_initial + p->num_local + p->chunk) * 4);
     w.attn_chunk_nsplit = chunk_attn_splits(p, k);
     if (w.attn_chunk_nsplit > 1) {
       w.attn_chunk_o = take(B * p->chunk * H * (size_t)w.attn_chunk_nsplit * D * 4);

@@ -95,6 +95,7 @@ struct PrefillArgs {
   float* votes;              // [B][max_seq_len]
   int B, C, H, H_kv, G, D, P, p_shift, max_seq_len;
   int RB;                    // 256-row blocks per KV head: ceil(C * G / 256)
+  int n_init, n_local;       // forced tokens: only cached tokens [min(n_init, Nc), max(that, Nc - n_local)) are ranked
   int TS;                    // token splits
   float scale, c2;
 };
@@ -117,6 +118,8 @@ struct ChunkAttnArgs {
   float* lse;                // [B][C][H] or null
   int C, H, H_kv, G, D, P, p_shift, idx_stride, max_seq_len;
   int nsplit;                // key-list splits per row block (1 = the kernel writes the result itself)
+  int n_init, n_local;       // forced cached tokens attended before / after the selected ones
+  int slot_stride;           // row stride of slots: idx_stride + n_init + n_local + C
   float* part_o;             // [B][C][H][nsplit][D] un-normalised partial outputs (nsplit > 1)
   float* part_ml;            // [B][C][H][nsplit][2] (reference exponent, row sum) of each partial
   float sm_scale;

@@ -116,8 +116,9 @@ class ChunkSelector:
     their sequences; two MFMA sweeps give the votes, ts_topk the shared index set."""
 
     def __init__(self, *, C, H, H_kv, D, P, k, k_pool, v_pool, page_indptr, page_indices, seq_lens, max_seq_len=None,
-                 device="cuda:0"):
+                 device="cuda:0", num_initial=0, num_local=0):
         self.C, self.H, self.H_kv, self.D, self.P, self.k = C, H, H_kv, D, P, k
+        self.num_initial, self.num_local = int(num_initial), int(num_local)   # forced cached tokens (Sec. 6.1)
         self.B = int(len(seq_lens))
         self.k_pool = k_pool if torch.is_tensor(k_pool) else to_device(k_pool, device)
         self.v_pool = v_pool if torch.is_tensor(v_pool) else to_device(v_pool, device)
@@ -128,7 +129,7 @@ class ChunkSelector:
         self.problem = ts.Problem(batch=self.B, chunk=C, num_q_heads=H, num_kv_heads=H_kv, head_dim=D, page_size=P,
                                   max_seq_len=self.max_seq_len, dtype=ts.TS_BF16, k_pool=self.k_pool,
                                   v_pool=self.v_pool, page_indptr=self.page_indptr, page_indices=self.page_indices,
-                                  seq_lens=self.seq_lens)
+                                  seq_lens=self.seq_lens, num_initial=self.num_initial, num_local=self.num_local)
         B, M = self.B, self.max_seq_len
         self.row_stats = torch.empty((B, C, H, 2), dtype=torch.float32, device=device)
         self.votes = torch.zeros((B, M), dtype=torch.float32, device=device)
@@ -141,9 +142,10 @@ class ChunkSelector:
         ts.ts_workspace_init(self.ws)
 
     @classmethod
-    def from_workload(cls, w, k=None, device="cuda:0"):
+    def from_workload(cls, w, k=None, device="cuda:0", num_initial=0, num_local=0):
         return cls(C=w.C, H=w.H, H_kv=w.H_kv, D=w.D, P=w.P, k=w.k if k is None else k, k_pool=w.k_pool, v_pool=w.v_pool,
-                   page_indptr=w.page_indptr, page_indices=w.page_indices, seq_lens=w.seq_lens, device=device)
+                   page_indptr=w.page_indptr, page_indices=w.page_indices, seq_lens=w.seq_lens, device=device,
+                   num_initial=num_initial, num_local=num_local)
 
     def select(self, q, score_scale=1.0):
         ts.ts_chunk_row_stats(self.problem, q, score_scale, self.row_stats, self.ws)
@@ -162,7 +164,8 @@ class ChunkSelector:
             cached = torch.clamp(self.seq_lens - self.C, min=0).to(torch.int32)
             prob = ts.Problem(batch=B, chunk=1, num_q_heads=self.H, num_kv_heads=self.H_kv, head_dim=self.D,
                               page_size=self.P, max_seq_len=M, dtype=ts.TS_BF16, k_pool=self.k_pool, v_pool=self.v_pool,
-                              page_indptr=self.page_indptr, page_indices=self.page_indices, seq_lens=cached)
+                              page_indptr=self.page_indptr, page_indices=self.page_indices, seq_lens=cached,
+                              num_initial=self.num_initial, num_local=self.num_local)
             nbytes = ts.ts_workspace_bytes(prob, self.k)
             ws = torch.empty((nbytes + 255) // 256 * 64, dtype=torch.int32, device=dev)
             ts.ts_workspace_init(ws)

@@ -22,9 +22,9 @@ def gpu():
     return ts
 
 
-def run_chunk_selection(ts, w, k, scale):
+def run_chunk_selection(ts, w, k, scale, n_init=0, n_local=0):
     from paper_2411_02886_amd.runtime import ChunkSelector, to_device, to_host
-    sel = ChunkSelector.from_workload(w, k=k)
+    sel = ChunkSelector.from_workload(w, k=k, num_initial=n_init, num_local=n_local)
     q = to_device(w.q)
     sel.select(q, scale)
     sel.attend(q)
@@ -33,43 +33,48 @@ def run_chunk_selection(ts, w, k, scale):
             to_host(sel.out, bits16=True), to_host(sel.lse))
 
 
-def check_chunk(ts, w, k, scale, label):
-    st_g, v_g, idx_g, cnt_g, out_g, lse_g_attn = run_chunk_selection(ts, w, k, scale)
+def check_chunk(ts, w, k, scale, label, n_init=0, n_local=0):
+    st_g, v_g, idx_g, cnt_g, out_g, lse_g_attn = run_chunk_selection(ts, w, k, scale, n_init, n_local)
     sm = float(np.float32(1.0 / math.sqrt(w.D)))
     c = float(np.float32(scale))
     for b in range(w.B):
-        Nc = int(w.seq_lens[b]) - w.C
+        Nc = max(int(w.seq_lens[b]) - w.C, 0)
+        lo, hi = oracle.ranked_range(Nc, n_init, n_local)          # forced blocks are taken from the cached tokens
         lab = "%s b=%d Nc=%d" % (label, b, Nc)
-        if Nc <= 0:
+        if hi <= lo:
             assert cnt_g[b] == 0 and np.all(idx_g[b] == -1), lab
-        # Eq. 2, chunk form: query c over the selected tokens plus the chunk's tokens 0..c (one softmax)
+        # Eq. 2, chunk form: query c over the forced and selected tokens plus the chunk's tokens 0..c (one softmax)
+        att = oracle.attended_tokens(idx_g[b], int(cnt_g[b]), Nc, n_init, n_local)
         for ci in sorted(set([0, 1, w.C // 2, w.C - 1]) if w.C > 8 else range(w.C)):
             o_ref, l_ref = oracle.sparse_attn(np.ascontiguousarray(w.q[b, ci]), w.k_pool, w.v_pool, w.dtype, w.H_kv, w.P,
-                                              w.pages_of(b), idx_g[b], int(cnt_g[b]), sm, extra_first=max(Nc, 0),
+                                              w.pages_of(b), att, len(att), sm, extra_first=Nc,
                                               n_extra=ci + 1, with_lse=True)
             err = np.abs(W.as_f32(out_g[b, ci], w.dtype).astype(np.float64) - o_ref).max()
             assert err <= 2e-2, (lab, "chunk attention", ci, err)
             assert np.abs(lse_g_attn[b, ci] - l_ref).max() <= 2e-2, (lab, "chunk attention lse", ci)
-        if Nc <= 0:
+        assert not v_g[b, :lo].any() and not v_g[b, hi:Nc].any(), (lab, "votes outside the ranked range must be 0")
+        if hi <= lo:
             continue
         votes = np.zeros(Nc)
         smax = 0.0
         for ci in range(w.C):
             S = oracle.paged_qk_scores(np.ascontiguousarray(w.q[b, ci]), w.k_pool, w.dtype, w.H_kv, w.P, w.pages_of(b), Nc)
-            v, m, z = oracle.soft_vote(S, c, with_stats=True)
-            votes += v
+            v, m, z = oracle.soft_vote(np.ascontiguousarray(S[:, lo:hi]), c, with_stats=True)
+            votes[lo:hi] += v
             smax = max(smax, float(np.abs(S).max()))
             # sweep 1: the row's log-sum-exp (stored base 2 as a high/low pair): score rounding + fast exp2
             lse_g = (st_g[b, ci, :, 0].astype(np.float64) + st_g[b, ci, :, 1]) * math.log(2.0)
             assert np.abs(lse_g - (m + np.log(z))).max() <= 8 * ulp32(smax) * c + 2e-5, (lab, ci, "row log-sum-exp")
         # sweep 2: votes; float arithmetic with the fast exponential: 3e-5 relative
-        np.testing.assert_allclose(v_g[b, :Nc], votes, rtol=3e-5, atol=1e-30, err_msg=lab + " votes")
-        assert abs(float(v_g[b, :Nc].astype(np.float64).sum()) - w.C * w.H) < 1e-4 * w.C * w.H, lab
+        np.testing.assert_allclose(v_g[b, lo:hi], votes[lo:hi], rtol=3e-5, atol=1e-30, err_msg=lab + " votes")
+        assert abs(float(v_g[b, lo:hi].astype(np.float64).sum()) - w.C * w.H) < 1e-4 * w.C * w.H, lab
         # radix select in isolation on the GPU's own votes: bit-exact
-        i_iso, c_iso = oracle.topk(v_g[b, :Nc].astype(np.float64), k)
+        i_iso, c_iso = oracle.topk(v_g[b, lo:hi].astype(np.float64), k)
+        i_iso = i_iso.copy(); i_iso[:c_iso] += lo
         assert cnt_g[b] == c_iso and np.array_equal(idx_g[b], i_iso), (lab, "radix select")
         # end to end against the oracle's chunk selection (1e-6 band rule)
-        i_o, c_o = oracle.topk(oracle.decision_votes(votes), k)
+        i_o, c_o = oracle.topk(oracle.decision_votes(votes[lo:hi]), k)
+        i_o = i_o.copy(); i_o[:c_o] += lo
         compare_index_sets(idx_g[b], int(cnt_g[b]), dict(idx=i_o, count=c_o, votes=votes), lab)
 
 
@@ -90,6 +95,19 @@ def test_chunk_selection_shapes(gpu, case):
     w = W.make_workload("chunk", dtype=W.BF16, C=C, H=H, H_kv=H_kv, D=D, P=P, seq_lens=[L], k=k, beta=2.5,
                         planted_per_head=max(1, (L - C) // 200), plant_limit=L - C, seed=L + C)
     check_chunk(gpu, w, k, scale, str(case))
+
+
+@pytest.mark.parametrize("forced", [(128, 512), (3, 0), (0, 70), (64, 64)])
+def test_chunk_selection_with_forced_tokens(gpu, forced):
+    # forced blocks are taken from the cached tokens before the chunk; sequences shorter than the blocks included
+    ni, nl = forced
+    C = 40
+    lens = [C + 3000, C + 640, C + 700, C + 100, C, C + 641, C + 63]
+    w = W.make_workload("chunkf", dtype=W.BF16, B=len(lens), C=C, H=8, H_kv=2, D=128, P=16, seq_lens=lens, k=50, seed=41 + ni)
+    print("chunk forced", forced, lens, flush=True)
+    check_chunk(gpu, w, 50, 0.0884, "chunk forced %d+%d" % forced, n_init=ni, n_local=nl)
+    w = W.make_workload("chunkf2", dtype=W.BF16, C=130, H=32, H_kv=8, D=128, P=16, seq_lens=[130 + 4000], k=256, seed=43)
+    check_chunk(gpu, w, 256, 1.0, "chunk forced cfg5 heads %d+%d" % forced, n_init=ni, n_local=nl)
 
 
 def test_chunk_selection_ragged_batch(gpu):
@@ -149,9 +167,9 @@ def test_config5_full_size_sampled(gpu):
 
 # ---------------------------------------------------------------- Sec. 5.2 as printed: mean-query selection
 
-def check_mean_query(ts, w, k, scale, label):
+def check_mean_query(ts, w, k, scale, label, n_init=0, n_local=0):
     from paper_2411_02886_amd.runtime import ChunkSelector, to_device, to_host
-    sel = ChunkSelector.from_workload(w, k=k)
+    sel = ChunkSelector.from_workload(w, k=k, num_initial=n_init, num_local=n_local)
     q = to_device(w.q)
     sel.select_mean_query(q, scale)
     sel.attend(q)
@@ -168,17 +186,24 @@ def check_mean_query(ts, w, k, scale, label):
         if Nc == 0:
             assert cnt_g[b] == 0 and np.all(idx_g[b] == -1), lab
             continue
+        lo, hi = oracle.ranked_range(Nc, n_init, n_local)
         i_o, c_o, votes, S = oracle.select_chunk_mean_query(np.ascontiguousarray(w.q[b]), w.k_pool, w.dtype, w.H_kv, w.P,
-                                                            w.pages_of(b), Nc, k, score_scale=c, details=True)
+                                                            w.pages_of(b), Nc, k, score_scale=c, details=True,
+                                                            n_init=n_init, n_local=n_local)
         Sg = np.ascontiguousarray(S_g[b, :Nc, :].T).astype(np.float64)
         assert np.abs(Sg - S).max() <= 6 * ulp32(np.abs(S).max()), (lab, "scores")
-        np.testing.assert_allclose(v_g[b, :Nc], oracle.soft_vote(Sg, c), rtol=5e-6, atol=1e-44, err_msg=lab)
-        i_iso, c_iso = oracle.topk(v_g[b, :Nc].astype(np.float64), k)
+        if hi > lo:
+            np.testing.assert_allclose(v_g[b, lo:hi], oracle.soft_vote(np.ascontiguousarray(Sg[:, lo:hi]), c), rtol=5e-6,
+                                       atol=1e-44, err_msg=lab)
+        assert not v_g[b, :lo].any() and not v_g[b, hi:Nc].any(), lab
+        i_iso, c_iso = oracle.topk(v_g[b, lo:hi].astype(np.float64), k)
+        i_iso = i_iso.copy(); i_iso[:c_iso] += lo
         assert cnt_g[b] == c_iso and np.array_equal(idx_g[b], i_iso), (lab, "radix select")
         compare_index_sets(idx_g[b], int(cnt_g[b]), dict(idx=i_o, count=c_o, votes=votes), lab)
+        att = oracle.attended_tokens(idx_g[b], int(cnt_g[b]), Nc, n_init, n_local)
         for ci in sorted(set([0, w.C // 2, w.C - 1])):
             o_ref = oracle.sparse_attn(np.ascontiguousarray(w.q[b, ci]), w.k_pool, w.v_pool, w.dtype, w.H_kv, w.P,
-                                       w.pages_of(b), idx_g[b], int(cnt_g[b]), sm, extra_first=Nc, n_extra=ci + 1)
+                                       w.pages_of(b), att, len(att), sm, extra_first=Nc, n_extra=ci + 1)
             assert np.abs(W.as_f32(out_g[b, ci], w.dtype).astype(np.float64) - o_ref).max() <= 2e-2, (lab, "attention", ci)
 
 
@@ -191,6 +216,14 @@ def test_mean_query_selection_shapes(gpu, case):
     w = W.make_workload("chunkmq", dtype=W.BF16, C=C, H=H, H_kv=H_kv, D=D, P=P, seq_lens=[L], k=k, beta=2.5,
                         planted_per_head=max(1, (L - C) // 200), plant_limit=L - C, seed=L + C + 1)
     check_mean_query(gpu, w, k, scale, "mq " + str(case))
+
+
+def test_mean_query_selection_with_forced_tokens(gpu):
+    C = 24
+    lens = [C + 2000, C + 100, C + 641, C]
+    w = W.make_workload("chunkmqf", dtype=W.BF16, B=len(lens), C=C, H=8, H_kv=2, D=128, P=16, seq_lens=lens, k=40, seed=45)
+    check_mean_query(gpu, w, 40, 0.0884, "mq forced", n_init=128, n_local=512)
+    check_mean_query(gpu, w, 40, 1.0, "mq forced small", n_init=5, n_local=9)
 
 
 def test_mean_query_selection_ragged_batch(gpu):
