@@ -11,6 +11,8 @@
  *
  * With forced tokens (ts_problem.num_initial / num_local) the same five calls rank only the middle of
  * each sequence and attend over initial block + selection + most recent block.
+ * A chunk of C > 1 queries (chunked prefill) uses ts_chunk_row_stats + ts_chunk_soft_vote (or
+ * ts_chunk_mean_query + the decode calls), ts_topk and ts_sparse_paged_attn with chunk = C.
  *
  * Conventions
  *   - Every pointer marked [device] is caller-owned device memory; [host] is host memory.
@@ -109,7 +111,9 @@ int32_t ts_paged_qk_scores(const ts_problem* p, const void* q, float* scores, fl
  *   row_stats[b][h][1] = sum_t exp(score_scale * (scores[b][t][h] - max))
  * then computes
  *   votes[b][t] = sum_h exp(score_scale*(scores[b][t][h] - max_h)) / sumexp_h        for t < N_b
- * in double precision from the float scores, rounded once to float.
+ * (difference, scaling and argument reduction in double precision, the fractional power of two by the
+ * float hardware exponential, the sum over heads in double, rounded once to float: about 1e-7 relative).
+ * With forced tokens the statistics and the votes cover the ranked range only; votes outside it are 0.
  * row_stats [device] float [B][H][2] out; votes [device] float [B][max_seq_len] (entries t >= N_b
  * untouched). */
 int32_t ts_soft_vote(const ts_problem* p, const float* scores, float score_scale, float* row_stats, float* votes,
