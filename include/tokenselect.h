@@ -131,6 +131,42 @@ int32_t ts_soft_vote(const ts_problem* p, const float* scores, float score_scale
 int32_t ts_topk(const ts_problem* p, const float* votes, int32_t k, int32_t* idx, int32_t* count,
                 const uint8_t* skip, int32_t flags, void* ws, size_t ws_bytes, void* stream);
 
+/* ---- Compact form of the selection (decode, chunk == 1): Algorithm 2, Eq. 5 and the TopK with the same result
+ * as ts_paged_qk_scores + ts_soft_vote + ts_topk, without the score matrix S ever reaching memory.  On this
+ * machine a write stream mixed into the K read stream costs several times its bytes, and S is 4*H bytes per
+ * token; the compact form writes H bytes per token and makes up for the lost precision by re-evaluating the few
+ * tokens that can still be among the k largest.
+ *
+ * ts_paged_qk_codes    Algorithm 2.  The scores are computed exactly as by ts_paged_qk_scores (same arithmetic,
+ *                      same bits) but leave as codes[b][t][h] = clamp(255 + ceil(4 * c2 * (s - M)), 0, 255), where
+ *                      c2 = score_scale * log2(e) and M is the maximum of head h over the ranked tokens of the
+ *                      token's block (a run of 32, 64 or 128 consecutive tokens, chosen per launch): the distance
+ *                      below the block maximum in quarter octaves of softmax weight, rounded towards the maximum;
+ *                      0 also stands for everything 63.75 octaves or more below it.  The exact (max, sum of
+ *                      exponentials) of every block and head go to the workspace.
+ * ts_soft_vote_bounds  Eq. 5.  Merges the block statistics into row_stats (as ts_soft_vote defines it) and gives
+ *                      every ranked token an interval that contains its vote as ts_soft_vote would compute it:
+ *                      vote_lo[b][t] <= votes[b][t] <= vote_hi[b][t], vote_hi / vote_lo about 2^(1/4); both 0
+ *                      outside the ranked range.  Must follow ts_paged_qk_codes with the same problem, workspace
+ *                      and score_scale.
+ * ts_topk_exact        The TopK of Eq. 5.  Every token whose upper bound reaches the k-th largest lower bound
+ *                      (a superset of the k largest votes; usually 1.1-1.5 k tokens) has its scores recomputed
+ *                      from K with the arithmetic of the score pass and its vote evaluated as by ts_soft_vote;
+ *                      the k largest of those votes are returned exactly as ts_topk returns them (ties to the
+ *                      lower token index, ascending token ids, unused slots -1).  Must follow
+ *                      ts_soft_vote_bounds with the same problem, workspace, q and score_scale.  Two launches.
+ * codes [device] uint8 [B][max_seq_len][H]; vote_hi, vote_lo [device] float [B][max_seq_len]; the other arguments
+ * as for the three calls they stand in for.  Sequences with skip[b] != 0 are left untouched.  The cost of
+ * ts_topk_exact grows with the number of candidates: flat votes (a small score_scale) give more of them, never a
+ * wrong result. */
+int32_t ts_paged_qk_codes(const ts_problem* p, const void* q, uint8_t* codes, float score_scale,
+                          const uint8_t* skip, void* ws, size_t ws_bytes, void* stream);
+int32_t ts_soft_vote_bounds(const ts_problem* p, const uint8_t* codes, float score_scale, float* row_stats,
+                            float* vote_hi, float* vote_lo, const uint8_t* skip, void* ws, size_t ws_bytes, void* stream);
+int32_t ts_topk_exact(const ts_problem* p, const void* q, const float* vote_hi, const float* row_stats,
+                      float score_scale, int32_t k, int32_t* idx, int32_t* count, const uint8_t* skip, void* ws,
+                      size_t ws_bytes, void* stream);
+
 /* The two selection functions the paper ablates against Eq. 5 (Sec. 5.1), as other ways to fill `votes`
  * from the scores of ts_paged_qk_scores; ts_topk then ranks them as usual (decode only, chunk == 1).
  *
@@ -204,6 +240,12 @@ int32_t ts_chunk_mean_query(const ts_problem* p, const void* q, void* q_mean, vo
  * or 0 = automatic (longer runs for longer sequences).  Results do not depend on wg or run_tiles.
  * Host only. */
 int32_t ts_debug_set_score_variant(int32_t variant, int32_t wg, int32_t run_tiles);
+
+/* Tuning knob (process-wide, tests and benchmarks): mfma = 1 (default) lets ts_paged_qk_codes run on the matrix
+ * cores where the shape allows (bf16; 3-4 query heads per KV head with at least 8 KV heads, or 5-8 with exactly 4),
+ * 0 forces the vector form; run_tiles = 32-token tiles whose bytes a wave collects before writing them (1..8),
+ * 0 = automatic.  The bytes and the selection do not depend on either.  Host only. */
+int32_t ts_debug_set_codes_path(int32_t mfma, int32_t run_tiles);
 
 /* Tuning knob (process-wide, tests and benchmarks): five_pass = 1 makes ts_topk / ts_head_vote use the
  * five-pass radix select (three global histogram passes, count, emit) that otherwise only serves sequences

@@ -68,6 +68,9 @@ def load():
         L.ts_paged_qk_scores.argtypes = [pp, vp, vp, f32, vp, vp, sz, vp]
         L.ts_soft_vote.argtypes = [pp, vp, f32, vp, vp, vp, vp, sz, vp]
         L.ts_topk.argtypes = [pp, vp, i32, vp, vp, vp, i32, vp, sz, vp]
+        L.ts_paged_qk_codes.argtypes = [pp, vp, vp, f32, vp, vp, sz, vp]
+        L.ts_soft_vote_bounds.argtypes = [pp, vp, f32, vp, vp, vp, vp, vp, sz, vp]
+        L.ts_topk_exact.argtypes = [pp, vp, vp, vp, f32, i32, vp, vp, vp, vp, sz, vp]
         L.ts_selcache_check.argtypes = [pp, vp, vp, vp, f32, vp, vp]
         L.ts_sparse_paged_attn.argtypes = [pp, vp, vp, i32, vp, f32, vp, vp, vp, sz, vp]
         L.ts_chunk_row_stats.argtypes = [pp, vp, f32, vp, vp, sz, vp]
@@ -78,6 +81,7 @@ def load():
         L.ts_head_vote.argtypes = [pp, vp, i32, vp, vp, vp, sz, vp]
         L.ts_debug_set_score_variant.argtypes = [i32, i32, i32]
         L.ts_debug_set_topk_path.argtypes = [i32]
+        L.ts_debug_set_codes_path.argtypes = [i32, i32]
         L.ts_debug_event_create.argtypes = [ctypes.POINTER(vp)]
         L.ts_debug_event_destroy.argtypes = [vp]
         L.ts_debug_event_elapsed_ms.argtypes = [vp, vp, ctypes.POINTER(f32)]
@@ -86,7 +90,8 @@ def load():
                      "ts_selcache_check", "ts_sparse_paged_attn", "ts_debug_set_score_variant", "ts_chunk_row_stats",
                      "ts_chunk_soft_vote", "ts_chunk_mean_query", "ts_sum_vote", "ts_head_vote_scratch_bytes",
                      "ts_head_vote", "ts_debug_set_topk_path", "ts_debug_event_create", "ts_debug_event_destroy",
-                     "ts_debug_event_elapsed_ms", "ts_debug_set_score_timing_events"):
+                     "ts_debug_event_elapsed_ms", "ts_debug_set_score_timing_events", "ts_paged_qk_codes",
+                     "ts_soft_vote_bounds", "ts_topk_exact", "ts_debug_set_codes_path"):
             getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -144,6 +149,10 @@ def ts_debug_set_score_variant(variant: int, wg: int = 0, run_tiles: int = 0) ->
     _ok(load().ts_debug_set_score_variant(int(variant), int(wg), int(run_tiles)), "ts_debug_set_score_variant")
 
 
+def ts_debug_set_codes_path(mfma: int, run_tiles: int = 0) -> None:
+    _ok(load().ts_debug_set_codes_path(int(mfma), int(run_tiles)), "ts_debug_set_codes_path")
+
+
 def ts_debug_set_topk_path(five_pass: int) -> None:
     _ok(load().ts_debug_set_topk_path(int(five_pass)), "ts_debug_set_topk_path")
 
@@ -183,6 +192,22 @@ def ts_paged_qk_scores(p: Problem, q, scores, score_scale: float, skip, ws, stre
 def ts_soft_vote(p: Problem, scores, score_scale: float, row_stats, votes, skip, ws, stream=None) -> None:
     _ok(load().ts_soft_vote(p.ref(), _ptr(scores), float(score_scale), _ptr(row_stats), _ptr(votes), _ptr(skip),
                             _ptr(ws), _nbytes(ws), _stream(stream)), "ts_soft_vote")
+
+
+def ts_paged_qk_codes(p: Problem, q, codes, score_scale: float, skip, ws, stream=None) -> None:
+    _ok(load().ts_paged_qk_codes(p.ref(), _ptr(q), _ptr(codes), float(score_scale), _ptr(skip), _ptr(ws), _nbytes(ws),
+                                 _stream(stream)), "ts_paged_qk_codes")
+
+
+def ts_soft_vote_bounds(p: Problem, codes, score_scale: float, row_stats, vote_hi, vote_lo, skip, ws, stream=None) -> None:
+    _ok(load().ts_soft_vote_bounds(p.ref(), _ptr(codes), float(score_scale), _ptr(row_stats), _ptr(vote_hi),
+                                   _ptr(vote_lo), _ptr(skip), _ptr(ws), _nbytes(ws), _stream(stream)),
+        "ts_soft_vote_bounds")
+
+
+def ts_topk_exact(p: Problem, q, vote_hi, row_stats, score_scale: float, k: int, idx, count, skip, ws, stream=None) -> None:
+    _ok(load().ts_topk_exact(p.ref(), _ptr(q), _ptr(vote_hi), _ptr(row_stats), float(score_scale), int(k), _ptr(idx),
+                             _ptr(count), _ptr(skip), _ptr(ws), _nbytes(ws), _stream(stream)), "ts_topk_exact")
 
 
 def ts_chunk_row_stats(p: Problem, q, score_scale: float, row_stats, ws, stream=None) -> None:

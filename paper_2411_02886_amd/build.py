@@ -16,7 +16,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtokenselect.so")
 SOURCES = ["api.hip", "score_decode.hip", "soft_vote.hip", "topk.hip", "selcache.hip", "sparse_attn_decode.hip", "prefill_select.hip", "sparse_attn_chunk.hip",
-           "chunk_mean_query.hip", "select_variants.hip"]
+           "chunk_mean_query.hip", "select_variants.hip", "select_compact.hip", "score_codes_mfma.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -11,6 +11,8 @@ static int g_score_variant = 1;   // 0 = fma, 1 = packed bf16 dot2 (tuning knob,
 static int g_score_wg = 0;        // 0 = automatic
 static int g_score_rr = 0;        // tiles per staged run; 0 = automatic
 static int g_topk_five_pass = 0;  // 1 = force the five-pass radix select (tuning knob)
+static int g_codes_mfma = 1;      // 1 = the compact score pass runs on the matrix cores where the shape allows
+static int g_codes_rr = 0;        // tiles per run of the matrix-core compact score pass; 0 = automatic
 
 // workgroups per sequence of the score pass (also the number of statistics partials it leaves)
 // Tiles a wave of the score pass stages before writing them out: longer runs make the score stores
@@ -23,7 +25,7 @@ static int score_run_tiles(const ts_problem* p) {
   const long ntiles = (long)(p->max_seq_len + kScoreTileTokens - 1) / kScoreTileTokens;
   for (int rr = 4; rr > 1; rr >>= 1) {
     const long runs = (ntiles + rr - 1) / rr * nu;   // per sequence: others of the batch may be skipped
-    if (runs >= 4096 && (size_t)4 * rr * kScoreTileTokens * hs * sizeof(float) <= 65536) return rr;
+    if (runs >= 4096 && (size_t)4 * rr * kScoreTileTokens * hs * sizeof(float) <= 65536 - 1024) return rr;   // 1 KiB goes to the block maxima of the compact form
   }
   return 1;
 }
@@ -34,7 +36,7 @@ static int score_run_tiles_eff(const ts_problem* p) {
   const int hb = p->num_kv_heads < 8 ? p->num_kv_heads : 8;
   const int hs = (hb * (p->num_q_heads / p->num_kv_heads) + 3) & ~3;
   int rr = g_score_rr;
-  while (rr > 1 && (size_t)4 * rr * kScoreTileTokens * hs * sizeof(float) > 65536) rr >>= 1;
+  while (rr > 1 && (size_t)4 * rr * kScoreTileTokens * hs * sizeof(float) > 65536 - 1024) rr >>= 1;
   return rr;
 }
 
@@ -141,6 +143,13 @@ int32_t ts_debug_event_elapsed_ms(void* start, void* stop, float* ms) {
 int32_t ts_debug_set_score_timing_events(void* start, void* stop) {
   if ((start == nullptr) != (stop == nullptr)) return TS_ERR_INVALID_ARG;
   set_score_timing_events((hipEvent_t)start, (hipEvent_t)stop);
+  set_codes_timing_events((hipEvent_t)start, (hipEvent_t)stop);
+  return TS_OK;
+}
+
+int32_t ts_debug_set_codes_path(int32_t mfma, int32_t run_tiles) {
+  if ((mfma != 0 && mfma != 1) || run_tiles < 0 || run_tiles > 8) return TS_ERR_INVALID_ARG;
+  g_codes_mfma = mfma; g_codes_rr = run_tiles;
   return TS_OK;
 }
 
@@ -150,35 +159,149 @@ int32_t ts_debug_set_topk_path(int32_t five_pass) {
   return TS_OK;
 }
 
+// argument block and launch shape shared by the two forms of the score pass
+static int32_t fill_score_args(const ts_problem* p, const void* q, float score_scale, const uint8_t* skip, void* ws,
+                               size_t ws_bytes, size_t ws_need, ScoreArgs* a, const WsLayout& w) {
+  if (q == nullptr || p->k_pool == nullptr) return TS_ERR_INVALID_ARG;
+  if (!(score_scale >= 0.f) || !(score_scale < 1e30f)) return TS_ERR_INVALID_ARG;
+  if (p->chunk != 1) return TS_ERR_UNSUPPORTED;
+  if (ws == nullptr || ((uintptr_t)ws & 255) != 0 || ws_bytes < ws_need) return TS_ERR_WORKSPACE;
+  const int G = p->num_q_heads / p->num_kv_heads;
+  a->q = (const uint8_t*)q; a->k_pool = (const uint8_t*)p->k_pool;
+  a->page_indptr = p->page_indptr; a->page_indices = p->page_indices; a->seq_lens = p->seq_lens; a->skip = skip;
+  a->partials = (float*)((uint8_t*)ws + w.score_partials);
+  a->hdr = (uint32_t*)((uint8_t*)ws + w.hdr);
+  a->H = p->num_q_heads; a->H_kv = p->num_kv_heads; a->P = p->page_size; a->p_shift = ilog2(p->page_size);
+  a->max_seq_len = p->max_seq_len;
+  a->HB = p->num_kv_heads < 8 ? p->num_kv_heads : 8; a->hb_shift = ilog2(a->HB); a->NU = p->num_kv_heads / a->HB;
+  a->uniform_page = p->page_size >= (8 / a->HB);
+  a->ncp_shift = ilog2(a->HB * G);
+  a->scale = score_scale; a->c2 = score_scale * 1.44269504088896340736f;
+  a->n_init = p->num_initial; a->n_local = p->num_local;
+  a->RR = score_run_tiles_eff(p);
+  return TS_OK;
+}
+
+static size_t score_lds_bytes(const ScoreArgs& a, int G) {
+  size_t per_wave = (size_t)a.RR * kScoreTileTokens * ((a.HB * G + 3) & ~3);
+  if (per_wave < 512) per_wave = 512;   // the closing statistics exchange needs 64 x 8 floats per wave
+  return 4 * (per_wave + 64) * sizeof(float);   // + 64 block maxima per wave (compact form)
+}
+
 int32_t ts_paged_qk_scores(const ts_problem* p, const void* q, float* scores, float score_scale,
                            const uint8_t* skip, void* ws, size_t ws_bytes, void* stream) {
   int32_t st = check_problem(p);
   if (st != TS_OK) return st;
-  if (q == nullptr || scores == nullptr || p->k_pool == nullptr) return TS_ERR_INVALID_ARG;
+  if (scores == nullptr) return TS_ERR_INVALID_ARG;
+  const WsLayout w = ws_layout(p, 1);
+  ScoreArgs a{};
+  st = fill_score_args(p, q, score_scale, skip, ws, ws_bytes, w.topk_blk, &a, w);   // needs the sections up to score_partials
+  if (st != TS_OK) return st;
+  const int G = p->num_q_heads / p->num_kv_heads;
+  a.scores = scores;
+  a.vec_store = (p->num_q_heads % 4 == 0) && ((a.HB * G) % 4 == 0) && (((uintptr_t)scores & 15) == 0);
+  const int wg = score_workgroups(p);
+  const int variant = (p->dtype == TS_BF16) ? g_score_variant : 0;
+  const hipError_t e = launch_score_decode(p->dtype, p->head_dim, G, variant, a, dim3(wg, p->batch), score_lds_bytes(a, G), (hipStream_t)stream);
+  return e == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
+// ---- compact form of the selection: Algorithm 2 + Eq. 5 + TopK without the score matrix in memory
+
+int32_t ts_paged_qk_codes(const ts_problem* p, const void* q, uint8_t* codes, float score_scale,
+                          const uint8_t* skip, void* ws, size_t ws_bytes, void* stream) {
+  int32_t st = check_problem(p);
+  if (st != TS_OK) return st;
+  if (codes == nullptr) return TS_ERR_INVALID_ARG;
+  const WsLayout w = ws_layout(p, 1);
+  ScoreArgs a{};
+  st = fill_score_args(p, q, score_scale, skip, ws, ws_bytes, w.attn_out, &a, w);   // needs the block statistics too
+  if (st != TS_OK) return st;
+  const int G = p->num_q_heads / p->num_kv_heads;
+  a.codes = codes;
+  a.blk_max = (float*)((uint8_t*)ws + w.blk_max); a.nblk = w.score_nblk;
+  if (g_codes_mfma && (p->num_q_heads % 4) == 0 && (((uintptr_t)codes & 3) == 0) &&
+      score_codes_mfma_supported(p->dtype, p->head_dim, G, p->num_kv_heads)) {
+    // matrix-core form: a wave owns one run of consecutive tiles where the sequence is short enough, so that
+    // its bytes leave in one burst at the end of its life; about 2048 waves per sequence (measured on MI355X:
+    // 131072 tokens 49 us with one tile per wave, 45.7 us with two)
+    a.HB = G <= 4 ? 8 : 4; a.hb_shift = ilog2(a.HB); a.NU = p->num_kv_heads / a.HB;
+    a.uniform_page = p->page_size >= (8 / a.HB);
+    const long ntt = (p->max_seq_len + kScoreTileTokens - 1) / kScoreTileTokens;
+    int rr = g_codes_rr > 0 ? g_codes_rr : (int)((ntt * a.NU + 2047) / 2048);
+    if (rr > 8) rr = 8;
+    if (rr < 1) rr = 1;
+    a.RR = rr;
+    long wgl = ((ntt + rr - 1) / rr * a.NU + 3) / 4;
+    if (wgl > kScoreMaxWg) wgl = kScoreMaxWg;
+    if (g_score_wg > 0) wgl = g_score_wg;
+    const hipError_t e = launch_score_codes_mfma(p->head_dim, G, a, dim3((unsigned)wgl, p->batch),
+                                                 score_codes_mfma_lds_bytes(p->head_dim, G, rr), (hipStream_t)stream);
+    return e == hipSuccess ? TS_OK : TS_ERR_HIP;
+  }
+  a.vec_store = (p->num_q_heads % 4 == 0) && ((a.HB * G) % 4 == 0) && (((uintptr_t)codes & 3) == 0);
+  const int wg = score_workgroups(p);
+  const int variant = (p->dtype == TS_BF16) ? g_score_variant : 0;
+  const hipError_t e = launch_score_decode(p->dtype, p->head_dim, G, variant, a, dim3(wg, p->batch), score_lds_bytes(a, G), (hipStream_t)stream);
+  return e == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
+int32_t ts_soft_vote_bounds(const ts_problem* p, const uint8_t* codes, float score_scale, float* row_stats,
+                            float* vote_hi, float* vote_lo, const uint8_t* skip, void* ws, size_t ws_bytes, void* stream) {
+  int32_t st = check_problem(p);
+  if (st != TS_OK) return st;
+  if (codes == nullptr || row_stats == nullptr || vote_hi == nullptr || vote_lo == nullptr) return TS_ERR_INVALID_ARG;
   if (!(score_scale >= 0.f) || !(score_scale < 1e30f)) return TS_ERR_INVALID_ARG;
   if (p->chunk != 1) return TS_ERR_UNSUPPORTED;
   const WsLayout w = ws_layout(p, 1);
-  if (ws == nullptr || ((uintptr_t)ws & 255) != 0 || ws_bytes < w.topk_blk) return TS_ERR_WORKSPACE;  // needs the sections up to score_partials
-  const int G = p->num_q_heads / p->num_kv_heads;
-  ScoreArgs a{};
-  a.q = (const uint8_t*)q; a.k_pool = (const uint8_t*)p->k_pool;
-  a.page_indptr = p->page_indptr; a.page_indices = p->page_indices; a.seq_lens = p->seq_lens; a.skip = skip;
-  a.scores = scores;
-  a.partials = (float*)((uint8_t*)ws + w.score_partials);
-  a.H = p->num_q_heads; a.H_kv = p->num_kv_heads; a.P = p->page_size; a.p_shift = ilog2(p->page_size);
-  a.max_seq_len = p->max_seq_len;
-  a.HB = p->num_kv_heads < 8 ? p->num_kv_heads : 8; a.hb_shift = ilog2(a.HB); a.NU = p->num_kv_heads / a.HB;
-  a.uniform_page = p->page_size >= (8 / a.HB);
-  a.vec_store = (p->num_q_heads % 4 == 0) && ((a.HB * G) % 4 == 0) && (((uintptr_t)scores & 15) == 0);
-  a.scale = score_scale; a.c2 = score_scale * 1.44269504088896340736f;
+  if (ws == nullptr || ((uintptr_t)ws & 255) != 0 || ws_bytes < w.attn_out) return TS_ERR_WORKSPACE;
+  BoundArgs a{};
+  a.codes = codes; a.blk_max = (const float*)((uint8_t*)ws + w.blk_max);
+  a.hdr = (const uint32_t*)((uint8_t*)ws + w.hdr);
+  a.row_stats = row_stats; a.vote_hi = vote_hi; a.vote_lo = vote_lo;
+  a.hist = (uint32_t*)((uint8_t*)ws + w.bound_hist);
+  a.seq_lens = p->seq_lens; a.skip = skip;
+  a.H = p->num_q_heads; a.max_seq_len = p->max_seq_len; a.nblk = w.score_nblk;
   a.n_init = p->num_initial; a.n_local = p->num_local;
-  const int wg = score_workgroups(p);
-  a.RR = score_run_tiles_eff(p);
-  size_t lds = (size_t)4 * a.RR * kScoreTileTokens * ((a.HB * G + 3) & ~3) * sizeof(float);
-  if (lds < 8192) lds = 8192;   // the closing statistics exchange needs 4 x 64 x 8 floats
-  const int variant = (p->dtype == TS_BF16) ? g_score_variant : 0;
-  const hipError_t e = launch_score_decode(p->dtype, p->head_dim, G, variant, a, dim3(wg, p->batch), lds, (hipStream_t)stream);
-  return e == hipSuccess ? TS_OK : TS_ERR_HIP;
+  a.vec = (p->num_q_heads % 4 == 0) && (((uintptr_t)codes & 3) == 0);
+  a.scale = score_scale;
+  VoteArgs m{};
+  m.partials = (const float*)((uint8_t*)ws + w.score_partials); m.hdr = a.hdr;
+  m.row_stats_out = row_stats; m.skip = skip; m.H = p->num_q_heads; m.scale = score_scale;
+  if (launch_stats_merge(m, p->batch, (hipStream_t)stream) != hipSuccess) return TS_ERR_HIP;
+  return launch_vote_bounds(a, p->batch, (hipStream_t)stream) == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
+int32_t ts_topk_exact(const ts_problem* p, const void* q, const float* vote_hi, const float* row_stats,
+                      float score_scale, int32_t k, int32_t* idx, int32_t* count, const uint8_t* skip, void* ws,
+                      size_t ws_bytes, void* stream) {
+  int32_t st = check_problem(p);
+  if (st != TS_OK) return st;
+  if (q == nullptr || vote_hi == nullptr || row_stats == nullptr || idx == nullptr || count == nullptr || k < 1)
+    return TS_ERR_INVALID_ARG;
+  if (p->k_pool == nullptr) return TS_ERR_INVALID_ARG;
+  if (!(score_scale >= 0.f) || !(score_scale < 1e30f)) return TS_ERR_INVALID_ARG;
+  if (p->chunk != 1) return TS_ERR_UNSUPPORTED;
+  const WsLayout w = ws_layout(p, k);
+  if (ws == nullptr || ((uintptr_t)ws & 255) != 0 || ws_bytes < w.attn_out) return TS_ERR_WORKSPACE;
+  if (w.topk_nblk > kTopkFinalMaxBlk) return TS_ERR_UNSUPPORTED;
+  RefineArgs a{};
+  a.t.head = p->num_initial; a.t.tail = p->num_local;
+  a.t.votes = vote_hi; a.t.seq_lens = p->seq_lens; a.t.skip = skip; a.t.idx = idx; a.t.count = count;
+  a.t.hist = (uint32_t*)((uint8_t*)ws + w.topk_hist);
+  a.t.bound_hist = (uint32_t*)((uint8_t*)ws + w.bound_hist);
+  a.t.state = (uint32_t*)((uint8_t*)ws + w.topk_state);
+  a.t.blk = (uint32_t*)((uint8_t*)ws + w.topk_blk);
+  a.t.list = (uint2*)((uint8_t*)ws + w.topk_list);
+  a.t.k = k; a.t.max_seq_len = p->max_seq_len; a.t.nblk = w.topk_nblk; a.t.heads = 1;
+  a.q = (const uint8_t*)q; a.k_pool = (const uint8_t*)p->k_pool;
+  a.page_indptr = p->page_indptr; a.page_indices = p->page_indices; a.row_stats = row_stats;
+  a.H = p->num_q_heads; a.H_kv = p->num_kv_heads; a.P = p->page_size; a.p_shift = ilog2(p->page_size);
+  a.HB = p->num_kv_heads < 8 ? p->num_kv_heads : 8; a.hb_shift = ilog2(a.HB); a.NU = p->num_kv_heads / a.HB;
+  a.scale = score_scale;
+  const int G = p->num_q_heads / p->num_kv_heads;
+  if (launch_topk_refine(p->dtype, p->head_dim, G, a, p->batch, (hipStream_t)stream) != hipSuccess) return TS_ERR_HIP;
+  return launch_topk_final_full(a.t, p->batch, (hipStream_t)stream) == hipSuccess ? TS_OK : TS_ERR_HIP;
 }
 
 int32_t ts_soft_vote(const ts_problem* p, const float* scores, float score_scale, float* row_stats, float* votes,
@@ -191,7 +314,7 @@ int32_t ts_soft_vote(const ts_problem* p, const float* scores, float score_scale
   const WsLayout w = ws_layout(p, 1);
   if (ws == nullptr || ((uintptr_t)ws & 255) != 0 || ws_bytes < w.topk_blk) return TS_ERR_WORKSPACE;
   VoteArgs a{};
-  a.partials = (const float*)((uint8_t*)ws + w.score_partials); a.nparts = score_workgroups(p);
+  a.partials = (const float*)((uint8_t*)ws + w.score_partials); a.hdr = (const uint32_t*)((uint8_t*)ws + w.hdr);
   a.scores = scores; a.row_stats = row_stats; a.row_stats_out = row_stats; a.votes = votes; a.seq_lens = p->seq_lens; a.skip = skip;
   a.H = p->num_q_heads; a.max_seq_len = p->max_seq_len; a.scale = score_scale;
   a.n_init = p->num_initial; a.n_local = p->num_local;

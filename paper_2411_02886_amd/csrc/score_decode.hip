@@ -13,69 +13,20 @@
 // longer sequences: on this memory system a write stream mixed into the read stream costs about three
 // times its bytes, and fewer, larger bursts reduce that.
 #include "ts_kernels.h"
+#include "ts_score_math.h"
 #include <hip/hip_ext.h>
 
 namespace ts {
 
 
-template <int DT> struct Elt;
-template <> struct Elt<TS_F32> { static constexpr int size = 4; };
-template <> struct Elt<TS_BF16> { static constexpr int size = 2; };
-
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
-
-// One 16-byte piece of a K row times the matching piece of one query head.
-template <int DT, bool DOT2> struct Piece;
-template <> struct Piece<TS_F32, false> {
-  struct Q { float v[4]; };
-  static __device__ __forceinline__ Q prep(uint4 w) {
-    Q q; q.v[0] = __uint_as_float(w.x); q.v[1] = __uint_as_float(w.y); q.v[2] = __uint_as_float(w.z); q.v[3] = __uint_as_float(w.w);
-    return q;
-  }
-  static __device__ __forceinline__ float dot(uint4 k, const Q& q, float acc) {
-    acc = fmaf(__uint_as_float(k.x), q.v[0], acc);
-    acc = fmaf(__uint_as_float(k.y), q.v[1], acc);
-    acc = fmaf(__uint_as_float(k.z), q.v[2], acc);
-    acc = fmaf(__uint_as_float(k.w), q.v[3], acc);
-    return acc;
-  }
-};
-template <> struct Piece<TS_BF16, false> {
-  struct Q { float v[8]; };
-  static __device__ __forceinline__ Q prep(uint4 w) {
-    Q q;
-    q.v[0] = bf16_lo(w.x); q.v[1] = bf16_hi(w.x); q.v[2] = bf16_lo(w.y); q.v[3] = bf16_hi(w.y);
-    q.v[4] = bf16_lo(w.z); q.v[5] = bf16_hi(w.z); q.v[6] = bf16_lo(w.w); q.v[7] = bf16_hi(w.w);
-    return q;
-  }
-  static __device__ __forceinline__ float dot(uint4 k, const Q& q, float acc) {
-    // bf16 x bf16 products are exact in float; each fma rounds once
-    acc = fmaf(bf16_lo(k.x), q.v[0], acc); acc = fmaf(bf16_hi(k.x), q.v[1], acc);
-    acc = fmaf(bf16_lo(k.y), q.v[2], acc); acc = fmaf(bf16_hi(k.y), q.v[3], acc);
-    acc = fmaf(bf16_lo(k.z), q.v[4], acc); acc = fmaf(bf16_hi(k.z), q.v[5], acc);
-    acc = fmaf(bf16_lo(k.w), q.v[6], acc); acc = fmaf(bf16_hi(k.w), q.v[7], acc);
-    return acc;
-  }
-};
-template <> struct Piece<TS_BF16, true> {
-  struct Q { uint4 w; };
-  static __device__ __forceinline__ Q prep(uint4 w) { Q q; q.w = w; return q; }
-  static __device__ __forceinline__ float d2(uint32_t a, uint32_t b, float acc) {
-    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), acc, false);
-  }
-  static __device__ __forceinline__ float dot(uint4 k, const Q& q, float acc) {
-    acc = d2(k.x, q.w.x, acc); acc = d2(k.y, q.w.y, acc); acc = d2(k.z, q.w.z, acc); acc = d2(k.w, q.w.w, acc);
-    return acc;
-  }
-};
-
-__device__ __forceinline__ void wave_lds_sync() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-template <int DT, int D, int G, bool DOT2>
+// Both modes keep running softmax statistics in the lanes that end as one partial per workgroup.
+// MODE 0: Algorithm 2's S leaves as fp32 rows.  MODE 1 (compact form): nothing but one byte per score leaves --
+// the score's distance below the maximum of its head inside the run (a "block" of RR x 32 tokens), in quarter
+// octaves of the softmax weight, rounded towards the maximum -- next to the block's per-head maximum; S itself
+// never reaches memory.  The bytes bound every softmax weight from both sides, which is enough to find the few
+// tokens whose votes have to be evaluated exactly.  (The matrix-core kernel in score_codes_mfma.hip is the fast
+// form of MODE 1 for bf16; this one serves fp32 and the shapes that one does not take.)
+template <int DT, int D, int G, bool DOT2, int MODE>
 __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
   constexpr int ES = Elt<DT>::size;
   constexpr int RB = D * ES;          // bytes per K row
@@ -96,7 +47,8 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
   const int H = a.H, HB = a.HB, HBG = HB * G;
   const int HS = (HBG + 3) & ~3;             // floats per token row of the staged tile
   const int RR = a.RR;                        // tiles a wave stages before it writes them out as one run
-  float* stage = smem + wave * max(RR * TT * HS, 512);   // [RR][TT][HS] staged scores, token-major (>= 512 floats: reused below)
+  const int stage_floats = max(RR * TT * HS, 512) + 64;  // [RR][TT][HS] staged scores, token-major (>= 512 floats: reused below) + 64 block maxima
+  float* stage = smem + wave * stage_floats;
 
   const int tps_shift = 3 - a.hb_shift;      // log2(tokens per wave step)
   const int STEPS = TT >> tps_shift;
@@ -188,8 +140,8 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
       float v = acc[0];
 #pragma unroll
       for (int g = 1; g < G; ++g) v = (j == g) ? acc[g] : v;
-      const bool act = (j < G) && (t0 + tl >= r_lo) && (t0 + tl < r_hi);
       if (j < G) tile[tl * HS + kvh_l * G + j] = v;
+      const bool act = (j < G) && (t0 + tl >= r_lo) && (t0 + tl < r_hi);
       if (__builtin_amdgcn_ballot_w64(act && v > rm) != 0) {   // rare after the first tiles: rescale to the new maximum
         const float mn = act ? fmaxf(rm, v) : rm;
         rl = (rm == -INFINITY) ? 0.f : rl * __builtin_amdgcn_exp2f(c2 * (rm - mn));
@@ -197,6 +149,48 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
       }
       if (act) rl += __builtin_amdgcn_exp2f(c2 * (v - rm));
     }
+  };
+  // compact form: the run's per-head maximum over its ranked tokens, then one byte per score
+  const int ncp_shift = a.ncp_shift;          // lanes per token subset: the power of two >= HBG (<= 64)
+  auto epilogue_codes = [&](int t0, int ntok) {
+    wave_lds_sync();
+    const int NCP = 1 << ncp_shift;
+    const int c = lane & (NCP - 1), sub = lane >> ncp_shift, groups = 64 >> ncp_shift;
+    const int tmin = max(0, r_lo - t0), tmax = min(ntok, r_hi - t0);   // staged tokens that take part in the softmax
+    float mx = -INFINITY;
+    if (c < HBG)
+      for (int tok = tmin + sub; tok < tmax; tok += groups) mx = fmaxf(mx, stage[tok * HS + c]);
+    for (int off = NCP; off < 64; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+    float* bmx = stage + (stage_floats - 64);
+    if (sub == 0) {
+      bmx[c] = (c < HBG) ? mx : -INFINITY;
+      if (c < HBG) a.blk_max[((size_t)b * a.nblk + (size_t)(t0 / (RR * TT))) * H + h_base + c] = mx;
+    }
+    wave_lds_sync();
+    for (int tok0 = 0; tok0 < ntok; tok0 += TPP) {
+      const int tok = tok0 + e_sub;
+      const int t = t0 + tok;
+      if (e_active && tok < ntok && t < N) {
+        const float4 v4 = *reinterpret_cast<const float4*>(&stage[tok * HS + e_hq * 4]);
+        const float4 m4 = *reinterpret_cast<const float4*>(&bmx[e_hq * 4]);
+        // 255 = at the maximum, one step = a quarter octave of softmax weight, rounded towards the maximum;
+        // 0 = 63.75 octaves or more below it (fmaxf drops the NaN of an empty block)
+        const uint32_t q0 = (uint32_t)fminf(fmaxf(255.f + ceilf(4.f * c2 * (v4.x - m4.x)), 0.f), 255.f);
+        const uint32_t q1 = (uint32_t)fminf(fmaxf(255.f + ceilf(4.f * c2 * (v4.y - m4.y)), 0.f), 255.f);
+        const uint32_t q2 = (uint32_t)fminf(fmaxf(255.f + ceilf(4.f * c2 * (v4.z - m4.z)), 0.f), 255.f);
+        const uint32_t q3 = (uint32_t)fminf(fmaxf(255.f + ceilf(4.f * c2 * (v4.w - m4.w)), 0.f), 255.f);
+        uint8_t* dst = a.codes + ((size_t)b * a.max_seq_len + t) * H + h_base + e_hq * 4;
+        if (a.vec_store) {
+          *reinterpret_cast<uint32_t*>(dst) = q0 | (q1 << 8) | (q2 << 16) | (q3 << 24);
+        } else {
+          const uint32_t qq[4] = {q0, q1, q2, q3};
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (e < e_nvh) dst[e] = (uint8_t)qq[e];
+        }
+      }
+    }
+    wave_lds_sync();
   };
   // the staged tiles leave as one contiguous run of token rows
   auto epilogue = [&](int t0, int ntok) {
@@ -251,7 +245,8 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
     if (++c_blk == NBLK) {
       c_blk = 0; ++done_tiles;
       if (c_r + 1 == RR || done_tiles == my_tiles) {
-        epilogue(tile_of(c_n, 0) * TT, (c_r + 1) * TT);
+        if (MODE == 0) epilogue(tile_of(c_n, 0) * TT, (c_r + 1) * TT);
+        else epilogue_codes(tile_of(c_n, 0) * TT, (c_r + 1) * TT);
         c_r = 0; ++c_n;
       } else {
         ++c_r;
@@ -259,6 +254,12 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
     }
   }
 
+  // what the following calls need to know about this launch (they read it from the workspace, not from the host)
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    a.hdr[b * 8 + 0] = gridDim.x;                          // statistics partials of this launch
+    if (MODE != 0) a.hdr[b * 8 + 1] = (uint32_t)(RR * TT); // tokens per block of the byte form
+    a.hdr[b * 8 + 2] = __float_as_uint(a.scale);
+  }
   // ---- merge the lanes' statistics per head: first inside the wave (its own LDS region, no workgroup
   // barrier), then over the waves of the workgroup that share a head block; publish the partial
   {
@@ -303,10 +304,17 @@ void set_score_timing_events(hipEvent_t start, hipEvent_t stop) { g_time_start =
 
 template <int DT, int D, int G, bool DOT2>
 static hipError_t launch_one(const ScoreArgs& a, dim3 grid, size_t lds, hipStream_t s) {
+  if (a.codes != nullptr) {
+    if (g_time_start != nullptr && g_time_stop != nullptr)
+      hipExtLaunchKernelGGL((score_decode_kernel<DT, D, G, DOT2, 1>), grid, dim3(256), (uint32_t)lds, s, g_time_start, g_time_stop, 0u, a);
+    else
+      hipLaunchKernelGGL((score_decode_kernel<DT, D, G, DOT2, 1>), grid, dim3(256), lds, s, a);
+    return hipGetLastError();
+  }
   if (g_time_start != nullptr && g_time_stop != nullptr)
-    hipExtLaunchKernelGGL((score_decode_kernel<DT, D, G, DOT2>), grid, dim3(256), (uint32_t)lds, s, g_time_start, g_time_stop, 0u, a);
+    hipExtLaunchKernelGGL((score_decode_kernel<DT, D, G, DOT2, 0>), grid, dim3(256), (uint32_t)lds, s, g_time_start, g_time_stop, 0u, a);
   else
-    hipLaunchKernelGGL((score_decode_kernel<DT, D, G, DOT2>), grid, dim3(256), lds, s, a);
+    hipLaunchKernelGGL((score_decode_kernel<DT, D, G, DOT2, 0>), grid, dim3(256), lds, s, a);
   return hipGetLastError();
 }
 

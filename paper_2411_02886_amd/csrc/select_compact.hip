@@ -1,0 +1,387 @@
+// Compact form of the decode selection (Algorithm 2 + Eq. 5 + TopK without the score matrix in memory).
+//
+// The score pass leaves one byte per score -- its distance below the head's maximum inside a block of
+// tokens, in quarter octaves of softmax weight, rounded towards the maximum -- the block maxima, and the
+// usual per-workgroup softmax statistics.  After the statistics merge (soft_vote.hip):
+//   vote_bounds_kernel   turns the bytes into an upper and a lower bound of every token's vote (they differ
+//                        by 2^(1/4) plus guards) and histograms the lower bounds;
+//   topk_refine_kernel   takes every token whose upper bound reaches the histogram bin of the k-th largest
+//                        lower bound -- a superset of the top-k, usually 1.05-1.5 k tokens -- recomputes its
+//                        scores from K (exact products, double accumulation) and its vote as Eq. 5 defines
+//                        it, and lists (vote key, token) in token order.
+// The finishing workgroup of the radix select (topk.hip) then picks the k largest of those votes.  Why the
+// candidates are a superset: k tokens have votes >= their lower bounds >= the k-th largest lower bound L_k,
+// so the k-th largest vote is >= L_k, and a token of the top-k has upper bound >= its vote >= L_k.
+#include "ts_kernels.h"
+#include "ts_score_math.h"
+
+namespace ts {
+
+// Guards that keep the bounds valid under rounding.  The byte was formed from the float score of the score pass
+// (a few ulp of the largest score away from the exact one that the candidates are re-evaluated with) through a
+// float product; the exponent offset of a block is rounded to float; the hardware exponential has 1 ulp; the
+// sum over heads rounds H times.
+constexpr float kCodeGuard = 1e-3f;               // octaves added to the decoded upper end of a byte ...
+constexpr float kScoreGuard = 1.0f / 262144.0f;   // ... plus c2 * |largest maximum| * 2^-18 for the score's own rounding
+constexpr float kBoundUp = 1.0002f;               // factor on the summed upper bound
+constexpr float kBoundDown = 0.9998f;             // factor on the summed lower bound
+
+// Eight lanes share a token; a lane decodes four heads per step (HQ steps: 1 for H <= 32); NP tokens per lane
+// group are in flight together.  A workgroup walks a contiguous range of tokens; the exponent offsets of the
+// blocks it meets (c2 * (block max - max_h) - log2 sumexp_h, formed in double) are tabulated in LDS first, and
+// its histogram of the lower bounds is flushed once.
+template <int NP, int HQ>
+__global__ __launch_bounds__(256) void vote_bounds_kernel(BoundArgs a, int tokens_per_wg) {
+  __shared__ double s_km[128];                  // c2 * max_h + log2(sumexp_h)
+  __shared__ float s_absmax[4];
+  __shared__ uint32_t hist[kTopkBins];
+  extern __shared__ float s_off[];              // [blocks of this workgroup][H]
+  const int b = blockIdx.y;
+  const int skip_flag = a.skip != nullptr ? (int)a.skip[b] : 0;
+  const int N = min(max(a.seq_lens[b], 0), a.max_seq_len);
+  const int bt = max((int)a.hdr[b * 8 + 1], kScoreTileTokens);    // tokens per block of the score launch
+  if (skip_flag != 0) return;
+  const int tbeg = blockIdx.x * tokens_per_wg;
+  if (tbeg >= N) return;
+  const int tend = min(N, tbeg + tokens_per_wg);
+  const int H = a.H;
+  const double c2d = (double)a.scale * 1.44269504088896340736;
+  float am = 0.f;
+  if (threadIdx.x < H) {
+    const float2 st = *reinterpret_cast<const float2*>(a.row_stats + ((size_t)b * H + threadIdx.x) * 2);
+    s_km[threadIdx.x] = c2d * (double)st.x + log2((double)st.y);
+    am = fabsf(st.x);
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) am = fmaxf(am, __shfl_xor(am, off));
+  if ((threadIdx.x & 63) == 0) s_absmax[threadIdx.x >> 6] = am;
+  for (int i = threadIdx.x; i < kTopkBins; i += 256) hist[i] = 0u;
+  __syncthreads();
+  am = fmaxf(fmaxf(s_absmax[0], s_absmax[1]), fmaxf(s_absmax[2], s_absmax[3]));
+  const float guard = kCodeGuard + (float)c2d * am * kScoreGuard;
+  const float lo_scale = kBoundDown * __builtin_amdgcn_exp2f(-0.25f - 2.f * guard);
+  const int blk0 = tbeg / bt, nblk_wg = (tend - 1) / bt - blk0 + 1;
+  for (int i = threadIdx.x; i < nblk_wg * H; i += 256) {
+    const int bl = i / H, h = i - bl * H;
+    const float mxb = a.blk_max[((size_t)b * a.nblk + min(blk0 + bl, a.nblk - 1)) * H + h];
+    s_off[i] = (float)(c2d * (double)mxb - s_km[h]) - 63.75f + guard;    // <= 0 before the shift; -inf for an empty block
+  }
+  __syncthreads();
+  const int jv = threadIdx.x & 7;
+  const int r_lo = min(a.n_init, N), r_hi = max(r_lo, N - a.n_local);
+  for (int t0 = tbeg; t0 < tend; t0 += 32 * NP) {
+    uint32_t q[NP][HQ][4];
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+      const int tc = min(t0 + p * 32 + (int)(threadIdx.x >> 3), N - 1);
+      const uint8_t* cp = a.codes + ((size_t)b * a.max_seq_len + tc) * H;
+#pragma unroll
+      for (int s4 = 0; s4 < HQ; ++s4) {
+        const int h0 = jv * 4 + s4 * 32;
+        if (a.vec) {
+          const uint32_t w = *reinterpret_cast<const uint32_t*>(cp + max(min(h0, H - 4), 0));   // lanes past the last head shadow it (masked below)
+          q[p][s4][0] = w & 255u; q[p][s4][1] = (w >> 8) & 255u; q[p][s4][2] = (w >> 16) & 255u; q[p][s4][3] = w >> 24;
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) q[p][s4][e] = cp[min(h0 + e, H - 1)];
+        }
+      }
+    }
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+      const int t = t0 + p * 32 + (int)(threadIdx.x >> 3);
+      const float* offp = s_off + (min(t, tend - 1) / bt - blk0) * H;
+      float up = 0.f, lo = 0.f;
+#pragma unroll
+      for (int s4 = 0; s4 < HQ; ++s4) {
+        const int h0 = jv * 4 + s4 * 32;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          if (h0 + e < H) {
+            const float tu = __builtin_amdgcn_exp2f(offp[h0 + e] + (float)q[p][s4][e] * 0.25f);
+            up += tu;
+            lo += q[p][s4][e] != 0u ? tu : 0.f;   // byte 0 is open towards minus infinity: no lower bound from it
+          }
+        }
+      }
+      up = group8_sum(up) * kBoundUp;
+      lo = group8_sum(lo) * lo_scale;
+      if (t < tend && jv == 0) {
+        const bool ranked = t >= r_lo && t < r_hi;
+        a.vote_hi[(size_t)b * a.max_seq_len + t] = ranked ? up : 0.f;
+        a.vote_lo[(size_t)b * a.max_seq_len + t] = ranked ? lo : 0.f;
+        if (ranked) atomicAdd(&hist[float_key(lo) >> 21], 1u);
+      }
+    }
+  }
+  __syncthreads();
+  uint32_t* gh = a.hist + ((size_t)b * kBoundHistCopies + (blockIdx.x % kBoundHistCopies)) * kTopkBins;
+  for (int i = threadIdx.x; i < kTopkBins; i += 256)
+    if (hist[i] != 0u) atomicAdd(&gh[i], hist[i]);
+}
+
+hipError_t launch_vote_bounds(const BoundArgs& a, int B, hipStream_t s) {
+  // a workgroup flushes one histogram: 512 tokens each for short sequences, at most about 2048 workgroups
+  int tpw = (a.max_seq_len + 2047) / 2048;
+  if (tpw < 512) tpw = 512;
+  tpw = (tpw + 127) / 128 * 128;
+  const int nwg = (a.max_seq_len + tpw - 1) / tpw;
+  const size_t lds = (size_t)(tpw / kScoreTileTokens + 1) * a.H * sizeof(float);   // blocks hold at least 32 tokens
+  if (a.H <= 32) hipLaunchKernelGGL((vote_bounds_kernel<4, 1>), dim3(nwg, B), dim3(256), lds, s, a, tpw);
+  else hipLaunchKernelGGL((vote_bounds_kernel<2, 4>), dim3(nwg, B), dim3(256), lds, s, a, tpw);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+constexpr int kRefineThreads = 512;       // 8 waves: the candidates of a chunk are few, their evaluation is a chain
+                                          // of dependent loads, so many waves per chunk shorten the kernel
+constexpr int kRefineWaves = kRefineThreads / 64;
+
+// exclusive prefix sum over the threads of the refine workgroup; *total receives the sum
+__device__ __forceinline__ uint32_t refine_block_scan(uint32_t v, uint32_t* total, uint32_t* lds /* >= kRefineWaves words */) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint32_t incl = v;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t o = __shfl_up(incl, off);
+    if (lane >= off) incl += o;
+  }
+  __syncthreads();
+  if (lane == 63) lds[wave] = incl;
+  __syncthreads();
+  uint32_t base = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < kRefineWaves; ++w) {
+    const uint32_t x = lds[w];
+    if (w < wave) base += x;
+    tot += x;
+  }
+  *total = tot;
+  return base + incl - v;
+}
+
+// bin of the k_rem-th largest key in the replicated 2048-bin histogram (kTopkBins if k_rem == 0); all threads get it
+__device__ __forceinline__ uint32_t refine_find_bin(const uint32_t* gh, uint32_t k_rem, uint32_t* lds /* >= kRefineWaves + 1 words */) {
+  constexpr int PER = kTopkBins / kRefineThreads;
+  uint32_t c[PER];
+  uint32_t sum = 0;
+#pragma unroll
+  for (int e = 0; e < PER; ++e) {
+    uint32_t x = 0;
+#pragma unroll
+    for (int r = 0; r < kBoundHistCopies; ++r) x += gh[r * kTopkBins + kTopkBins - 1 - (threadIdx.x * PER + e)];
+    c[e] = x; sum += x;
+  }
+  uint32_t total;
+  uint32_t above = refine_block_scan(sum, &total, lds);
+  __syncthreads();
+  if (threadIdx.x == 0) lds[kRefineWaves] = kTopkBins;
+  __syncthreads();
+  if (k_rem != 0) {
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+      if (above < k_rem && k_rem <= above + c[e]) lds[kRefineWaves] = kTopkBins - 1 - (threadIdx.x * PER + e);
+      above += c[e];
+    }
+  }
+  __syncthreads();
+  const uint32_t d = lds[kRefineWaves];
+  __syncthreads();
+  return d;
+}
+
+// exp(c * d) as ts_soft_vote forms it: argument reduced in double, 2^fraction from the float hardware exponential
+__device__ __forceinline__ float refine_vote_exp(double d, double c2) {
+  const double t = fmax(d * c2, -1000.0);
+  const double n = rint(t);
+  const float f = (float)(t - n);
+  return ldexpf(__builtin_amdgcn_exp2f(f), (int)n);
+}
+
+constexpr int ST_KEFF_WORD = 2;   // state word that carries min(k, ranked tokens) to the finishing workgroup
+
+// sum of a double over the 8 lanes of an aligned lane group (both halves through the DPP network)
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double v) {
+  const long long u = __double_as_longlong(v);
+  const int lo = __builtin_amdgcn_update_dpp(0, (int)(u & 0xffffffffLL), CTRL, 0xf, 0xf, true);
+  const int hi = __builtin_amdgcn_update_dpp(0, (int)(u >> 32), CTRL, 0xf, 0xf, true);
+  return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+__device__ __forceinline__ double group8_sum_f64(double v) {
+  v += dpp_f64<0xB1>(v);    // quad_perm [1,0,3,2]
+  v += dpp_f64<0x4E>(v);    // quad_perm [2,3,0,1]
+  v += dpp_f64<0x141>(v);   // row_half_mirror
+  return v;
+}
+
+// exact products of one 16-byte piece of a K row with the matching piece of a query head, accumulated in double
+template <int DT>
+__device__ __forceinline__ double piece_dot_f64(uint4 k, uint4 q, double acc);
+template <>
+__device__ __forceinline__ double piece_dot_f64<TS_BF16>(uint4 k, uint4 q, double acc) {
+  // a product of two bf16 values is exact in float; the sum runs in double
+  acc += (double)(bf16_lo(k.x) * bf16_lo(q.x)); acc += (double)(bf16_hi(k.x) * bf16_hi(q.x));
+  acc += (double)(bf16_lo(k.y) * bf16_lo(q.y)); acc += (double)(bf16_hi(k.y) * bf16_hi(q.y));
+  acc += (double)(bf16_lo(k.z) * bf16_lo(q.z)); acc += (double)(bf16_hi(k.z) * bf16_hi(q.z));
+  acc += (double)(bf16_lo(k.w) * bf16_lo(q.w)); acc += (double)(bf16_hi(k.w) * bf16_hi(q.w));
+  return acc;
+}
+template <>
+__device__ __forceinline__ double piece_dot_f64<TS_F32>(uint4 k, uint4 q, double acc) {
+  acc = fma((double)__uint_as_float(k.x), (double)__uint_as_float(q.x), acc);
+  acc = fma((double)__uint_as_float(k.y), (double)__uint_as_float(q.y), acc);
+  acc = fma((double)__uint_as_float(k.z), (double)__uint_as_float(q.z), acc);
+  acc = fma((double)__uint_as_float(k.w), (double)__uint_as_float(q.w), acc);
+  return acc;
+}
+
+template <int DT, int D, int G>
+__global__ __launch_bounds__(kRefineThreads) void topk_refine_kernel(RefineArgs a) {
+  constexpr int ES = Elt<DT>::size;
+  constexpr int RB = D * ES;
+  constexpr int L = RB / 128;
+  constexpr int PER = kTopkChunk / kRefineThreads;
+  constexpr int UB = 2;                         // wave steps whose K rows are in flight together
+  __shared__ uint32_t lds[kRefineWaves + 2];
+  __shared__ uint32_t scan_lds[kRefineWaves];
+  __shared__ int ctok[kTopkChunk];
+  __shared__ int cpid[kTopkChunk];
+  __shared__ double s_m[128];
+  __shared__ double s_inv[128];
+  extern __shared__ uint4 q_lds[];              // the sequence's query, [H][row bytes]
+  const TopkArgs& ta = a.t;
+  const int b = blockIdx.y;
+  const int skip_flag = ta.skip != nullptr ? (int)ta.skip[b] : 0;
+  const int Nb = min(max(ta.seq_lens[b], 0), ta.max_seq_len);
+  const int indptr = a.page_indptr[b];
+  if (skip_flag != 0) return;
+  const int LO = min(ta.head, Nb), N = max(LO, Nb - ta.tail);      // ranked range [LO, N)
+  const uint32_t k_eff = (uint32_t)min(ta.k, N - LO);
+  const int H = a.H;
+  const int base = blockIdx.x * kTopkChunk;
+  const int t0 = base + threadIdx.x * PER;      // PER consecutive tokens per thread: order is preserved
+  const float* v = ta.votes + (size_t)b * ta.max_seq_len;
+  uint32_t key[PER];
+  bool valid[PER];
+#pragma unroll
+  for (int e = 0; e < PER; ++e) {
+    valid[e] = (t0 + e) >= LO && (t0 + e) < N;
+    key[e] = valid[e] ? float_key(v[t0 + e]) : 0u;
+  }
+  if (threadIdx.x < H) {
+    const float2 st = *reinterpret_cast<const float2*>(a.row_stats + ((size_t)b * H + threadIdx.x) * 2);
+    s_m[threadIdx.x] = (double)st.x; s_inv[threadIdx.x] = 1.0 / (double)st.y;
+  }
+  for (int i = threadIdx.x; i < H * (RB / 16); i += kRefineThreads)
+    q_lds[i] = reinterpret_cast<const uint4*>(a.q + (size_t)b * H * RB)[i];
+  const uint32_t d0 = refine_find_bin(ta.bound_hist + (size_t)b * kBoundHistCopies * kTopkBins, k_eff, lds);
+  if (blockIdx.x == 0 && threadIdx.x == 0) ta.state[b * 8 + ST_KEFF_WORD] = k_eff;
+  uint32_t n = 0;
+#pragma unroll
+  for (int e = 0; e < PER; ++e) n += valid[e] && (key[e] >> 21) >= d0;      // d0 == kTopkBins (empty selection) matches nothing
+  uint32_t total;
+  uint32_t pos = refine_block_scan(n, &total, scan_lds);
+  const int npages = (Nb + a.P - 1) >> a.p_shift;
+#pragma unroll
+  for (int e = 0; e < PER; ++e)
+    if (valid[e] && (key[e] >> 21) >= d0) {
+      ctok[pos] = t0 + e;
+      cpid[pos] = a.page_indices[indptr + min((t0 + e) >> a.p_shift, npages - 1)];
+      ++pos;
+    }
+  if (threadIdx.x == 0) ta.blk[(size_t)b * ta.nblk + blockIdx.x] = total;
+  __syncthreads();
+  if (total == 0) return;
+
+  // ---- votes of the candidates from exact scores: a wave step covers 8 K rows = HB KV heads of 8 / HB candidates
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int j = lane & 7, r = lane >> 3;
+  const int HB = a.HB;
+  const int kvh_l = r & (HB - 1);
+  const int tis = r >> a.hb_shift;
+  const int tps_shift = 3 - a.hb_shift;
+  const int ngroups = ((int)total + (1 << tps_shift) - 1) >> tps_shift;
+  const double c2d = (double)a.scale * 1.44269504088896340736;
+  uint2* list = ta.list + ((size_t)b * ta.nblk + blockIdx.x) * kTopkChunk;
+  for (int g0 = wave * UB; g0 < ngroups; g0 += kRefineWaves * UB) {
+    double vote[UB];
+#pragma unroll
+    for (int uu = 0; uu < UB; ++uu) vote[uu] = 0.0;
+    for (int u = 0; u < a.NU; ++u) {
+      const int kvh = u * HB + kvh_l;
+      uint4 kr[UB][L];
+#pragma unroll
+      for (int uu = 0; uu < UB; ++uu) {
+        const int ci = min(((g0 + uu) << tps_shift) + tis, (int)total - 1);
+        const int t = ctok[ci], pid = cpid[ci];
+        const uint8_t* kp = a.k_pool + (((size_t)pid << a.p_shift) + (size_t)(t & (a.P - 1))) * ((size_t)a.H_kv * RB) +
+                            (size_t)kvh * RB + j * 16;
+#pragma unroll
+        for (int i = 0; i < L; ++i) kr[uu][i] = *reinterpret_cast<const uint4*>(kp + i * 128);
+      }
+      double svv[UB];
+#pragma unroll
+      for (int uu = 0; uu < UB; ++uu) svv[uu] = 0.0;
+#pragma unroll 1
+      for (int g = 0; g < G; ++g) {             // one query head at a time: its pieces come from LDS
+        uint4 qv[L];
+#pragma unroll
+        for (int i = 0; i < L; ++i) qv[i] = q_lds[((kvh * G + g) * RB + i * 128 + j * 16) >> 4];
+#pragma unroll
+        for (int uu = 0; uu < UB; ++uu) {
+          double sc = 0.0;
+#pragma unroll
+          for (int i = 0; i < L; ++i) sc = piece_dot_f64<DT>(kr[uu][i], qv[i], sc);
+          sc = group8_sum_f64(sc);                // the eight lanes of the row
+          svv[uu] = (j == g) ? sc : svv[uu];
+        }
+      }
+#pragma unroll
+      for (int uu = 0; uu < UB; ++uu) {
+        const double sv = svv[uu];
+        const int hh = min(kvh * G + j, H - 1);
+        double term = (j < G) ? (double)refine_vote_exp(sv - s_m[hh], c2d) * s_inv[hh] : 0.0;
+        // sum over the lanes of this candidate: the eight lanes of a row, then the HB rows
+        term = group8_sum_f64(term);
+        for (int off = 8; off < (8 << a.hb_shift); off <<= 1) term += __shfl_xor(term, off);
+        vote[uu] += term;
+      }
+    }
+#pragma unroll
+    for (int uu = 0; uu < UB; ++uu) {
+      const int ci = ((g0 + uu) << tps_shift) + tis;
+      if (ci < (int)total && kvh_l == 0 && j == 0) list[ci] = make_uint2(float_key((float)vote[uu]), (uint32_t)ctok[ci]);
+    }
+  }
+}
+
+template <int DT, int D, int GG>
+static hipError_t refine_one(const RefineArgs& a, dim3 grid, hipStream_t s) {
+  const size_t lds = (size_t)a.H * D * Elt<DT>::size;     // the query in LDS (next to about 19 KiB of static LDS)
+  if (lds > 40960) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&topk_refine_kernel<DT, D, GG>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL((topk_refine_kernel<DT, D, GG>), grid, dim3(kRefineThreads), lds, s, a);
+  return hipGetLastError();
+}
+
+template <int DT, int D>
+static hipError_t refine_g(int G, const RefineArgs& a, dim3 grid, hipStream_t s) {
+  switch (G) {
+#define TS_CASE(GG) case GG: return refine_one<DT, D, GG>(a, grid, s);
+    TS_CASE(1) TS_CASE(2) TS_CASE(3) TS_CASE(4) TS_CASE(5) TS_CASE(6) TS_CASE(7) TS_CASE(8)
+#undef TS_CASE
+  }
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_topk_refine(int dtype, int D, int G, const RefineArgs& a, int B, hipStream_t s) {
+  const dim3 grid(a.t.nblk, B);
+  if (dtype == TS_F32) return D == 64 ? refine_g<TS_F32, 64>(G, a, grid, s) : refine_g<TS_F32, 128>(G, a, grid, s);
+  return D == 64 ? refine_g<TS_BF16, 64>(G, a, grid, s) : refine_g<TS_BF16, 128>(G, a, grid, s);
+}
+
+}  // namespace ts

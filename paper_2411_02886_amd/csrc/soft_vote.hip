@@ -14,23 +14,25 @@ namespace ts {
 // One workgroup per (head, sequence); every partial is loaded at once (one memory round trip), the
 // rescaling exponentials and the sum are double precision.
 __global__ __launch_bounds__(256) void score_stats_merge_kernel(VoteArgs a) {
-  const int nparts = a.nparts;
   __shared__ float s_m[4];
   __shared__ double s_l[4];
   const int h = blockIdx.x, b = blockIdx.y;
   const int skip_flag = a.skip != nullptr ? (int)a.skip[b] : 0;   // checked after the partials' loads have been issued
+  // the partial count is what the score launch recorded in the workspace, whatever the host believes now; every
+  // slot is loaded at once (one memory round trip, the slots all exist) and the unused ones are masked afterwards
+  const int nparts = min((int)a.hdr[b * 8 + 0], kScoreMaxWg);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   constexpr int PER = kScoreMaxWg / 256;
   float mp[PER], lp[PER];
 #pragma unroll
   for (int i = 0; i < PER; ++i) {
     const int p = threadIdx.x + 256 * i;
-    mp[i] = -INFINITY; lp[i] = 0.f;
-    if (p < nparts) {
-      const float2 v = *reinterpret_cast<const float2*>(a.partials + (((size_t)b * kScoreMaxWg + p) * a.H + h) * 2);
-      mp[i] = v.x; lp[i] = v.y;
-    }
+    const float2 v = *reinterpret_cast<const float2*>(a.partials + (((size_t)b * kScoreMaxWg + p) * a.H + h) * 2);
+    mp[i] = v.x; lp[i] = v.y;
   }
+#pragma unroll
+  for (int i = 0; i < PER; ++i)
+    if (threadIdx.x + 256 * i >= nparts) { mp[i] = -INFINITY; lp[i] = 0.f; }
   if (skip_flag != 0) return;
   float m = mp[0];
 #pragma unroll
@@ -123,6 +125,11 @@ __global__ __launch_bounds__(256) void soft_vote_kernel(VoteArgs a, int lpt_shif
     for (int off = 1; off < LPT; off <<= 1) vote += __shfl_xor(vote, off);
     if (t < N && jv == 0) a.votes[(size_t)b * a.max_seq_len + t] = (t >= r_lo && t < r_hi) ? (float)vote : 0.f;
   }
+}
+
+hipError_t launch_stats_merge(const VoteArgs& a, int B, hipStream_t s) {
+  hipLaunchKernelGGL(score_stats_merge_kernel, dim3(a.H, B), dim3(256), 0, s, a);
+  return hipGetLastError();
 }
 
 hipError_t launch_soft_vote(const VoteArgs& a, int B, hipStream_t s) {

@@ -378,7 +378,9 @@ __device__ __forceinline__ void final_find_digit(const uint32_t* h, uint32_t k_r
 }
 
 // passes 2, 3 and the emit of the short path: one workgroup per (virtual) sequence
-template <int kFinalPer>                   // consecutive list entries per thread and batch
+// FULL: the list holds exact votes whose top digit has not been fixed yet (compact selection: the entries are
+// the re-evaluated candidates), so digit 0 is found here too, over the entries.
+template <int kFinalPer, bool FULL>        // consecutive list entries per thread and batch
 __global__ __launch_bounds__(kFinalThreads) void topk_final_kernel(TopkArgs a) {
   __shared__ uint32_t off[kFinalMaxBlk + 1];   // exclusive prefix of the chunks' entry counts
   __shared__ uint32_t h[kTopkBins];
@@ -387,7 +389,7 @@ __global__ __launch_bounds__(kFinalThreads) void topk_final_kernel(TopkArgs a) {
   const int b = blockIdx.x;
   const int skip_flag = a.skip != nullptr ? (int)a.skip[b / a.heads] : 0;   // issued together with the state words
   const int tid = threadIdx.x;
-  const uint32_t d0 = a.state[b * 8 + ST_PREFIX0] >> 21, krem0 = a.state[b * 8 + ST_KREM0];
+  uint32_t d0 = FULL ? 0u : a.state[b * 8 + ST_PREFIX0] >> 21, krem0 = FULL ? 0u : a.state[b * 8 + ST_KREM0];
   const int k_eff = (int)a.state[b * 8 + ST_KEFF];
   if (skip_flag != 0) return;
   const bool as_votes = a.vote_acc != nullptr;
@@ -397,7 +399,10 @@ __global__ __launch_bounds__(kFinalThreads) void topk_final_kernel(TopkArgs a) {
     for (int i = k_eff + tid; i < a.k; i += kFinalThreads) out[i] = -1;
     if (tid == 0) a.count[b] = k_eff;
   }
-  {  // histogram 0 has been consumed by the compact pass: leave it zeroed for the next call
+  if (FULL) {  // the replicated histogram of the lower bounds has been consumed by the refine pass: zero it again
+    uint32_t* g0 = a.bound_hist + (size_t)b * kBoundHistCopies * kTopkBins;
+    for (int i = tid; i < kBoundHistCopies * kTopkBins; i += kFinalThreads) g0[i] = 0u;
+  } else {     // histogram 0 has been consumed by the compact pass: leave it zeroed for the next call
     uint32_t* g0 = a.hist + ((size_t)b * 3 + 0) * kTopkBins;
     for (int i = tid; i < kTopkBins; i += kFinalThreads) g0[i] = 0u;
   }
@@ -442,6 +447,18 @@ __global__ __launch_bounds__(kFinalThreads) void topk_final_kernel(TopkArgs a) {
   uint2 e[kFinalPer];
   if (single) load_batch(0, e);
 
+  if (FULL) {   // ---- digit 0: bits 31..21 over all entries
+    for (int i = tid; i < kTopkBins; i += kFinalThreads) h[i] = 0u;
+    __syncthreads();
+    for (uint32_t base = 0; base < total; base += kFinalThreads * kFinalPer) {
+      if (!single) load_batch(base, e);
+#pragma unroll
+      for (int i = 0; i < kFinalPer; ++i)
+        if (e[i].y != 0xffffffffu) atomicAdd(&h[e[i].x >> 21], 1u);
+    }
+    __syncthreads();
+    final_find_digit<kTopkBins>(h, (uint32_t)k_eff, &d0, &krem0, scan_lds, res);
+  }
   // ---- digit 1: bits 20..10 of the candidates (entries of bin d0)
   for (int i = tid; i < kTopkBins; i += kFinalThreads) h[i] = 0u;
   __syncthreads();
@@ -509,14 +526,21 @@ hipError_t launch_topk(const TopkArgs& a, int B, hipStream_t s) {
   if (a.list != nullptr && a.nblk <= kFinalMaxBlk) {
     hipLaunchKernelGGL(topk_compact_kernel, grid, dim3(256), 0, s, a);
     // the list holds about k entries plus the few that share the k-th key's bin: one batch in the usual case
-    if (a.k <= 3072) hipLaunchKernelGGL(topk_final_kernel<4>, dim3(B), dim3(kFinalThreads), 0, s, a);
-    else hipLaunchKernelGGL(topk_final_kernel<8>, dim3(B), dim3(kFinalThreads), 0, s, a);
+    if (a.k <= 3072) hipLaunchKernelGGL((topk_final_kernel<4, false>), dim3(B), dim3(kFinalThreads), 0, s, a);
+    else hipLaunchKernelGGL((topk_final_kernel<8, false>), dim3(B), dim3(kFinalThreads), 0, s, a);
     return hipGetLastError();
   }
   hipLaunchKernelGGL(topk_hist1_kernel, grid, dim3(256), 0, s, a);
   hipLaunchKernelGGL(topk_hist2_kernel, grid, dim3(256), 0, s, a);
   hipLaunchKernelGGL(topk_count_kernel, grid, dim3(256), 0, s, a);
   hipLaunchKernelGGL(topk_emit_kernel, grid, dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+// finishing workgroup over a list of exact votes (compact selection)
+hipError_t launch_topk_final_full(const TopkArgs& a, int B, hipStream_t s) {
+  if (a.k <= 2048) hipLaunchKernelGGL((topk_final_kernel<4, true>), dim3(B), dim3(kFinalThreads), 0, s, a);
+  else hipLaunchKernelGGL((topk_final_kernel<8, true>), dim3(B), dim3(kFinalThreads), 0, s, a);
   return hipGetLastError();
 }
 

@@ -13,16 +13,22 @@ constexpr int kScoreLdsStride = 36;    // floats per head row of the staged scor
 constexpr int kScoreMaxWg = 1024;      // upper bound on workgroups per sequence in the score pass
 constexpr int kTopkBins = 2048;        // 11-bit radix digit
 constexpr int kTopkChunk = 2048;       // keys per workgroup in the top-k passes
+constexpr int kBoundHistCopies = 16;   // replicas of the lower-bound histogram (same-address atomics are what its flush costs)
 constexpr int kAttnChunk = 64;         // selected tokens per workgroup in sparse attention
 constexpr int kAttnMaxSplit = 512;     // splits the merge kernel can stage (k <= 32768)
 
 // ---------------------------------------------------------------- workspace layout (host + device)
 struct WsLayout {
   size_t topk_hist;        // uint32 [B][3][kTopkBins] : one histogram per radix pass (must start zeroed)
+  size_t bound_hist;       // uint32 [B][kBoundHistCopies][kTopkBins] : compact selection, histogram of the vote lower bounds
+                           // (must start zeroed too; decode only)
   size_t topk_state;       // uint32 [B][8] : digits and remaining ranks fixed so far
+  size_t hdr;              // uint32 [B][8] : left by the score pass for the calls that follow it
   size_t score_partials;   // float [B][kScoreMaxWg][H][2]
   size_t topk_blk;         // uint32 [B][nblk] : per-chunk counts
   size_t topk_list;        // uint2 [B][nblk][kTopkChunk] : compacted (key, token) entries of the short top-k path
+  size_t blk_max;          // float [B][score_nblk][H] : compact score pass, per-block head maxima (decode only)
+  int score_nblk;          // ceil(max_seq_len / kScoreTileTokens)
   size_t attn_out;         // float [B][H][nsplit][D]
   size_t attn_ml;          // float [B][H][nsplit][2]
   size_t pf_stat_part;     // float [B][TS][C][H][2]            (chunk > 1 only)
@@ -63,10 +69,16 @@ inline WsLayout ws_layout(const ts_problem* p, int k) {
   if (w.attn_nsplit < 1) w.attn_nsplit = 1;
   // the histograms come first: they are the part that must start (and is left) zeroed
   w.topk_hist = take(B * 3 * kTopkBins * 4);
+  if (p->chunk == 1) w.bound_hist = take(B * kBoundHistCopies * kTopkBins * 4);
   w.topk_state = take(B * 8 * 4);
+  w.hdr = take(B * 8 * 4);
   w.score_partials = take(B * kScoreMaxWg * H * 2 * 4);
   w.topk_blk = take(B * (size_t)w.topk_nblk * 4);
   w.topk_list = take(B * (size_t)w.topk_nblk * kTopkChunk * 8);
+  w.score_nblk = (p->max_seq_len + kScoreTileTokens - 1) / kScoreTileTokens;
+  if (p->chunk == 1) {
+    w.blk_max = take(B * (size_t)w.score_nblk * H * 4);
+  }
   if (p->chunk > 1) {
     const int G = p->num_q_heads / p->num_kv_heads;
     w.pf_rb = (p->chunk * G + 255) / 256;

@@ -20,12 +20,35 @@ struct ScoreArgs {
   int RR;                 // consecutive tiles a wave stages in LDS and writes out as one run (1, 2 or 4)
   int n_init, n_local;    // forced tokens: the statistics cover [min(n_init, N), max(that, N - n_local)) only
   float scale, c2;        // score_scale and score_scale * log2(e)
+  uint32_t* hdr;          // [B][8] what later calls must know about this launch (partials / block size, score_scale)
+  // compact form (codes != nullptr): one byte per score plus exact per-block statistics instead of S
+  uint8_t* codes;         // [B][max_seq_len][H]
+  float* blk_max;         // [B][nblk][H] maximum of each head over the block's ranked tokens
+  int nblk;               // blocks per sequence the array is strided by: ceil(max_seq_len / 32)
+  int ncp_shift;          // log2 of the power of two >= HB * G
+};
+
+// compact form of the selection: statistics merge, vote bounds, exact re-evaluation of the candidates
+struct BoundArgs {
+  const uint8_t* codes;
+  const float* blk_max;
+  const uint32_t* hdr;
+  const float* row_stats; // [B][H][2] merged (max, sum-exp)
+  float* vote_hi;         // [B][max_seq_len] upper bound of every vote
+  float* vote_lo;         // [B][max_seq_len] lower bound
+  uint32_t* hist;         // [B][kBoundHistCopies][kTopkBins]: top 11 key bits of the lower bounds, one replica per workgroup residue
+  const int32_t* seq_lens;
+  const uint8_t* skip;
+  int H, max_seq_len, nblk;
+  int n_init, n_local;
+  int vec;                // H % 4 == 0 and aligned buffers: codes and block maxima are read four heads at a time
+  float scale;
 };
 
 struct VoteArgs {
   const float* scores;
   const float* partials;  // per-workgroup statistics left by the score pass
-  int nparts;             // workgroups per sequence the score pass ran with
+  const uint32_t* hdr;    // [B][8]: word 0 = workgroups per sequence the score pass ran with (its partials)
   float* row_stats_out;   // merged (max, sum-exp) per head, written by the merge kernel
   const float* row_stats; // same buffer, read by the vote kernel
   float* votes;
@@ -51,6 +74,20 @@ struct TopkArgs {
   int k, max_seq_len, nblk;
   int heads;            // virtual sequences per real one (Eq. 4: one per head over transposed scores); 1 = plain
   float* vote_acc;      // Eq. 4: the emit pass adds 1 to vote_acc[real sequence][t] for every winner instead of writing idx
+  uint32_t* bound_hist; // compact selection: [B][kBoundHistCopies][kTopkBins] histogram of the vote lower bounds (else nullptr)
+};
+
+// exact votes of the candidates (tokens whose upper bound reaches the bin of the k-th largest lower bound)
+struct RefineArgs {
+  TopkArgs t;             // votes = the upper bounds; hist / state / blk / list as in the short top-k path
+  const uint8_t* q;
+  const uint8_t* k_pool;
+  const int32_t* page_indptr;
+  const int32_t* page_indices;
+  const float* row_stats;
+  int H, H_kv, P, p_shift;
+  int HB, hb_shift, NU;
+  float scale;
 };
 
 struct SelcacheArgs {
@@ -129,7 +166,12 @@ hipError_t launch_sparse_attn_chunk(const ChunkAttnArgs& a, int B, hipStream_t s
 // variant: 0 = fma arithmetic, 1 = packed bf16 dot2 (bf16 only)
 hipError_t launch_score_decode(int dtype, int D, int G, int variant, const ScoreArgs& a, dim3 grid, size_t lds, hipStream_t s);
 hipError_t launch_soft_vote(const VoteArgs& a, int B, hipStream_t s);
+hipError_t launch_stats_merge(const VoteArgs& a, int B, hipStream_t s);
+hipError_t launch_vote_bounds(const BoundArgs& a, int B, hipStream_t s);
+hipError_t launch_topk_refine(int dtype, int D, int G, const RefineArgs& a, int B, hipStream_t s);
 hipError_t launch_topk(const TopkArgs& a, int B, hipStream_t s);
+hipError_t launch_topk_final_full(const TopkArgs& a, int B, hipStream_t s);
+constexpr int kTopkFinalMaxBlk = 8192;   // chunks per sequence the finishing workgroup can index (16 Mi tokens)
 hipError_t launch_selcache(const SelcacheArgs& a, int B, hipStream_t s);
 hipError_t launch_sparse_attn_decode(int dtype, int D, int G, const AttnArgs& a, int B, hipStream_t s);
 hipError_t launch_chunk_mean_query(const void* q, void* out, int B, int C, int n, hipStream_t s);
@@ -138,5 +180,9 @@ hipError_t launch_transpose_scores(const VoteArgs& a, float* st, int B, hipStrea
 hipError_t launch_zero_votes(const VoteArgs& a, int B, hipStream_t s);
 hipError_t launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t s);
 void set_score_timing_events(hipEvent_t start, hipEvent_t stop);
+void set_codes_timing_events(hipEvent_t start, hipEvent_t stop);
+bool score_codes_mfma_supported(int dtype, int D, int G, int H_kv);
+size_t score_codes_mfma_lds_bytes(int D, int G, int RR);
+hipError_t launch_score_codes_mfma(int D, int G, const ScoreArgs& a, dim3 grid, size_t lds, hipStream_t s);
 
 }  // namespace ts

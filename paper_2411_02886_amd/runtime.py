@@ -96,10 +96,24 @@ class DecodeLayer:
             raise ValueError(kind)
         ts.ts_topk(self.problem, self.votes, self.k, self.idx, self.count, skip, self.ws)
 
+    def select_compact(self, q, score_scale=1.0, skip=None):
+        """Eq. 5 selection without the score matrix in memory: one byte per score, vote bounds, exact votes of
+        the candidates.  Same idx / count as select(kind="soft")."""
+        if getattr(self, "codes", None) is None:
+            B, M = self.B, self.max_seq_len
+            self.codes = torch.empty((B, M, self.H), dtype=torch.uint8, device=self.device)
+            self.vote_hi = torch.empty((B, M), dtype=torch.float32, device=self.device)
+            self.vote_lo = torch.empty((B, M), dtype=torch.float32, device=self.device)
+        ts.ts_paged_qk_codes(self.problem, q, self.codes, score_scale, skip, self.ws)
+        ts.ts_soft_vote_bounds(self.problem, self.codes, score_scale, self.row_stats, self.vote_hi, self.vote_lo, skip,
+                               self.ws)
+        ts.ts_topk_exact(self.problem, q, self.vote_hi, self.row_stats, score_scale, self.k, self.idx, self.count, skip,
+                         self.ws)
+
     def attend(self, q, sm_scale):
         ts.ts_sparse_paged_attn(self.problem, q, self.idx, self.k, self.count, sm_scale, self.out, self.lse, self.ws)
 
-    def step(self, q, *, theta=None, score_scale=1.0, sm_scale=None):
+    def step(self, q, *, theta=None, score_scale=1.0, sm_scale=None, compact=False):
         """One decode step: Selection Cache check (when theta is given), selection on a miss, sparse
         attention.  No host synchronisation."""
         sm = sm_scale if sm_scale is not None else 1.0 / float(np.sqrt(self.D))
@@ -107,7 +121,10 @@ class DecodeLayer:
         if theta is not None:
             self.selcache_check(q, theta)
             skip = self.reuse
-        self.select(q, score_scale, skip)
+        if compact:
+            self.select_compact(q, score_scale, skip)
+        else:
+            self.select(q, score_scale, skip)
         self.attend(q, sm)
 
 
