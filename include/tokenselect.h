@@ -131,6 +131,18 @@ int32_t ts_soft_vote(const ts_problem* p, const float* scores, float score_scale
 int32_t ts_topk(const ts_problem* p, const float* votes, int32_t k, int32_t* idx, int32_t* count,
                 const uint8_t* skip, int32_t flags, void* ws, size_t ws_bytes, void* stream);
 
+/* ts_topk for callers that cannot allocate or bring a workspace: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same result as ts_topk, but the radix select's
+ * histograms, state words, chunk counts and candidate list live in a device array that is part of the library
+ * image (about 4.4 MiB per GPU, held until the process ends) instead of a caller workspace.  The call allocates
+ * nothing and frees nothing.
+ * Limits: batch <= 16 and batch * ceil(max_seq_len / 2048) <= 256 (524288 tokens over the batch), else
+ * TS_ERR_UNSUPPORTED before anything is launched.  Every call on a GPU shares that GPU's array: calls that
+ * overlap in time on one GPU (different streams, different threads) race; the histograms are cleared at the
+ * start of every call, so a call that was abandoned half way does not disturb the next one. */
+int32_t ts_topk_noalloc(const ts_problem* p, const float* votes, int32_t k, int32_t* idx, int32_t* count,
+                        const uint8_t* skip, int32_t flags, void* stream);
+
 /* ---- Compact form of the selection (decode, chunk == 1): Algorithm 2, Eq. 5 and the TopK with the same result
  * as ts_paged_qk_scores + ts_soft_vote + ts_topk, without the score matrix S ever reaching memory.  On this
  * machine a write stream mixed into the K read stream costs several times its bytes, and S is 4*H bytes per

@@ -68,6 +68,7 @@ def load():
         L.ts_paged_qk_scores.argtypes = [pp, vp, vp, f32, vp, vp, sz, vp]
         L.ts_soft_vote.argtypes = [pp, vp, f32, vp, vp, vp, vp, sz, vp]
         L.ts_topk.argtypes = [pp, vp, i32, vp, vp, vp, i32, vp, sz, vp]
+        L.ts_topk_noalloc.argtypes = [pp, vp, i32, vp, vp, vp, i32, vp]
         L.ts_paged_qk_codes.argtypes = [pp, vp, vp, f32, vp, vp, sz, vp]
         L.ts_soft_vote_bounds.argtypes = [pp, vp, f32, vp, vp, vp, vp, vp, sz, vp]
         L.ts_topk_exact.argtypes = [pp, vp, vp, vp, f32, i32, vp, vp, vp, vp, sz, vp]
@@ -91,7 +92,7 @@ def load():
                      "ts_chunk_soft_vote", "ts_chunk_mean_query", "ts_sum_vote", "ts_head_vote_scratch_bytes",
                      "ts_head_vote", "ts_debug_set_topk_path", "ts_debug_event_create", "ts_debug_event_destroy",
                      "ts_debug_event_elapsed_ms", "ts_debug_set_score_timing_events", "ts_paged_qk_codes",
-                     "ts_soft_vote_bounds", "ts_topk_exact", "ts_debug_set_codes_path"):
+                     "ts_soft_vote_bounds", "ts_topk_exact", "ts_debug_set_codes_path", "ts_topk_noalloc"):
             getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -242,6 +243,11 @@ def ts_chunk_mean_query(p: Problem, q, q_mean, stream=None) -> None:
 def ts_topk(p: Problem, votes, k: int, idx, count, skip, ws, stream=None, flags: int = 0) -> None:
     _ok(load().ts_topk(p.ref(), _ptr(votes), int(k), _ptr(idx), _ptr(count), _ptr(skip), int(flags), _ptr(ws), _nbytes(ws),
                        _stream(stream)), "ts_topk")
+
+
+def ts_topk_noalloc(p: Problem, votes, k: int, idx, count, skip, stream=None, flags: int = 0) -> None:
+    _ok(load().ts_topk_noalloc(p.ref(), _ptr(votes), int(k), _ptr(idx), _ptr(count), _ptr(skip), int(flags),
+                               _stream(stream)), "ts_topk_noalloc")
 
 
 def ts_selcache_check(p: Problem, q, cached_q, first, theta: float, reuse, stream=None) -> None:

@@ -79,6 +79,32 @@ static int32_t check_problem(const ts_problem* p) {
   return TS_OK;
 }
 
+// ---- scratch of the entry point that allocates nothing: one file-scope device array per GPU, kept until the
+// process ends; the name below is a host-side stand-in, the device address comes from hipGetSymbolAddress
+constexpr int kNoAllocMaxBatch = 16;
+constexpr int kNoAllocMaxChunks = 256;                       // 2048-token chunks over the whole batch: 524288 tokens
+constexpr size_t kNoAllocHist = 0;                           // uint32 [16][3][2048]
+constexpr size_t kNoAllocState = kNoAllocHist + (size_t)kNoAllocMaxBatch * 3 * kTopkBins * 4;
+constexpr size_t kNoAllocBlk = kNoAllocState + 1024;         // uint32 [256]
+constexpr size_t kNoAllocList = kNoAllocBlk + 1024;          // uint2 [256][2048]
+constexpr size_t kNoAllocBytes = kNoAllocList + (size_t)kNoAllocMaxChunks * kTopkChunk * 8;
+static __device__ __align__(256) uint8_t scratch[kNoAllocBytes];
+constexpr int kMaxDevices = 64;
+static uint8_t* g_scratch_ptr[kMaxDevices] = {nullptr};
+
+// device address of this GPU's copy of the array (looked up once per device, with that device current)
+static int32_t noalloc_scratch(uint8_t** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return TS_ERR_HIP;
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return TS_ERR_HIP;
+    g_scratch_ptr[dev] = (uint8_t*)ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return TS_OK;
+}
+
 }  // namespace ts
 
 using namespace ts;
@@ -342,6 +368,33 @@ int32_t ts_topk(const ts_problem* p, const float* votes, int32_t k, int32_t* idx
   // distribution.
   a.list = (g_topk_five_pass || p->chunk > 1 || (flags & TS_TOPK_FLAT_VOTES)) ? nullptr : (uint2*)((uint8_t*)ws + w.topk_list);
   a.k = k; a.max_seq_len = p->max_seq_len; a.nblk = w.topk_nblk; a.heads = 1;
+  return launch_topk(a, p->batch, (hipStream_t)stream) == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
+int32_t ts_topk_noalloc(const ts_problem* p, const float* votes, int32_t k, int32_t* idx, int32_t* count,
+                        const uint8_t* skip, int32_t flags, void* stream) {
+  int32_t st = check_problem(p);
+  if (st != TS_OK) return st;
+  if (votes == nullptr || idx == nullptr || count == nullptr || k < 1) return TS_ERR_INVALID_ARG;
+  if ((flags & ~TS_TOPK_FLAT_VOTES) != 0) return TS_ERR_INVALID_ARG;
+  const int nblk = (p->max_seq_len + kTopkChunk - 1) / kTopkChunk;
+  if (p->batch > kNoAllocMaxBatch || (int64_t)p->batch * nblk > kNoAllocMaxChunks) return TS_ERR_UNSUPPORTED;
+  uint8_t* base = nullptr;
+  st = noalloc_scratch(&base);
+  if (st != TS_OK) return st;
+  TopkArgs a{};
+  a.head = p->num_initial;
+  a.tail = (p->chunk > 1 ? p->chunk : 0) + p->num_local;
+  a.votes = votes; a.seq_lens = p->seq_lens; a.skip = skip; a.idx = idx; a.count = count;
+  a.hist = (uint32_t*)(base + kNoAllocHist);
+  a.state = (uint32_t*)(base + kNoAllocState);
+  a.blk = (uint32_t*)(base + kNoAllocBlk);
+  a.list = (g_topk_five_pass || p->chunk > 1 || (flags & TS_TOPK_FLAT_VOTES)) ? nullptr : (uint2*)(base + kNoAllocList);
+  a.k = k; a.max_seq_len = p->max_seq_len; a.nblk = nblk; a.heads = 1;
+  // the array keeps whatever the last call on this GPU left: the histograms must start at zero (a fill kernel,
+  // not a memset node: callers may be under graph capture)
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(24), dim3(256), 0, (hipStream_t)stream, a.hist, (size_t)p->batch * 3 * kTopkBins);
+  if (hipGetLastError() != hipSuccess) return TS_ERR_HIP;
   return launch_topk(a, p->batch, (hipStream_t)stream) == hipSuccess ? TS_OK : TS_ERR_HIP;
 }
 
