@@ -300,7 +300,6 @@ __global__ __launch_bounds__(256) void score_codes_mfma_kernel(ScoreArgs a) {
   }
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     a.hdr[b * 8 + 0] = gridDim.x;                          // statistics partials of this launch
-    a.hdr[b * 8 + 1] = (uint32_t)TT;                       // tokens per block of the byte form
     a.hdr[b * 8 + 2] = __float_as_uint(a.scale);
   }
 }

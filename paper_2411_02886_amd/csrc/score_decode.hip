@@ -21,7 +21,7 @@ namespace ts {
 
 // Both modes keep running softmax statistics in the lanes that end as one partial per workgroup.
 // MODE 0: Algorithm 2's S leaves as fp32 rows.  MODE 1 (compact form): nothing but one byte per score leaves --
-// the score's distance below the maximum of its head inside the run (a "block" of RR x 32 tokens), in quarter
+// the score's distance below the maximum of its head inside its 32-token tile (a "block"), in quarter
 // octaves of the softmax weight, rounded towards the maximum -- next to the block's per-head maximum; S itself
 // never reaches memory.  The bytes bound every softmax weight from both sides, which is enough to find the few
 // tokens whose votes have to be evaluated exactly.  (The matrix-core kernel in score_codes_mfma.hip is the fast
@@ -152,45 +152,49 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
   };
   // compact form: the run's per-head maximum over its ranked tokens, then one byte per score
   const int ncp_shift = a.ncp_shift;          // lanes per token subset: the power of two >= HBG (<= 64)
-  auto epilogue_codes = [&](int t0, int ntok) {
+  auto epilogue_codes = [&](int run_t0, int run_ntok) {
     wave_lds_sync();
     const int NCP = 1 << ncp_shift;
     const int c = lane & (NCP - 1), sub = lane >> ncp_shift, groups = 64 >> ncp_shift;
-    const int tmin = max(0, r_lo - t0), tmax = min(ntok, r_hi - t0);   // staged tokens that take part in the softmax
-    float mx = -INFINITY;
-    if (c < HBG)
-      for (int tok = tmin + sub; tok < tmax; tok += groups) mx = fmaxf(mx, stage[tok * HS + c]);
-    for (int off = NCP; off < 64; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
     float* bmx = stage + (stage_floats - 64);
-    if (sub == 0) {
-      bmx[c] = (c < HBG) ? mx : -INFINITY;
-      if (c < HBG) a.blk_max[((size_t)b * a.nblk + (size_t)(t0 / (RR * TT))) * H + h_base + c] = mx;
-    }
-    wave_lds_sync();
-    for (int tok0 = 0; tok0 < ntok; tok0 += TPP) {
-      const int tok = tok0 + e_sub;
-      const int t = t0 + tok;
-      if (e_active && tok < ntok && t < N) {
-        const float4 v4 = *reinterpret_cast<const float4*>(&stage[tok * HS + e_hq * 4]);
-        const float4 m4 = *reinterpret_cast<const float4*>(&bmx[e_hq * 4]);
-        // 255 = at the maximum, one step = a quarter octave of softmax weight, rounded towards the maximum;
-        // 0 = 63.75 octaves or more below it (fmaxf drops the NaN of an empty block)
-        const uint32_t q0 = (uint32_t)fminf(fmaxf(255.f + ceilf(4.f * c2 * (v4.x - m4.x)), 0.f), 255.f);
-        const uint32_t q1 = (uint32_t)fminf(fmaxf(255.f + ceilf(4.f * c2 * (v4.y - m4.y)), 0.f), 255.f);
-        const uint32_t q2 = (uint32_t)fminf(fmaxf(255.f + ceilf(4.f * c2 * (v4.z - m4.z)), 0.f), 255.f);
-        const uint32_t q3 = (uint32_t)fminf(fmaxf(255.f + ceilf(4.f * c2 * (v4.w - m4.w)), 0.f), 255.f);
-        uint8_t* dst = a.codes + ((size_t)b * a.max_seq_len + t) * H + h_base + e_hq * 4;
-        if (a.vec_store) {
-          *reinterpret_cast<uint32_t*>(dst) = q0 | (q1 << 8) | (q2 << 16) | (q3 << 24);
-        } else {
-          const uint32_t qq[4] = {q0, q1, q2, q3};
+    for (int f0 = 0; f0 < run_ntok; f0 += TT) {            // a block of the byte form is one 32-token tile
+      const int t0 = run_t0 + f0;
+      const float* tile = stage + f0 * HS;
+      const int tmin = max(0, r_lo - t0), tmax = min(TT, r_hi - t0);   // tokens of the tile that take part in the softmax
+      float mx = -INFINITY;
+      if (c < HBG)
+        for (int tok = tmin + sub; tok < tmax; tok += groups) mx = fmaxf(mx, tile[tok * HS + c]);
+      for (int off = NCP; off < 64; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+      if (sub == 0) {
+        bmx[c] = (c < HBG) ? mx : -INFINITY;
+        if (c < HBG) a.blk_max[((size_t)b * a.nblk + (size_t)(t0 / TT)) * H + h_base + c] = mx;
+      }
+      wave_lds_sync();
+      for (int tok0 = 0; tok0 < TT; tok0 += TPP) {
+        const int tok = tok0 + e_sub;
+        const int t = t0 + tok;
+        if (e_active && tok < TT && t < N) {
+          const float4 v4 = *reinterpret_cast<const float4*>(&tile[tok * HS + e_hq * 4]);
+          const float4 m4 = *reinterpret_cast<const float4*>(&bmx[e_hq * 4]);
+          // 255 = at the maximum, one step = a quarter octave of softmax weight, rounded towards the maximum;
+          // 0 = 63.75 octaves or more below it (fmaxf drops the NaN of an empty block)
+          const uint32_t q0 = (uint32_t)fminf(fmaxf(255.f + ceilf(4.f * c2 * (v4.x - m4.x)), 0.f), 255.f);
+          const uint32_t q1 = (uint32_t)fminf(fmaxf(255.f + ceilf(4.f * c2 * (v4.y - m4.y)), 0.f), 255.f);
+          const uint32_t q2 = (uint32_t)fminf(fmaxf(255.f + ceilf(4.f * c2 * (v4.z - m4.z)), 0.f), 255.f);
+          const uint32_t q3 = (uint32_t)fminf(fmaxf(255.f + ceilf(4.f * c2 * (v4.w - m4.w)), 0.f), 255.f);
+          uint8_t* dst = a.codes + ((size_t)b * a.max_seq_len + t) * H + h_base + e_hq * 4;
+          if (a.vec_store) {
+            *reinterpret_cast<uint32_t*>(dst) = q0 | (q1 << 8) | (q2 << 16) | (q3 << 24);
+          } else {
+            const uint32_t qq[4] = {q0, q1, q2, q3};
 #pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if (e < e_nvh) dst[e] = (uint8_t)qq[e];
+            for (int e = 0; e < 4; ++e)
+              if (e < e_nvh) dst[e] = (uint8_t)qq[e];
+          }
         }
       }
+      wave_lds_sync();
     }
-    wave_lds_sync();
   };
   // the staged tiles leave as one contiguous run of token rows
   auto epilogue = [&](int t0, int ntok) {
@@ -257,7 +261,6 @@ __global__ __launch_bounds__(256) void score_decode_kernel(ScoreArgs a) {
   // what the following calls need to know about this launch (they read it from the workspace, not from the host)
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     a.hdr[b * 8 + 0] = gridDim.x;                          // statistics partials of this launch
-    if (MODE != 0) a.hdr[b * 8 + 1] = (uint32_t)(RR * TT); // tokens per block of the byte form
     a.hdr[b * 8 + 2] = __float_as_uint(a.scale);
   }
   // ---- merge the lanes' statistics per head: first inside the wave (its own LDS region, no workgroup

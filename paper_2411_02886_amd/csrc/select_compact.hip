@@ -26,25 +26,38 @@ constexpr float kScoreGuard = 1.0f / 262144.0f;   // ... plus c2 * |largest maxi
 constexpr float kBoundUp = 1.0002f;               // factor on the summed upper bound
 constexpr float kBoundDown = 0.9998f;             // factor on the summed lower bound
 
-// Eight lanes share a token; a lane decodes four heads per step (HQ steps: 1 for H <= 32); NP tokens per lane
-// group are in flight together.  A workgroup walks a contiguous range of tokens; the exponent offsets of the
-// blocks it meets (c2 * (block max - max_h) - log2 sumexp_h, formed in double) are tabulated in LDS first, and
-// its histogram of the lower bounds is flushed once.
-template <int NP, int HQ>
+// One lane per token: a lane reads its token's H bytes (a wave reads 64 consecutive rows) and sums, head by head,
+// weight(block, head) * 2^((byte - 255) / 4), both factors from LDS tables: the weight of a byte-255 score of
+// each 32-token block this workgroup meets (2^(c2 * (block max - max_h)) / sumexp_h, exponent formed in double)
+// and the 256 powers.  The next 256 tokens' bytes are in flight while the current ones are summed.  The
+// workgroup's histogram of the lower bounds is flushed once.
+template <int HW>                                // dwords per token row (H / 4); 0 = any H, byte loads
 __global__ __launch_bounds__(256) void vote_bounds_kernel(BoundArgs a, int tokens_per_wg) {
+  constexpr int BT = kScoreTileTokens;          // tokens per block of the byte form
+  constexpr int NW = HW > 0 ? HW : 1;
   __shared__ double s_km[128];                  // c2 * max_h + log2(sumexp_h)
   __shared__ float s_absmax[4];
   __shared__ uint32_t hist[kTopkBins];
+  __shared__ float s_pow[256];                  // 2^((byte - 255) / 4)
   extern __shared__ float s_off[];              // [blocks of this workgroup][H]
   const int b = blockIdx.y;
+  const int H = a.H;
+  const int tbeg = blockIdx.x * tokens_per_wg;
+  uint32_t qn[NW];
+  auto load_codes = [&](int t0) {               // rows past the sequence are read too (they exist) and ignored
+    if (HW > 0) {
+      const int tc = min(t0 + (int)threadIdx.x, a.max_seq_len - 1);
+      const uint32_t* cp = reinterpret_cast<const uint32_t*>(a.codes + ((size_t)b * a.max_seq_len + tc) * H);
+#pragma unroll
+      for (int w = 0; w < NW; ++w) qn[w] = cp[w];
+    }
+  };
+  if (tbeg < a.max_seq_len) load_codes(tbeg);
   const int skip_flag = a.skip != nullptr ? (int)a.skip[b] : 0;
   const int N = min(max(a.seq_lens[b], 0), a.max_seq_len);
-  const int bt = max((int)a.hdr[b * 8 + 1], kScoreTileTokens);    // tokens per block of the score launch
   if (skip_flag != 0) return;
-  const int tbeg = blockIdx.x * tokens_per_wg;
   if (tbeg >= N) return;
   const int tend = min(N, tbeg + tokens_per_wg);
-  const int H = a.H;
   const double c2d = (double)a.scale * 1.44269504088896340736;
   float am = 0.f;
   if (threadIdx.x < H) {
@@ -52,66 +65,66 @@ __global__ __launch_bounds__(256) void vote_bounds_kernel(BoundArgs a, int token
     s_km[threadIdx.x] = c2d * (double)st.x + log2((double)st.y);
     am = fabsf(st.x);
   }
+  const int blk0 = tbeg / BT, nblk_wg = (tend - 1) / BT - blk0 + 1;
+  // block maxima of this workgroup's tokens: loaded before the barrier, turned into weights after it
+  float mxb[4];
+#pragma unroll
+  for (int i4 = 0; i4 < 4; ++i4) {
+    const int i = threadIdx.x + i4 * 256;
+    mxb[i4] = i < nblk_wg * H ? a.blk_max[((size_t)b * a.nblk + min(blk0 + i / H, a.nblk - 1)) * H + i % H] : 0.f;
+  }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) am = fmaxf(am, __shfl_xor(am, off));
   if ((threadIdx.x & 63) == 0) s_absmax[threadIdx.x >> 6] = am;
   for (int i = threadIdx.x; i < kTopkBins; i += 256) hist[i] = 0u;
+  s_pow[threadIdx.x] = __builtin_amdgcn_exp2f(((float)threadIdx.x - 255.f) * 0.25f);
   __syncthreads();
   am = fmaxf(fmaxf(s_absmax[0], s_absmax[1]), fmaxf(s_absmax[2], s_absmax[3]));
   const float guard = kCodeGuard + (float)c2d * am * kScoreGuard;
   const float lo_scale = kBoundDown * __builtin_amdgcn_exp2f(-0.25f - 2.f * guard);
-  const int blk0 = tbeg / bt, nblk_wg = (tend - 1) / bt - blk0 + 1;
   for (int i = threadIdx.x; i < nblk_wg * H; i += 256) {
-    const int bl = i / H, h = i - bl * H;
-    const float mxb = a.blk_max[((size_t)b * a.nblk + min(blk0 + bl, a.nblk - 1)) * H + h];
-    s_off[i] = (float)(c2d * (double)mxb - s_km[h]) - 63.75f + guard;    // <= 0 before the shift; -inf for an empty block
+    const int i4 = i >> 8;                      // the first 1024 entries were loaded above
+    float m;
+    if (i4 < 4) m = i4 == 0 ? mxb[0] : i4 == 1 ? mxb[1] : i4 == 2 ? mxb[2] : mxb[3];
+    else m = a.blk_max[((size_t)b * a.nblk + min(blk0 + i / H, a.nblk - 1)) * H + i % H];
+    s_off[i] = __builtin_amdgcn_exp2f((float)(c2d * (double)m - s_km[i % H]) + guard);   // exponent <= guard; 0 for an empty block
   }
   __syncthreads();
-  const int jv = threadIdx.x & 7;
   const int r_lo = min(a.n_init, N), r_hi = max(r_lo, N - a.n_local);
-  for (int t0 = tbeg; t0 < tend; t0 += 32 * NP) {
-    uint32_t q[NP][HQ][4];
+  for (int t0 = tbeg; t0 < tend; t0 += 256) {
+    uint32_t qc[NW];
 #pragma unroll
-    for (int p = 0; p < NP; ++p) {
-      const int tc = min(t0 + p * 32 + (int)(threadIdx.x >> 3), N - 1);
-      const uint8_t* cp = a.codes + ((size_t)b * a.max_seq_len + tc) * H;
+    for (int w = 0; w < NW; ++w) qc[w] = qn[w];
+    if (t0 + 256 < tend) load_codes(t0 + 256);
+    const int t = t0 + (int)threadIdx.x;
+    const float* offp = s_off + (min(t, tend - 1) / BT - blk0) * H;
+    float up = 0.f, lo = 0.f;
+    if (HW > 0) {
 #pragma unroll
-      for (int s4 = 0; s4 < HQ; ++s4) {
-        const int h0 = jv * 4 + s4 * 32;
-        if (a.vec) {
-          const uint32_t w = *reinterpret_cast<const uint32_t*>(cp + max(min(h0, H - 4), 0));   // lanes past the last head shadow it (masked below)
-          q[p][s4][0] = w & 255u; q[p][s4][1] = (w >> 8) & 255u; q[p][s4][2] = (w >> 16) & 255u; q[p][s4][3] = w >> 24;
-        } else {
-#pragma unroll
-          for (int e = 0; e < 4; ++e) q[p][s4][e] = cp[min(h0 + e, H - 1)];
-        }
+      for (int w = 0; w < NW; ++w) {
+        const float4 o4 = *reinterpret_cast<const float4*>(offp + w * 4);
+        const uint32_t c0 = qc[w] & 255u, c1 = (qc[w] >> 8) & 255u, c2b = (qc[w] >> 16) & 255u, c3 = qc[w] >> 24;
+        const float t0f = o4.x * s_pow[c0], t1f = o4.y * s_pow[c1], t2f = o4.z * s_pow[c2b], t3f = o4.w * s_pow[c3];
+        up += (t0f + t1f) + (t2f + t3f);
+        // byte 0 is open towards minus infinity: no lower bound from it
+        lo += ((c0 != 0u ? t0f : 0.f) + (c1 != 0u ? t1f : 0.f)) + ((c2b != 0u ? t2f : 0.f) + (c3 != 0u ? t3f : 0.f));
+      }
+    } else {
+      const uint8_t* cp = a.codes + ((size_t)b * a.max_seq_len + min(t, N - 1)) * H;
+      for (int h = 0; h < H; ++h) {
+        const uint32_t c = cp[h];
+        const float tu = offp[h] * s_pow[c];
+        up += tu;
+        lo += c != 0u ? tu : 0.f;
       }
     }
-#pragma unroll
-    for (int p = 0; p < NP; ++p) {
-      const int t = t0 + p * 32 + (int)(threadIdx.x >> 3);
-      const float* offp = s_off + (min(t, tend - 1) / bt - blk0) * H;
-      float up = 0.f, lo = 0.f;
-#pragma unroll
-      for (int s4 = 0; s4 < HQ; ++s4) {
-        const int h0 = jv * 4 + s4 * 32;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          if (h0 + e < H) {
-            const float tu = __builtin_amdgcn_exp2f(offp[h0 + e] + (float)q[p][s4][e] * 0.25f);
-            up += tu;
-            lo += q[p][s4][e] != 0u ? tu : 0.f;   // byte 0 is open towards minus infinity: no lower bound from it
-          }
-        }
-      }
-      up = group8_sum(up) * kBoundUp;
-      lo = group8_sum(lo) * lo_scale;
-      if (t < tend && jv == 0) {
-        const bool ranked = t >= r_lo && t < r_hi;
-        a.vote_hi[(size_t)b * a.max_seq_len + t] = ranked ? up : 0.f;
-        a.vote_lo[(size_t)b * a.max_seq_len + t] = ranked ? lo : 0.f;
-        if (ranked) atomicAdd(&hist[float_key(lo) >> 21], 1u);
-      }
+    up *= kBoundUp;
+    lo *= lo_scale;
+    if (t < tend) {
+      const bool ranked = t >= r_lo && t < r_hi;
+      a.vote_hi[(size_t)b * a.max_seq_len + t] = ranked ? up : 0.f;
+      a.vote_lo[(size_t)b * a.max_seq_len + t] = ranked ? lo : 0.f;
+      if (ranked) atomicAdd(&hist[float_key(lo) >> 21], 1u);
     }
   }
   __syncthreads();
@@ -121,23 +134,30 @@ __global__ __launch_bounds__(256) void vote_bounds_kernel(BoundArgs a, int token
 }
 
 hipError_t launch_vote_bounds(const BoundArgs& a, int B, hipStream_t s) {
-  // a workgroup flushes one histogram: 512 tokens each for short sequences, at most about 2048 workgroups
-  int tpw = (a.max_seq_len + 2047) / 2048;
-  if (tpw < 512) tpw = 512;
-  tpw = (tpw + 127) / 128 * 128;
+  // a workgroup flushes one histogram: 256 tokens each for short sequences, at most about 1024 workgroups per
+  // sequence for long ones
+  int tpw = (a.max_seq_len + 1023) / 1024;
+  if (tpw < 256) tpw = 256;
+  tpw = (tpw + 255) / 256 * 256;
   const int nwg = (a.max_seq_len + tpw - 1) / tpw;
-  const size_t lds = (size_t)(tpw / kScoreTileTokens + 1) * a.H * sizeof(float);   // blocks hold at least 32 tokens
-  if (a.H <= 32) hipLaunchKernelGGL((vote_bounds_kernel<4, 1>), dim3(nwg, B), dim3(256), lds, s, a, tpw);
-  else hipLaunchKernelGGL((vote_bounds_kernel<2, 4>), dim3(nwg, B), dim3(256), lds, s, a, tpw);
+  const size_t lds = (size_t)(tpw / kScoreTileTokens + 1) * a.H * sizeof(float);
+  const dim3 grid(nwg, B);
+  const int hw = a.vec ? a.H / 4 : 0;
+#define TS_VB(W) case W: hipLaunchKernelGGL((vote_bounds_kernel<W>), grid, dim3(256), lds, s, a, tpw); break;
+  switch (hw) {
+    TS_VB(1) TS_VB(2) TS_VB(3) TS_VB(4) TS_VB(5) TS_VB(6) TS_VB(7) TS_VB(8) TS_VB(10) TS_VB(12) TS_VB(14) TS_VB(16) TS_VB(24) TS_VB(32)
+    default: hipLaunchKernelGGL((vote_bounds_kernel<0>), grid, dim3(256), lds, s, a, tpw); break;
+  }
+#undef TS_VB
   return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------------
-constexpr int kRefineThreads = 512;       // 8 waves: the candidates of a chunk are few, their evaluation is a chain
-                                          // of dependent loads, so many waves per chunk shorten the kernel
-constexpr int kRefineWaves = kRefineThreads / 64;
-
+// The refine workgroup has 256 threads, or 1024 when a sequence has few chunks: the candidates of a chunk are few,
+// their evaluation is a chain of dependent loads, so every candidate should get a wave step of its own in the
+// first round; with many chunks small workgroups keep every chunk resident at once.
 // exclusive prefix sum over the threads of the refine workgroup; *total receives the sum
+template <int kRefineWaves>
 __device__ __forceinline__ uint32_t refine_block_scan(uint32_t v, uint32_t* total, uint32_t* lds /* >= kRefineWaves words */) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   uint32_t incl = v;
@@ -161,7 +181,9 @@ __device__ __forceinline__ uint32_t refine_block_scan(uint32_t v, uint32_t* tota
 }
 
 // bin of the k_rem-th largest key in the replicated 2048-bin histogram (kTopkBins if k_rem == 0); all threads get it
+template <int kRefineWaves>
 __device__ __forceinline__ uint32_t refine_find_bin(const uint32_t* gh, uint32_t k_rem, uint32_t* lds /* >= kRefineWaves + 1 words */) {
+  constexpr int kRefineThreads = kRefineWaves * 64;
   constexpr int PER = kTopkBins / kRefineThreads;
   uint32_t c[PER];
   uint32_t sum = 0;
@@ -173,7 +195,7 @@ __device__ __forceinline__ uint32_t refine_find_bin(const uint32_t* gh, uint32_t
     c[e] = x; sum += x;
   }
   uint32_t total;
-  uint32_t above = refine_block_scan(sum, &total, lds);
+  uint32_t above = refine_block_scan<kRefineWaves>(sum, &total, lds);
   __syncthreads();
   if (threadIdx.x == 0) lds[kRefineWaves] = kTopkBins;
   __syncthreads();
@@ -236,13 +258,14 @@ __device__ __forceinline__ double piece_dot_f64<TS_F32>(uint4 k, uint4 q, double
   return acc;
 }
 
-template <int DT, int D, int G>
+template <int DT, int D, int G, int kRefineThreads>
 __global__ __launch_bounds__(kRefineThreads) void topk_refine_kernel(RefineArgs a) {
+  constexpr int kRefineWaves = kRefineThreads / 64;
   constexpr int ES = Elt<DT>::size;
   constexpr int RB = D * ES;
   constexpr int L = RB / 128;
   constexpr int PER = kTopkChunk / kRefineThreads;
-  constexpr int UB = 2;                         // wave steps whose K rows are in flight together
+  constexpr int UB = DT == TS_F32 ? 2 : 4;      // wave steps whose K rows are in flight together
   __shared__ uint32_t lds[kRefineWaves + 2];
   __shared__ uint32_t scan_lds[kRefineWaves];
   __shared__ int ctok[kTopkChunk];
@@ -275,13 +298,14 @@ __global__ __launch_bounds__(kRefineThreads) void topk_refine_kernel(RefineArgs 
   }
   for (int i = threadIdx.x; i < H * (RB / 16); i += kRefineThreads)
     q_lds[i] = reinterpret_cast<const uint4*>(a.q + (size_t)b * H * RB)[i];
-  const uint32_t d0 = refine_find_bin(ta.bound_hist + (size_t)b * kBoundHistCopies * kTopkBins, k_eff, lds);
+  const uint32_t d0 = refine_find_bin<kRefineWaves>(ta.bound_hist + (size_t)b * kBoundHistCopies * kTopkBins, k_eff, lds);
+
   if (blockIdx.x == 0 && threadIdx.x == 0) ta.state[b * 8 + ST_KEFF_WORD] = k_eff;
   uint32_t n = 0;
 #pragma unroll
   for (int e = 0; e < PER; ++e) n += valid[e] && (key[e] >> 21) >= d0;      // d0 == kTopkBins (empty selection) matches nothing
   uint32_t total;
-  uint32_t pos = refine_block_scan(n, &total, scan_lds);
+  uint32_t pos = refine_block_scan<kRefineWaves>(n, &total, scan_lds);
   const int npages = (Nb + a.P - 1) >> a.p_shift;
 #pragma unroll
   for (int e = 0; e < PER; ++e)
@@ -304,7 +328,7 @@ __global__ __launch_bounds__(kRefineThreads) void topk_refine_kernel(RefineArgs 
   const int ngroups = ((int)total + (1 << tps_shift) - 1) >> tps_shift;
   const double c2d = (double)a.scale * 1.44269504088896340736;
   uint2* list = ta.list + ((size_t)b * ta.nblk + blockIdx.x) * kTopkChunk;
-  for (int g0 = wave * UB; g0 < ngroups; g0 += kRefineWaves * UB) {
+  for (int g0 = wave; g0 < ngroups; g0 += kRefineWaves * UB) {   // group uu of this round: g0 + uu * kRefineWaves
     double vote[UB];
 #pragma unroll
     for (int uu = 0; uu < UB; ++uu) vote[uu] = 0.0;
@@ -313,7 +337,7 @@ __global__ __launch_bounds__(kRefineThreads) void topk_refine_kernel(RefineArgs 
       uint4 kr[UB][L];
 #pragma unroll
       for (int uu = 0; uu < UB; ++uu) {
-        const int ci = min(((g0 + uu) << tps_shift) + tis, (int)total - 1);
+        const int ci = min(((g0 + uu * kRefineWaves) << tps_shift) + tis, (int)total - 1);
         const int t = ctok[ci], pid = cpid[ci];
         const uint8_t* kp = a.k_pool + (((size_t)pid << a.p_shift) + (size_t)(t & (a.P - 1))) * ((size_t)a.H_kv * RB) +
                             (size_t)kvh * RB + j * 16;
@@ -330,9 +354,12 @@ __global__ __launch_bounds__(kRefineThreads) void topk_refine_kernel(RefineArgs 
         for (int i = 0; i < L; ++i) qv[i] = q_lds[((kvh * G + g) * RB + i * 128 + j * 16) >> 4];
 #pragma unroll
         for (int uu = 0; uu < UB; ++uu) {
-          double sc = 0.0;
+          double pc[L];                           // independent chains, summed at the end
 #pragma unroll
-          for (int i = 0; i < L; ++i) sc = piece_dot_f64<DT>(kr[uu][i], qv[i], sc);
+          for (int i = 0; i < L; ++i) pc[i] = piece_dot_f64<DT>(kr[uu][i], qv[i], 0.0);
+          double sc = pc[0];
+#pragma unroll
+          for (int i = 1; i < L; ++i) sc += pc[i];
           sc = group8_sum_f64(sc);                // the eight lanes of the row
           svv[uu] = (j == g) ? sc : svv[uu];
         }
@@ -350,22 +377,31 @@ __global__ __launch_bounds__(kRefineThreads) void topk_refine_kernel(RefineArgs 
     }
 #pragma unroll
     for (int uu = 0; uu < UB; ++uu) {
-      const int ci = ((g0 + uu) << tps_shift) + tis;
+      const int ci = ((g0 + uu * kRefineWaves) << tps_shift) + tis;
       if (ci < (int)total && kvh_l == 0 && j == 0) list[ci] = make_uint2(float_key((float)vote[uu]), (uint32_t)ctok[ci]);
     }
   }
 }
 
-template <int DT, int D, int GG>
-static hipError_t refine_one(const RefineArgs& a, dim3 grid, hipStream_t s) {
+template <int DT, int D, int GG, int NT>
+static hipError_t refine_launch(const RefineArgs& a, dim3 grid, hipStream_t s) {
   const size_t lds = (size_t)a.H * D * Elt<DT>::size;     // the query in LDS (next to about 19 KiB of static LDS)
   if (lds > 40960) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&topk_refine_kernel<DT, D, GG>),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&topk_refine_kernel<DT, D, GG, NT>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL((topk_refine_kernel<DT, D, GG>), grid, dim3(kRefineThreads), lds, s, a);
+  hipLaunchKernelGGL((topk_refine_kernel<DT, D, GG, NT>), grid, dim3(NT), lds, s, a);
   return hipGetLastError();
+}
+
+template <int DT, int D, int GG>
+static hipError_t refine_one(const RefineArgs& a, dim3 grid, hipStream_t s) {
+  // few chunks: one fat workgroup per CU at most anyway, so take 16 waves per chunk (bf16; the fp32 form needs the
+  // registers); many chunks: small workgroups, so that all of them are resident at once (a workgroup's run is one
+  // chain of dependent loads, about 10 us, whatever its size)
+  if (DT == TS_BF16 && (long)grid.x * grid.y <= 256) return refine_launch<DT, D, GG, 1024>(a, grid, s);
+  return refine_launch<DT, D, GG, 256>(a, grid, s);
 }
 
 template <int DT, int D>

@@ -13,7 +13,7 @@ constexpr int kScoreLdsStride = 36;    // floats per head row of the staged scor
 constexpr int kScoreMaxWg = 1024;      // upper bound on workgroups per sequence in the score pass
 constexpr int kTopkBins = 2048;        // 11-bit radix digit
 constexpr int kTopkChunk = 2048;       // keys per workgroup in the top-k passes
-constexpr int kBoundHistCopies = 16;   // replicas of the lower-bound histogram (same-address atomics are what its flush costs)
+constexpr int kBoundHistCopies = 8;    // replicas of the lower-bound histogram (same-address atomics are what its flush costs)
 constexpr int kAttnChunk = 64;         // selected tokens per workgroup in sparse attention
 constexpr int kAttnMaxSplit = 512;     // splits the merge kernel can stage (k <= 32768)
 
