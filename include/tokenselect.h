@@ -87,11 +87,18 @@ int32_t ts_version(void);
 const char* ts_strerror(int32_t status);
 
 /* Bytes of device workspace that the calls below need for this problem when selecting at most
- * `k` tokens.  One workspace serves all five calls of a step.  [host] out. */
+ * `k` tokens.  One workspace serves all calls of a step.  [host] out.
+ * Decode (chunk == 1): ts_sparse_paged_attn attends over at most 32768 tokens, so
+ * k + num_initial + num_local > 32768 is TS_ERR_UNSUPPORTED here already (and in ts_sparse_paged_attn). */
 int32_t ts_workspace_bytes(const ts_problem* p, int32_t k, size_t* bytes);
 
 /* Clears a fresh workspace (launches a fill kernel on `stream`; safe under graph capture).  Must
- * run once before the first use of a workspace; the kernels leave it ready for the next call. */
+ * run once before the first use of a workspace; the kernels leave it ready for the next call.
+ * The radix-select histograms inside it must be zero when a selection starts and are zeroed again by the last
+ * kernel of every ts_topk / ts_topk_exact / ts_head_vote call.  If one of those calls (or ts_soft_vote_bounds) returns
+ * an error after it has launched part of its kernels, or a stream is torn down between its launches, the
+ * workspace is in an undefined state: call ts_workspace_init again before reusing it.  The call zeroes every
+ * byte, so the next selection must start with its score pass (which it does anyway). */
 int32_t ts_workspace_init(void* ws, size_t ws_bytes, void* stream);
 
 /* Algorithm 2 (Paged Dot Product Kernel).  For every sequence b, head h, cached token t < N_b:
@@ -144,18 +151,19 @@ int32_t ts_topk_noalloc(const ts_problem* p, const float* votes, int32_t k, int3
                         const uint8_t* skip, int32_t flags, void* stream);
 
 /* ---- Compact form of the selection (decode, chunk == 1): Algorithm 2, Eq. 5 and the TopK with the same result
- * as ts_paged_qk_scores + ts_soft_vote + ts_topk, without the score matrix S ever reaching memory.  On this
+ * as ts_paged_qk_scores + ts_soft_vote + ts_topk (up to tokens whose votes differ from the k-th vote by less than
+ * the float scores' own rounding, about 1e-5 relative), without the score matrix S ever reaching memory.  On this
  * machine a write stream mixed into the K read stream costs several times its bytes, and S is 4*H bytes per
  * token; the compact form writes H bytes per token and makes up for the lost precision by re-evaluating the few
  * tokens that can still be among the k largest.
  *
- * ts_paged_qk_codes    Algorithm 2.  The scores are computed exactly as by ts_paged_qk_scores (same arithmetic,
- *                      same bits) but leave as codes[b][t][h] = clamp(255 + ceil(4 * c2 * (s - M)), 0, 255), where
- *                      c2 = score_scale * log2(e) and M is the maximum of head h over the ranked tokens of the
- *                      token's block (a run of 32, 64 or 128 consecutive tokens, chosen per launch): the distance
- *                      below the block maximum in quarter octaves of softmax weight, rounded towards the maximum;
- *                      0 also stands for everything 63.75 octaves or more below it.  The exact (max, sum of
- *                      exponentials) of every block and head go to the workspace.
+ * ts_paged_qk_codes    Algorithm 2.  The scores (float accumulation of exact products; on the matrix cores for bf16
+ *                      where the shape allows, else with the arithmetic of ts_paged_qk_scores) leave as
+ *                      codes[b][t][h] = clamp(255 + ceil(4 * c2 * (s - M)), 0, 255), where c2 = score_scale * log2(e)
+ *                      and M is the maximum of head h over the ranked tokens of the token's block (32 consecutive
+ *                      tokens, aligned): the distance below the block maximum in quarter octaves of softmax weight,
+ *                      rounded towards the maximum; 0 also stands for everything 63.75 octaves or more below it.
+ *                      The block maxima and per-workgroup softmax statistics go to the workspace.
  * ts_soft_vote_bounds  Eq. 5.  Merges the block statistics into row_stats (as ts_soft_vote defines it) and gives
  *                      every ranked token an interval that contains its vote as ts_soft_vote would compute it:
  *                      vote_lo[b][t] <= votes[b][t] <= vote_hi[b][t], vote_hi / vote_lo about 2^(1/4); both 0
@@ -163,9 +171,11 @@ int32_t ts_topk_noalloc(const ts_problem* p, const float* votes, int32_t k, int3
  *                      and score_scale.
  * ts_topk_exact        The TopK of Eq. 5.  Every token whose upper bound reaches the k-th largest lower bound
  *                      (a superset of the k largest votes; usually 1.1-1.5 k tokens) has its scores recomputed
- *                      from K with the arithmetic of the score pass and its vote evaluated as by ts_soft_vote;
+ *                      from K (exact products, double accumulation: closer to Eq. 5 than the float scores of the score
+ *                      pass) and its vote evaluated with the arithmetic of ts_soft_vote;
  *                      the k largest of those votes are returned exactly as ts_topk returns them (ties to the
- *                      lower token index, ascending token ids, unused slots -1).  Must follow
+ *                      lower token index, ascending token ids, unused slots -1); sel_votes [device] float [B][k],
+ *                      if not NULL, receives the vote of idx[b][j] at [b][j] (0 in unused slots).  Must follow
  *                      ts_soft_vote_bounds with the same problem, workspace, q and score_scale.  Two launches.
  * codes [device] uint8 [B][max_seq_len][H]; vote_hi, vote_lo [device] float [B][max_seq_len]; the other arguments
  * as for the three calls they stand in for.  Sequences with skip[b] != 0 are left untouched.  The cost of
@@ -176,8 +186,8 @@ int32_t ts_paged_qk_codes(const ts_problem* p, const void* q, uint8_t* codes, fl
 int32_t ts_soft_vote_bounds(const ts_problem* p, const uint8_t* codes, float score_scale, float* row_stats,
                             float* vote_hi, float* vote_lo, const uint8_t* skip, void* ws, size_t ws_bytes, void* stream);
 int32_t ts_topk_exact(const ts_problem* p, const void* q, const float* vote_hi, const float* row_stats,
-                      float score_scale, int32_t k, int32_t* idx, int32_t* count, const uint8_t* skip, void* ws,
-                      size_t ws_bytes, void* stream);
+                      float score_scale, int32_t k, int32_t* idx, int32_t* count, float* sel_votes, const uint8_t* skip,
+                      void* ws, size_t ws_bytes, void* stream);
 
 /* The two selection functions the paper ablates against Eq. 5 (Sec. 5.1), as other ways to fill `votes`
  * from the scores of ts_paged_qk_scores; ts_topk then ranks them as usual (decode only, chunk == 1).
@@ -243,6 +253,14 @@ int32_t ts_chunk_soft_vote(const ts_problem* p, const void* q, const float* row_
  * problem over the same pool whose seq_lens hold the cached lengths N_b - C, then attend with the chunk
  * problem.  q [device] [B][C][H][D] bf16; q_mean [device] [B][1][H][D] bf16.  fp32: TS_ERR_UNSUPPORTED. */
 int32_t ts_chunk_mean_query(const ts_problem* p, const void* q, void* q_mean, void* stream);
+
+/* ======================================================================================================
+ * Everything below is for benchmarks and tests, not for serving code: process-wide tuning knobs and timing
+ * helpers.  They are not thread-safe and must not be changed while a call on another thread is between
+ * its argument checks and its launches.  No result depends on them: what a later call of a step needs to know
+ * about an earlier launch (how many statistics partials it left) travels through the workspace, so a knob that
+ * changes between two calls of one step does not change the step's result.
+ * ====================================================================================================== */
 
 /* Tuning knob for benchmarks and tests (process-wide, not thread-safe, not part of the method):
  * variant 0 = score pass with fma arithmetic, 1 = packed bf16 dot2 arithmetic (bf16 inputs only; the

@@ -71,7 +71,7 @@ def load():
         L.ts_topk_noalloc.argtypes = [pp, vp, i32, vp, vp, vp, i32, vp]
         L.ts_paged_qk_codes.argtypes = [pp, vp, vp, f32, vp, vp, sz, vp]
         L.ts_soft_vote_bounds.argtypes = [pp, vp, f32, vp, vp, vp, vp, vp, sz, vp]
-        L.ts_topk_exact.argtypes = [pp, vp, vp, vp, f32, i32, vp, vp, vp, vp, sz, vp]
+        L.ts_topk_exact.argtypes = [pp, vp, vp, vp, f32, i32, vp, vp, vp, vp, vp, sz, vp]
         L.ts_selcache_check.argtypes = [pp, vp, vp, vp, f32, vp, vp]
         L.ts_sparse_paged_attn.argtypes = [pp, vp, vp, i32, vp, f32, vp, vp, vp, sz, vp]
         L.ts_chunk_row_stats.argtypes = [pp, vp, f32, vp, vp, sz, vp]
@@ -206,9 +206,10 @@ def ts_soft_vote_bounds(p: Problem, codes, score_scale: float, row_stats, vote_h
         "ts_soft_vote_bounds")
 
 
-def ts_topk_exact(p: Problem, q, vote_hi, row_stats, score_scale: float, k: int, idx, count, skip, ws, stream=None) -> None:
+def ts_topk_exact(p: Problem, q, vote_hi, row_stats, score_scale: float, k: int, idx, count, skip, ws, stream=None,
+                  sel_votes=None) -> None:
     _ok(load().ts_topk_exact(p.ref(), _ptr(q), _ptr(vote_hi), _ptr(row_stats), float(score_scale), int(k), _ptr(idx),
-                             _ptr(count), _ptr(skip), _ptr(ws), _nbytes(ws), _stream(stream)), "ts_topk_exact")
+                             _ptr(count), _ptr(sel_votes), _ptr(skip), _ptr(ws), _nbytes(ws), _stream(stream)), "ts_topk_exact")
 
 
 def ts_chunk_row_stats(p: Problem, q, score_scale: float, row_stats, ws, stream=None) -> None:

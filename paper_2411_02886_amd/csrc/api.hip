@@ -128,7 +128,10 @@ int32_t ts_workspace_bytes(const ts_problem* p, int32_t k, size_t* bytes) {
   if (bytes == nullptr || k < 1) return TS_ERR_INVALID_ARG;
   const int32_t st = check_problem(p);
   if (st != TS_OK) return st;
-  *bytes = ws_layout(p, k).total;
+  const WsLayout w = ws_layout(p, k);
+  // the decode attention merges at most kAttnMaxSplit partials: say so here, before a selection has been run for nothing
+  if (p->chunk == 1 && w.attn_nsplit > kAttnMaxSplit) return TS_ERR_UNSUPPORTED;
+  *bytes = w.total;
   return TS_OK;
 }
 
@@ -299,8 +302,8 @@ int32_t ts_soft_vote_bounds(const ts_problem* p, const uint8_t* codes, float sco
 }
 
 int32_t ts_topk_exact(const ts_problem* p, const void* q, const float* vote_hi, const float* row_stats,
-                      float score_scale, int32_t k, int32_t* idx, int32_t* count, const uint8_t* skip, void* ws,
-                      size_t ws_bytes, void* stream) {
+                      float score_scale, int32_t k, int32_t* idx, int32_t* count, float* sel_votes, const uint8_t* skip,
+                      void* ws, size_t ws_bytes, void* stream) {
   int32_t st = check_problem(p);
   if (st != TS_OK) return st;
   if (q == nullptr || vote_hi == nullptr || row_stats == nullptr || idx == nullptr || count == nullptr || k < 1)
@@ -316,6 +319,7 @@ int32_t ts_topk_exact(const ts_problem* p, const void* q, const float* vote_hi, 
   a.t.votes = vote_hi; a.t.seq_lens = p->seq_lens; a.t.skip = skip; a.t.idx = idx; a.t.count = count;
   a.t.hist = (uint32_t*)((uint8_t*)ws + w.topk_hist);
   a.t.bound_hist = (uint32_t*)((uint8_t*)ws + w.bound_hist);
+  a.t.sel_votes = sel_votes;
   a.t.state = (uint32_t*)((uint8_t*)ws + w.topk_state);
   a.t.blk = (uint32_t*)((uint8_t*)ws + w.topk_blk);
   a.t.list = (uint2*)((uint8_t*)ws + w.topk_list);

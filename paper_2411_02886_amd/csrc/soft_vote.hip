@@ -117,9 +117,9 @@ __global__ __launch_bounds__(256) void soft_vote_kernel(VoteArgs a, int lpt_shif
       const int h0 = (jv + i * LPT) * 4;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        const int hh = min(h0 + e, H - 1);
-        const double w = (h0 + e < H) ? s_inv[hh] : 0.0;
-        vote = fma((double)vote_exp((double)s[p][i][e] - s_m[hh], c2), w, vote);
+        // lanes past the last head hold a shadow of heads H-4..H-1: they are skipped, not weighted by zero
+        // (a shadowed score can lie far above the maximum of the head it would be compared with: inf * 0)
+        if (h0 + e < H) vote = fma((double)vote_exp((double)s[p][i][e] - s_m[h0 + e], c2), s_inv[h0 + e], vote);
       }
     }
     for (int off = 1; off < LPT; off <<= 1) vote += __shfl_xor(vote, off);

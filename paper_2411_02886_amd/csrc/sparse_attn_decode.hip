@@ -2,7 +2,7 @@
 // selected tokens, gathered row by row through the page table (the selection is handed over as k
 // indices, never as gathered K/V copies).
 //
-// Split-k: a workgroup takes 128 selected tokens of one KV head (all G query heads of the group share
+// Split-k: a workgroup takes 64 selected tokens (kAttnChunk) of one KV head (all G query heads of the group share
 // the gathered K and V rows).  Memory latency, not bandwidth, bounds this step (a few MiB are
 // gathered), so every K and V load of a wave is issued before the first multiply; logits use eight
 // lanes per K row, a local softmax sits in LDS, the P.V product uses 16-byte V pieces per lane.  A

@@ -397,6 +397,8 @@ __global__ __launch_bounds__(kFinalThreads) void topk_final_kernel(TopkArgs a) {
   float* acc = as_votes ? a.vote_acc + (size_t)(b / a.heads) * a.max_seq_len : nullptr;
   if (!as_votes) {
     for (int i = k_eff + tid; i < a.k; i += kFinalThreads) out[i] = -1;
+    if (FULL && a.sel_votes != nullptr)
+      for (int i = k_eff + tid; i < a.k; i += kFinalThreads) a.sel_votes[(size_t)b * a.k + i] = 0.f;
     if (tid == 0) a.count[b] = k_eff;
   }
   if (FULL) {  // the replicated histogram of the lower bounds has been consumed by the refine pass: zero it again
@@ -505,12 +507,18 @@ __global__ __launch_bounds__(kFinalThreads) void topk_final_kernel(TopkArgs a) {
       const int t = (int)e[i].y;
       if (e[i].x > thr) {
         if (as_votes) atomicAdd(&acc[t], 1.0f);
-        else out[gt_before + min(eq_before, need_eq)] = t;
+        else {
+          out[gt_before + min(eq_before, need_eq)] = t;
+          if (FULL && a.sel_votes != nullptr) a.sel_votes[(size_t)b * a.k + gt_before + min(eq_before, need_eq)] = key_float(e[i].x);
+        }
         ++gt_before;
       } else if (e[i].x == thr) {
         if (eq_before < need_eq) {
           if (as_votes) atomicAdd(&acc[t], 1.0f);
-          else out[gt_before + eq_before] = t;
+          else {
+            out[gt_before + eq_before] = t;
+            if (FULL && a.sel_votes != nullptr) a.sel_votes[(size_t)b * a.k + gt_before + eq_before] = key_float(e[i].x);
+          }
         }
         ++eq_before;
       }

@@ -148,6 +148,11 @@ __device__ __forceinline__ uint32_t float_key(float v) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// inverse of float_key
+__device__ __forceinline__ float key_float(uint32_t k) {
+  return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
+
 // exp(x) for x <= 0 (larger x also fine up to ~700); result below 1e-300 flushes to 0
 __device__ __forceinline__ double exp_f64(double x) {
   const bool tiny = x < -690.0;

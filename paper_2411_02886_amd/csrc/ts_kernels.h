@@ -74,6 +74,7 @@ struct TopkArgs {
   int k, max_seq_len, nblk;
   int heads;            // virtual sequences per real one (Eq. 4: one per head over transposed scores); 1 = plain
   float* vote_acc;      // Eq. 4: the emit pass adds 1 to vote_acc[real sequence][t] for every winner instead of writing idx
+  float* sel_votes;     // compact selection: [B][k] votes of the selected tokens in idx order, or nullptr
   uint32_t* bound_hist; // compact selection: [B][kBoundHistCopies][kTopkBins] histogram of the vote lower bounds (else nullptr)
 };
 

@@ -104,11 +104,12 @@ class DecodeLayer:
             self.codes = torch.empty((B, M, self.H), dtype=torch.uint8, device=self.device)
             self.vote_hi = torch.empty((B, M), dtype=torch.float32, device=self.device)
             self.vote_lo = torch.empty((B, M), dtype=torch.float32, device=self.device)
+            self.sel_votes = torch.zeros((B, self.k), dtype=torch.float32, device=self.device)
         ts.ts_paged_qk_codes(self.problem, q, self.codes, score_scale, skip, self.ws)
         ts.ts_soft_vote_bounds(self.problem, self.codes, score_scale, self.row_stats, self.vote_hi, self.vote_lo, skip,
                                self.ws)
         ts.ts_topk_exact(self.problem, q, self.vote_hi, self.row_stats, score_scale, self.k, self.idx, self.count, skip,
-                         self.ws)
+                         self.ws, sel_votes=getattr(self, "sel_votes", None))
 
     def attend(self, q, sm_scale):
         ts.ts_sparse_paged_attn(self.problem, q, self.idx, self.k, self.count, sm_scale, self.out, self.lse, self.ws)
