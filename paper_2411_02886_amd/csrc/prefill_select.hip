@@ -44,8 +44,6 @@ __global__ __launch_bounds__(256, 2) void prefill_qk_kernel(PrefillArgs a) {
   constexpr int KS = D / 16;                    // MFMA k-steps
   constexpr int RBYTES = D * 2;                 // bytes per K row
   constexpr int PPR = RBYTES / 16;              // 16-byte pieces per row
-  constexpr int RPP = 256 / PPR;                // rows staged per pass of the workgroup
-  constexpr int NLD = kPfTile / RPP;            // staging loads per thread per tile
   constexpr int LROW = RBYTES + 16;             // padded LDS row
   __shared__ __attribute__((aligned(16))) uint8_t s_k[2][kPfTile * LROW];
   __shared__ float s_col[3][4][kPfTile];
@@ -108,25 +106,43 @@ __global__ __launch_bounds__(256, 2) void prefill_qk_kernel(PrefillArgs a) {
       }
     }
 
-  // ---- K staging: thread -> (row within pass, 16-byte piece)
-  const int st_row = threadIdx.x / PPR, st_piece = threadIdx.x % PPR;
+  // ---- K staging: a wave stages 16 consecutive tokens of the tile (lane -> row within a pass of 64 / PPR rows,
+  // 16-byte piece).  With pages of 16 tokens or more those 16 tokens lie in one page: the page id is one scalar
+  // load per wave and tile, and the lanes' addresses are a scalar base plus a constant lane offset (the address
+  // arithmetic of a per-lane page lookup, with its integer multiplies, was a quarter of the vector instructions
+  // of the loop).
+  constexpr int RPW = 64 / PPR;                  // rows per pass of a wave
+  constexpr int NLD = 16 / RPW;                  // staging loads per lane per tile
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const int st_row = lane / PPR, st_piece = lane % PPR;
+  const size_t tok_stride = (size_t)a.H_kv * RBYTES;
+  const uint32_t lane_off = (uint32_t)(st_row * (int)tok_stride + st_piece * 16);
   struct KRows { uint4 v[NLD]; };
   auto fetch = [&](int tile) -> KRows {
     KRows r;
+    const int tbase = tile * kPfTile + wave_u * 16;
+    if (a.P >= 16 && tbase + 16 <= Nc) {                      // uniform per wave
+      const int page = a.page_indices[indptr + (tbase >> a.p_shift)];
+      const uint8_t* base = a.k_pool + ((((size_t)page << a.p_shift) + (size_t)(tbase & (a.P - 1))) * a.H_kv + kvh) * RBYTES;
 #pragma unroll
-    for (int it = 0; it < NLD; ++it) {
-      int t = tile * kPfTile + st_row + it * RPP;
-      t = min(t, Nc - 1);                                     // the last tile may be ragged: shadow the last token
-      const int page = a.page_indices[indptr + (t >> a.p_shift)];
-      const uint8_t* kp = a.k_pool + ((((size_t)page << a.p_shift) + (t & (a.P - 1))) * a.H_kv + kvh) * RBYTES + st_piece * 16;
-      r.v[it] = *reinterpret_cast<const uint4*>(kp);
+      for (int it = 0; it < NLD; ++it)
+        r.v[it] = *reinterpret_cast<const uint4*>(base + (size_t)it * RPW * tok_stride + lane_off);
+    } else {
+#pragma unroll
+      for (int it = 0; it < NLD; ++it) {
+        int t = tbase + st_row + it * RPW;
+        t = max(min(t, Nc - 1), 0);                           // the last tile may be ragged: shadow the last token
+        const int page = a.page_indices[indptr + (t >> a.p_shift)];
+        const uint8_t* kp = a.k_pool + ((((size_t)page << a.p_shift) + (t & (a.P - 1))) * a.H_kv + kvh) * RBYTES + st_piece * 16;
+        r.v[it] = *reinterpret_cast<const uint4*>(kp);
+      }
     }
     return r;
   };
   auto stage = [&](int buf, const KRows& r) {
 #pragma unroll
     for (int it = 0; it < NLD; ++it)
-      *reinterpret_cast<uint4*>(&s_k[buf][(st_row + it * RPP) * LROW + st_piece * 16]) = r.v[it];
+      *reinterpret_cast<uint4*>(&s_k[buf][(wave_u * 16 + st_row + it * RPW) * LROW + st_piece * 16]) = r.v[it];
   };
 
   KRows kreg;
@@ -211,18 +227,20 @@ __global__ __launch_bounds__(256, 2) void prefill_qk_kernel(PrefillArgs a) {
   // Software pipeline over the blocks (tile, first half) (tile, second half) ...: the MFMAs of the next
   // block are issued before the softmax of the current one, so the matrix cores work while the vector
   // ALU exponentiates.  One barrier per tile publishes the staged K rows of the next tile.
+  // The loop body is straight-line code (staging, fetching and the look-ahead MFMAs also run on the last tiles,
+  // where their results are not used): only then can the compiler's scheduler mix MFMAs and vector instructions.
   f32x16_t acc0[2], acc1[2];
   if (tile_begin < tile_end) mfma_block(0, 0, acc0);
   for (int tile = tile_begin; tile < tile_end; ++tile) {
     const int it = tile - tile_begin;
     const int buf = it & 1, cbuf = it % 3;
-    if (tile + 1 < tile_end) stage(buf ^ 1, kreg);           // rows fetched during the previous iteration
-    if (tile + 2 < tile_end) kreg = fetch(tile + 2);
+    stage(buf ^ 1, kreg);                                    // rows fetched during the previous iteration
+    kreg = fetch(min(tile + 2, tile_end - 1));
     mfma_block(buf, 1, acc1);
     softmax_block(acc0, tile, 0, cbuf);
     __syncthreads();                                         // next tile's rows are staged; all waves are done with tile - 1
     if (it > 0) write_votes(tile - 1, (it - 1) % 3);
-    if (tile + 1 < tile_end) mfma_block(buf ^ 1, 0, acc0);
+    mfma_block(buf ^ 1, 0, acc0);
     softmax_block(acc1, tile, 1, cbuf);
   }
   if (tile_begin < tile_end) {
