@@ -3,7 +3,8 @@
 // with S = Q K^T computed on the matrix cores and never written to memory.  Two sweeps over K:
 //   sweep 1  per-row (query, head) log-sum-exp of scale * s over the cached tokens   -> row_stats
 //   sweep 2  e = exp(scale * s - lse_row) summed over the rows of a tile column          -> votes
-// Both sweeps run the same instruction sequence for S, so a score has the same bits in both.
+// Both sweeps form S from the same fragments with the same MFMA instruction (sweep 1 with the operands exchanged, which
+// transposes the result and leaves the products and their order of summation alone).
 //
 // Work split.  For one KV head the G query heads x C queries are 'rows' that all meet the same K
 // rows.  A workgroup (4 waves) owns 256 rows (64 per wave = two 32-row MFMA blocks, query fragments
@@ -14,6 +15,7 @@
 // is multiplied.  Workgroups that share a K range are placed on the same XCD and adjacent in launch
 // order, so that one of them pulls a tile from HBM and the others find it in that XCD's L2.
 #include "ts_kernels.h"
+#include <type_traits>
 
 namespace ts {
 
@@ -82,20 +84,23 @@ __global__ __launch_bounds__(256, 2) void prefill_qk_kernel(PrefillArgs a) {
   }
   (void)row_of;
 
-  // ---- per-row state.  In the MFMA result a lane holds, for column `col`, the 16 rows
-  // 8 * i + 4 * half + j (i, j < 4) of each 32-row block: 32 rows per lane.
-  // Sweep 1 keeps, per lane and row, a reference exponent `off` (log2 units) and the sum of
-  // exp2(c2 * s - off) over the lane's columns; the reference is raised only when an argument would
-  // exceed 2^64 (rare: a raised reference gets 2^32 of head room), so the common path is one fma, one exp2 and one add per score.
-  // Sweep 2 holds the row's log2-sum-exp: the high float as the exponent offset, 2^-low as a weight.
-  float off[2][16], aux[2][16];
+  // ---- per-row state.
+  // Sweep 2 multiplies Q (A operand) with the K tile (B operand): in the result a lane holds, for token `col`, the 16
+  // query rows 8 * i + 4 * half + j (i, j < 4) of each 32-row block, so the sum over the rows of a column is a sum inside
+  // the lane; per lane and row it holds the row's log2-sum-exp: the high float as the exponent offset, 2^-low as a weight.
+  // Sweep 1 multiplies the same fragments the other way round (K tile as A, Q as B: the same products summed in the same
+  // order, S transposed): a lane then holds 16 tokens of ONE query row per block, so the row's running statistics are two
+  // registers per block instead of 32 -- a reference exponent `off1` (log2 units) and the sum of exp2(c2 * s - off1) over
+  // the lane's tokens.  The reference is raised only when an argument would exceed 2^64 (rare: a raised reference gets
+  // 2^32 of head room), so the common path is one fma, one exp2 and one add per score plus half a max.
+  float off[2][16], aux[2][16];                  // sweep 2 only
+  float off1[2] = {-INFINITY, -INFINITY}, aux1[2] = {0.f, 0.f};   // sweep 1 only (see below)
+  if (SWEEP == 2) {
 #pragma unroll
-  for (int mb = 0; mb < 2; ++mb)
+    for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      const int row = rb * kPfRowsPerWg + wave * 64 + mb * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
-      if (SWEEP == 1) { off[mb][e] = -INFINITY; aux[mb][e] = 0.f; }
-      else {
+      for (int e = 0; e < 16; ++e) {
+        const int row = rb * kPfRowsPerWg + wave * 64 + mb * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
         float hi = INFINITY, lo = 0.f;           // rows past the end never vote: exp2(-inf) = 0
         if (row < nrows) {
           const int c = row / G, g = row % G;
@@ -104,7 +109,7 @@ __global__ __launch_bounds__(256, 2) void prefill_qk_kernel(PrefillArgs a) {
         }
         off[mb][e] = hi; aux[mb][e] = __builtin_amdgcn_exp2f(-lo);   // |lo| < 2^-17: the factor 2^-lo, exact to an ulp
       }
-    }
+  }
 
   // ---- K staging: a wave stages 16 consecutive tokens of the tile (lane -> row within a pass of 64 / PPR rows,
   // 16-byte piece).  With pages of 16 tokens or more those 16 tokens lie in one page: the page id is one scalar
@@ -118,7 +123,7 @@ __global__ __launch_bounds__(256, 2) void prefill_qk_kernel(PrefillArgs a) {
   const size_t tok_stride = (size_t)a.H_kv * RBYTES;
   const uint32_t lane_off = (uint32_t)(st_row * (int)tok_stride + st_piece * 16);
   struct KRows { uint4 v[NLD]; };
-  auto fetch = [&](int tile) -> KRows {
+  auto fetch = [&](int tile) __attribute__((always_inline)) -> KRows {
     KRows r;
     const int tbase = tile * kPfTile + wave_u * 16;
     if (a.P >= 16 && tbase + 16 <= Nc) {                      // uniform per wave
@@ -156,65 +161,88 @@ __global__ __launch_bounds__(256, 2) void prefill_qk_kernel(PrefillArgs a) {
 
   float* vout = (SWEEP == 2) ? a.vote_part + ((size_t)b * a.RB * a.H_kv + (size_t)rb * a.H_kv + kvh) * a.max_seq_len : nullptr;
 
-  // one 64-row x 32-token block on the matrix cores
-  auto mfma_block = [&](int buf, int nb, f32x16_t (&acc)[2]) {
+  // one 64-row x 32-token block on the matrix cores; k-steps [ks0, ks1) (the first clears the accumulators)
+  auto mfma_part = [&](int buf, int nb, f32x16_t (&acc)[2], auto ks0_c, auto ks1_c) __attribute__((always_inline)) {
+    constexpr int ks0 = decltype(ks0_c)::value, ks1 = decltype(ks1_c)::value;
+    if (ks0 == 0) {
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
+      for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[mb][e] = 0.f;
+        for (int e = 0; e < 16; ++e) acc[mb][e] = 0.f;
+    }
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
+    for (int ks = ks0; ks < ks1; ++ks) {
       // B[k][n] = K[token n][d k]: lane holds token n = col, d = 16 * ks + 8 * half .. + 8
       const uint4 bv = *reinterpret_cast<const uint4*>(&s_k[buf][(nb * 32 + col) * LROW + (ks * 2 + half) * 16]);
       const bf16x8_t bfrag = __builtin_bit_cast(bf16x8_t, bv);
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
-        acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[mb][ks], bfrag, acc[mb], 0, 0, 0);
+        acc[mb] = SWEEP == 1 ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag, afrag[mb][ks], acc[mb], 0, 0, 0)
+                             : __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[mb][ks], bfrag, acc[mb], 0, 0, 0);
     }
   };
-  // the softmax arithmetic of one block on the vector ALU
-  auto softmax_block = [&](const f32x16_t (&acc)[2], int tile, int nb, int cbuf) {
-    const int tcol = tile * kPfTile + nb * 32 + col;
-    const bool cvalid = tcol >= r_lo && tcol < r_hi;
+  using K0 = std::integral_constant<int, 0>;
+  using KH = std::integral_constant<int, KS / 2>;
+  using KE = std::integral_constant<int, KS>;
+  auto mfma_block = [&](int buf, int nb, f32x16_t (&acc)[2]) { mfma_part(buf, nb, acc, K0{}, KE{}); };
+
+  // Softmax arithmetic of one block on the vector ALU, overlapped with the MFMAs of the next block `nacc`.
+  // Sweep 1 has a (rare) branch in the middle -- a reference has to be raised -- and the scheduler cannot move MFMAs
+  // across it, so half of the next block's k-steps are issued before it and half after it.  RAGGED: the tile holds
+  // columns outside the ranked range; they get weight 0 in the sum (a full tile needs neither mask nor weight).
+  auto step = [&](auto ragged, const f32x16_t (&acc)[2], int tile, int nb, int cbuf, int nbuf, int nnb, f32x16_t (&nacc)[2]) __attribute__((always_inline)) {
+    constexpr bool RAGGED = decltype(ragged)::value;
     if (SWEEP == 1) {
-      if (cvalid) {   // lane predication (one exec-mask update per block): columns past the end take no part
-        float ar[2][16];
-        float amax = -INFINITY;
+      // acc[mb][e]: token 8 * (e / 4) + 4 * half + e % 4 of the block, query row mb * 32 + col
+      mfma_part(nbuf, nnb, nacc, K0{}, KH{});
+      float mraw[2], xm[2];
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb) {
+        float m = acc[mb][0];
+#pragma unroll
+        for (int e = 1; e < 16; ++e) m = fmaxf(m, acc[mb][e]);
+        mraw[mb] = m;
+        xm[mb] = fmaf(c2, m, -off1[mb]);          // the largest argument (c2 >= 0); +inf while off1 is unset
+      }
+      // first block of a lane, or a score far above the reference (tokens outside the ranked range shadow a real
+      // token or are real tokens: a reference they raise is as good as any other)
+      if (__builtin_amdgcn_ballot_w64(fmaxf(xm[0], xm[1]) > 64.f) != 0) {
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const float v = fmaf(c2, acc[mb][e], -off[mb][e]);   // +inf while off is unset
-            ar[mb][e] = v;
-            amax = fmaxf(amax, v);
+          if (xm[mb] > 64.f) {
+            // the new reference sits kRefHead above the value that forced it: without head room the next larger
+            // score would raise it again
+            const float noff = c2 * mraw[mb] + kRefHead;
+            aux1[mb] = (off1[mb] == -INFINITY) ? 0.f : aux1[mb] * __builtin_amdgcn_exp2f(off1[mb] - noff);
+            off1[mb] = noff;
           }
-        if (__builtin_amdgcn_ballot_w64(amax > 64.f) != 0) {   // first column of a lane, or a score far above the reference
+      }
+      mfma_part(nbuf, nnb, nacc, KH{}, KE{});
 #pragma unroll
-          for (int mb = 0; mb < 2; ++mb)
+      for (int mb = 0; mb < 2; ++mb) {
+        float s0 = 0.f, s1 = 0.f;
 #pragma unroll
-            for (int e = 0; e < 16; ++e)
-              if (ar[mb][e] > 64.f) {
-                // the new reference sits kRefHead above the value that forced it: a lane's first score is a typical
-                // one, not a large one, and without head room nearly every block would raise some reference again
-                const float noff = c2 * acc[mb][e] + kRefHead;
-                aux[mb][e] = (off[mb][e] == -INFINITY) ? 0.f : aux[mb][e] * __builtin_amdgcn_exp2f(off[mb][e] - noff);
-                off[mb][e] = noff;
-                ar[mb][e] = -kRefHead;
-              }
+        for (int e = 0; e < 16; e += 2) {
+          float e0 = __builtin_amdgcn_exp2f(fmaf(c2, acc[mb][e], -off1[mb]));        // arguments are <= 64: finite
+          float e1 = __builtin_amdgcn_exp2f(fmaf(c2, acc[mb][e + 1], -off1[mb]));
+          if (RAGGED) {
+            const int t0 = tile * kPfTile + nb * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
+            e0 = (t0 >= r_lo && t0 < r_hi) ? e0 : 0.f;
+            e1 = (t0 + 1 >= r_lo && t0 + 1 < r_hi) ? e1 : 0.f;
+          }
+          s0 += e0; s1 += e1;
         }
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) aux[mb][e] += __builtin_amdgcn_exp2f(ar[mb][e]);
+        aux1[mb] += s0 + s1;
       }
     } else {
+      mfma_part(nbuf, nnb, nacc, K0{}, KE{});
       float cs = 0.f;
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
         for (int e = 0; e < 16; ++e) cs = fmaf(__builtin_amdgcn_exp2f(fmaf(c2, acc[mb][e], -off[mb][e])), aux[mb][e], cs);
       cs += __shfl_xor(cs, 32);                              // the other 16 rows of each block
-      if (half == 0) s_col[cbuf][wave][nb * 32 + col] = cs;
+      if (half == 0) s_col[cbuf][wave][nb * 32 + col] = cs;  // columns outside the range are dropped by write_votes
     }
   };
   auto write_votes = [&](int tile, int cbuf) {
@@ -225,51 +253,50 @@ __global__ __launch_bounds__(256, 2) void prefill_qk_kernel(PrefillArgs a) {
   };
 
   // Software pipeline over the blocks (tile, first half) (tile, second half) ...: the MFMAs of the next
-  // block are issued before the softmax of the current one, so the matrix cores work while the vector
+  // block are issued with the softmax of the current one, so the matrix cores work while the vector
   // ALU exponentiates.  One barrier per tile publishes the staged K rows of the next tile.
   // The loop body is straight-line code (staging, fetching and the look-ahead MFMAs also run on the last tiles,
   // where their results are not used): only then can the compiler's scheduler mix MFMAs and vector instructions.
   f32x16_t acc0[2], acc1[2];
   if (tile_begin < tile_end) mfma_block(0, 0, acc0);
-  for (int tile = tile_begin; tile < tile_end; ++tile) {
+  auto body = [&](auto ragged, int tile) __attribute__((always_inline)) {
     const int it = tile - tile_begin;
     const int buf = it & 1, cbuf = it % 3;
     stage(buf ^ 1, kreg);                                    // rows fetched during the previous iteration
     kreg = fetch(min(tile + 2, tile_end - 1));
-    mfma_block(buf, 1, acc1);
-    softmax_block(acc0, tile, 0, cbuf);
+    step(ragged, acc0, tile, 0, cbuf, buf, 1, acc1);
     __syncthreads();                                         // next tile's rows are staged; all waves are done with tile - 1
     if (it > 0) write_votes(tile - 1, (it - 1) % 3);
-    mfma_block(buf ^ 1, 0, acc0);
-    softmax_block(acc1, tile, 1, cbuf);
-  }
+    step(ragged, acc1, tile, 1, cbuf, buf ^ 1, 0, acc0);
+  };
+  // only the first and the last tile of the ranked range can be ragged: they are peeled off, so that the loop over
+  // the full tiles holds one variant of the body
+  int tile = tile_begin;
+  if (SWEEP == 1 && tile < tile_end && tile * kPfTile < r_lo) { body(std::true_type{}, tile); ++tile; }
+  const int full_end = (SWEEP == 1 && tile_end * kPfTile > r_hi) ? max(tile, tile_end - 1) : tile_end;
+  for (; tile < full_end; ++tile) body(std::false_type{}, tile);
+  for (; tile < tile_end; ++tile) body(std::true_type{}, tile);
   if (tile_begin < tile_end) {
     __syncthreads();
     write_votes(tile_end - 1, (tile_end - 1 - tile_begin) % 3);
   }
 
   if (SWEEP == 1) {
-    // a row's sums are spread over the 32 lanes of its half-wave (one column each): merge them
+    // a query row's sums sit in the two lanes col and col + 32 (disjoint tokens): merge them
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        float m = off[mb][e], l = aux[mb][e];
-#pragma unroll
-        for (int o = 1; o < 32; o <<= 1) {
-          const float mo = __shfl_xor(m, o), lo = __shfl_xor(l, o);
-          const float mn = fmaxf(m, mo);
-          const float la = (m == -INFINITY) ? 0.f : l * __builtin_amdgcn_exp2f(m - mn);
-          const float lb = (mo == -INFINITY) ? 0.f : lo * __builtin_amdgcn_exp2f(mo - mn);
-          m = mn; l = la + lb;
-        }
-        const int row = rb * kPfRowsPerWg + wave * 64 + mb * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
-        if (col == 0 && row < nrows) {
-          const int c = row / G, g = row % G;
-          float* pp = a.stat_part + ((((size_t)b * a.TS + split) * C + c) * H + kvh * G + g) * 2;
-          pp[0] = m; pp[1] = l;                                // (reference exponent, sum of exp2(arg - reference))
-        }
+    for (int mb = 0; mb < 2; ++mb) {
+      const float m = off1[mb], l = aux1[mb];
+      const float mo = __shfl_xor(m, 32), lo = __shfl_xor(l, 32);
+      const float mn = fmaxf(m, mo);
+      const float la = (m == -INFINITY) ? 0.f : l * __builtin_amdgcn_exp2f(m - mn);
+      const float lb = (mo == -INFINITY) ? 0.f : lo * __builtin_amdgcn_exp2f(mo - mn);
+      const int row = rb * kPfRowsPerWg + wave * 64 + mb * 32 + col;
+      if (half == 0 && row < nrows) {
+        const int c = row / G, g = row % G;
+        float* pp = a.stat_part + ((((size_t)b * a.TS + split) * C + c) * H + kvh * G + g) * 2;
+        pp[0] = mn; pp[1] = la + lb;                             // (reference exponent, sum of exp2(arg - reference))
       }
+    }
   }
 }
 
