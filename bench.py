@@ -49,9 +49,10 @@ def parse():
     ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4, 5],
                     help="4 (default) is the headline workload, the largest single-GPU configuration (1 Mi tokens), with "
                          "configuration 2 (131072 tokens) carried as `secondary`; 3 is the Selection Cache decode run; 5 is chunked prefill")
-    ap.add_argument("--path", choices=["compact", "dense"], default="compact",
-                    help="compact (default): selection without the score matrix in memory (ts_paged_qk_codes + ts_soft_vote_bounds + "
-                         "ts_topk_exact); dense: the five calls with the fp32 score matrix")
+    ap.add_argument("--path", choices=["compact", "dense"], default=None,
+                    help="compact (default for configurations 1, 2, 4): selection without the score matrix in memory "
+                         "(ts_paged_qk_codes + ts_soft_vote_bounds + ts_topk_exact); dense (default for configuration 3, a batch "
+                         "of short sequences, where it is the faster form): the five calls with the fp32 score matrix")
     ap.add_argument("--no-secondary", action="store_true", help="config 4: do not run configuration 2 as well")
     ap.add_argument("--pools", type=int, default=0, help="physical pool copies to rotate over (0 = enough for >= 2 GiB)")
     ap.add_argument("--variant", type=int, default=-1, help="score-pass arithmetic: 0 fma, 1 bf16 dot2, -1 library default")
@@ -117,6 +118,7 @@ def selection_cache_run(args):
     kflat = layer.k_pool.view(-1, w.H_kv, w.D); vflat = layer.v_pool.view(-1, w.H_kv, w.D)
     len0 = layer.seq_lens.clone()
     sm, theta, scale = 1.0 / math.sqrt(w.D), args.theta, 1.0
+    compact = args.path == "compact"                           # default here: the five-call form
     reuse_log = torch.zeros((steps, w.B), dtype=torch.uint8, device=dev)
 
     def run(theta=theta):
@@ -124,7 +126,7 @@ def selection_cache_run(args):
         for t in range(steps):
             kflat.index_copy_(0, slots_d[t], ksd[t]); vflat.index_copy_(0, slots_d[t], vsd[t])   # append this step's K/V rows
             layer.seq_lens.add_(1)
-            layer.step(qs[t], theta=theta, score_scale=scale, sm_scale=sm)
+            layer.step(qs[t], theta=theta, score_scale=scale, sm_scale=sm, compact=compact)
             reuse_log[t].copy_(layer.reuse)
 
     run(); torch.cuda.synchronize()
@@ -178,7 +180,9 @@ def selection_cache_run(args):
            "reuse_rate": float(reuse.mean()), "sequence_steps_per_s": steps * w.B / dt,
            "tokens_scanned_per_s": scanned / dt,
            "execution": mode, "eager_batch_steps_per_s": steps / dt_eager,
-           "note": "10 library launches + 4 torch launches per step; 'graph' = the whole 64-step run captured once as a HIP graph "
+           "selection_form": "compact (no score matrix in memory)" if compact else "five calls (fp32 score matrix)",
+           "note": ("%d library launches + 4 torch launches per step; " % (8 if compact else 10)) +
+                   "'graph' = the whole 64-step run captured once as a HIP graph "
                    "and replayed (replays checked against the eager run), 'eager' = host-driven loop"}
     if args.theta_sweep:
         sweep = []
@@ -274,7 +278,7 @@ def decode_bench(cfg, args, *, steps, warmup, with_cpu_baseline, with_graph):
     N = int(w.seq_lens[0])
     if args.variant >= 0 or args.score_wg:
         ts.ts_debug_set_score_variant(args.variant if args.variant >= 0 else 1, args.score_wg)
-    compact = args.path == "compact" and args.selection == "soft"
+    compact = args.path != "dense" and args.selection == "soft"
     layer = DecodeLayer.from_workload(w, device=dev, num_initial=args.n_init, num_local=args.n_local)
     esize = w.esize()
     k_bytes = N * w.H_kv * w.D * esize                      # algorithmic bytes of the score pass
