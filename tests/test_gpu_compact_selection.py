@@ -166,6 +166,14 @@ SHAPES = [
     (W.BF16, 2, 2, 128, 16, 200, 16),
     (W.BF16, 64, 32, 64, 16, 260, 20),
     (W.BF16, 128, 16, 128, 16, 180, 20),
+    # shapes of the matrix-core score pass: every group size it takes, both head dims, both wave-tile widths,
+    # pages shorter than a wave step, two KV-head units per token
+    (W.BF16, 24, 8, 128, 16, 1500, 100),
+    (W.BF16, 24, 4, 64, 16, 900, 64),
+    (W.BF16, 32, 4, 128, 4, 700, 50),
+    (W.BF16, 64, 16, 64, 2, 400, 40),
+    (W.BF16, 20, 4, 128, 1, 350, 30),
+    (W.BF16, 32, 8, 64, 16, 1234, 77),
 ]
 
 
@@ -190,6 +198,21 @@ def test_longer_blocks(gpu, run_tiles):
         check_compact(w, layer, q, score_scale=1.0, label="rr%d" % run_tiles)
     finally:
         gpu.ts_debug_set_score_variant(1, 0, 0)
+
+
+@pytest.mark.parametrize("rr,wg", [(1, 0), (3, 5), (8, 2), (5, 0), (2, 1)])
+@pytest.mark.parametrize("heads", [(32, 8), (28, 4)])
+def test_matrix_core_score_pass_run_lengths_and_grids(gpu, rr, wg, heads):
+    """The matrix-core score pass with other run lengths and with grids so small that a wave takes several runs."""
+    gpu.ts_debug_set_codes_path(1, rr); gpu.ts_debug_set_score_variant(1, wg, 0)
+    try:
+        w = W.make_workload("mfma_runs", dtype=W.BF16, H=heads[0], H_kv=heads[1], D=128, P=16, B=2, seq_lens=[9000, 3333],
+                            k=300, beta=2.5, planted_per_head=2, seed=77 + rr)
+        layer, q = make_layer(w)
+        print("compact matrix-core run_tiles", rr, "workgroups", wg, heads, flush=True)
+        check_compact(w, layer, q, score_scale=1.0, label="mfma rr%d wg%d" % (rr, wg))
+    finally:
+        gpu.ts_debug_set_codes_path(1, 0); gpu.ts_debug_set_score_variant(1, 0, 0)
 
 
 def test_batch_ragged_and_forced(gpu):
