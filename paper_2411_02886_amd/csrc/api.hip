@@ -257,12 +257,32 @@ int32_t ts_paged_qk_codes(const ts_problem* p, const void* q, uint8_t* codes, fl
     a.HB = G <= 4 ? 8 : 4; a.hb_shift = ilog2(a.HB); a.NU = p->num_kv_heads / a.HB;
     a.uniform_page = p->page_size >= (8 / a.HB);
     const long ntt = (p->max_seq_len + kScoreTileTokens - 1) / kScoreTileTokens;
-    int rr = g_codes_rr > 0 ? g_codes_rr : (int)((ntt * a.NU + 2047) / 2048);
+    auto wgs_of = [&](int r) -> long {
+      long n = ((ntt + r - 1) / r * a.NU + 3) / 4;
+      return n > kScoreMaxWg ? (long)kScoreMaxWg : n;
+    };
+    int rr = g_codes_rr;
+    if (rr <= 0) {
+      // Longest run that still gives every CU two workgroups, among those the one whose workgroups fill the
+      // rounds best: the CU holds floor(160 KiB / LDS) workgroups, three at most (registers), and a last round
+      // that is half empty costs as much as a full one (786432 tokens of H 28/4: 8-tile runs 151 us, 6-tile runs
+      // two full rounds).
+      rr = 1;
+      double best = -1.0;
+      for (int r = 8; r >= 1; --r) {
+        const long n = wgs_of(r);
+        if (r > 1 && n < 512) continue;
+        long per_cu = (long)(163840 / score_codes_mfma_lds_bytes(p->head_dim, G, r));
+        if (per_cu > 3) per_cu = 3;
+        if (per_cu < 1) continue;
+        const long slots = 256 * per_cu, rounds = (n + slots - 1) / slots;
+        const double fill = (double)n / (double)(rounds * slots);
+        if (fill > best + 0.05) { best = fill; rr = r; }
+      }
+    }
     if (rr > 8) rr = 8;
-    if (rr < 1) rr = 1;
     a.RR = rr;
-    long wgl = ((ntt + rr - 1) / rr * a.NU + 3) / 4;
-    if (wgl > kScoreMaxWg) wgl = kScoreMaxWg;
+    long wgl = wgs_of(rr);
     if (g_score_wg > 0) wgl = g_score_wg;
     const hipError_t e = launch_score_codes_mfma(p->head_dim, G, a, dim3((unsigned)wgl, p->batch),
                                                  score_codes_mfma_lds_bytes(p->head_dim, G, rr), (hipStream_t)stream);
