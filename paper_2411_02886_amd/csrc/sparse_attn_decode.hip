@@ -195,41 +195,65 @@ __global__ __launch_bounds__(256) void sparse_attn_decode_kernel(AttnArgs a) {
 }
 
 // Merges the split partials of one (sequence, head): out = sum_s e^{m_s - M} o_s / sum_s e^{m_s - M} l_s.
-// One workgroup of D threads per head; the partial loads of a thread are independent of each other.
+// One workgroup of D x kMergeGroups threads per head: thread (d, g) takes the splits g, g + kMergeGroups, ... (eight at a
+// time, all loads of a thread in flight together: the step is a chain of memory round trips, not bandwidth), the
+// groups' sums meet in LDS.
+constexpr int kMergeGroups = 8;
 template <int DT, int D>
-__global__ __launch_bounds__(D) void sparse_attn_merge_kernel(AttnArgs a) {
+__global__ __launch_bounds__(D * kMergeGroups) void sparse_attn_merge_kernel(AttnArgs a) {
   __shared__ float s_w[kAttnMaxSplit];
-  __shared__ float s_l[kAttnMaxSplit];
-  const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
+  __shared__ float s_red[2 * D * kMergeGroups / 64];
+  __shared__ float s_o[kMergeGroups][D];
+  const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x % D, g = threadIdx.x / D;
   const size_t hb = (size_t)b * a.H + h;
   const float* ml = a.part_ml + hb * a.nsplit * 2;
   const int nb = min(max(a.seq_lens[b], 0), a.max_seq_len);
   const int f_lo = min(a.n_init, nb), f_hi = max(f_lo, nb - a.n_local);
   const int total = f_lo + min(max(a.count[b], 0), a.idx_stride) + (nb - f_hi);
   const int ns = min(a.nsplit, (total + kAttnChunk - 1) / kAttnChunk);   // splits that hold tokens
-  for (int s = d; s < ns; s += D) {
-    const float2 v = *reinterpret_cast<const float2*>(ml + 2 * s);
-    s_w[s] = v.x; s_l[s] = v.y;
-  }
-  __syncthreads();
-  float M = -INFINITY;
-  for (int s = 0; s < ns; ++s) M = fmaxf(M, s_w[s]);
-  float Lsum = 0.f;
-  for (int s = 0; s < ns; ++s) Lsum += expf(s_w[s] - M) * s_l[s];
-  __syncthreads();
-  for (int s = d; s < ns; s += D) s_w[s] = expf(s_w[s] - M);
-  __syncthreads();
-  float o = 0.f;
+  // the partial outputs do not depend on the weights: their loads go out first
   const float* po = a.part_out + hb * a.nsplit * D + d;
-  int s = 0;
-  for (; s + 8 <= ns; s += 8) {
-    float v[8];
+  float v[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = po[(size_t)(s + e) * D];
+  for (int e = 0; e < 8; ++e) { const int s = g + e * kMergeGroups; v[e] = s < ns ? po[(size_t)s * D] : 0.f; }
+  // thread s owns split s (ns <= kAttnMaxSplit <= threads): block maximum, then the weights and their sum
+  constexpr int NT = D * kMergeGroups, NW = NT / 64;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float2 mine = make_float2(-INFINITY, 0.f);
+  if ((int)threadIdx.x < ns) mine = *reinterpret_cast<const float2*>(ml + 2 * threadIdx.x);
+  float M = mine.x;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) o = fmaf(s_w[s + e], v[e], o);
+  for (int off = 32; off > 0; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
+  if (lane == 0) s_red[wave] = M;
+  __syncthreads();
+  M = s_red[0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) M = fmaxf(M, s_red[w]);
+  const float wgt = (int)threadIdx.x < ns ? expf(mine.x - M) : 0.f;
+  if ((int)threadIdx.x < ns) s_w[threadIdx.x] = wgt;
+  float Lsum = wgt * mine.y;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) Lsum += __shfl_xor(Lsum, off);
+  if (lane == 0) s_red[NW + wave] = Lsum;
+  __syncthreads();
+  Lsum = 0.f;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) Lsum += s_red[NW + w];
+  float o = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { const int s = g + e * kMergeGroups; if (s < ns) o = fmaf(s_w[s], v[e], o); }
+  for (int s0 = 8 * kMergeGroups; s0 < ns; s0 += 8 * kMergeGroups) {      // more than 64 splits (k > 4096)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { const int s = s0 + g + e * kMergeGroups; v[e] = s < ns ? po[(size_t)s * D] : 0.f; }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { const int s = s0 + g + e * kMergeGroups; if (s < ns) o = fmaf(s_w[s], v[e], o); }
   }
-  for (; s < ns; ++s) o = fmaf(s_w[s], po[(size_t)s * D], o);
+  s_o[g][d] = o;
+  __syncthreads();
+  if (g != 0) return;
+  o = 0.f;
+#pragma unroll
+  for (int gg = 0; gg < kMergeGroups; ++gg) o += s_o[gg][d];
   const float res = Lsum > 0.f ? o / Lsum : 0.f;
   if (DT == TS_BF16) reinterpret_cast<uint16_t*>(a.out)[hb * D + d] = (uint16_t)f32_to_bf16_bits(res);
   else reinterpret_cast<float*>(a.out)[hb * D + d] = res;
@@ -244,7 +268,7 @@ static hipError_t attn_launch_g(int G, const AttnArgs& a, dim3 grid, hipStream_t
     default: return hipErrorInvalidValue;
   }
 #undef TS_CASE
-  hipLaunchKernelGGL((sparse_attn_merge_kernel<DT, D>), dim3(a.H, grid.z), dim3(D), 0, s, a);
+  hipLaunchKernelGGL((sparse_attn_merge_kernel<DT, D>), dim3(a.H, grid.z), dim3(D * kMergeGroups), 0, s, a);
   return hipGetLastError();
 }
 
