@@ -519,6 +519,14 @@ def main():
         sec = decode_bench(2, args, steps=args.steps, warmup=args.warmup, with_cpu_baseline=False, with_graph=False)
         res["secondary"] = {k: sec[k] for k in ("config", "ms_per_step", "tokens_scanned_per_s", "decode_steps_per_s",
                                                  "selection_ms", "whole_step_roofline", "roofline")}
+        if args.path != "dense" and args.selection == "soft":
+            # at 128K tokens the five-call form (fp32 score matrix in memory) is the faster step although its score
+            # pass is the slower kernel: both on record
+            import copy
+            a2 = copy.copy(args); a2.path = "dense"
+            d2 = decode_bench(2, a2, steps=args.steps, warmup=args.warmup, with_cpu_baseline=False, with_graph=False)
+            res["secondary"]["five_call_form"] = {"ms_per_step": d2["ms_per_step"], "score_pass_frac": d2["roofline"]["frac"],
+                                                  "score_pass_ms": d2["roofline"]["avg_launch_ms"]}
     print(json.dumps(res))
 
 
