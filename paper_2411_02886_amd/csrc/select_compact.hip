@@ -139,6 +139,8 @@ hipError_t launch_vote_bounds(const BoundArgs& a, int B, hipStream_t s) {
   int tpw = (a.max_seq_len + 1023) / 1024;
   if (tpw < 256) tpw = 256;
   tpw = (tpw + 255) / 256 * 256;
+  // the table of block factors has to fit beside 11 KiB of static LDS without asking for more than the default 64 KiB
+  while (tpw > 256 && (size_t)(tpw / kScoreTileTokens + 1) * a.H * sizeof(float) > 49152) tpw -= 256;
   const int nwg = (a.max_seq_len + tpw - 1) / tpw;
   const size_t lds = (size_t)(tpw / kScoreTileTokens + 1) * a.H * sizeof(float);
   const dim3 grid(nwg, B);

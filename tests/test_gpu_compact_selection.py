@@ -437,3 +437,35 @@ def test_compact_selection_cache_run_and_graph_replay(gpu):
         g.replay(); torch.cuda.synchronize()
         assert np.array_equal(to_host(idx_log), idx_e) and np.array_equal(to_host(reuse_log), reuse_e), ("graph replay", rep)
         _ = (layer.votes * 2).sum().item()                   # eager work between the replays
+
+
+@pytest.mark.parametrize("N,H,H_kv,D,k", [(3_900_000, 128, 16, 64, 1024), (16_000_000, 8, 2, 64, 4096)])
+def test_long_sequences_both_forms_agree(gpu, N, H, H_kv, D, k):
+    """Sizes no oracle run covers (K generated on the GPU): 3.9M tokens with 128 heads, where the vote-bounds kernel has to
+    shorten its workgroups' token range to keep its table in LDS, and 16M tokens, the longest the finishing workgroup
+    indexes.  Properties: the compact form selects the five-call form's tokens, its bounds contain the five-call votes."""
+    from paper_2411_02886_amd.runtime import DecodeLayer, to_host
+    dev = "cuda:0"
+    g = torch.Generator(device=dev); g.manual_seed(5)
+    P = 16
+    npages = (N + P - 1) // P
+    kp = torch.randn((npages, P, H_kv, D), device=dev, dtype=torch.bfloat16, generator=g).view(torch.int16)
+    vp = torch.randn((npages, P, H_kv, D), device=dev, dtype=torch.bfloat16, generator=g).view(torch.int16)
+    perm = np.random.default_rng(1).permutation(npages).astype(np.int32)
+    layer = DecodeLayer(dtype=gpu.TS_BF16, H=H, H_kv=H_kv, D=D, P=P, k=k, k_pool=kp, v_pool=vp, page_indptr=[0, npages],
+                        page_indices=perm, seq_lens=[N], device=dev)
+    q = torch.randn((1, 1, H, D), device=dev, dtype=torch.bfloat16, generator=g).view(torch.int16)
+    print("long sequence", N, H, H_kv, D, "five-call form", flush=True)
+    layer.select(q, 1.0, None); torch.cuda.synchronize()
+    idx_d = to_host(layer.idx).copy(); v = to_host(layer.votes)[0, :N]
+    print("long sequence", N, "compact form", flush=True)
+    layer.idx.fill_(-5); layer.select_compact(q, 1.0, None); torch.cuda.synchronize()
+    idx_c = to_host(layer.idx)
+    assert int(to_host(layer.count)[0]) == k
+    kth = np.sort(v)[::-1][k - 1]
+    for t in np.setxor1d(idx_d[0], idx_c[0]):
+        assert abs(v[t] - kth) / kth <= 1e-5, ("forms differ away from the k-th vote", int(t))
+    vh = to_host(layer.vote_hi)[0, :N]; vl = to_host(layer.vote_lo)[0, :N]
+    assert np.all(vl <= v) and np.all(v <= vh)
+    del layer, kp, vp
+    torch.cuda.empty_cache()
