@@ -321,3 +321,55 @@ def test_config5_full_size_against_the_oracles_selection(gpu):
         assert t in band, ("token differs far from the k-th vote", t)
         assert abs(band[t] - kth) / kth <= 1e-6, ("token differs outside the 1e-6 band", t, abs(band[t] - kth) / kth)
     print("cfg5: index set identical to the oracle's except %d tokens inside the 1e-6 band" % len(diff), flush=True)
+
+
+@pytest.mark.parametrize("name,C,H,H_kv,D,P,lens,k,ni,nl,scale", [
+    ("512 queries x 1M cached", 512, 32, 8, 128, 16, [1_048_576 + 512], 4096, 0, 0, 1.0),
+    ("100 queries, G 7", 100, 28, 4, 128, 16, [300_100], 2048, 0, 0, 1.0),
+    ("33 queries, G 1, D 64", 33, 16, 16, 64, 16, [50_033], 512, 0, 0, 1.0),
+    ("1024 queries, forced tokens", 1024, 32, 8, 128, 16, [200_000], 4096, 128, 512, 1.0),
+    ("batch of 3, ragged", 256, 32, 8, 128, 16, [70_000, 300, 12_345], 1024, 0, 0, 1.0),
+    ("page size 1", 128, 32, 8, 64, 1, [40_128], 512, 0, 0, 1.0),
+    ("G 3, 2 queries, scale 1/sqrt(D)", 2, 24, 8, 128, 16, [10_002], 100, 0, 0, 1.0 / math.sqrt(128)),
+])
+def test_chunk_selection_invariants_at_sizes_no_oracle_run_covers(gpu, name, C, H, H_kv, D, P, lens, k, ni, nl, scale):
+    """Properties that hold at any size (inputs generated on the GPU): every softmax row sums to one, so the votes of the
+    ranked range sum to C * H -- which also ties the two sweeps together, the second normalises with the first's
+    log-sum-exps; count = min(k, ranked tokens); indices ascending, inside the ranked range, none below the k-th vote."""
+    from paper_2411_02886_amd.runtime import ChunkSelector, to_host
+    dev = "cuda:0"
+    g = torch.Generator(device=dev); g.manual_seed(9)
+    B = len(lens)
+    pages = [(n + P - 1) // P for n in lens]
+    npages = sum(pages) + 3
+    kp = torch.randn((npages, P, H_kv, D), device=dev, dtype=torch.bfloat16, generator=g).view(torch.int16)
+    vp = torch.randn((npages, P, H_kv, D), device=dev, dtype=torch.bfloat16, generator=g).view(torch.int16)
+    q = torch.randn((B, C, H, D), device=dev, dtype=torch.bfloat16, generator=g).view(torch.int16)
+    perm = np.random.default_rng(1).permutation(npages).astype(np.int32)[: sum(pages)]
+    indptr = np.concatenate([[0], np.cumsum(pages)]).astype(np.int32)
+    print("chunk invariants:", name, flush=True)
+    sel = ChunkSelector(C=C, H=H, H_kv=H_kv, D=D, P=P, k=k, k_pool=kp, v_pool=vp, page_indptr=indptr, page_indices=perm,
+                        seq_lens=lens, device=dev, num_initial=ni, num_local=nl)
+    sel.select(q, scale)
+    torch.cuda.synchronize()
+    v = to_host(sel.votes); idx = to_host(sel.idx); cnt = to_host(sel.count)
+    for b in range(B):
+        Nc = max(lens[b] - C, 0)
+        lo = min(ni, Nc); hi = max(lo, Nc - nl)
+        c = int(cnt[b])
+        assert c == min(k, hi - lo), (name, b, c)
+        want = float(C * H) if hi > lo else 0.0
+        tot = float(v[b, lo:hi].astype(np.float64).sum())
+        assert abs(tot - want) <= 2e-5 * max(want, 1.0), (name, b, tot, want)
+        assert np.all(np.diff(idx[b, :c]) > 0) and np.all(idx[b, c:] == -1), (name, b)
+        if c > 0:
+            assert idx[b, 0] >= lo and idx[b, c - 1] < hi, (name, b)
+        if 0 < c < hi - lo:
+            kth = np.sort(v[b, lo:hi])[::-1][c - 1]
+            assert v[b, idx[b, :c]].min() >= kth, (name, b, "a selected token lies below the k-th vote")
+    sel.attend(q)
+    torch.cuda.synchronize()
+    o = (to_host(sel.out).view(np.uint16).astype(np.uint32) << 16).view(np.float32)
+    assert np.isfinite(o).all(), (name, "attention")
+    del sel, kp, vp
+    torch.cuda.empty_cache()
