@@ -269,7 +269,7 @@ int32_t ts_paged_qk_codes(const ts_problem* p, const void* q, uint8_t* codes, fl
       // two full rounds).
       rr = 1;
       double best = -1.0;
-      for (int r = 8; r >= 1; --r) {
+      for (int r = 8; r >= 1; r -= (r > 2 ? 2 : 1)) {     // 8, 6, 4, 2, 1: odd run lengths measured slower throughout
         const long n = wgs_of(r);
         if (r > 1 && n < 512) continue;
         long per_cu = (long)(163840 / score_codes_mfma_lds_bytes(p->head_dim, G, r));
