@@ -189,13 +189,31 @@ __device__ __forceinline__ uint32_t refine_find_bin(const uint32_t* gh, uint32_t
   constexpr int PER = kTopkBins / kRefineThreads;
   uint32_t c[PER];
   uint32_t sum = 0;
+  // the thread's PER bins are consecutive in memory (descending bin order = ascending address from `lowest`): vector loads
+  const int lowest = kTopkBins - PER - (int)threadIdx.x * PER;
 #pragma unroll
-  for (int e = 0; e < PER; ++e) {
-    uint32_t x = 0;
+  for (int e = 0; e < PER; ++e) c[e] = 0u;
 #pragma unroll
-    for (int r = 0; r < kBoundHistCopies; ++r) x += gh[r * kTopkBins + kTopkBins - 1 - (threadIdx.x * PER + e)];
-    c[e] = x; sum += x;
+  for (int r = 0; r < kBoundHistCopies; ++r) {
+    uint32_t v[PER];
+    if (PER % 4 == 0) {
+#pragma unroll
+      for (int q4 = 0; q4 < PER / 4; ++q4) {
+        const uint4 w = *reinterpret_cast<const uint4*>(gh + r * kTopkBins + lowest + q4 * 4);
+        v[q4 * 4] = w.x; v[q4 * 4 + 1] = w.y; v[q4 * 4 + 2] = w.z; v[q4 * 4 + 3] = w.w;
+      }
+    } else {
+#pragma unroll
+      for (int q2 = 0; q2 < PER / 2; ++q2) {
+        const uint2 w = *reinterpret_cast<const uint2*>(gh + r * kTopkBins + lowest + q2 * 2);
+        v[q2 * 2] = w.x; v[q2 * 2 + 1] = w.y;
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < PER; ++e) c[e] += v[PER - 1 - e];     // c[e] is bin kTopkBins - 1 - (threadIdx.x * PER + e)
   }
+#pragma unroll
+  for (int e = 0; e < PER; ++e) sum += c[e];
   uint32_t total;
   uint32_t above = refine_block_scan<kRefineWaves>(sum, &total, lds);
   __syncthreads();
