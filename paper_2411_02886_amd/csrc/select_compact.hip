@@ -307,10 +307,25 @@ __global__ __launch_bounds__(kRefineThreads) void topk_refine_kernel(RefineArgs 
   const float* v = ta.votes + (size_t)b * ta.max_seq_len;
   uint32_t key[PER];
   bool valid[PER];
+  if (PER % 4 == 0 && ((reinterpret_cast<uintptr_t>(v) & 15) == 0) && base + kTopkChunk <= ta.max_seq_len) {
+    // the usual case: the chunk's upper bounds as 16-byte loads (the row exists up to max_seq_len)
 #pragma unroll
-  for (int e = 0; e < PER; ++e) {
-    valid[e] = (t0 + e) >= LO && (t0 + e) < N;
-    key[e] = valid[e] ? float_key(v[t0 + e]) : 0u;
+    for (int q4 = 0; q4 < PER / 4; ++q4) {
+      const float4 w = *reinterpret_cast<const float4*>(v + t0 + q4 * 4);
+      const float x[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int e = q4 * 4 + i;
+        valid[e] = (t0 + e) >= LO && (t0 + e) < N;
+        key[e] = valid[e] ? float_key(x[i]) : 0u;
+      }
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+      valid[e] = (t0 + e) >= LO && (t0 + e) < N;
+      key[e] = valid[e] ? float_key(v[t0 + e]) : 0u;
+    }
   }
   if (threadIdx.x < H) {
     const float2 st = *reinterpret_cast<const float2*>(a.row_stats + ((size_t)b * H + threadIdx.x) * 2);

@@ -402,8 +402,8 @@ __global__ __launch_bounds__(kFinalThreads) void topk_final_kernel(TopkArgs a) {
     if (tid == 0) a.count[b] = k_eff;
   }
   if (FULL) {  // the replicated histogram of the lower bounds has been consumed by the refine pass: zero it again
-    uint32_t* g0 = a.bound_hist + (size_t)b * kBoundHistCopies * kTopkBins;
-    for (int i = tid; i < kBoundHistCopies * kTopkBins; i += kFinalThreads) g0[i] = 0u;
+    uint4* g0 = reinterpret_cast<uint4*>(a.bound_hist + (size_t)b * kBoundHistCopies * kTopkBins);   // 256-byte aligned section
+    for (int i = tid; i < kBoundHistCopies * kTopkBins / 4; i += kFinalThreads) g0[i] = make_uint4(0u, 0u, 0u, 0u);
   } else {     // histogram 0 has been consumed by the compact pass: leave it zeroed for the next call
     uint32_t* g0 = a.hist + ((size_t)b * 3 + 0) * kTopkBins;
     for (int i = tid; i < kTopkBins; i += kFinalThreads) g0[i] = 0u;
