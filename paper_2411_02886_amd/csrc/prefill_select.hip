@@ -300,19 +300,33 @@ __global__ __launch_bounds__(256, 2) void prefill_qk_kernel(PrefillArgs a) {
   }
 }
 
-// row_stats[b][c][h] = log2 sum_t exp2(c2 * s_t) as a (high, low) float pair, from the splits' partials
+// row_stats[b][c][h] = log2 sum_t exp2(c2 * s_t) as a (high, low) float pair, from the splits' partials.
+// 32 lanes per row, one split each (two when there are more than 32 splits): the partials of a row are a
+// strided gather, so they should all be in flight at once.
 __global__ __launch_bounds__(256) void prefill_stats_merge_kernel(PrefillArgs a) {
-  const int i = blockIdx.x * 256 + threadIdx.x;          // (b, c, h) flattened
+  const int lane32 = threadIdx.x & 31;
+  const int i = blockIdx.x * 8 + (threadIdx.x >> 5);     // (b, c, h) flattened; eight rows per workgroup
   const int n = a.B * a.C * a.H;
-  if (i >= n) return;
-  const int b = i / (a.C * a.H), ch = i % (a.C * a.H);
-  float m = -INFINITY;
-  for (int s = 0; s < a.TS; ++s) m = fmaxf(m, a.stat_part[(((size_t)b * a.TS + s) * a.C * a.H + ch) * 2]);
-  double l = 0.0;
-  for (int s = 0; s < a.TS; ++s) {
-    const float2 v = *reinterpret_cast<const float2*>(a.stat_part + (((size_t)b * a.TS + s) * a.C * a.H + ch) * 2);
-    if (v.x != -INFINITY) l += (double)v.y * exp_f64(0.69314718055994530942 * ((double)v.x - (double)m));
+  const bool row_ok = i < n;
+  const int ic = row_ok ? i : n - 1;
+  const int b = ic / (a.C * a.H), ch = ic % (a.C * a.H);
+  float2 v[2];
+#pragma unroll
+  for (int e = 0; e < 2; ++e) {
+    const int sp = lane32 + 32 * e;
+    v[e] = make_float2(-INFINITY, 0.f);
+    if (sp < a.TS) v[e] = *reinterpret_cast<const float2*>(a.stat_part + (((size_t)b * a.TS + sp) * a.C * a.H + ch) * 2);
   }
+  float m = fmaxf(v[0].x, v[1].x);
+#pragma unroll
+  for (int o = 1; o < 32; o <<= 1) m = fmaxf(m, __shfl_xor(m, o));
+  double l = 0.0;
+#pragma unroll
+  for (int e = 0; e < 2; ++e)
+    if (v[e].x != -INFINITY) l += (double)v[e].y * exp_f64(0.69314718055994530942 * ((double)v[e].x - (double)m));
+#pragma unroll
+  for (int o = 1; o < 32; o <<= 1) l += __shfl_xor(l, o);
+  if (!row_ok || lane32 != 0) return;
   const double lse2 = (m == -INFINITY) ? -INFINITY : (double)m + log2(l);
   const float hi = (float)lse2;
   a.row_stats_out[(size_t)i * 2] = hi;
@@ -347,7 +361,7 @@ hipError_t launch_prefill_stats(const PrefillArgs& a, hipStream_t s) {
   const int grid = (groups + 7) / 8 * 8 * a.RB;
   if (a.D == 128) hipLaunchKernelGGL((prefill_qk_kernel<128, 1>), dim3(grid), dim3(256), 0, s, a);
   else hipLaunchKernelGGL((prefill_qk_kernel<64, 1>), dim3(grid), dim3(256), 0, s, a);
-  hipLaunchKernelGGL(prefill_stats_merge_kernel, dim3((a.B * a.C * a.H + 255) / 256), dim3(256), 0, s, a);
+  hipLaunchKernelGGL(prefill_stats_merge_kernel, dim3((a.B * a.C * a.H + 7) / 8), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 
