@@ -44,8 +44,8 @@ MEASURED_TRAFFIC_BYTES = {(4, "compact"): int((512.25 * 1.966 + 31.72 * 1.00) * 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4, 5],
                     help="4 (default) is the headline workload, the largest single-GPU configuration (1 Mi tokens), with "
                          "configuration 2 (131072 tokens) carried as `secondary`; 3 is the Selection Cache decode run; 5 is chunked prefill")
