@@ -364,6 +364,8 @@ __global__ __launch_bounds__(kRefineThreads) void topk_refine_kernel(RefineArgs 
   const double c2d = (double)a.scale * 1.44269504088896340736;
   uint2* list = ta.list + ((size_t)b * ta.nblk + blockIdx.x) * kTopkChunk;
   for (int g0 = wave; g0 < ngroups; g0 += kRefineWaves * UB) {   // group uu of this round: g0 + uu * kRefineWaves
+    // groups of this round that exist (the same for the whole wave): the others cost neither loads nor arithmetic
+    const int nact = min(UB, (ngroups - g0 + kRefineWaves - 1) / kRefineWaves);
     double vote[UB];
 #pragma unroll
     for (int uu = 0; uu < UB; ++uu) vote[uu] = 0.0;
@@ -372,6 +374,7 @@ __global__ __launch_bounds__(kRefineThreads) void topk_refine_kernel(RefineArgs 
       uint4 kr[UB][L];
 #pragma unroll
       for (int uu = 0; uu < UB; ++uu) {
+        if (uu >= nact) continue;
         const int ci = min(((g0 + uu * kRefineWaves) << tps_shift) + tis, (int)total - 1);
         const int t = ctok[ci], pid = cpid[ci];
         const uint8_t* kp = a.k_pool + (((size_t)pid << a.p_shift) + (size_t)(t & (a.P - 1))) * ((size_t)a.H_kv * RB) +
@@ -389,6 +392,7 @@ __global__ __launch_bounds__(kRefineThreads) void topk_refine_kernel(RefineArgs 
         for (int i = 0; i < L; ++i) qv[i] = q_lds[((kvh * G + g) * RB + i * 128 + j * 16) >> 4];
 #pragma unroll
         for (int uu = 0; uu < UB; ++uu) {
+          if (uu >= nact) continue;
           double pc[L];                           // independent chains, summed at the end
 #pragma unroll
           for (int i = 0; i < L; ++i) pc[i] = piece_dot_f64<DT>(kr[uu][i], qv[i], 0.0);
@@ -401,6 +405,7 @@ __global__ __launch_bounds__(kRefineThreads) void topk_refine_kernel(RefineArgs 
       }
 #pragma unroll
       for (int uu = 0; uu < UB; ++uu) {
+        if (uu >= nact) continue;
         const double sv = svv[uu];
         const int hh = min(kvh * G + j, H - 1);
         double term = (j < G) ? (double)refine_vote_exp(sv - s_m[hh], c2d) * s_inv[hh] : 0.0;
