@@ -331,8 +331,16 @@ __global__ __launch_bounds__(kRefineThreads) void topk_refine_kernel(RefineArgs 
     const float2 st = *reinterpret_cast<const float2*>(a.row_stats + ((size_t)b * H + threadIdx.x) * 2);
     s_m[threadIdx.x] = (double)st.x; s_inv[threadIdx.x] = 1.0 / (double)st.y;
   }
-  for (int i = threadIdx.x; i < H * (RB / 16); i += kRefineThreads)
-    q_lds[i] = reinterpret_cast<const uint4*>(a.q + (size_t)b * H * RB)[i];
+  // the sequence's query goes to LDS as floats ([H][D]): a product then costs one conversion and one double fma
+  for (int i = threadIdx.x; i < H * (RB / 16); i += kRefineThreads) {
+    const uint4 w = reinterpret_cast<const uint4*>(a.q + (size_t)b * H * RB)[i];
+    if (DT == TS_BF16) {
+      q_lds[2 * i] = make_uint4(w.x << 16, w.x & 0xffff0000u, w.y << 16, w.y & 0xffff0000u);
+      q_lds[2 * i + 1] = make_uint4(w.z << 16, w.z & 0xffff0000u, w.w << 16, w.w & 0xffff0000u);
+    } else {
+      q_lds[i] = w;
+    }
+  }
   const uint32_t d0 = refine_find_bin<kRefineWaves>(ta.bound_hist + (size_t)b * kBoundHistCopies * kTopkBins, k_eff, lds);
 
   if (blockIdx.x == 0 && threadIdx.x == 0) ta.state[b * 8 + ST_KEFF_WORD] = k_eff;
@@ -385,17 +393,38 @@ __global__ __launch_bounds__(kRefineThreads) void topk_refine_kernel(RefineArgs 
       double svv[UB];
 #pragma unroll
       for (int uu = 0; uu < UB; ++uu) svv[uu] = 0.0;
+      constexpr int EPP = 16 / ES;               // elements per 16-byte piece of K
+#pragma unroll
+      for (int uu = 0; uu < UB; ++uu) {
+        if (uu >= nact) continue;
+        // the candidate's K pieces as doubles, once for all G query heads of the row's KV head
+        double kd[L][EPP];
+#pragma unroll
+        for (int i = 0; i < L; ++i) {
+          const uint4 k4 = kr[uu][i];
+          if (DT == TS_BF16) {
+            kd[i][0] = (double)bf16_lo(k4.x); kd[i][1] = (double)bf16_hi(k4.x); kd[i][2] = (double)bf16_lo(k4.y); kd[i][3] = (double)bf16_hi(k4.y);
+            kd[i][4 % EPP] = (double)bf16_lo(k4.z); kd[i][5 % EPP] = (double)bf16_hi(k4.z); kd[i][6 % EPP] = (double)bf16_lo(k4.w); kd[i][7 % EPP] = (double)bf16_hi(k4.w);
+          } else {
+            kd[i][0] = (double)__uint_as_float(k4.x); kd[i][1] = (double)__uint_as_float(k4.y);
+            kd[i][2] = (double)__uint_as_float(k4.z); kd[i][3] = (double)__uint_as_float(k4.w);
+          }
+        }
 #pragma unroll 1
-      for (int g = 0; g < G; ++g) {             // one query head at a time: its pieces come from LDS
-        uint4 qv[L];
+        for (int g = 0; g < G; ++g) {           // one query head at a time: its elements come from LDS as floats
+          const float* qf = reinterpret_cast<const float*>(q_lds) + (size_t)(kvh * G + g) * D + j * EPP;
+          double pc[L];                          // independent chains (products of two floats are exact in double)
 #pragma unroll
-        for (int i = 0; i < L; ++i) qv[i] = q_lds[((kvh * G + g) * RB + i * 128 + j * 16) >> 4];
+          for (int i = 0; i < L; ++i) {
+            double acc = 0.0;
 #pragma unroll
-        for (int uu = 0; uu < UB; ++uu) {
-          if (uu >= nact) continue;
-          double pc[L];                           // independent chains, summed at the end
-#pragma unroll
-          for (int i = 0; i < L; ++i) pc[i] = piece_dot_f64<DT>(kr[uu][i], qv[i], 0.0);
+            for (int e4 = 0; e4 < EPP / 4; ++e4) {
+              const float4 q4 = *reinterpret_cast<const float4*>(qf + i * (128 / ES) + e4 * 4);
+              acc = fma(kd[i][e4 * 4], (double)q4.x, acc); acc = fma(kd[i][e4 * 4 + 1], (double)q4.y, acc);
+              acc = fma(kd[i][e4 * 4 + 2], (double)q4.z, acc); acc = fma(kd[i][e4 * 4 + 3], (double)q4.w, acc);
+            }
+            pc[i] = acc;
+          }
           double sc = pc[0];
 #pragma unroll
           for (int i = 1; i < L; ++i) sc += pc[i];
@@ -425,7 +454,7 @@ __global__ __launch_bounds__(kRefineThreads) void topk_refine_kernel(RefineArgs 
 
 template <int DT, int D, int GG, int NT>
 static hipError_t refine_launch(const RefineArgs& a, dim3 grid, hipStream_t s) {
-  const size_t lds = (size_t)a.H * D * Elt<DT>::size;     // the query in LDS (next to about 19 KiB of static LDS)
+  const size_t lds = (size_t)a.H * D * sizeof(float);     // the query as floats in LDS (next to about 19 KiB of static LDS)
   if (lds > 40960) {
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&topk_refine_kernel<DT, D, GG, NT>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
