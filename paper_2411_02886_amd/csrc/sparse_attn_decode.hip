@@ -39,7 +39,7 @@ __global__ __launch_bounds__(256) void sparse_attn_decode_kernel(AttnArgs a) {
   constexpr int VS = WT / RPL;         // V loads per lane
   __shared__ long long s_slot[CH];
   __shared__ float s_p[G][CH];
-  __shared__ float s_red[4][G][D];
+  __shared__ __attribute__((aligned(16))) float s_red[4 * (64 / (D * AElt<DT>::size / 16))][G][D];   // [wave x row group][head][d]
   __shared__ float s_ml[G][2];
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -169,23 +169,20 @@ __global__ __launch_bounds__(256) void sparse_attn_decode_kernel(AttnArgs a) {
       for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(p, vf[e], acc[g][e]);
     }
   }
-  // lanes with the same piece but different rsub hold partial sums of the same outputs
+  // lanes with the same piece but different rsub hold partial sums of the same outputs: all of them go to LDS (16-byte
+  // stores) and meet there -- a cross-lane exchange of the G * EPL accumulators costs more LDS operations than that
 #pragma unroll
-  for (int off = LPR; off < 64; off <<= 1)
+  for (int g = 0; g < G; ++g)
 #pragma unroll
-    for (int g = 0; g < G; ++g)
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) acc[g][e] += __shfl_xor(acc[g][e], off);
-  if (rsub == 0) {
-#pragma unroll
-    for (int g = 0; g < G; ++g)
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) s_red[wave][g][piece * EPL + e] = acc[g][e];
-  }
+    for (int e4 = 0; e4 < EPL / 4; ++e4)
+      *reinterpret_cast<float4*>(&s_red[wave * RPL + rsub][g][piece * EPL + e4 * 4]) =
+          make_float4(acc[g][e4 * 4], acc[g][e4 * 4 + 1], acc[g][e4 * 4 + 2], acc[g][e4 * 4 + 3]);
   __syncthreads();
   for (int i = threadIdx.x; i < G * D; i += 256) {
     const int g = i / D, d = i % D;
-    const float o = s_red[0][g][d] + s_red[1][g][d] + s_red[2][g][d] + s_red[3][g][d];
+    float o = 0.f;
+#pragma unroll
+    for (int r4 = 0; r4 < 4 * RPL; ++r4) o += s_red[r4][g][d];
     a.part_out[(((size_t)b * H + kvh * G + g) * a.nsplit + split) * D + d] = o;
   }
   if (threadIdx.x < G) {
