@@ -130,24 +130,24 @@ __global__ __launch_bounds__(256) void sparse_attn_decode_kernel(AttnArgs a) {
   }
   __syncthreads();
 
-  // ---- local softmax: wave w normalises heads w, w+4, ...; CH / 64 tokens per lane
-  for (int g = wave; g < G; g += 4) {
-    float x[CH / 64];
+  // ---- local softmax: eight lanes per head, eight tokens per lane, the lanes of a head meet through DPP
+  if (threadIdx.x < G * 8) {
+    constexpr int TPL = CH / 8;                  // tokens per lane
+    const int g = threadIdx.x >> 3, part = threadIdx.x & 7;
+    float x[TPL];
     float m = -INFINITY;
 #pragma unroll
-    for (int e = 0; e < CH / 64; ++e) { x[e] = s_p[g][lane + 64 * e]; m = fmaxf(m, x[e]); }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+    for (int e = 0; e < TPL; ++e) { x[e] = s_p[g][part + 8 * e]; m = fmaxf(m, x[e]); }
+    m = group8_max(m);
     float l = 0.f;
 #pragma unroll
-    for (int e = 0; e < CH / 64; ++e) {
+    for (int e = 0; e < TPL; ++e) {
       const float p = (x[e] == -INFINITY) ? 0.f : expf(x[e] - m);
-      s_p[g][lane + 64 * e] = p;
+      s_p[g][part + 8 * e] = p;
       l += p;
     }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) l += __shfl_xor(l, off);
-    if (lane == 0) { s_ml[g][0] = m; s_ml[g][1] = l; }
+    l = group8_sum(l);
+    if (part == 0) { s_ml[g][0] = m; s_ml[g][1] = l; }
   }
   __syncthreads();
 
