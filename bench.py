@@ -115,19 +115,27 @@ def selection_cache_run(args):
         pos = int(w.seq_lens[b]) + np.arange(steps)
         slots[:, b] = w.pages_of(b).astype(np.int64)[pos // w.P] * w.P + pos % w.P
     slots_d = torch.from_numpy(slots).to(dev)
-    kflat = layer.k_pool.view(-1, w.H_kv, w.D); vflat = layer.v_pool.view(-1, w.H_kv, w.D)
-    len0 = layer.seq_lens.clone()
+    # K and V pools as the two halves of one tensor, so that a step's new K/V rows go in with one launch
+    kv = torch.stack([layer.k_pool, layer.v_pool])
+    layer.swap_pool(kv[0], kv[1])
+    kvflat = kv.view(2, -1, w.H_kv, w.D)
+    kvsd = torch.stack([ksd, vsd], dim=1).contiguous()          # [steps][2][B][H_kv][D]
+    del ksd, vsd
+    # the lengths of every step are inputs of the run (a scheduler knows them): one ts_problem per step points at its row
+    lens_all = (layer.seq_lens[None, :] + 1 + torch.arange(steps, device=dev, dtype=torch.int32)[:, None]).contiguous()
+    problems = []
+    for t in range(steps):
+        layer.seq_lens = lens_all[t]; layer._make_problem(); problems.append(layer.problem)
     sm, theta, scale = 1.0 / math.sqrt(w.D), args.theta, 1.0
     compact = args.path == "compact"                           # default here: the five-call form
     reuse_log = torch.zeros((steps, w.B), dtype=torch.uint8, device=dev)
 
     def run(theta=theta):
-        layer.seq_lens.copy_(len0); layer.first.fill_(1)
+        layer.first.fill_(1)
         for t in range(steps):
-            kflat.index_copy_(0, slots_d[t], ksd[t]); vflat.index_copy_(0, slots_d[t], vsd[t])   # append this step's K/V rows
-            layer.seq_lens.add_(1)
+            kvflat.index_copy_(1, slots_d[t], kvsd[t])          # append this step's K/V rows
+            layer.problem, layer.reuse = problems[t], reuse_log[t]   # the step's lengths; its reuse flags go straight to the log
             layer.step(qs[t], theta=theta, score_scale=scale, sm_scale=sm, compact=compact)
-            reuse_log[t].copy_(layer.reuse)
 
     run(); torch.cuda.synchronize()
     reps = max(1, args.steps // steps)
@@ -137,7 +145,7 @@ def selection_cache_run(args):
     torch.cuda.synchronize()
     dt_eager = (time.perf_counter() - t0) / reps
     reuse_eager = to_host(reuse_log).copy(); idx_eager = to_host(layer.idx).copy(); out_eager = to_host(layer.out).copy()
-    # The 64-step run is launch-bound on the host (14 launches per step), so it is also captured once as a HIP
+    # The 64-step run is launch-bound on the host (11 launches per step), so it is also captured once as a HIP
     # graph (every hit/miss decision is taken on the device, nothing in it depends on the host) and replayed.
     dt, mode = dt_eager, "eager"
     if not args.no_graph:
@@ -181,7 +189,7 @@ def selection_cache_run(args):
            "tokens_scanned_per_s": scanned / dt,
            "execution": mode, "eager_batch_steps_per_s": steps / dt_eager,
            "selection_form": "compact (no score matrix in memory)" if compact else "five calls (fp32 score matrix)",
-           "note": ("%d library launches + 4 torch launches per step; " % (8 if compact else 10)) +
+           "note": ("%d library launches + 1 torch launch (the append of the step's K/V rows) per step; " % (8 if compact else 10)) +
                    "'graph' = the whole 64-step run captured once as a HIP graph "
                    "and replayed (replays checked against the eager run), 'eager' = host-driven loop"}
     if args.theta_sweep:
