@@ -189,7 +189,7 @@ def selection_cache_run(args):
            "tokens_scanned_per_s": scanned / dt,
            "execution": mode, "eager_batch_steps_per_s": steps / dt_eager,
            "selection_form": "compact (no score matrix in memory)" if compact else "five calls (fp32 score matrix)",
-           "note": ("%d library launches + 1 torch launch (the append of the step's K/V rows) per step; " % (8 if compact else 10)) +
+           "note": ("%d library launches + 1 torch launch (the append of the step's K/V rows) per step; " % (8 if compact else 9)) +
                    "'graph' = the whole 64-step run captured once as a HIP graph "
                    "and replayed (replays checked against the eager run), 'eager' = host-driven loop"}
     if args.theta_sweep:
@@ -467,7 +467,7 @@ def decode_bench(cfg, args, *, steps, warmup, with_cpu_baseline, with_graph):
                                           "head": "Eq. 4 head vote"}[args.selection],
                    "selection_form": ("compact: ts_paged_qk_codes + ts_soft_vote_bounds + ts_topk_exact (no score matrix in memory)"
                                       if compact else "five calls: ts_paged_qk_scores + ts_soft_vote + ts_topk (fp32 score matrix)")},
-        "launches_per_step": 8 if compact else 10,
+        "launches_per_step": 8 if compact else 9,
         "planted_token_quality": quality,
         "compact_vs_five_call_index_overlap": dense_agrees,
         "hip_graph_replay": graph_info,
