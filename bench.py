@@ -66,9 +66,15 @@ def parse():
     ap.add_argument("--page-size", type=int, default=16, help="tokens per page (16 in the configurations; 1 is the paper's own setting)")
     ap.add_argument("--selection", choices=["soft", "sum", "head"], default="soft",
                     help="selection function: soft = Eq. 5 (the method, default), sum = Eq. 3, head = Eq. 4 (ablation baselines)")
+    ap.add_argument("--check", choices=["fused", "call"], default=None,
+                    help="Selection Cache test: inside the score launch (fused) or as the ts_selcache_check call before it "
+                         "(default: fused, except for the batch of config 3, where the call is the faster form)")
     ap.add_argument("--n-init", type=int, default=0, help="forced initial tokens (the paper's runs use 128); default 0 as in the configurations")
     ap.add_argument("--n-local", type=int, default=0, help="forced most recent tokens (the paper's runs use 512); default 0")
-    return ap.parse_args()
+    args = ap.parse_args()
+    if args.check is None:
+        args.check = "call" if args.config == 3 else "fused"
+    return args
 
 
 def cpu_baseline(w, budget_s=12.0, n_init=0, n_local=0):
@@ -135,7 +141,7 @@ def selection_cache_run(args):
         for t in range(steps):
             kvflat.index_copy_(1, slots_d[t], kvsd[t])          # append this step's K/V rows
             layer.problem, layer.reuse = problems[t], reuse_log[t]   # the step's lengths; its reuse flags go straight to the log
-            layer.step(qs[t], theta=theta, score_scale=scale, sm_scale=sm, compact=compact)
+            layer.step(qs[t], theta=theta, score_scale=scale, sm_scale=sm, compact=compact, fused_check=args.check == "fused")
 
     run(); torch.cuda.synchronize()
     reps = max(1, args.steps // steps)
@@ -189,7 +195,9 @@ def selection_cache_run(args):
            "tokens_scanned_per_s": scanned / dt,
            "execution": mode, "eager_batch_steps_per_s": steps / dt_eager,
            "selection_form": "compact (no score matrix in memory)" if compact else "five calls (fp32 score matrix)",
-           "note": ("%d library launches + 1 torch launch (the append of the step's K/V rows) per step; " % (8 if compact else 9)) +
+           "selection_cache_check": "inside the score launch" if args.check == "fused" else "ts_selcache_check before the score launch",
+           "note": ("%d library launches + 1 torch launch (the append of the step's K/V rows) per step; " %
+                    ((8 if compact else 9) - (1 if args.check == "fused" else 0))) +
                    "'graph' = the whole 64-step run captured once as a HIP graph "
                    "and replayed (replays checked against the eager run), 'eager' = host-driven loop"}
     if args.theta_sweep:
@@ -325,8 +333,17 @@ def decode_bench(cfg, args, *, steps, warmup, with_cpu_baseline, with_graph):
         layer.vote_hi = torch.empty((w.B, layer.max_seq_len), dtype=torch.float32, device=dev)
         layer.vote_lo = torch.empty((w.B, layer.max_seq_len), dtype=torch.float32, device=dev)
 
+    fused_check = args.check == "fused"       # Algorithm 1's test inside the score launch (one launch less)
+
     def score_pass(p, q, stream):
-        if compact:
+        if fused_check:
+            st = (layer.cached_q, layer.cached_q_next, layer.first, layer.first_next, layer.reuse, theta)
+            if compact:
+                ts.ts_paged_qk_codes_checked(p, q, *st, layer.codes, scale, layer.ws, stream)
+            else:
+                ts.ts_paged_qk_scores_checked(p, q, *st, layer.scores, scale, layer.ws, stream)
+            layer._swap_selcache_state()
+        elif compact:
             ts.ts_paged_qk_codes(p, q, layer.codes, scale, layer.reuse, layer.ws, stream)
         else:
             ts.ts_paged_qk_scores(p, q, layer.scores, scale, layer.reuse, layer.ws, stream)
@@ -335,7 +352,8 @@ def decode_bench(cfg, args, *, steps, warmup, with_cpu_baseline, with_graph):
         p = problems[i % R]
         q = qs[i % R]
         stream = torch.cuda.current_stream()      # the capture stream while a graph is being recorded
-        ts.ts_selcache_check(p, q, layer.cached_q, layer.first, theta, layer.reuse, stream)
+        if not fused_check:
+            ts.ts_selcache_check(p, q, layer.cached_q, layer.first, theta, layer.reuse, stream)
         if ev is not None:
             ev[0].record(stream)
         if kev is not None:          # HIP events bound to the score kernel's own start and end
@@ -418,17 +436,18 @@ def decode_bench(cfg, args, *, steps, warmup, with_cpu_baseline, with_graph):
     # The same steps as one HIP graph (R consecutive steps, one per pool copy), replayed: what the step costs
     # without the host in the loop.  Informational; `value` is the host-driven loop above.
     graph_info = None
+    RG = 2 * R if (fused_check and R % 2) else R      # an even number of steps: the fused check alternates two state buffers
     if with_graph:
         try:
             idx_ref = []
-            for i in range(R):
+            for i in range(RG):
                 step(i); torch.cuda.synchronize(); idx_ref.append(to_host(layer.idx).copy())
             side = torch.cuda.Stream()
             side.wait_stream(torch.cuda.current_stream())
-            idx_log = torch.zeros((R,) + tuple(layer.idx.shape), dtype=torch.int32, device=dev)
+            idx_log = torch.zeros((RG,) + tuple(layer.idx.shape), dtype=torch.int32, device=dev)
 
             def steps_r():
-                for i in range(R):
+                for i in range(RG):
                     step(i); idx_log[i].copy_(layer.idx)
             with torch.cuda.stream(side):
                 steps_r()
@@ -440,19 +459,19 @@ def decode_bench(cfg, args, *, steps, warmup, with_cpu_baseline, with_graph):
             for _ in range(3):
                 idx_log.fill_(-3); layer.idx.fill_(-3); torch.cuda.synchronize()
                 g.replay(); torch.cuda.synchronize()
-                ok = ok and all(np.array_equal(to_host(idx_log[i]), idx_ref[i]) for i in range(R))
-            nrep = max(1, steps // R)
+                ok = ok and all(np.array_equal(to_host(idx_log[i]), idx_ref[i]) for i in range(RG))
+            nrep = max(1, steps // RG)
             tg = time.perf_counter()
             for _ in range(nrep):
                 g.replay()
             torch.cuda.synchronize()
-            graph_info = {"ms_per_step": (time.perf_counter() - tg) * 1e3 / (nrep * R), "steps": nrep * R,
+            graph_info = {"ms_per_step": (time.perf_counter() - tg) * 1e3 / (nrep * RG), "steps": nrep * RG,
                           "replays_match_eager": bool(ok)}
         except Exception as e:
             graph_info = {"error": str(e)[:200]}
 
-    kernel_name = "ts::score_codes_mfma_kernel (the one launch of ts_paged_qk_codes)" if compact else \
-        "ts::score_decode_kernel (the one launch of ts_paged_qk_scores)"
+    kernel_name = ("ts::score_codes_mfma_kernel (the one launch of ts_paged_qk_codes%s)" if compact else
+                   "ts::score_decode_kernel (the one launch of ts_paged_qk_scores%s)") % ("_checked, Selection Cache test included" if fused_check else "")
     traffic = MEASURED_TRAFFIC_BYTES.get((cfg, "compact" if compact else "dense")) if not args.tokens and args.page_size == 16 else None
     res = {
         "ms_per_step": ms_step,
@@ -467,7 +486,8 @@ def decode_bench(cfg, args, *, steps, warmup, with_cpu_baseline, with_graph):
                                           "head": "Eq. 4 head vote"}[args.selection],
                    "selection_form": ("compact: ts_paged_qk_codes + ts_soft_vote_bounds + ts_topk_exact (no score matrix in memory)"
                                       if compact else "five calls: ts_paged_qk_scores + ts_soft_vote + ts_topk (fp32 score matrix)")},
-        "launches_per_step": 8 if compact else 9,
+        "launches_per_step": (8 if compact else 9) - (1 if fused_check else 0),
+        "selection_cache_check": ("inside the score launch (ts_paged_qk_%s_checked)" % ("codes" if compact else "scores")) if fused_check else "ts_selcache_check before the score launch",
         "planted_token_quality": quality,
         "compact_vs_five_call_index_overlap": dense_agrees,
         "hip_graph_replay": graph_info,
@@ -518,7 +538,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": head["dtype"], "data": "synthetic",
     }
-    for k in ("config", "decode_steps_per_s", "launches_per_step", "planted_token_quality", "compact_vs_five_call_index_overlap",
+    for k in ("config", "decode_steps_per_s", "launches_per_step", "selection_cache_check", "planted_token_quality", "compact_vs_five_call_index_overlap",
               "hip_graph_replay", "selection_ms", "whole_step_roofline", "roofline", "cpu_baseline"):
         if k in head:
             res[k] = head[k]
@@ -526,7 +546,7 @@ def main():
     if args.config == 4 and not args.no_secondary and not args.tokens:
         sec = decode_bench(2, args, steps=args.steps, warmup=args.warmup, with_cpu_baseline=False, with_graph=False)
         res["secondary"] = {k: sec[k] for k in ("config", "ms_per_step", "tokens_scanned_per_s", "decode_steps_per_s",
-                                                 "selection_ms", "whole_step_roofline", "roofline")}
+                                                 "launches_per_step", "selection_ms", "whole_step_roofline", "roofline")}
         if args.path != "dense" and args.selection == "soft":
             # at 128K tokens the five-call form (fp32 score matrix in memory) is the faster step although its score
             # pass is the slower kernel: both on record

@@ -9,6 +9,8 @@
  *   ts_topk               the TopK of Eq. 5 (radix select, ties to the lower token index)
  *   ts_sparse_paged_attn  Eq. 2, attention over the selected tokens read through the page table
  *
+ * (ts_paged_qk_scores_checked / ts_paged_qk_codes_checked take Algorithm 1's condition inside the score launch,
+ * which makes the first call unnecessary.)
  * With forced tokens (ts_problem.num_initial / num_local) the same five calls rank only the middle of
  * each sequence and attend over initial block + selection + most recent block.
  * A chunk of C > 1 queries (chunked prefill) uses ts_chunk_row_stats + ts_chunk_soft_vote (or
@@ -214,6 +216,32 @@ int32_t ts_head_vote(const ts_problem* p, const float* scores, int32_t k_head, f
  * first [device] uint8 [B] in/out; reuse [device] uint8 [B] out. */
 int32_t ts_selcache_check(const ts_problem* p, const void* q, void* cached_q, uint8_t* first, float theta,
                           uint8_t* reuse, void* stream);
+
+/* Algorithm 1's test inside the score launch (one launch less per decode step): ts_paged_qk_scores_checked and
+ * ts_paged_qk_codes_checked are ts_paged_qk_scores / ts_paged_qk_codes with the condition of ts_selcache_check
+ * evaluated in the prologue of every workgroup — the same sums in the same order, hence the same decision as
+ * ts_selcache_check, bit for bit — instead of a `skip` mask.  Sequences whose test passes are skipped; workgroup 0
+ * of every sequence writes the state after the step.  Because other workgroups of the launch still read the state
+ * before the step, the two live in different buffers: the caller keeps two (cached_q, first) pairs and swaps them
+ * after every step.
+ *   reuse[b]         = (first[b] == 0) and cos(q[b], cached_q[b]) >= theta        (out; pass it as `skip` to the
+ *                      calls that follow in the step)
+ *   cached_q_next[b] = reuse[b] ? cached_q[b] : q[b];   first_next[b] = reuse[b] ? first[b] : 0
+ * cached_q, cached_q_next [device] [B][H][D] in p->dtype, 16-byte aligned, not overlapping; first, first_next,
+ * reuse [device] uint8 [B], first_next not overlapping first.  Errors as for the plain calls; a null or
+ * overlapping member of sc is TS_ERR_INVALID_ARG. */
+typedef struct {
+  const void*    cached_q;
+  void*          cached_q_next;
+  const uint8_t* first;
+  uint8_t*       first_next;
+  uint8_t*       reuse;
+  float          theta;
+} ts_selcache;
+int32_t ts_paged_qk_scores_checked(const ts_problem* p, const void* q, const ts_selcache* sc, float* scores,
+                                   float score_scale, void* ws, size_t ws_bytes, void* stream);
+int32_t ts_paged_qk_codes_checked(const ts_problem* p, const void* q, const ts_selcache* sc, uint8_t* codes,
+                                  float score_scale, void* ws, size_t ws_bytes, void* stream);
 
 /* Eq. 2 (selective sparse attention), decode form (chunk == 1): for every b, h
  *   out[b][0][h][:] = sum_j softmax_j( <q[b][0][h], K[slot(b, idx[b][j])][h/G]> * sm_scale ) * V[slot(b, idx[b][j])][h/G]

@@ -36,6 +36,11 @@ class _CProblem(ctypes.Structure):
     ]
 
 
+class _CSelcache(ctypes.Structure):
+    _fields_ = [("cached_q", ctypes.c_void_p), ("cached_q_next", ctypes.c_void_p), ("first", ctypes.c_void_p),
+                ("first_next", ctypes.c_void_p), ("reuse", ctypes.c_void_p), ("theta", ctypes.c_float)]
+
+
 _lib = None
 
 
@@ -73,6 +78,8 @@ def load():
         L.ts_soft_vote_bounds.argtypes = [pp, vp, f32, vp, vp, vp, vp, vp, sz, vp]
         L.ts_topk_exact.argtypes = [pp, vp, vp, vp, f32, i32, vp, vp, vp, vp, vp, sz, vp]
         L.ts_selcache_check.argtypes = [pp, vp, vp, vp, f32, vp, vp]
+        L.ts_paged_qk_scores_checked.argtypes = [pp, vp, ctypes.POINTER(_CSelcache), vp, f32, vp, sz, vp]
+        L.ts_paged_qk_codes_checked.argtypes = [pp, vp, ctypes.POINTER(_CSelcache), vp, f32, vp, sz, vp]
         L.ts_sparse_paged_attn.argtypes = [pp, vp, vp, i32, vp, f32, vp, vp, vp, sz, vp]
         L.ts_chunk_row_stats.argtypes = [pp, vp, f32, vp, vp, sz, vp]
         L.ts_chunk_soft_vote.argtypes = [pp, vp, vp, f32, vp, vp, sz, vp]
@@ -92,7 +99,8 @@ def load():
                      "ts_chunk_soft_vote", "ts_chunk_mean_query", "ts_sum_vote", "ts_head_vote_scratch_bytes",
                      "ts_head_vote", "ts_debug_set_topk_path", "ts_debug_event_create", "ts_debug_event_destroy",
                      "ts_debug_event_elapsed_ms", "ts_debug_set_score_timing_events", "ts_paged_qk_codes",
-                     "ts_soft_vote_bounds", "ts_topk_exact", "ts_debug_set_codes_path", "ts_topk_noalloc"):
+                     "ts_soft_vote_bounds", "ts_topk_exact", "ts_debug_set_codes_path", "ts_topk_noalloc",
+                     "ts_paged_qk_scores_checked", "ts_paged_qk_codes_checked"):
             getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -193,6 +201,24 @@ def ts_paged_qk_scores(p: Problem, q, scores, score_scale: float, skip, ws, stre
 def ts_soft_vote(p: Problem, scores, score_scale: float, row_stats, votes, skip, ws, stream=None) -> None:
     _ok(load().ts_soft_vote(p.ref(), _ptr(scores), float(score_scale), _ptr(row_stats), _ptr(votes), _ptr(skip),
                             _ptr(ws), _nbytes(ws), _stream(stream)), "ts_soft_vote")
+
+
+def _selcache(cached_q, cached_q_next, first, first_next, reuse, theta) -> _CSelcache:
+    return _CSelcache(_ptr(cached_q), _ptr(cached_q_next), _ptr(first), _ptr(first_next), _ptr(reuse), float(theta))
+
+
+def ts_paged_qk_scores_checked(p: Problem, q, cached_q, cached_q_next, first, first_next, reuse, theta: float, scores,
+                               score_scale: float, ws, stream=None) -> None:
+    sc = _selcache(cached_q, cached_q_next, first, first_next, reuse, theta)
+    _ok(load().ts_paged_qk_scores_checked(p.ref(), _ptr(q), ctypes.byref(sc), _ptr(scores), float(score_scale), _ptr(ws),
+                                          _nbytes(ws), _stream(stream)), "ts_paged_qk_scores_checked")
+
+
+def ts_paged_qk_codes_checked(p: Problem, q, cached_q, cached_q_next, first, first_next, reuse, theta: float, codes,
+                              score_scale: float, ws, stream=None) -> None:
+    sc = _selcache(cached_q, cached_q_next, first, first_next, reuse, theta)
+    _ok(load().ts_paged_qk_codes_checked(p.ref(), _ptr(q), ctypes.byref(sc), _ptr(codes), float(score_scale), _ptr(ws),
+                                         _nbytes(ws), _stream(stream)), "ts_paged_qk_codes_checked")
 
 
 def ts_paged_qk_codes(p: Problem, q, codes, score_scale: float, skip, ws, stream=None) -> None:

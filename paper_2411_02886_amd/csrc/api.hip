@@ -217,8 +217,27 @@ static size_t score_lds_bytes(const ScoreArgs& a, int G) {
   return 4 * (per_wave + 64) * sizeof(float);   // + 64 block maxima per wave (compact form)
 }
 
-int32_t ts_paged_qk_scores(const ts_problem* p, const void* q, float* scores, float score_scale,
-                           const uint8_t* skip, void* ws, size_t ws_bytes, void* stream) {
+// Algorithm 1's state for the score launches that run the test themselves
+static int32_t fill_selcache(const ts_problem* p, const void* q, const ts_selcache* sc, ScoreArgs* a) {
+  if (sc == nullptr || sc->cached_q == nullptr || sc->cached_q_next == nullptr || sc->first == nullptr ||
+      sc->first_next == nullptr || sc->reuse == nullptr) return TS_ERR_INVALID_ARG;
+  if (!(sc->theta == sc->theta)) return TS_ERR_INVALID_ARG;
+  const size_t es = p->dtype == TS_BF16 ? 2 : 4;
+  const size_t qbytes = (size_t)p->batch * p->num_q_heads * p->head_dim * es;
+  const uintptr_t c0 = (uintptr_t)sc->cached_q, c1 = (uintptr_t)sc->cached_q_next, q0 = (uintptr_t)q;
+  if (((c0 | c1 | q0) & 15) != 0) return TS_ERR_INVALID_ARG;
+  if (c0 < c1 + qbytes && c1 < c0 + qbytes) return TS_ERR_INVALID_ARG;              // the two C_Q buffers overlap
+  if (q0 < c1 + qbytes && c1 < q0 + qbytes) return TS_ERR_INVALID_ARG;              // the query is overwritten
+  const uintptr_t f0 = (uintptr_t)sc->first, f1 = (uintptr_t)sc->first_next;
+  if (f0 < f1 + (size_t)p->batch && f1 < f0 + (size_t)p->batch) return TS_ERR_INVALID_ARG;
+  a->sc_cached_q = (const uint8_t*)sc->cached_q; a->sc_cached_q_next = (uint8_t*)sc->cached_q_next;
+  a->sc_first = sc->first; a->sc_first_next = sc->first_next; a->sc_reuse = sc->reuse; a->sc_theta = sc->theta;
+  a->skip = nullptr;
+  return TS_OK;
+}
+
+static int32_t paged_qk_scores_impl(const ts_problem* p, const void* q, const ts_selcache* sc, float* scores,
+                                    float score_scale, const uint8_t* skip, void* ws, size_t ws_bytes, void* stream) {
   int32_t st = check_problem(p);
   if (st != TS_OK) return st;
   if (scores == nullptr) return TS_ERR_INVALID_ARG;
@@ -226,6 +245,7 @@ int32_t ts_paged_qk_scores(const ts_problem* p, const void* q, float* scores, fl
   ScoreArgs a{};
   st = fill_score_args(p, q, score_scale, skip, ws, ws_bytes, w.topk_blk, &a, w);   // needs the sections up to score_partials
   if (st != TS_OK) return st;
+  if (sc != nullptr && (st = fill_selcache(p, q, sc, &a)) != TS_OK) return st;
   const int G = p->num_q_heads / p->num_kv_heads;
   a.scores = scores;
   a.vec_store = (p->num_q_heads % 4 == 0) && ((a.HB * G) % 4 == 0) && (((uintptr_t)scores & 15) == 0);
@@ -235,10 +255,21 @@ int32_t ts_paged_qk_scores(const ts_problem* p, const void* q, float* scores, fl
   return e == hipSuccess ? TS_OK : TS_ERR_HIP;
 }
 
+int32_t ts_paged_qk_scores(const ts_problem* p, const void* q, float* scores, float score_scale,
+                           const uint8_t* skip, void* ws, size_t ws_bytes, void* stream) {
+  return paged_qk_scores_impl(p, q, nullptr, scores, score_scale, skip, ws, ws_bytes, stream);
+}
+
+int32_t ts_paged_qk_scores_checked(const ts_problem* p, const void* q, const ts_selcache* sc, float* scores,
+                                   float score_scale, void* ws, size_t ws_bytes, void* stream) {
+  if (sc == nullptr) return TS_ERR_INVALID_ARG;
+  return paged_qk_scores_impl(p, q, sc, scores, score_scale, nullptr, ws, ws_bytes, stream);
+}
+
 // ---- compact form of the selection: Algorithm 2 + Eq. 5 + TopK without the score matrix in memory
 
-int32_t ts_paged_qk_codes(const ts_problem* p, const void* q, uint8_t* codes, float score_scale,
-                          const uint8_t* skip, void* ws, size_t ws_bytes, void* stream) {
+static int32_t paged_qk_codes_impl(const ts_problem* p, const void* q, const ts_selcache* sc, uint8_t* codes,
+                                   float score_scale, const uint8_t* skip, void* ws, size_t ws_bytes, void* stream) {
   int32_t st = check_problem(p);
   if (st != TS_OK) return st;
   if (codes == nullptr) return TS_ERR_INVALID_ARG;
@@ -246,6 +277,7 @@ int32_t ts_paged_qk_codes(const ts_problem* p, const void* q, uint8_t* codes, fl
   ScoreArgs a{};
   st = fill_score_args(p, q, score_scale, skip, ws, ws_bytes, w.attn_out, &a, w);   // needs the block statistics too
   if (st != TS_OK) return st;
+  if (sc != nullptr && (st = fill_selcache(p, q, sc, &a)) != TS_OK) return st;
   const int G = p->num_q_heads / p->num_kv_heads;
   a.codes = codes;
   a.blk_max = (float*)((uint8_t*)ws + w.blk_max); a.nblk = w.score_nblk;
@@ -293,6 +325,17 @@ int32_t ts_paged_qk_codes(const ts_problem* p, const void* q, uint8_t* codes, fl
   const int variant = (p->dtype == TS_BF16) ? g_score_variant : 0;
   const hipError_t e = launch_score_decode(p->dtype, p->head_dim, G, variant, a, dim3(wg, p->batch), score_lds_bytes(a, G), (hipStream_t)stream);
   return e == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
+int32_t ts_paged_qk_codes(const ts_problem* p, const void* q, uint8_t* codes, float score_scale,
+                          const uint8_t* skip, void* ws, size_t ws_bytes, void* stream) {
+  return paged_qk_codes_impl(p, q, nullptr, codes, score_scale, skip, ws, ws_bytes, stream);
+}
+
+int32_t ts_paged_qk_codes_checked(const ts_problem* p, const void* q, const ts_selcache* sc, uint8_t* codes,
+                                  float score_scale, void* ws, size_t ws_bytes, void* stream) {
+  if (sc == nullptr) return TS_ERR_INVALID_ARG;
+  return paged_qk_codes_impl(p, q, sc, codes, score_scale, nullptr, ws, ws_bytes, stream);
 }
 
 int32_t ts_soft_vote_bounds(const ts_problem* p, const uint8_t* codes, float score_scale, float* row_stats,

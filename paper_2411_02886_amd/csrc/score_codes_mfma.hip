@@ -22,6 +22,7 @@
 // one contiguous burst at the end of the run: on this memory system small writes sprinkled into the read
 // stream cost many times their bytes, a burst at the end of a wave's life costs about its own time.
 #include "ts_kernels.h"
+#include "selcache_device.h"
 #include "ts_score_math.h"
 #include <hip/hip_ext.h>
 
@@ -57,10 +58,22 @@ __global__ __launch_bounds__(256) void score_codes_mfma_kernel(ScoreArgs a) {
   const int j = lane & 7, r = lane >> 3;
   const int mrow = lane & 15, kg = lane >> 4;            // MFMA row / column and k-group of this lane
   const int b = blockIdx.y;
-  const int skip_flag = a.skip != nullptr ? (int)a.skip[b] : 0;
   const int N = min(max(a.seq_lens[b], 0), a.max_seq_len);
   const int indptr = a.page_indptr[b];
-  if (skip_flag != 0) return;
+  // Algorithm 1's test inside this launch: the vectors' loads and partial sums go first, the decision is taken below,
+  // once the first page ids are on their way (the same sums in the same order in every workgroup of the sequence).
+  // The reduction uses the head of the dynamic LDS, which nothing else touches before the decision.
+  const bool sc_on = a.sc_cached_q != nullptr;
+  double (*sc_red)[4] = reinterpret_cast<double (*)[4]>(smem8);
+  int sc_first0 = 0;
+  if (sc_on) {
+    uint4 qkeep[kSelcacheKeep];
+    sc_first0 = a.sc_first[b];
+    selcache_sums<TS_BF16>(reinterpret_cast<const uint4*>(a.q + (size_t)b * a.H * RB),
+                      reinterpret_cast<const uint4*>(a.sc_cached_q + (size_t)b * a.H * RB), a.H * RB / 16, sc_red, qkeep);
+  } else if (a.skip != nullptr && a.skip[b] != 0) {
+    return;
+  }
   const int H = a.H;
   const int RR = a.RR;                                    // tiles per run: bytes and statistics leave once per run
   // wave-private LDS: K tile, code bytes of the run, statistics of the run
@@ -255,6 +268,20 @@ __global__ __launch_bounds__(256) void score_codes_mfma_kernel(ScoreArgs a) {
   if (total_blocks > 0) {
     i_pid = load_pids(tile_of(0, 0));
     i_pid_next = load_pids(next_tile(0, 0));
+  }
+  if (sc_on) {
+    const int reselect = selcache_decide(sc_red, reinterpret_cast<int*>(sc_red + 3), sc_first0, a.sc_theta);
+    if (blockIdx.x == 0) {                                // the state after the step: C_Q <- Q on a miss, kept on a hit
+      const int npieces = a.H * RB / 16;
+      const uint4* qv = reinterpret_cast<const uint4*>(a.q + (size_t)b * a.H * RB);
+      const uint4* cv = reinterpret_cast<const uint4*>(a.sc_cached_q + (size_t)b * a.H * RB);
+      uint4* nv = reinterpret_cast<uint4*>(a.sc_cached_q_next + (size_t)b * a.H * RB);
+      for (int p = threadIdx.x; p < npieces; p += 256) nv[p] = reselect ? qv[p] : cv[p];
+      if (threadIdx.x == 0) { a.sc_reuse[b] = (uint8_t)(!reselect); a.sc_first_next[b] = (uint8_t)(reselect ? 0 : sc_first0); }
+    }
+    if (!reselect) return;
+  }
+  if (total_blocks > 0) {
     issue(buf, tile_of(0, 0), 0, i_pid);
     advance_issue();
   }

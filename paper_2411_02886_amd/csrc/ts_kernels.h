@@ -26,6 +26,14 @@ struct ScoreArgs {
   float* blk_max;         // [B][nblk][H] maximum of each head over the block's ranked tokens
   int nblk;               // blocks per sequence the array is strided by: ceil(max_seq_len / 32)
   int ncp_shift;          // log2 of the power of two >= HB * G
+  // Algorithm 1's test inside this launch (sc_cached_q != nullptr; `skip` is then unused): every workgroup takes
+  // the decision itself from Q and C_Q, workgroup 0 of a sequence writes the state after the step
+  const uint8_t* sc_cached_q;   // [B][H][D] C_Q before the step, read only
+  uint8_t* sc_cached_q_next;    // [B][H][D] C_Q after the step, another buffer
+  const uint8_t* sc_first;      // [B]
+  uint8_t* sc_first_next;       // [B]
+  uint8_t* sc_reuse;            // [B] out
+  float sc_theta;
 };
 
 // compact form of the selection: statistics merge, vote bounds, exact re-evaluation of the candidates

@@ -52,6 +52,9 @@ class DecodeLayer:
         self.cached_q = torch.zeros((B, Hq, D), dtype=edt, device=device)
         self.first = torch.ones((B,), dtype=torch.uint8, device=device)
         self.reuse = torch.zeros((B,), dtype=torch.uint8, device=device)
+        # second (C_Q, first) pair of the steps that run Algorithm 1's test inside the score launch
+        self.cached_q_next = torch.zeros((B, Hq, D), dtype=edt, device=device)
+        self.first_next = torch.ones((B,), dtype=torch.uint8, device=device)
         nbytes = ts.ts_workspace_bytes(self.problem, k)
         self.ws = torch.empty((nbytes + 255) // 256 * 64, dtype=torch.int32, device=device)
         ts.ts_workspace_init(self.ws)
@@ -80,9 +83,20 @@ class DecodeLayer:
     def selcache_check(self, q, theta):
         ts.ts_selcache_check(self.problem, q, self.cached_q, self.first, theta, self.reuse)
 
-    def select(self, q, score_scale=1.0, skip=None, kind="soft"):
-        """kind: "soft" = Eq. 5 (the method), "sum" = Eq. 3, "head" = Eq. 4 (the paper's ablation baselines)."""
-        ts.ts_paged_qk_scores(self.problem, q, self.scores, score_scale, skip, self.ws)
+    def _swap_selcache_state(self):
+        self.cached_q, self.cached_q_next = self.cached_q_next, self.cached_q
+        self.first, self.first_next = self.first_next, self.first
+
+    def select(self, q, score_scale=1.0, skip=None, kind="soft", check_theta=None):
+        """kind: "soft" = Eq. 5 (the method), "sum" = Eq. 3, "head" = Eq. 4 (the paper's ablation baselines).
+        check_theta: run Algorithm 1's test inside the score launch (skip is then self.reuse)."""
+        if check_theta is not None:
+            ts.ts_paged_qk_scores_checked(self.problem, q, self.cached_q, self.cached_q_next, self.first, self.first_next,
+                                          self.reuse, check_theta, self.scores, score_scale, self.ws)
+            self._swap_selcache_state()
+            skip = self.reuse
+        else:
+            ts.ts_paged_qk_scores(self.problem, q, self.scores, score_scale, skip, self.ws)
         if kind == "soft":
             ts.ts_soft_vote(self.problem, self.scores, score_scale, self.row_stats, self.votes, skip, self.ws)
         elif kind == "sum":
@@ -96,7 +110,7 @@ class DecodeLayer:
             raise ValueError(kind)
         ts.ts_topk(self.problem, self.votes, self.k, self.idx, self.count, skip, self.ws)
 
-    def select_compact(self, q, score_scale=1.0, skip=None):
+    def select_compact(self, q, score_scale=1.0, skip=None, check_theta=None):
         """Eq. 5 selection without the score matrix in memory: one byte per score, vote bounds, exact votes of
         the candidates.  Same idx / count as select(kind="soft")."""
         if getattr(self, "codes", None) is None:
@@ -105,7 +119,13 @@ class DecodeLayer:
             self.vote_hi = torch.empty((B, M), dtype=torch.float32, device=self.device)
             self.vote_lo = torch.empty((B, M), dtype=torch.float32, device=self.device)
             self.sel_votes = torch.zeros((B, self.k), dtype=torch.float32, device=self.device)
-        ts.ts_paged_qk_codes(self.problem, q, self.codes, score_scale, skip, self.ws)
+        if check_theta is not None:
+            ts.ts_paged_qk_codes_checked(self.problem, q, self.cached_q, self.cached_q_next, self.first, self.first_next,
+                                         self.reuse, check_theta, self.codes, score_scale, self.ws)
+            self._swap_selcache_state()
+            skip = self.reuse
+        else:
+            ts.ts_paged_qk_codes(self.problem, q, self.codes, score_scale, skip, self.ws)
         ts.ts_soft_vote_bounds(self.problem, self.codes, score_scale, self.row_stats, self.vote_hi, self.vote_lo, skip,
                                self.ws)
         ts.ts_topk_exact(self.problem, q, self.vote_hi, self.row_stats, score_scale, self.k, self.idx, self.count, skip,
@@ -114,18 +134,22 @@ class DecodeLayer:
     def attend(self, q, sm_scale):
         ts.ts_sparse_paged_attn(self.problem, q, self.idx, self.k, self.count, sm_scale, self.out, self.lse, self.ws)
 
-    def step(self, q, *, theta=None, score_scale=1.0, sm_scale=None, compact=False):
+    def step(self, q, *, theta=None, score_scale=1.0, sm_scale=None, compact=False, fused_check=False):
         """One decode step: Selection Cache check (when theta is given), selection on a miss, sparse
-        attention.  No host synchronisation."""
+        attention.  No host synchronisation.  fused_check: the check runs inside the score launch (one launch
+        less; self.cached_q / self.first are swapped with their second copies after the step)."""
         sm = sm_scale if sm_scale is not None else 1.0 / float(np.sqrt(self.D))
-        skip = None
+        skip, check_theta = None, None
         if theta is not None:
-            self.selcache_check(q, theta)
-            skip = self.reuse
+            if fused_check:
+                check_theta = theta
+            else:
+                self.selcache_check(q, theta)
+                skip = self.reuse
         if compact:
-            self.select_compact(q, score_scale, skip)
+            self.select_compact(q, score_scale, skip, check_theta=check_theta)
         else:
-            self.select(q, score_scale, skip)
+            self.select(q, score_scale, skip, check_theta=check_theta)
         self.attend(q, sm)
 
 

@@ -56,6 +56,28 @@ int main(void) {
   EXPECT(ts_paged_qk_codes(&p, x, x, 1.f, NULL, ws, 4096, NULL), TS_ERR_WORKSPACE);
   c = p; c.chunk = 8;          EXPECT(ts_paged_qk_codes(&c, x, x, 1.f, NULL, ws, big, NULL), TS_ERR_UNSUPPORTED);
 
+  {
+    /* the score calls that run Algorithm 1's test themselves: a complete, non-overlapping state or an error */
+    static char dev[4][65536];          /* stand-ins for four 16-byte aligned device buffers (never dereferenced) */
+    void* qa = (void*)(((uintptr_t)dev[0] + 15) & ~(uintptr_t)15);
+    void* ca = (void*)(((uintptr_t)dev[1] + 15) & ~(uintptr_t)15);
+    void* cb = (void*)(((uintptr_t)dev[2] + 15) & ~(uintptr_t)15);
+    uint8_t* fl = (uint8_t*)dev[3];
+    ts_selcache sc, bad;
+    sc.cached_q = ca; sc.cached_q_next = cb; sc.first = fl; sc.first_next = fl + 64; sc.reuse = fl + 128; sc.theta = 0.9f;
+    EXPECT(ts_paged_qk_scores_checked(&p, qa, NULL, x, 1.f, ws, big, NULL), TS_ERR_INVALID_ARG);
+    EXPECT(ts_paged_qk_codes_checked(&p, qa, NULL, x, 1.f, ws, big, NULL), TS_ERR_INVALID_ARG);
+    EXPECT(ts_paged_qk_scores_checked(&p, qa, &sc, NULL, 1.f, ws, big, NULL), TS_ERR_INVALID_ARG);
+    EXPECT(ts_paged_qk_codes_checked(&p, qa, &sc, x, 1.f, ws, 4096, NULL), TS_ERR_WORKSPACE);
+    bad = sc; bad.cached_q_next = NULL;             EXPECT(ts_paged_qk_scores_checked(&p, qa, &bad, x, 1.f, ws, big, NULL), TS_ERR_INVALID_ARG);
+    bad = sc; bad.reuse = NULL;                     EXPECT(ts_paged_qk_codes_checked(&p, qa, &bad, x, 1.f, ws, big, NULL), TS_ERR_INVALID_ARG);
+    bad = sc; bad.cached_q_next = ca;               EXPECT(ts_paged_qk_codes_checked(&p, qa, &bad, x, 1.f, ws, big, NULL), TS_ERR_INVALID_ARG);   /* one buffer for both states */
+    bad = sc; bad.cached_q_next = (char*)ca + 4096; EXPECT(ts_paged_qk_scores_checked(&p, qa, &bad, x, 1.f, ws, big, NULL), TS_ERR_INVALID_ARG);  /* overlapping */
+    bad = sc; bad.cached_q_next = qa;               EXPECT(ts_paged_qk_scores_checked(&p, qa, &bad, x, 1.f, ws, big, NULL), TS_ERR_INVALID_ARG);  /* would overwrite the query */
+    bad = sc; bad.cached_q = (char*)ca + 2;         EXPECT(ts_paged_qk_codes_checked(&p, qa, &bad, x, 1.f, ws, big, NULL), TS_ERR_INVALID_ARG);   /* not 16-byte aligned */
+    bad = sc; bad.first_next = fl + 1;              EXPECT(ts_paged_qk_codes_checked(&p, qa, &bad, x, 1.f, ws, big, NULL), TS_ERR_INVALID_ARG);   /* flags overlap (B = 2) */
+  }
+
   /* votes */
   EXPECT(ts_soft_vote(&p, NULL, 1.f, x, x, NULL, ws, big, NULL), TS_ERR_INVALID_ARG);
   EXPECT(ts_soft_vote(&p, x, 1.f, NULL, x, NULL, ws, big, NULL), TS_ERR_INVALID_ARG);

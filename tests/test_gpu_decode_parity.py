@@ -217,7 +217,10 @@ def test_k_larger_than_n_equals_full_attention(gpu):
     assert np.abs(to_host(layer.out)[0, 0] - full).max() < 1e-4
 
 
-def test_selection_cache_loop_matches_algorithm_1(gpu):
+@pytest.mark.parametrize("fused,compact", [(False, False), (True, False), (True, True)],
+                         ids=["check-call", "check-in-score-launch", "check-in-codes-launch"])
+def test_selection_cache_loop_matches_algorithm_1(gpu, fused, compact):
+    # fused: ts_paged_qk_scores_checked / ts_paged_qk_codes_checked take the decision in the score launch
     from paper_2411_02886_amd.runtime import to_device, to_host
     steps, theta = 12, 0.9
     w = W.make_workload("sc", dtype=W.BF16, B=3, H=8, H_kv=2, D=128, P=16, seq_lens=[300, 1000, 64], k=32, seed=19,
@@ -233,10 +236,11 @@ def test_selection_cache_loop_matches_algorithm_1(gpu):
     for t in range(steps):
         print("selcache step", t, flush=True)
         qd = to_device(qs[t])
-        layer.step(qd, theta=theta, score_scale=0.1)
+        layer.step(qd, theta=theta, score_scale=0.1, fused_check=fused, compact=compact)
         torch.cuda.synchronize()
         reuse_g = to_host(layer.reuse); idx_g = to_host(layer.idx); cnt_g = to_host(layer.count)
         out_g = to_host(layer.out, bits16=True)
+        assert not to_host(layer.first).any(), t
         for b in range(w.B):
             qb = np.ascontiguousarray(qs[t][b, 0])
             sel = lambda qq, b=b: oracle.select(qq, w.k_pool, w.dtype, w.H_kv, w.P, w.pages_of(b), int(w.seq_lens[b]), w.k,
@@ -410,6 +414,38 @@ def test_config3_full_size_selection_cache_run(gpu):
     rate = reuse_total / (steps * w.B)
     print("cfg3 full size: reuse rate %.4f, tolerated near-tie exceptions %d" % (rate, exceptions))
     assert 0.5 < rate < 0.75
+
+
+@pytest.mark.parametrize("dtype,H,H_kv,D,compact", [(W.F32, 8, 2, 64, False), (W.F32, 8, 2, 64, True), (W.BF16, 32, 8, 128, False),
+                                                   (W.BF16, 32, 8, 128, True), (W.BF16, 28, 4, 128, True), (W.BF16, 6, 2, 64, True)],
+                         ids=["f32-scores", "f32-codes", "bf16-scores", "bf16-codes-mfma", "bf16-28/4-codes-mfma", "bf16-6/2-codes"])
+def test_check_inside_the_score_launch_equals_the_separate_check(gpu, dtype, H, H_kv, D, compact):
+    """Algorithm 1 with the test taken in the prologue of the score kernels against the run that calls
+    ts_selcache_check first: same reuse flags, C_Q, first flags, index sets and attention outputs, bit for bit, at
+    every step of a run with hits and misses (the thresholds sit where the AR(1) queries cross them)."""
+    from paper_2411_02886_amd.runtime import to_device, to_host
+    steps = 16
+    w = W.make_workload("scf", dtype=dtype, B=5, H=H, H_kv=H_kv, D=D, P=16, seq_lens=[900, 2500, 0, 70, 4100], k=64, seed=77,
+                        beta=3.0, planted_per_head=1)
+    qs = W.ar1_queries(w, steps, rho=0.95)
+    bits16 = dtype == W.BF16
+    hits = 0
+    for theta in (0.9, 0.8):
+        la, _ = make_layer(w); lb, _ = make_layer(w)
+        for t in range(steps):
+            print("fused check", theta, t, flush=True)
+            qd = to_device(qs[t])
+            la.step(qd, theta=theta, score_scale=0.2, compact=compact)
+            lb.step(qd, theta=theta, score_scale=0.2, compact=compact, fused_check=True)
+            torch.cuda.synchronize()
+            ra, rb = to_host(la.reuse), to_host(lb.reuse)
+            assert np.array_equal(ra, rb), (theta, t)
+            hits += int(ra.sum())
+            assert np.array_equal(to_host(la.cached_q, bits16=bits16), to_host(lb.cached_q, bits16=bits16)), (theta, t)
+            assert np.array_equal(to_host(la.first), to_host(lb.first)), (theta, t)
+            assert np.array_equal(to_host(la.idx), to_host(lb.idx)) and np.array_equal(to_host(la.count), to_host(lb.count)), (theta, t)
+            assert np.array_equal(to_host(la.out, bits16=bits16), to_host(lb.out, bits16=bits16)), (theta, t)
+    assert 0 < hits < 2 * steps * w.B
 
 
 def test_kernels_are_deterministic(gpu):
