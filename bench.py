@@ -55,7 +55,7 @@ def parse():
                          "of short sequences, where it is the faster form): the five calls with the fp32 score matrix")
     ap.add_argument("--no-secondary", action="store_true", help="config 4: do not run configuration 2 as well")
     ap.add_argument("--pools", type=int, default=0, help="physical pool copies to rotate over (0 = enough for >= 2 GiB)")
-    ap.add_argument("--variant", type=int, default=-1, help="score-pass arithmetic: 0 fma, 1 bf16 dot2, -1 library default")
+    ap.add_argument("--variant", type=int, default=-1, help="score pass of the five-call form: 0 fma, 1 bf16 dot2, 2 matrix cores, -1 library default (2)")
     ap.add_argument("--score-wg", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tokens", type=int, default=0, help="override the number of cached tokens (profiling only)")
@@ -293,7 +293,7 @@ def decode_bench(cfg, args, *, steps, warmup, with_cpu_baseline, with_graph):
     w = W.CONFIGS[cfg](**kw)
     N = int(w.seq_lens[0])
     if args.variant >= 0 or args.score_wg:
-        ts.ts_debug_set_score_variant(args.variant if args.variant >= 0 else 1, args.score_wg)
+        ts.ts_debug_set_score_variant(args.variant if args.variant >= 0 else 2, args.score_wg)
     compact = args.path != "dense" and args.selection == "soft"
     layer = DecodeLayer.from_workload(w, device=dev, num_initial=args.n_init, num_local=args.n_local)
     esize = w.esize()

@@ -291,8 +291,9 @@ int32_t ts_chunk_mean_query(const ts_problem* p, const void* q, void* q_mean, vo
  * ====================================================================================================== */
 
 /* Tuning knob for benchmarks and tests (process-wide, not thread-safe, not part of the method):
- * variant 0 = score pass with fma arithmetic, 1 = packed bf16 dot2 arithmetic (bf16 inputs only; the
- * default for bf16: same measured accuracy, fewer registers);
+ * variant 0 = score pass with fma arithmetic, 1 = packed bf16 dot2 arithmetic (bf16 inputs only),
+ * 2 = the matrix-core kernel for the shapes it covers (bf16, 3 to 8 query heads per KV head; elsewhere as 1): the
+ * default;
  * wg = workgroups per sequence in the score pass, 0 = automatic;
  * run_tiles = 32-token tiles a wave stages in LDS before it writes their scores as one run: 1, 2, 4,
  * or 0 = automatic (longer runs for longer sequences).  Results do not depend on wg or run_tiles.

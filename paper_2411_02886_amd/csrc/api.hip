@@ -7,7 +7,7 @@ __global__ void fill_zero_kernel(uint32_t* p, size_t n) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0u;
 }
 
-static int g_score_variant = 1;   // 0 = fma, 1 = packed bf16 dot2 (tuning knob, see ts_debug_set_score_variant)
+static int g_score_variant = 2;   // 0 = fma, 1 = packed bf16 dot2, 2 = matrix cores where the shape allows, else 1 (tuning knob, see ts_debug_set_score_variant)
 static int g_score_wg = 0;        // 0 = automatic
 static int g_score_rr = 0;        // tiles per staged run; 0 = automatic
 static int g_topk_five_pass = 0;  // 1 = force the five-pass radix select (tuning knob)
@@ -142,10 +142,10 @@ int32_t ts_workspace_init(void* ws, size_t ws_bytes, void* stream) {
 }
 
 /* Tuning knobs used by the benchmark and the tests to compare kernel variants; not part of the
- * method.  variant: 0 = fma arithmetic, 1 = packed bf16 dot2; wg: workgroups per sequence in the
- * score pass (0 = automatic). */
+ * method.  variant: 0 = fma arithmetic, 1 = packed bf16 dot2, 2 = the matrix-core kernel where the shape
+ * allows (the default; elsewhere as 1); wg: workgroups per sequence in the score pass (0 = automatic). */
 int32_t ts_debug_set_score_variant(int32_t variant, int32_t wg, int32_t run_tiles) {
-  if (variant < 0 || variant > 1 || wg < 0 || wg > kScoreMaxWg) return TS_ERR_INVALID_ARG;
+  if (variant < 0 || variant > 2 || wg < 0 || wg > kScoreMaxWg) return TS_ERR_INVALID_ARG;
   if (run_tiles != 0 && run_tiles != 1 && run_tiles != 2 && run_tiles != 4) return TS_ERR_INVALID_ARG;
   g_score_variant = variant; g_score_wg = wg; g_score_rr = run_tiles;
   return TS_OK;
@@ -217,6 +217,46 @@ static size_t score_lds_bytes(const ScoreArgs& a, int G) {
   return 4 * (per_wave + 64) * sizeof(float);   // + 64 block maxima per wave (compact form)
 }
 
+// Launch shape of the matrix-core score kernel (both forms): fills the wave-tile fields and a.RR, returns the
+// workgroups per sequence.  A wave owns one run of consecutive tiles where the sequence is short enough, so that
+// its output leaves in one burst at the end of its life; about 2048 waves per sequence (measured on MI355X:
+// 131072 tokens 49 us with one tile per wave, 45.7 us with two).
+static void mfma_launch_shape(const ts_problem* p, int G, bool dense, ScoreArgs* a, long* wg_out) {
+  a->HB = G <= 4 ? 8 : 4; a->hb_shift = ilog2(a->HB); a->NU = p->num_kv_heads / a->HB;
+  a->uniform_page = p->page_size >= (8 / a->HB);
+  const long ntt = (p->max_seq_len + kScoreTileTokens - 1) / kScoreTileTokens;
+  const int NU = a->NU;
+  auto wgs_of = [&](int r) -> long {
+    long n = ((ntt + r - 1) / r * NU + 3) / 4;
+    return n > kScoreMaxWg ? (long)kScoreMaxWg : n;
+  };
+  int rr = g_codes_rr;
+  if (rr <= 0) {
+    // Longest run that still gives every CU two workgroups, among those the one whose workgroups fill the
+    // rounds best: the CU holds floor(160 KiB / LDS) workgroups, three at most (registers), and a last round
+    // that is half empty costs as much as a full one (786432 tokens of H 28/4: 8-tile runs 151 us, 6-tile runs
+    // two full rounds).
+    rr = 1;
+    double best = -1.0;
+    for (int r = 8; r >= 1; r -= (r > 2 ? 2 : 1)) {     // 8, 6, 4, 2, 1: odd run lengths measured slower throughout
+      const long n = wgs_of(r);
+      if (r > 1 && n < 512) continue;
+      long per_cu = (long)(163840 / score_codes_mfma_lds_bytes(p->head_dim, G, r, dense));
+      if (per_cu > 3) per_cu = 3;
+      if (per_cu < 1) continue;
+      const long slots = 256 * per_cu, rounds = (n + slots - 1) / slots;
+      const double fill = (double)n / (double)(rounds * slots);
+      if (fill > best + 0.05) { best = fill; rr = r; }
+    }
+  }
+  if (rr > 8) rr = 8;
+  while (rr > 1 && score_codes_mfma_lds_bytes(p->head_dim, G, rr, dense) > 163840) --rr;
+  a->RR = rr;
+  long wgl = wgs_of(rr);
+  if (g_score_wg > 0) wgl = g_score_wg;
+  *wg_out = wgl;
+}
+
 // Algorithm 1's state for the score launches that run the test themselves
 static int32_t fill_selcache(const ts_problem* p, const void* q, const ts_selcache* sc, ScoreArgs* a) {
   if (sc == nullptr || sc->cached_q == nullptr || sc->cached_q_next == nullptr || sc->first == nullptr ||
@@ -248,9 +288,17 @@ static int32_t paged_qk_scores_impl(const ts_problem* p, const void* q, const ts
   if (sc != nullptr && (st = fill_selcache(p, q, sc, &a)) != TS_OK) return st;
   const int G = p->num_q_heads / p->num_kv_heads;
   a.scores = scores;
+  if (g_score_variant == 2 && g_codes_mfma && (p->num_q_heads % 4) == 0 && (((uintptr_t)scores & 3) == 0) &&
+      score_codes_mfma_supported(p->dtype, p->head_dim, G, p->num_kv_heads)) {
+    long wgl = 0;
+    mfma_launch_shape(p, G, true, &a, &wgl);
+    const hipError_t e = launch_score_codes_mfma(p->head_dim, G, a, dim3((unsigned)wgl, p->batch),
+                                                 score_codes_mfma_lds_bytes(p->head_dim, G, a.RR, true), (hipStream_t)stream);
+    return e == hipSuccess ? TS_OK : TS_ERR_HIP;
+  }
   a.vec_store = (p->num_q_heads % 4 == 0) && ((a.HB * G) % 4 == 0) && (((uintptr_t)scores & 15) == 0);
   const int wg = score_workgroups(p);
-  const int variant = (p->dtype == TS_BF16) ? g_score_variant : 0;
+  const int variant = (p->dtype == TS_BF16) ? (g_score_variant != 0 ? 1 : 0) : 0;
   const hipError_t e = launch_score_decode(p->dtype, p->head_dim, G, variant, a, dim3(wg, p->batch), score_lds_bytes(a, G), (hipStream_t)stream);
   return e == hipSuccess ? TS_OK : TS_ERR_HIP;
 }
@@ -283,46 +331,15 @@ static int32_t paged_qk_codes_impl(const ts_problem* p, const void* q, const ts_
   a.blk_max = (float*)((uint8_t*)ws + w.blk_max); a.nblk = w.score_nblk;
   if (g_codes_mfma && (p->num_q_heads % 4) == 0 && (((uintptr_t)codes & 3) == 0) &&
       score_codes_mfma_supported(p->dtype, p->head_dim, G, p->num_kv_heads)) {
-    // matrix-core form: a wave owns one run of consecutive tiles where the sequence is short enough, so that
-    // its bytes leave in one burst at the end of its life; about 2048 waves per sequence (measured on MI355X:
-    // 131072 tokens 49 us with one tile per wave, 45.7 us with two)
-    a.HB = G <= 4 ? 8 : 4; a.hb_shift = ilog2(a.HB); a.NU = p->num_kv_heads / a.HB;
-    a.uniform_page = p->page_size >= (8 / a.HB);
-    const long ntt = (p->max_seq_len + kScoreTileTokens - 1) / kScoreTileTokens;
-    auto wgs_of = [&](int r) -> long {
-      long n = ((ntt + r - 1) / r * a.NU + 3) / 4;
-      return n > kScoreMaxWg ? (long)kScoreMaxWg : n;
-    };
-    int rr = g_codes_rr;
-    if (rr <= 0) {
-      // Longest run that still gives every CU two workgroups, among those the one whose workgroups fill the
-      // rounds best: the CU holds floor(160 KiB / LDS) workgroups, three at most (registers), and a last round
-      // that is half empty costs as much as a full one (786432 tokens of H 28/4: 8-tile runs 151 us, 6-tile runs
-      // two full rounds).
-      rr = 1;
-      double best = -1.0;
-      for (int r = 8; r >= 1; r -= (r > 2 ? 2 : 1)) {     // 8, 6, 4, 2, 1: odd run lengths measured slower throughout
-        const long n = wgs_of(r);
-        if (r > 1 && n < 512) continue;
-        long per_cu = (long)(163840 / score_codes_mfma_lds_bytes(p->head_dim, G, r));
-        if (per_cu > 3) per_cu = 3;
-        if (per_cu < 1) continue;
-        const long slots = 256 * per_cu, rounds = (n + slots - 1) / slots;
-        const double fill = (double)n / (double)(rounds * slots);
-        if (fill > best + 0.05) { best = fill; rr = r; }
-      }
-    }
-    if (rr > 8) rr = 8;
-    a.RR = rr;
-    long wgl = wgs_of(rr);
-    if (g_score_wg > 0) wgl = g_score_wg;
+    long wgl = 0;
+    mfma_launch_shape(p, G, false, &a, &wgl);
     const hipError_t e = launch_score_codes_mfma(p->head_dim, G, a, dim3((unsigned)wgl, p->batch),
-                                                 score_codes_mfma_lds_bytes(p->head_dim, G, rr), (hipStream_t)stream);
+                                                 score_codes_mfma_lds_bytes(p->head_dim, G, a.RR, false), (hipStream_t)stream);
     return e == hipSuccess ? TS_OK : TS_ERR_HIP;
   }
   a.vec_store = (p->num_q_heads % 4 == 0) && ((a.HB * G) % 4 == 0) && (((uintptr_t)codes & 3) == 0);
   const int wg = score_workgroups(p);
-  const int variant = (p->dtype == TS_BF16) ? g_score_variant : 0;
+  const int variant = (p->dtype == TS_BF16) ? (g_score_variant != 0 ? 1 : 0) : 0;
   const hipError_t e = launch_score_decode(p->dtype, p->head_dim, G, variant, a, dim3(wg, p->batch), score_lds_bytes(a, G), (hipStream_t)stream);
   return e == hipSuccess ? TS_OK : TS_ERR_HIP;
 }

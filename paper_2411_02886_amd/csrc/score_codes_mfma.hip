@@ -32,7 +32,8 @@ typedef __attribute__((ext_vector_type(8))) __bf16 mfma_bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) float mfma_f32x4_t;
 
 // G in 3..4: CP = 4, column block = 4 KV heads, wave tile = 8 KV heads.  G in 5..8: CP = 8, 2 and 4.
-template <int D, int G>
+// DENSE: Algorithm 2's score matrix itself leaves the chip (fp32 rows, ts_paged_qk_scores) instead of the bytes.
+template <int D, int G, bool DENSE>
 __global__ __launch_bounds__(256) void score_codes_mfma_kernel(ScoreArgs a) {
   constexpr int RB = D * 2;            // bytes per K row
   constexpr int L = RB / 128;          // 16-byte loads per lane per row
@@ -77,7 +78,7 @@ __global__ __launch_bounds__(256) void score_codes_mfma_kernel(ScoreArgs a) {
   const int H = a.H;
   const int RR = a.RR;                                    // tiles per run: bytes and statistics leave once per run
   // wave-private LDS: K tile, code bytes of the run, statistics of the run
-  const int code_bytes = RR * TT * HBG;
+  const int code_bytes = RR * TT * HBG * (DENSE ? 4 : 1);
   const int wave_bytes = 32 * ROWP + code_bytes + RR * HBG * 4;
   uint8_t* ktile = smem8 + (size_t)wave * wave_bytes;
   uint8_t* cbuf = ktile + 32 * ROWP;
@@ -205,15 +206,23 @@ __global__ __launch_bounds__(256) void score_codes_mfma_kernel(ScoreArgs a) {
       if (mx != -INFINITY) wl[cb] += sm * __builtin_amdgcn_exp2f(c2 * (mx - wm[cb]));
       const int hc = (cb * KB + kvo) * G + gq;             // column among the wave's HBG
       if (col_ok) {
-        if (kg == 0) smax[f * HBG + hc] = mx;
+        if (DENSE) {
+          float* sbuf = reinterpret_cast<float*>(cbuf);
 #pragma unroll
-        for (int bb = 0; bb < NBLK; ++bb)
+          for (int bb = 0; bb < NBLK; ++bb)
 #pragma unroll
-          for (int e = 0; e < UPL; ++e) {
-            const int tl = bb * TB + kg * UPL + e;
-            const float qf = fminf(fmaxf(255.f + ceilf(4.f * c2 * (sv[bb][cb][e] - mx)), 0.f), 255.f);
-            cbuf[(f * TT + tl) * HBG + hc] = (uint8_t)(uint32_t)qf;
-          }
+            for (int e = 0; e < UPL; ++e) sbuf[(f * TT + bb * TB + kg * UPL + e) * HBG + hc] = sv[bb][cb][e];
+        } else {
+          if (kg == 0) smax[f * HBG + hc] = mx;
+#pragma unroll
+          for (int bb = 0; bb < NBLK; ++bb)
+#pragma unroll
+            for (int e = 0; e < UPL; ++e) {
+              const int tl = bb * TB + kg * UPL + e;
+              const float qf = fminf(fmaxf(255.f + ceilf(4.f * c2 * (sv[bb][cb][e] - mx)), 0.f), 255.f);
+              cbuf[(f * TT + tl) * HBG + hc] = (uint8_t)(uint32_t)qf;
+            }
+        }
       }
     }
   };
@@ -222,6 +231,28 @@ __global__ __launch_bounds__(256) void score_codes_mfma_kernel(ScoreArgs a) {
     wave_lds_sync();
     const int t0 = tile0 * TT;
     const int ntok = min(ntiles * TT, N - t0);
+    if (DENSE) {
+      // fp32 rows, token-major; streamed out (the vote kernel reads them from memory anyway)
+      typedef float v4f __attribute__((ext_vector_type(4)));
+      const float* sbuf = reinterpret_cast<const float*>(cbuf);
+      if (a.NU == 1) {
+        float* dst = a.scores + ((size_t)b * a.max_seq_len + t0) * H;
+        const int nf = ntok * H;                          // H is a multiple of 4
+        if ((reinterpret_cast<uintptr_t>(dst) & 15) == 0) {
+          for (int i = lane; i < (nf >> 2); i += 64)
+            __builtin_nontemporal_store(reinterpret_cast<const v4f*>(sbuf)[i], reinterpret_cast<v4f*>(dst) + i);
+        } else {
+          for (int i = lane; i < nf; i += 64) __builtin_nontemporal_store(sbuf[i], dst + i);
+        }
+      } else {
+        for (int i = lane; i < ntok * HBG; i += 64) {
+          const int tok = i / HBG, c = i - tok * HBG;
+          __builtin_nontemporal_store(sbuf[i], a.scores + ((size_t)b * a.max_seq_len + t0 + tok) * H + h_base + c);
+        }
+      }
+      wave_lds_sync();
+      return;
+    }
     if (a.NU == 1) {
       uint8_t* dst = a.codes + ((size_t)b * a.max_seq_len + t0) * H;
       const int nbytes = ntok * H;
@@ -342,28 +373,34 @@ bool score_codes_mfma_supported(int dtype, int D, int G, int H_kv) {
   return false;
 }
 
-size_t score_codes_mfma_lds_bytes(int D, int G, int RR) {
+// dense: the run's fp32 rows are staged instead of its bytes
+size_t score_codes_mfma_lds_bytes(int D, int G, int RR, bool dense) {
   const int HB = G <= 4 ? 8 : 4;
-  const size_t per_wave = (size_t)32 * (D * 2 + 16) + (size_t)RR * kScoreTileTokens * HB * G + (size_t)RR * HB * G * 4;
+  const size_t per_wave = (size_t)32 * (D * 2 + 16) + (size_t)RR * kScoreTileTokens * HB * G * (dense ? 4 : 1) +
+                          (size_t)RR * HB * G * 4;
   return 4 * per_wave;
 }
 
-template <int D, int G>
+template <int D, int G, bool DENSE>
 static hipError_t launch_cm(const ScoreArgs& a, dim3 grid, size_t lds, hipStream_t s) {
   if (lds > 65536) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_codes_mfma_kernel<D, G>),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_codes_mfma_kernel<D, G, DENSE>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
   }
   if (g_codes_time_start != nullptr && g_codes_time_stop != nullptr)
-    hipExtLaunchKernelGGL((score_codes_mfma_kernel<D, G>), grid, dim3(256), (uint32_t)lds, s, g_codes_time_start, g_codes_time_stop, 0u, a);
+    hipExtLaunchKernelGGL((score_codes_mfma_kernel<D, G, DENSE>), grid, dim3(256), (uint32_t)lds, s, g_codes_time_start, g_codes_time_stop, 0u, a);
   else
-    hipLaunchKernelGGL((score_codes_mfma_kernel<D, G>), grid, dim3(256), lds, s, a);
+    hipLaunchKernelGGL((score_codes_mfma_kernel<D, G, DENSE>), grid, dim3(256), lds, s, a);
   return hipGetLastError();
 }
 
+// a.codes != nullptr: the compact form; else a.scores receives the fp32 score matrix
 hipError_t launch_score_codes_mfma(int D, int G, const ScoreArgs& a, dim3 grid, size_t lds, hipStream_t s) {
-#define TS_CM(GG) case GG: return D == 64 ? launch_cm<64, GG>(a, grid, lds, s) : launch_cm<128, GG>(a, grid, lds, s);
+  const bool dense = a.codes == nullptr;
+#define TS_CM(GG) case GG: \
+    if (dense) return D == 64 ? launch_cm<64, GG, true>(a, grid, lds, s) : launch_cm<128, GG, true>(a, grid, lds, s); \
+    return D == 64 ? launch_cm<64, GG, false>(a, grid, lds, s) : launch_cm<128, GG, false>(a, grid, lds, s);
   switch (G) { TS_CM(3) TS_CM(4) TS_CM(5) TS_CM(6) TS_CM(7) TS_CM(8) }
 #undef TS_CM
   return hipErrorInvalidValue;

@@ -191,7 +191,7 @@ hipError_t launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t s);
 void set_score_timing_events(hipEvent_t start, hipEvent_t stop);
 void set_codes_timing_events(hipEvent_t start, hipEvent_t stop);
 bool score_codes_mfma_supported(int dtype, int D, int G, int H_kv);
-size_t score_codes_mfma_lds_bytes(int D, int G, int RR);
+size_t score_codes_mfma_lds_bytes(int D, int G, int RR, bool dense = false);
 hipError_t launch_score_codes_mfma(int D, int G, const ScoreArgs& a, dim3 grid, size_t lds, hipStream_t s);
 
 }  // namespace ts

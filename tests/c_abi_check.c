@@ -131,6 +131,7 @@ int main(void) {
   EXPECT(ts_debug_set_score_variant(7, 0, 0), TS_ERR_INVALID_ARG);
   EXPECT(ts_debug_set_score_variant(1, 0, 3), TS_ERR_INVALID_ARG);
   EXPECT(ts_debug_set_score_variant(1, 0, 0), TS_OK);
+  EXPECT(ts_debug_set_score_variant(2, 0, 0), TS_OK);
   EXPECT(ts_debug_set_codes_path(2, 0), TS_ERR_INVALID_ARG);
   EXPECT(ts_debug_set_codes_path(1, 9), TS_ERR_INVALID_ARG);
   EXPECT(ts_debug_set_codes_path(1, 0), TS_OK);

@@ -70,6 +70,7 @@ def test_calls_reject_bad_arguments_without_launching():
     assert L.ts_debug_set_score_variant(7, 0, 0) == -1
     assert L.ts_debug_set_score_variant(1, 0, 3) == -1
     assert L.ts_debug_set_score_variant(1, 0, 0) == 0
+    assert L.ts_debug_set_score_variant(2, 0, 0) == 0
     assert L.ts_debug_set_topk_path(2) == -1 and L.ts_debug_set_topk_path(0) == 0
 
 

@@ -50,14 +50,18 @@ def codes_from_definition(S, lo, hi, bt, c2):
     return out
 
 
-def check_compact(w, layer, q_dev, *, score_scale=1.0, label=""):
-    """Both forms of the compact score pass: the vector form shares the dense path's score arithmetic (its bytes
-    follow from the dense scores bit for bit), the matrix-core form may differ by a few ulp per score."""
+def check_compact(w, layer, q_dev, *, score_scale=1.0, label="", score_variant=2, codes_run_tiles=0):
+    """Both forms of the compact score pass against the five-call form.  With the matrix-core kernels switched off
+    both passes run the vector kernel, with them on (and the score variant at its default, 2) both run the
+    matrix-core kernel: the bytes then follow from the five-call form's scores bit for bit.  A caller that has set
+    score variant 0 or 1 (the vector kernel for the score matrix) says so: the matrix-core bytes may then differ
+    from that matrix by a few ulp per score."""
     import paper_2411_02886_amd as ts
     for mfma in (0, 1):
-        ts.ts_debug_set_codes_path(mfma, 0)
+        ts.ts_debug_set_codes_path(mfma, codes_run_tiles if mfma else 0)
         try:
-            _check_compact(w, layer, q_dev, score_scale=score_scale, label=label + (" mfma" if mfma else " valu"), exact_bytes=(mfma == 0))
+            _check_compact(w, layer, q_dev, score_scale=score_scale, label=label + (" mfma" if mfma else " valu"),
+                           exact_bytes=(mfma == 0 or score_variant == 2))
         finally:
             ts.ts_debug_set_codes_path(1, 0)
 
@@ -140,7 +144,7 @@ def test_config1_tiny_fp32(gpu):
         check_compact(w, layer, q, score_scale=scale, label="cfg1 c=%.3f" % scale)
 
 
-@pytest.mark.parametrize("variant", [0, 1])
+@pytest.mark.parametrize("variant", [0, 1, 2], ids=["fma", "dot2", "matrix-cores"])
 def test_config2_shape_reduced(gpu, variant):
     gpu.ts_debug_set_score_variant(variant, 0)
     try:
@@ -148,9 +152,9 @@ def test_config2_shape_reduced(gpu, variant):
         layer, q = make_layer(w)
         for scale in (1.0, 1.0 / math.sqrt(w.D)):
             print("compact cfg2-small variant", variant, "scale", scale, flush=True)
-            check_compact(w, layer, q, score_scale=scale, label="cfg2s v%d c=%.3f" % (variant, scale))
+            check_compact(w, layer, q, score_scale=scale, label="cfg2s v%d c=%.3f" % (variant, scale), score_variant=variant)
     finally:
-        gpu.ts_debug_set_score_variant(1, 0)
+        gpu.ts_debug_set_score_variant(2, 0)
 
 
 SHAPES = [
@@ -195,24 +199,24 @@ def test_longer_blocks(gpu, run_tiles):
         w = W.config2(N=9000, k=500, seed=5)
         layer, q = make_layer(w)
         print("compact run_tiles", run_tiles, flush=True)
-        check_compact(w, layer, q, score_scale=1.0, label="rr%d" % run_tiles)
+        check_compact(w, layer, q, score_scale=1.0, label="rr%d" % run_tiles, score_variant=1)
     finally:
-        gpu.ts_debug_set_score_variant(1, 0, 0)
+        gpu.ts_debug_set_score_variant(2, 0, 0)
 
 
 @pytest.mark.parametrize("rr,wg", [(1, 0), (3, 5), (8, 2), (5, 0), (2, 1)])
 @pytest.mark.parametrize("heads", [(32, 8), (28, 4)])
 def test_matrix_core_score_pass_run_lengths_and_grids(gpu, rr, wg, heads):
     """The matrix-core score pass with other run lengths and with grids so small that a wave takes several runs."""
-    gpu.ts_debug_set_codes_path(1, rr); gpu.ts_debug_set_score_variant(1, wg, 0)
+    gpu.ts_debug_set_score_variant(2, wg, 0)              # both forms on the matrix cores, same grid and run length
     try:
         w = W.make_workload("mfma_runs", dtype=W.BF16, H=heads[0], H_kv=heads[1], D=128, P=16, B=2, seq_lens=[9000, 3333],
                             k=300, beta=2.5, planted_per_head=2, seed=77 + rr)
         layer, q = make_layer(w)
         print("compact matrix-core run_tiles", rr, "workgroups", wg, heads, flush=True)
-        check_compact(w, layer, q, score_scale=1.0, label="mfma rr%d wg%d" % (rr, wg))
+        check_compact(w, layer, q, score_scale=1.0, label="mfma rr%d wg%d" % (rr, wg), codes_run_tiles=rr)
     finally:
-        gpu.ts_debug_set_codes_path(1, 0); gpu.ts_debug_set_score_variant(1, 0, 0)
+        gpu.ts_debug_set_codes_path(1, 0); gpu.ts_debug_set_score_variant(2, 0, 0)
 
 
 def test_batch_ragged_and_forced(gpu):
@@ -324,7 +328,7 @@ def test_tuning_knob_changed_between_the_calls_of_a_step(gpu):
         v = to_host(layer.votes)[0].astype(np.float64)
         np.testing.assert_allclose(v, ora["votes"], rtol=3e-5, atol=1e-44)
         compare_index_sets(to_host(layer.idx)[0], int(to_host(layer.count)[0]), ora, "knob flip, five calls")
-        gpu.ts_debug_set_score_variant(1, 0, 0)
+        gpu.ts_debug_set_score_variant(2, 0, 0)
         gpu.ts_paged_qk_codes(layer.problem, q, layer_codes(layer), 1.0, None, layer.ws)
         gpu.ts_debug_set_score_variant(0, 3, 1); gpu.ts_debug_set_codes_path(0, 1)
         gpu.ts_soft_vote_bounds(layer.problem, layer.codes, 1.0, layer.row_stats, layer.vote_hi, layer.vote_lo, None, layer.ws)
@@ -332,7 +336,7 @@ def test_tuning_knob_changed_between_the_calls_of_a_step(gpu):
         torch.cuda.synchronize()
         compare_index_sets(to_host(layer.idx)[0], int(to_host(layer.count)[0]), ora, "knob flip, compact")
     finally:
-        gpu.ts_debug_set_score_variant(1, 0, 0); gpu.ts_debug_set_codes_path(1, 0)
+        gpu.ts_debug_set_score_variant(2, 0, 0); gpu.ts_debug_set_codes_path(1, 0)
 
 
 def layer_codes(layer):

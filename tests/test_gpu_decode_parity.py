@@ -36,7 +36,7 @@ def test_config1_tiny_fp32(gpu):
         check_decode_against_oracle(w, layer, q, score_scale=scale, label="cfg1 c=%.3f" % scale)
 
 
-@pytest.mark.parametrize("variant", [0, 1])
+@pytest.mark.parametrize("variant", [0, 1, 2], ids=["fma", "dot2", "matrix-cores"])
 def test_config2_shape_bf16_reduced_length(gpu, variant):
     # config 2's head shapes at 5000 tokens (not a multiple of the 32-token tile nor of the page)
     gpu.ts_debug_set_score_variant(variant, 0)
@@ -47,7 +47,7 @@ def test_config2_shape_bf16_reduced_length(gpu, variant):
             print("cfg2-small variant", variant, "scale", scale, flush=True)
             check_decode_against_oracle(w, layer, q, score_scale=scale, label="cfg2s v%d c=%.3f" % (variant, scale))
     finally:
-        gpu.ts_debug_set_score_variant(1, 0)          # back to the library default
+        gpu.ts_debug_set_score_variant(2, 0)          # back to the library default
 
 
 SHAPES = [
@@ -98,7 +98,7 @@ def test_staged_runs_of_several_tiles(gpu, run_tiles):
         print("run_tiles", run_tiles, "ragged batch", lens, flush=True)
         check_decode_against_oracle(w, layer, q, score_scale=0.1, label="ragged run%d" % run_tiles)
     finally:
-        gpu.ts_debug_set_score_variant(1, 0, 0)
+        gpu.ts_debug_set_score_variant(2, 0, 0)
 
 
 @pytest.mark.parametrize("n_init,n_local", [(128, 512), (5, 0), (0, 33), (16, 100)])
