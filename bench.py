@@ -37,8 +37,8 @@ HBM_PEAK_GBS = 8000.0
 # profiles/decode_step_cfg4_hbm_traffic.md, profiles/decode_step_cfg2_hbm_traffic.md)
 MEASURED_TRAFFIC_BYTES = {(4, "compact"): int((512.30 * 1.966 + 31.73 * 1.00) * 2**20),
                           (2, "compact"): int((128.26 * 1.983 + 4.63 * 1.00) * 2**20),
-                          (4, "dense"): int((512.23 * 1.966 + 114.65 * 1.00) * 2**20),
-                          (2, "dense"): int((128.16 * 1.983 + 16.25 * 1.00) * 2**20)}
+                          (4, "dense"): int((512.26 * 1.966 + 112.38 * 1.00) * 2**20),
+                          (2, "dense"): int((128.21 * 1.983 + 16.13 * 1.00) * 2**20)}
 
 
 def parse():
@@ -471,7 +471,7 @@ def decode_bench(cfg, args, *, steps, warmup, with_cpu_baseline, with_graph):
             graph_info = {"error": str(e)[:200]}
 
     kernel_name = ("ts::score_codes_mfma_kernel (the one launch of ts_paged_qk_codes%s)" if compact else
-                   "ts::score_decode_kernel (the one launch of ts_paged_qk_scores%s)") % ("_checked, Selection Cache test included" if fused_check else "")
+                   "the one launch of ts_paged_qk_scores%s (ts::score_codes_mfma_kernel<.., DENSE> for bf16 with 3..8 query heads per KV head, else ts::score_decode_kernel)") % ("_checked, Selection Cache test included" if fused_check else "")
     traffic = MEASURED_TRAFFIC_BYTES.get((cfg, "compact" if compact else "dense")) if not args.tokens and args.page_size == 16 else None
     res = {
         "ms_per_step": ms_step,
