@@ -66,6 +66,8 @@ def parse():
     ap.add_argument("--page-size", type=int, default=16, help="tokens per page (16 in the configurations; 1 is the paper's own setting)")
     ap.add_argument("--selection", choices=["soft", "sum", "head"], default="soft",
                     help="selection function: soft = Eq. 5 (the method, default), sum = Eq. 3, head = Eq. 4 (ablation baselines)")
+    ap.add_argument("--vote", choices=["ranked", "plain"], default="ranked",
+                    help="five-call form: ts_soft_vote_ranked + ts_topk(TS_TOPK_VOTE_HIST) (one launch less) or ts_soft_vote + ts_topk")
     ap.add_argument("--check", choices=["fused", "call"], default=None,
                     help="Selection Cache test: inside the score launch (fused) or as the ts_selcache_check call before it "
                          "(default: fused, except for the batch of config 3, where the call is the faster form)")
@@ -141,7 +143,7 @@ def selection_cache_run(args):
         for t in range(steps):
             kvflat.index_copy_(1, slots_d[t], kvsd[t])          # append this step's K/V rows
             layer.problem, layer.reuse = problems[t], reuse_log[t]   # the step's lengths; its reuse flags go straight to the log
-            layer.step(qs[t], theta=theta, score_scale=scale, sm_scale=sm, compact=compact, fused_check=args.check == "fused")
+            layer.step(qs[t], theta=theta, score_scale=scale, sm_scale=sm, compact=compact, fused_check=args.check == "fused", ranked_vote=args.vote == "ranked")
 
     run(); torch.cuda.synchronize()
     reps = max(1, args.steps // steps)
@@ -197,7 +199,7 @@ def selection_cache_run(args):
            "selection_form": "compact (no score matrix in memory)" if compact else "five calls (fp32 score matrix)",
            "selection_cache_check": "inside the score launch" if args.check == "fused" else "ts_selcache_check before the score launch",
            "note": ("%d library launches + 1 torch launch (the append of the step's K/V rows) per step; " %
-                    ((8 if compact else 9) - (1 if args.check == "fused" else 0))) +
+                    ((8 if compact else (8 if args.vote == "ranked" else 9)) - (1 if args.check == "fused" else 0))) +
                    "'graph' = the whole 64-step run captured once as a HIP graph "
                    "and replayed (replays checked against the eager run), 'eager' = host-driven loop"}
     if args.theta_sweep:
@@ -334,6 +336,7 @@ def decode_bench(cfg, args, *, steps, warmup, with_cpu_baseline, with_graph):
         layer.vote_lo = torch.empty((w.B, layer.max_seq_len), dtype=torch.float32, device=dev)
 
     fused_check = args.check == "fused"       # Algorithm 1's test inside the score launch (one launch less)
+    ranked_vote = args.vote == "ranked"       # five-call form: the TopK's first histogram is built inside the vote launch
 
     def score_pass(p, q, stream):
         if fused_check:
@@ -365,13 +368,16 @@ def decode_bench(cfg, args, *, steps, warmup, with_cpu_baseline, with_graph):
             ts.ts_soft_vote_bounds(p, layer.codes, scale, layer.row_stats, layer.vote_hi, layer.vote_lo, layer.reuse, layer.ws, stream)
             ts.ts_topk_exact(p, q, layer.vote_hi, layer.row_stats, scale, layer.k, layer.idx, layer.count, layer.reuse, layer.ws, stream)
         else:
-            if args.selection == "soft":
+            if args.selection == "soft" and ranked_vote:
+                ts.ts_soft_vote_ranked(p, layer.scores, scale, layer.row_stats, layer.votes, layer.reuse, layer.ws, stream)
+            elif args.selection == "soft":
                 ts.ts_soft_vote(p, layer.scores, scale, layer.row_stats, layer.votes, layer.reuse, layer.ws, stream)
             elif args.selection == "sum":
                 ts.ts_sum_vote(p, layer.scores, layer.votes, layer.reuse, stream)
             else:
                 ts.ts_head_vote(p, layer.scores, layer.k, layer.votes, layer.reuse, hv_scratch, stream)
-            ts.ts_topk(p, layer.votes, layer.k, layer.idx, layer.count, layer.reuse, layer.ws, stream)
+            ts.ts_topk(p, layer.votes, layer.k, layer.idx, layer.count, layer.reuse, layer.ws, stream,
+                       flags=ts.TS_TOPK_VOTE_HIST if (args.selection == "soft" and ranked_vote) else 0)
         if ev is not None:
             ev[1].record(stream)
         ts.ts_sparse_paged_attn(p, q, layer.idx, layer.k, layer.count, sm, layer.out, layer.lse, layer.ws, stream)
@@ -485,8 +491,9 @@ def decode_bench(cfg, args, *, steps, warmup, with_cpu_baseline, with_graph):
                    "selection_function": {"soft": "Eq. 5 head soft vote", "sum": "Eq. 3 summed dot products",
                                           "head": "Eq. 4 head vote"}[args.selection],
                    "selection_form": ("compact: ts_paged_qk_codes + ts_soft_vote_bounds + ts_topk_exact (no score matrix in memory)"
-                                      if compact else "five calls: ts_paged_qk_scores + ts_soft_vote + ts_topk (fp32 score matrix)")},
-        "launches_per_step": (8 if compact else 9) - (1 if fused_check else 0),
+                                      if compact else ("five calls: ts_paged_qk_scores + ts_soft_vote_ranked + ts_topk (fp32 score matrix; the TopK's first histogram built inside the vote launch)"
+                                            if (ranked_vote and args.selection == "soft") else "five calls: ts_paged_qk_scores + ts_soft_vote + ts_topk (fp32 score matrix)"))},
+        "launches_per_step": (8 if compact else (8 if (ranked_vote and args.selection == "soft") else 9)) - (1 if fused_check else 0),
         "selection_cache_check": ("inside the score launch (ts_paged_qk_%s_checked)" % ("codes" if compact else "scores")) if fused_check else "ts_selcache_check before the score launch",
         "planted_token_quality": quality,
         "compact_vs_five_call_index_overlap": dense_agrees,

@@ -128,6 +128,15 @@ int32_t ts_paged_qk_scores(const ts_problem* p, const void* q, float* scores, fl
 int32_t ts_soft_vote(const ts_problem* p, const float* scores, float score_scale, float* row_stats, float* votes,
                      const uint8_t* skip, void* ws, size_t ws_bytes, void* stream);
 
+/* Eq. 5 and the start of the TopK in one launch: ts_soft_vote that also counts, while the votes are in registers,
+ * the histogram of their top 11 key bits -- the first pass of ts_topk's radix select (one launch less per decode
+ * step).  Same arguments, same row_stats and votes as ts_soft_vote, bit for bit.
+ * Contract: the histogram lives in ws until a ts_topk call with TS_TOPK_VOTE_HIST, the same votes, skip mask and ws
+ * consumes and clears it; that call must be the next selection call on ws (ts_soft_vote_bounds / ts_topk_exact share
+ * the section).  After a call that was not followed that way, ts_workspace_init restores the workspace. */
+int32_t ts_soft_vote_ranked(const ts_problem* p, const float* scores, float score_scale, float* row_stats,
+                            float* votes, const uint8_t* skip, void* ws, size_t ws_bytes, void* stream);
+
 /* TopK of Eq. 3-5 over votes[b][0..N_b): the min(k, N_b) largest values, equal values taken in
  * order of increasing token index, written as ascending logical token ids.
  * idx [device] int32 [B][k] (slots past the count are set to -1); count [device] int32 [B].
@@ -135,8 +144,11 @@ int32_t ts_soft_vote(const ts_problem* p, const float* scores, float score_scale
  * flags: 0, or TS_TOPK_FLAT_VOTES.  By default (decode) the radix select runs as three launches whose last one
  * finishes each sequence on one workgroup: fast when few votes lie within a quarter octave of the k-th vote, as
  * with the peaked votes of Eq. 5, and slow (still exact) when most do.  TS_TOPK_FLAT_VOTES selects the five-launch
- * form whose time does not depend on the distribution; chunk problems (chunk > 1) always use it. */
+ * form whose time does not depend on the distribution; chunk problems (chunk > 1) always use it.
+ * TS_TOPK_VOTE_HIST: the votes were written by ts_soft_vote_ranked, which left the radix select's first histogram in
+ * ws (see there): the pass that builds it is skipped (decode only; not for ts_topk_noalloc). */
 #define TS_TOPK_FLAT_VOTES 1
+#define TS_TOPK_VOTE_HIST 2
 int32_t ts_topk(const ts_problem* p, const float* votes, int32_t k, int32_t* idx, int32_t* count,
                 const uint8_t* skip, int32_t flags, void* ws, size_t ws_bytes, void* stream);
 

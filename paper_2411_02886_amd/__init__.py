@@ -9,5 +9,5 @@ from .binding import (  # noqa: F401
     ts_chunk_mean_query, ts_sum_vote, ts_head_vote, ts_head_vote_scratch_bytes,
     ts_debug_set_topk_path, ts_debug_event_create, ts_debug_event_destroy, ts_debug_event_elapsed_ms,
     ts_debug_set_score_timing_events, ts_paged_qk_codes, ts_soft_vote_bounds, ts_topk_exact, ts_debug_set_codes_path, ts_topk_noalloc,
-    ts_paged_qk_scores_checked, ts_paged_qk_codes_checked,
+    ts_paged_qk_scores_checked, ts_paged_qk_codes_checked, ts_soft_vote_ranked, TS_TOPK_VOTE_HIST,
 )

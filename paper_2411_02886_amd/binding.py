@@ -17,6 +17,7 @@ _HEADER = os.path.join(os.path.dirname(_HERE), "include", "tokenselect.h")
 
 TS_F32, TS_BF16 = 0, 1
 TS_TOPK_FLAT_VOTES = 1
+TS_TOPK_VOTE_HIST = 2
 
 
 class TokenSelectError(RuntimeError):
@@ -72,6 +73,7 @@ def load():
         L.ts_workspace_init.argtypes = [vp, sz, vp]
         L.ts_paged_qk_scores.argtypes = [pp, vp, vp, f32, vp, vp, sz, vp]
         L.ts_soft_vote.argtypes = [pp, vp, f32, vp, vp, vp, vp, sz, vp]
+        L.ts_soft_vote_ranked.argtypes = [pp, vp, f32, vp, vp, vp, vp, sz, vp]
         L.ts_topk.argtypes = [pp, vp, i32, vp, vp, vp, i32, vp, sz, vp]
         L.ts_topk_noalloc.argtypes = [pp, vp, i32, vp, vp, vp, i32, vp]
         L.ts_paged_qk_codes.argtypes = [pp, vp, vp, f32, vp, vp, sz, vp]
@@ -100,7 +102,7 @@ def load():
                      "ts_head_vote", "ts_debug_set_topk_path", "ts_debug_event_create", "ts_debug_event_destroy",
                      "ts_debug_event_elapsed_ms", "ts_debug_set_score_timing_events", "ts_paged_qk_codes",
                      "ts_soft_vote_bounds", "ts_topk_exact", "ts_debug_set_codes_path", "ts_topk_noalloc",
-                     "ts_paged_qk_scores_checked", "ts_paged_qk_codes_checked"):
+                     "ts_paged_qk_scores_checked", "ts_paged_qk_codes_checked", "ts_soft_vote_ranked"):
             getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -219,6 +221,11 @@ def ts_paged_qk_codes_checked(p: Problem, q, cached_q, cached_q_next, first, fir
     sc = _selcache(cached_q, cached_q_next, first, first_next, reuse, theta)
     _ok(load().ts_paged_qk_codes_checked(p.ref(), _ptr(q), ctypes.byref(sc), _ptr(codes), float(score_scale), _ptr(ws),
                                          _nbytes(ws), _stream(stream)), "ts_paged_qk_codes_checked")
+
+
+def ts_soft_vote_ranked(p: Problem, scores, score_scale: float, row_stats, votes, skip, ws, stream=None) -> None:
+    _ok(load().ts_soft_vote_ranked(p.ref(), _ptr(scores), float(score_scale), _ptr(row_stats), _ptr(votes), _ptr(skip),
+                                   _ptr(ws), _nbytes(ws), _stream(stream)), "ts_soft_vote_ranked")
 
 
 def ts_paged_qk_codes(p: Problem, q, codes, score_scale: float, skip, ws, stream=None) -> None:

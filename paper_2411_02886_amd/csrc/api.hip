@@ -431,12 +431,31 @@ int32_t ts_soft_vote(const ts_problem* p, const float* scores, float score_scale
   return launch_soft_vote(a, p->batch, (hipStream_t)stream) == hipSuccess ? TS_OK : TS_ERR_HIP;
 }
 
+int32_t ts_soft_vote_ranked(const ts_problem* p, const float* scores, float score_scale, float* row_stats, float* votes,
+                            const uint8_t* skip, void* ws, size_t ws_bytes, void* stream) {
+  int32_t st = check_problem(p);
+  if (st != TS_OK) return st;
+  if (scores == nullptr || row_stats == nullptr || votes == nullptr) return TS_ERR_INVALID_ARG;
+  if (!(score_scale >= 0.f) || !(score_scale < 1e30f)) return TS_ERR_INVALID_ARG;
+  if (p->chunk != 1) return TS_ERR_UNSUPPORTED;
+  const WsLayout w = ws_layout(p, 1);
+  if (ws == nullptr || ((uintptr_t)ws & 255) != 0 || ws_bytes < w.topk_blk) return TS_ERR_WORKSPACE;
+  VoteArgs a{};
+  a.partials = (const float*)((uint8_t*)ws + w.score_partials); a.hdr = (const uint32_t*)((uint8_t*)ws + w.hdr);
+  a.scores = scores; a.row_stats = row_stats; a.row_stats_out = row_stats; a.votes = votes; a.seq_lens = p->seq_lens; a.skip = skip;
+  a.H = p->num_q_heads; a.max_seq_len = p->max_seq_len; a.scale = score_scale;
+  a.n_init = p->num_initial; a.n_local = p->num_local;
+  a.rank_hist = (uint32_t*)((uint8_t*)ws + w.bound_hist);
+  return launch_soft_vote_ranked(a, p->batch, (hipStream_t)stream) == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
 int32_t ts_topk(const ts_problem* p, const float* votes, int32_t k, int32_t* idx, int32_t* count,
                 const uint8_t* skip, int32_t flags, void* ws, size_t ws_bytes, void* stream) {
   int32_t st = check_problem(p);
   if (st != TS_OK) return st;
   if (votes == nullptr || idx == nullptr || count == nullptr || k < 1) return TS_ERR_INVALID_ARG;
-  if ((flags & ~TS_TOPK_FLAT_VOTES) != 0) return TS_ERR_INVALID_ARG;
+  if ((flags & ~(TS_TOPK_FLAT_VOTES | TS_TOPK_VOTE_HIST)) != 0) return TS_ERR_INVALID_ARG;
+  if ((flags & TS_TOPK_VOTE_HIST) != 0 && p->chunk != 1) return TS_ERR_UNSUPPORTED;
   const WsLayout w = ws_layout(p, k);
   if (ws == nullptr || ((uintptr_t)ws & 255) != 0 || ws_bytes < w.attn_out) return TS_ERR_WORKSPACE;
   TopkArgs a{};
@@ -452,6 +471,7 @@ int32_t ts_topk(const ts_problem* p, const float* votes, int32_t k, int32_t* idx
   // distribution.
   a.list = (g_topk_five_pass || p->chunk > 1 || (flags & TS_TOPK_FLAT_VOTES)) ? nullptr : (uint2*)((uint8_t*)ws + w.topk_list);
   a.k = k; a.max_seq_len = p->max_seq_len; a.nblk = w.topk_nblk; a.heads = 1;
+  if ((flags & TS_TOPK_VOTE_HIST) != 0) a.rep_hist = (uint32_t*)((uint8_t*)ws + w.bound_hist);
   return launch_topk(a, p->batch, (hipStream_t)stream) == hipSuccess ? TS_OK : TS_ERR_HIP;
 }
 

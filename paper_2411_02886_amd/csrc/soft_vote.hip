@@ -127,6 +127,108 @@ __global__ __launch_bounds__(256) void soft_vote_kernel(VoteArgs a, int lpt_shif
   }
 }
 
+// Eq. 5 and the start of the TopK in one launch.  A workgroup of 1024 threads owns kRankTokens consecutive tokens:
+// it computes their votes as soft_vote_kernel does (same arithmetic, LPT lanes per token row, four passes of loads in
+// flight), counts the top 11 key bits of the ranked tokens' votes in an LDS histogram and adds the non-empty bins to
+// one of the replicated global histograms -- one flush per workgroup, spread over kBoundHistCopies copies, so the
+// same-address atomics stay few.  (Measured and dropped: merging the score pass's statistics partials inside this
+// kernel as well, every workgroup for itself.  At 128K tokens that is 128 KiB of partials per workgroup, 32 MiB of
+// L2 reads per launch, and costs the kernel 4.7 us -- what the merge launch costs.)
+constexpr int kRankTokens = 512;     // per workgroup: one round of four passes for H = 32, and a workgroup for every CU at 128K tokens
+
+template <int CPL, bool VEC>
+__global__ __launch_bounds__(1024) void soft_vote_ranked_kernel(VoteArgs a, int lpt_shift) {
+  __shared__ double s_m[128];
+  __shared__ double s_inv[128];
+  __shared__ uint32_t hist[kTopkBins];
+  constexpr int NP = 4;
+  const int b = blockIdx.y;
+  const int skip_flag = a.skip != nullptr ? (int)a.skip[b] : 0;   // issued together with the length
+  const int N = min(max(a.seq_lens[b], 0), a.max_seq_len);
+  if (skip_flag != 0) return;
+  const int tok0 = blockIdx.x * kRankTokens;
+  if (tok0 >= N) return;
+  const int H = a.H;
+  const double c2 = (double)a.scale * 1.44269504088896340736;
+  const int LPT = 1 << lpt_shift;
+  const int tpp = 1024 >> lpt_shift;                 // tokens per pass
+  const int jv = threadIdx.x & (LPT - 1);
+  const int npass = (kRankTokens + tpp - 1) / tpp;   // LPT / 2 passes, one for the narrowest rows
+  float s[NP][CPL][4];
+  // the scores of a round of NP passes: all loads issued up front
+  auto load_round = [&](int p0) {
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+      const int tc = min(tok0 + (p0 + p) * tpp + (int)(threadIdx.x >> lpt_shift), N - 1);   // out-of-range threads shadow the last token
+      const float* sp = a.scores + ((size_t)b * a.max_seq_len + tc) * H;
+#pragma unroll
+      for (int i = 0; i < CPL; ++i) {
+        const int h0 = (jv + i * LPT) * 4;
+        if (VEC) {
+          const float4 v = *reinterpret_cast<const float4*>(sp + min(h0, H - 4));   // clamped: no branch between loads
+          s[p][i][0] = v.x; s[p][i][1] = v.y; s[p][i][2] = v.z; s[p][i][3] = v.w;
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) s[p][i][e] = sp[min(h0 + e, H - 1)];
+        }
+      }
+    }
+  };
+  load_round(0);
+  for (int i = threadIdx.x; i < kTopkBins; i += 1024) hist[i] = 0u;
+  if (threadIdx.x < H) {
+    const float2 stv = *reinterpret_cast<const float2*>(a.row_stats + ((size_t)b * H + threadIdx.x) * 2);
+    s_m[threadIdx.x] = (double)stv.x; s_inv[threadIdx.x] = 1.0 / (double)stv.y;
+  }
+  __syncthreads();
+  const int r_lo = min(a.n_init, N), r_hi = max(r_lo, N - a.n_local);
+  for (int p0 = 0; p0 < npass; p0 += NP) {
+    if (tok0 + p0 * tpp >= N) break;
+    if (p0 != 0) load_round(p0);
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+      if (p0 + p >= npass) break;
+      const int tl = (p0 + p) * tpp + (int)(threadIdx.x >> lpt_shift);   // token inside the workgroup's range
+      const int t = tl < kRankTokens ? tok0 + tl : N;                     // (a pass of the narrowest rows is wider than the range)
+      double vote = 0.0;
+#pragma unroll
+      for (int i = 0; i < CPL; ++i) {
+        const int h0 = (jv + i * LPT) * 4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (h0 + e < H) vote = fma((double)vote_exp((double)s[p][i][e] - s_m[h0 + e], c2), s_inv[h0 + e], vote);
+      }
+      for (int off = 1; off < LPT; off <<= 1) vote += __shfl_xor(vote, off);
+      if (t < N && jv == 0) {
+        const bool ranked = t >= r_lo && t < r_hi;
+        const float vf = ranked ? (float)vote : 0.f;
+        a.votes[(size_t)b * a.max_seq_len + t] = vf;
+        if (ranked) atomicAdd(&hist[float_key(vf) >> 21], 1u);
+      }
+    }
+  }
+  __syncthreads();
+  uint32_t* gh = a.rank_hist + ((size_t)b * kBoundHistCopies + (blockIdx.x & (kBoundHistCopies - 1))) * kTopkBins;
+  for (int i = threadIdx.x; i < kTopkBins; i += 1024)
+    if (hist[i] != 0u) atomicAdd(&gh[i], hist[i]);
+}
+
+hipError_t launch_soft_vote_ranked(const VoteArgs& a, int B, hipStream_t s) {
+  const int hq = (a.H + 3) / 4;                     // 16-byte chunks per token row
+  int lpt_shift = 0;
+  while ((1 << lpt_shift) < hq && lpt_shift < 3) ++lpt_shift;
+  const int cpl = (hq + (1 << lpt_shift) - 1) >> lpt_shift;   // 1, 2 or 4 for H <= 128
+  const bool vec = (a.H % 4 == 0) && (((uintptr_t)a.scores & 15) == 0);
+  hipLaunchKernelGGL(score_stats_merge_kernel, dim3(a.H, B), dim3(256), 0, s, a);
+  dim3 grid((a.max_seq_len + kRankTokens - 1) / kRankTokens, B);
+#define TS_RV(C, V) hipLaunchKernelGGL((soft_vote_ranked_kernel<C, V>), grid, dim3(1024), 0, s, a, lpt_shift)
+  if (cpl <= 1) { if (vec) TS_RV(1, true); else TS_RV(1, false); }
+  else if (cpl <= 2) { if (vec) TS_RV(2, true); else TS_RV(2, false); }
+  else { if (vec) TS_RV(4, true); else TS_RV(4, false); }
+#undef TS_RV
+  return hipGetLastError();
+}
+
 hipError_t launch_stats_merge(const VoteArgs& a, int B, hipStream_t s) {
   hipLaunchKernelGGL(score_stats_merge_kernel, dim3(a.H, B), dim3(256), 0, s, a);
   return hipGetLastError();

@@ -68,6 +68,58 @@ __device__ __forceinline__ void find_digit(const uint32_t* gh, uint32_t k_rem, u
   __syncthreads();
 }
 
+// find_digit over a histogram kept as kBoundHistCopies replicas (the vote kernel's flush spreads its atomics
+// over them): the copies are summed on the way in.
+template <int NB>
+__device__ __forceinline__ void find_digit_rep(const uint32_t* gh, uint32_t k_rem, uint32_t* digit, uint32_t* k_next,
+                                               uint32_t* lds /* >= 8 words */) {
+  constexpr int PER = NB / 256;
+  static_assert(PER % 4 == 0, "vector loads of the thread's bins");
+  uint32_t c[PER];
+  // the thread's PER bins are consecutive in memory (descending bin order = ascending address from `lowest`)
+  const int lowest = NB - PER - (int)threadIdx.x * PER;
+#pragma unroll
+  for (int e = 0; e < PER; ++e) c[e] = 0u;
+#pragma unroll
+  for (int r = 0; r < kBoundHistCopies; ++r)
+#pragma unroll
+    for (int q4 = 0; q4 < PER / 4; ++q4) {
+      const uint4 w = *reinterpret_cast<const uint4*>(gh + r * NB + lowest + q4 * 4);
+      c[PER - 1 - q4 * 4] += w.x; c[PER - 2 - q4 * 4] += w.y; c[PER - 3 - q4 * 4] += w.z; c[PER - 4 - q4 * 4] += w.w;
+    }
+  uint32_t sum = 0;
+#pragma unroll
+  for (int e = 0; e < PER; ++e) sum += c[e];
+  uint32_t total;
+  uint32_t above = block_exclusive_scan(sum, &total, lds);
+  __syncthreads();
+  if (threadIdx.x == 0) { lds[5] = NB; lds[6] = 0u; }
+  __syncthreads();
+  if (k_rem != 0) {
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+      if (above < k_rem && k_rem <= above + c[e]) { lds[5] = NB - 1 - (threadIdx.x * PER + e); lds[6] = k_rem - above; }
+      above += c[e];
+    }
+  }
+  __syncthreads();
+  *digit = lds[5];
+  *k_next = lds[6];
+  __syncthreads();
+}
+
+// the replicated first histogram folded into histogram 0 and cleared: the five-pass form reads one copy
+__global__ __launch_bounds__(256) void topk_fold_rep_hist_kernel(TopkArgs a) {
+  const int b = blockIdx.y;
+  if (a.skip != nullptr && a.skip[b / a.heads] != 0) return;
+  const int i = blockIdx.x * 256 + threadIdx.x;         // gridDim.x * 256 == kTopkBins
+  uint32_t* rep = a.rep_hist + (size_t)b * kBoundHistCopies * kTopkBins;
+  uint32_t sum = 0;
+#pragma unroll
+  for (int r = 0; r < kBoundHistCopies; ++r) { sum += rep[r * kTopkBins + i]; rep[r * kTopkBins + i] = 0u; }
+  a.hist[((size_t)b * 3 + 0) * kTopkBins + i] = sum;
+}
+
 // state words per sequence
 enum { ST_PREFIX0 = 0, ST_KREM0 = 1, ST_KEFF = 2, ST_PREFIX1 = 3, ST_KREM1 = 4, ST_THR = 5, ST_NEED_EQ = 6, ST_NONE = 7 };
 
@@ -312,7 +364,8 @@ __global__ __launch_bounds__(256) void topk_compact_kernel(TopkArgs a) {
     key[e] = valid[e] ? float_key(v[t0 + e]) : 0u;
   }
   uint32_t d0, krem0;
-  find_digit<kTopkBins>(a.hist + ((size_t)b * 3 + 0) * kTopkBins, k_eff, &d0, &krem0, lds);
+  if (a.rep_hist != nullptr) find_digit_rep<kTopkBins>(a.rep_hist + (size_t)b * kBoundHistCopies * kTopkBins, k_eff, &d0, &krem0, lds);
+  else find_digit<kTopkBins>(a.hist + ((size_t)b * 3 + 0) * kTopkBins, k_eff, &d0, &krem0, lds);
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     a.state[b * 8 + ST_PREFIX0] = d0 << 21; a.state[b * 8 + ST_KREM0] = krem0; a.state[b * 8 + ST_KEFF] = k_eff;
   }
@@ -403,6 +456,9 @@ __global__ __launch_bounds__(kFinalThreads) void topk_final_kernel(TopkArgs a) {
   }
   if (FULL) {  // the replicated histogram of the lower bounds has been consumed by the refine pass: zero it again
     uint4* g0 = reinterpret_cast<uint4*>(a.bound_hist + (size_t)b * kBoundHistCopies * kTopkBins);   // 256-byte aligned section
+    for (int i = tid; i < kBoundHistCopies * kTopkBins / 4; i += kFinalThreads) g0[i] = make_uint4(0u, 0u, 0u, 0u);
+  } else if (a.rep_hist != nullptr) {   // the vote kernel's replicated histogram has been consumed by the compact pass
+    uint4* g0 = reinterpret_cast<uint4*>(a.rep_hist + (size_t)b * kBoundHistCopies * kTopkBins);
     for (int i = tid; i < kBoundHistCopies * kTopkBins / 4; i += kFinalThreads) g0[i] = make_uint4(0u, 0u, 0u, 0u);
   } else {     // histogram 0 has been consumed by the compact pass: leave it zeroed for the next call
     uint32_t* g0 = a.hist + ((size_t)b * 3 + 0) * kTopkBins;
@@ -530,8 +586,13 @@ __global__ __launch_bounds__(kFinalThreads) void topk_final_kernel(TopkArgs a) {
 
 hipError_t launch_topk(const TopkArgs& a, int B, hipStream_t s) {
   dim3 grid(a.nblk, B);
-  hipLaunchKernelGGL(topk_hist0_kernel, dim3(a.nblk < 128 ? a.nblk : 128, B), dim3(256), 0, s, a);
-  if (a.list != nullptr && a.nblk <= kFinalMaxBlk) {
+  const bool short_path = a.list != nullptr && a.nblk <= kFinalMaxBlk;
+  if (a.rep_hist == nullptr) {
+    hipLaunchKernelGGL(topk_hist0_kernel, dim3(a.nblk < 128 ? a.nblk : 128, B), dim3(256), 0, s, a);
+  } else if (!short_path) {
+    hipLaunchKernelGGL(topk_fold_rep_hist_kernel, dim3(kTopkBins / 256, B), dim3(256), 0, s, a);
+  }
+  if (short_path) {
     hipLaunchKernelGGL(topk_compact_kernel, grid, dim3(256), 0, s, a);
     // the list holds about k entries plus the few that share the k-th key's bin: one batch in the usual case
     if (a.k <= 3072) hipLaunchKernelGGL((topk_final_kernel<4, false>), dim3(B), dim3(kFinalThreads), 0, s, a);

@@ -65,6 +65,7 @@ struct VoteArgs {
   int H, max_seq_len;
   int n_init, n_local;    // forced tokens: votes outside [min(n_init, N), max(that, N - n_local)) are 0
   float scale;
+  uint32_t* rank_hist;    // ranked vote only: [B][kBoundHistCopies][kTopkBins], top 11 key bits of the votes it writes
 };
 
 struct TopkArgs {
@@ -84,6 +85,7 @@ struct TopkArgs {
   float* vote_acc;      // Eq. 4: the emit pass adds 1 to vote_acc[real sequence][t] for every winner instead of writing idx
   float* sel_votes;     // compact selection: [B][k] votes of the selected tokens in idx order, or nullptr
   uint32_t* bound_hist; // compact selection: [B][kBoundHistCopies][kTopkBins] histogram of the vote lower bounds (else nullptr)
+  uint32_t* rep_hist;   // the first histogram was left by the vote kernel, replicated like bound_hist (else nullptr: pass 0 builds it)
 };
 
 // exact votes of the candidates (tokens whose upper bound reaches the bin of the k-th largest lower bound)
@@ -175,6 +177,8 @@ hipError_t launch_sparse_attn_chunk(const ChunkAttnArgs& a, int B, hipStream_t s
 // variant: 0 = fma arithmetic, 1 = packed bf16 dot2 (bf16 only)
 hipError_t launch_score_decode(int dtype, int D, int G, int variant, const ScoreArgs& a, dim3 grid, size_t lds, hipStream_t s);
 hipError_t launch_soft_vote(const VoteArgs& a, int B, hipStream_t s);
+// Eq. 5 (statistics merge + vote) plus the first radix histogram of the votes (a.rank_hist)
+hipError_t launch_soft_vote_ranked(const VoteArgs& a, int B, hipStream_t s);
 hipError_t launch_stats_merge(const VoteArgs& a, int B, hipStream_t s);
 hipError_t launch_vote_bounds(const BoundArgs& a, int B, hipStream_t s);
 hipError_t launch_topk_refine(int dtype, int D, int G, const RefineArgs& a, int B, hipStream_t s);

@@ -87,9 +87,11 @@ class DecodeLayer:
         self.cached_q, self.cached_q_next = self.cached_q_next, self.cached_q
         self.first, self.first_next = self.first_next, self.first
 
-    def select(self, q, score_scale=1.0, skip=None, kind="soft", check_theta=None):
+    def select(self, q, score_scale=1.0, skip=None, kind="soft", check_theta=None, ranked_vote=False):
         """kind: "soft" = Eq. 5 (the method), "sum" = Eq. 3, "head" = Eq. 4 (the paper's ablation baselines).
-        check_theta: run Algorithm 1's test inside the score launch (skip is then self.reuse)."""
+        check_theta: run Algorithm 1's test inside the score launch (skip is then self.reuse).
+        ranked_vote (Eq. 5 only): the vote launch also builds the first histogram of the TopK
+        (ts_soft_vote_ranked + TS_TOPK_VOTE_HIST)."""
         if check_theta is not None:
             ts.ts_paged_qk_scores_checked(self.problem, q, self.cached_q, self.cached_q_next, self.first, self.first_next,
                                           self.reuse, check_theta, self.scores, score_scale, self.ws)
@@ -97,6 +99,10 @@ class DecodeLayer:
             skip = self.reuse
         else:
             ts.ts_paged_qk_scores(self.problem, q, self.scores, score_scale, skip, self.ws)
+        if kind == "soft" and ranked_vote:
+            ts.ts_soft_vote_ranked(self.problem, self.scores, score_scale, self.row_stats, self.votes, skip, self.ws)
+            ts.ts_topk(self.problem, self.votes, self.k, self.idx, self.count, skip, self.ws, flags=ts.TS_TOPK_VOTE_HIST)
+            return
         if kind == "soft":
             ts.ts_soft_vote(self.problem, self.scores, score_scale, self.row_stats, self.votes, skip, self.ws)
         elif kind == "sum":
@@ -134,7 +140,7 @@ class DecodeLayer:
     def attend(self, q, sm_scale):
         ts.ts_sparse_paged_attn(self.problem, q, self.idx, self.k, self.count, sm_scale, self.out, self.lse, self.ws)
 
-    def step(self, q, *, theta=None, score_scale=1.0, sm_scale=None, compact=False, fused_check=False):
+    def step(self, q, *, theta=None, score_scale=1.0, sm_scale=None, compact=False, fused_check=False, ranked_vote=False):
         """One decode step: Selection Cache check (when theta is given), selection on a miss, sparse
         attention.  No host synchronisation.  fused_check: the check runs inside the score launch (one launch
         less; self.cached_q / self.first are swapped with their second copies after the step)."""
@@ -149,7 +155,7 @@ class DecodeLayer:
         if compact:
             self.select_compact(q, score_scale, skip, check_theta=check_theta)
         else:
-            self.select(q, score_scale, skip, check_theta=check_theta)
+            self.select(q, score_scale, skip, check_theta=check_theta, ranked_vote=ranked_vote)
         self.attend(q, sm)
 
 

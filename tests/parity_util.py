@@ -51,6 +51,11 @@ def compare_index_sets(gpu_idx, gpu_cnt, ora, label=""):
     return exc
 
 
+# True: the five-call selection of check_decode_against_oracle runs ts_soft_vote_ranked + ts_topk(TS_TOPK_VOTE_HIST)
+# instead of ts_soft_vote + ts_topk (tests/test_gpu_ranked_vote.py runs the parity cases again that way)
+RANKED_VOTE = False
+
+
 def check_decode_against_oracle(w, layer, q_dev, *, score_scale=1.0, attn_tol=None, label="", skip_rows=(),
                                 expect_tol_S=None):
     """Runs select + attend on the GPU for the workload's query and checks every stage.  Forced tokens
@@ -58,7 +63,7 @@ def check_decode_against_oracle(w, layer, q_dev, *, score_scale=1.0, attn_tol=No
     import torch
     from paper_2411_02886_amd.runtime import to_host
     sm = 1.0 / math.sqrt(w.D)
-    layer.select(q_dev, score_scale, None)
+    layer.select(q_dev, score_scale, None, ranked_vote=RANKED_VOTE)
     layer.attend(q_dev, sm)
     torch.cuda.synchronize()
     S_g = to_host(layer.scores); st_g = to_host(layer.row_stats); v_g = to_host(layer.votes)

@@ -61,7 +61,11 @@ def test_calls_reject_bad_arguments_without_launching():
     assert L.ts_soft_vote(p, 0x1000, 1.0, 0x1000, 0x1000, None, ws, 16, None) == -3
     assert L.ts_topk(p, 0x1000, 0, 0x1000, 0x1000, None, 0, ws, big, None) == -1
     assert L.ts_topk(p, 0x1000, 16, 0x1000, 0x1000, None, 0, ws, 8, None) == -3
-    assert L.ts_topk(p, 0x1000, 16, 0x1000, 0x1000, None, 2, ws, big, None) == -1
+    assert L.ts_topk(p, 0x1000, 16, 0x1000, 0x1000, None, 4, ws, big, None) == -1          # an unknown flag
+    assert L.ts_topk(ctypes.byref(cproblem(chunk=4)), 0x1000, 16, 0x1000, 0x1000, None, 2, ws, big, None) == -2   # TS_TOPK_VOTE_HIST is decode only
+    assert L.ts_soft_vote_ranked(p, 0x1000, 1.0, None, 0x1000, None, ws, big, None) == -1
+    assert L.ts_soft_vote_ranked(p, 0x1000, 1.0, 0x1000, 0x1000, None, ws, 16, None) == -3
+    assert L.ts_soft_vote_ranked(ctypes.byref(cproblem(chunk=4)), 0x1000, 1.0, 0x1000, 0x1000, None, ws, big, None) == -2
     assert L.ts_selcache_check(p, 0x1000, 0x1000, None, 0.9, 0x1000, None) == -1
     assert L.ts_sparse_paged_attn(p, 0x1000, 0x1000, 0, 0x1000, 0.125, 0x1000, None, ws, big, None) == -1
     assert L.ts_sparse_paged_attn(ctypes.byref(cproblem(v_pool=None)), 0x1000, 0x1000, 16, 0x1000, 0.125, 0x1000, None, ws, big, None) == -1

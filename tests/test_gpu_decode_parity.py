@@ -217,9 +217,9 @@ def test_k_larger_than_n_equals_full_attention(gpu):
     assert np.abs(to_host(layer.out)[0, 0] - full).max() < 1e-4
 
 
-@pytest.mark.parametrize("fused,compact", [(False, False), (True, False), (True, True)],
-                         ids=["check-call", "check-in-score-launch", "check-in-codes-launch"])
-def test_selection_cache_loop_matches_algorithm_1(gpu, fused, compact):
+@pytest.mark.parametrize("fused,compact,ranked", [(False, False, False), (True, False, False), (True, True, False), (True, False, True)],
+                         ids=["check-call", "check-in-score-launch", "check-in-codes-launch", "check-in-score-launch+ranked-vote"])
+def test_selection_cache_loop_matches_algorithm_1(gpu, fused, compact, ranked):
     # fused: ts_paged_qk_scores_checked / ts_paged_qk_codes_checked take the decision in the score launch
     from paper_2411_02886_amd.runtime import to_device, to_host
     steps, theta = 12, 0.9
@@ -236,7 +236,7 @@ def test_selection_cache_loop_matches_algorithm_1(gpu, fused, compact):
     for t in range(steps):
         print("selcache step", t, flush=True)
         qd = to_device(qs[t])
-        layer.step(qd, theta=theta, score_scale=0.1, fused_check=fused, compact=compact)
+        layer.step(qd, theta=theta, score_scale=0.1, fused_check=fused, compact=compact, ranked_vote=ranked)
         torch.cuda.synchronize()
         reuse_g = to_host(layer.reuse); idx_g = to_host(layer.idx); cnt_g = to_host(layer.count)
         out_g = to_host(layer.out, bits16=True)
