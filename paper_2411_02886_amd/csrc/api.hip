@@ -111,7 +111,7 @@ using namespace ts;
 
 extern "C" {
 
-int32_t ts_version(void) { return 200; }   // 0.2.0: the compact form of the selection and ts_topk_noalloc joined the five calls
+int32_t ts_version(void) { return 300; }   // 0.3.0: the checked score calls and the ranked vote joined (0.2.0: the compact form, ts_topk_noalloc)
 
 const char* ts_strerror(int32_t status) {
   switch (status) {
