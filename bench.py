@@ -493,7 +493,8 @@ def decode_bench(cfg, args, *, steps, warmup, with_cpu_baseline, with_graph):
                    "selection_form": ("compact: ts_paged_qk_codes + ts_soft_vote_bounds + ts_topk_exact (no score matrix in memory)"
                                       if compact else ("five calls: ts_paged_qk_scores + ts_soft_vote_ranked + ts_topk (fp32 score matrix; the TopK's first histogram built inside the vote launch)"
                                             if (ranked_vote and args.selection == "soft") else "five calls: ts_paged_qk_scores + ts_soft_vote + ts_topk (fp32 score matrix)"))},
-        "launches_per_step": (8 if compact else (8 if (ranked_vote and args.selection == "soft") else 9)) - (1 if fused_check else 0),
+        "launches_per_step": None if args.selection != "soft" else
+        (8 if compact else (8 if ranked_vote else 9)) - (1 if fused_check else 0),
         "selection_cache_check": ("inside the score launch (ts_paged_qk_%s_checked)" % ("codes" if compact else "scores")) if fused_check else "ts_selcache_check before the score launch",
         "planted_token_quality": quality,
         "compact_vs_five_call_index_overlap": dense_agrees,
