@@ -333,6 +333,11 @@ static int32_t paged_qk_codes_impl(const ts_problem* p, const void* q, const ts_
       score_codes_mfma_supported(p->dtype, p->head_dim, G, p->num_kv_heads)) {
     long wgl = 0;
     mfma_launch_shape(p, G, false, &a, &wgl);
+    // Bytes and block maxima that fit the chip's L2 (eight XCDs x 4 MiB) with room to spare stay there as dirty lines
+    // until the kernel ends and cost the read stream nothing; more than that thrashes it, and streaming them past the
+    // L2 is the cheaper way (measured, H 28/4: 524288 tokens 89.2 us cached / 90.2 streamed, 786432 tokens 142.0 / 135.7,
+    // 1048576 tokens 184.5 / 176.1; H 32/8: 524288 tokens 167.4 / 168.7, 786432 tokens 267.4 / 254.4)
+    a.nt_codes = (double)p->batch * p->max_seq_len * p->num_q_heads * 1.125 > 20.0 * 1048576.0;
     const hipError_t e = launch_score_codes_mfma(p->head_dim, G, a, dim3((unsigned)wgl, p->batch),
                                                  score_codes_mfma_lds_bytes(p->head_dim, G, a.RR, false), (hipStream_t)stream);
     return e == hipSuccess ? TS_OK : TS_ERR_HIP;

@@ -258,13 +258,18 @@ __global__ __launch_bounds__(256) void score_codes_mfma_kernel(ScoreArgs a) {
       const int nbytes = ntok * H;
       if ((reinterpret_cast<uintptr_t>(dst) & 15) == 0) {
         const int n16 = nbytes >> 4;
-        for (int i = lane; i < n16; i += 64) reinterpret_cast<uint4*>(dst)[i] = reinterpret_cast<const uint4*>(cbuf)[i];
+        if (a.nt_codes) {
+          for (int i = lane; i < n16; i += 64) { const v4u w = reinterpret_cast<const v4u*>(cbuf)[i]; __builtin_nontemporal_store(w, reinterpret_cast<v4u*>(dst) + i); }
+        } else {
+          for (int i = lane; i < n16; i += 64) reinterpret_cast<uint4*>(dst)[i] = reinterpret_cast<const uint4*>(cbuf)[i];
+        }
         for (int i = (n16 << 2) + lane; i < (nbytes >> 2); i += 64) reinterpret_cast<uint32_t*>(dst)[i] = reinterpret_cast<const uint32_t*>(cbuf)[i];
       } else {
         for (int i = lane; i < (nbytes >> 2); i += 64) reinterpret_cast<uint32_t*>(dst)[i] = reinterpret_cast<const uint32_t*>(cbuf)[i];
       }
       float* dm = a.blk_max + ((size_t)b * a.nblk + tile0) * H;
-      for (int i = lane; i < ntiles * H; i += 64) dm[i] = smax[i];
+      if (a.nt_codes) { for (int i = lane; i < ntiles * H; i += 64) __builtin_nontemporal_store(smax[i], dm + i); }
+      else { for (int i = lane; i < ntiles * H; i += 64) dm[i] = smax[i]; }
     } else {
       constexpr int WPT = HBG / 4;                         // dwords per token row piece
       for (int i = lane; i < ntok * WPT; i += 64) {

@@ -26,6 +26,7 @@ struct ScoreArgs {
   float* blk_max;         // [B][nblk][H] maximum of each head over the block's ranked tokens
   int nblk;               // blocks per sequence the array is strided by: ceil(max_seq_len / 32)
   int ncp_shift;          // log2 of the power of two >= HB * G
+  int nt_codes;           // matrix-core compact form, whole token rows per wave (NU == 1): bytes and block maxima leave as non-temporal stores
   // Algorithm 1's test inside this launch (sc_cached_q != nullptr; `skip` is then unused): every workgroup takes
   // the decision itself from Q and C_Q, workgroup 0 of a sequence writes the state after the step
   const uint8_t* sc_cached_q;   // [B][H][D] C_Q before the step, read only
