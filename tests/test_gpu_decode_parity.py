@@ -461,10 +461,12 @@ def test_kernels_are_deterministic(gpu):
         assert np.array_equal(a, b)
 
 
-def test_decode_steps_captured_in_a_hip_graph_replay_identically(gpu):
+@pytest.mark.parametrize("fused", [False, True], ids=["plain-calls", "check-in-score-launch+ranked-vote"])
+def test_decode_steps_captured_in_a_hip_graph_replay_identically(gpu, fused):
     # Every hit/miss decision is taken on the device and the library neither allocates nor synchronises, so a
     # run of decode steps can be captured once and replayed.  Several replays, with eager work and
     # synchronisations in between, must each reproduce the eager run (indices, reuse flags, outputs).
+    # fused: the run alternates the two (C_Q, first) buffers; an even number of steps leaves them where they began.
     from paper_2411_02886_amd.runtime import to_device, to_host
     steps, theta = 6, 0.9
     w = W.make_workload("graph", dtype=W.BF16, B=3, H=8, H_kv=2, D=128, P=16, seq_lens=[900, 2500, 70], k=48, seed=51,
@@ -478,7 +480,7 @@ def test_decode_steps_captured_in_a_hip_graph_replay_identically(gpu):
     def run():
         layer.first.fill_(1)
         for t in range(steps):
-            layer.step(qs[t], theta=theta, score_scale=0.1)
+            layer.step(qs[t], theta=theta, score_scale=0.1, fused_check=fused, ranked_vote=fused)
             reuse_log[t].copy_(layer.reuse); idx_log[t].copy_(layer.idx); out_log[t].copy_(layer.out)
 
     run(); torch.cuda.synchronize()
@@ -494,7 +496,7 @@ def test_decode_steps_captured_in_a_hip_graph_replay_identically(gpu):
         run()
     for rep in range(4):
         reuse_log.zero_(); idx_log.fill_(-9); out_log.zero_()
-        layer.idx.fill_(-9); layer.cached_q.zero_()             # eager work between the replays
+        layer.idx.fill_(-9); layer.cached_q.zero_(); layer.cached_q_next.zero_()   # eager work between the replays
         torch.cuda.synchronize()
         g.replay(); torch.cuda.synchronize()
         got = (to_host(reuse_log), to_host(idx_log), to_host(out_log))
