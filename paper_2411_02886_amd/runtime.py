@@ -140,11 +140,20 @@ class DecodeLayer:
     def attend(self, q, sm_scale):
         ts.ts_sparse_paged_attn(self.problem, q, self.idx, self.k, self.count, sm_scale, self.out, self.lse, self.ws)
 
+    def compact_form_pays(self) -> bool:
+        """Which form of the Eq. 5 selection is the faster step here (measured on MI355X): while the fp32 score matrix
+        fits the L2 with room to spare (131072 tokens of 32 heads: 16 MiB) the five-call form is, beyond that the
+        compact form, which never writes it (crossover between 128K and 256K tokens of 32 heads)."""
+        return self.B * self.max_seq_len * self.H * 4 > 24 * 2**20
+
     def step(self, q, *, theta=None, score_scale=1.0, sm_scale=None, compact=False, fused_check=False, ranked_vote=False):
         """One decode step: Selection Cache check (when theta is given), selection on a miss, sparse
-        attention.  No host synchronisation.  fused_check: the check runs inside the score launch (one launch
+        attention.  No host synchronisation.  compact: the form of the selection (None = whichever is the faster one
+        at this size, see compact_form_pays).  fused_check: the check runs inside the score launch (one launch
         less; self.cached_q / self.first are swapped with their second copies after the step)."""
         sm = sm_scale if sm_scale is not None else 1.0 / float(np.sqrt(self.D))
+        if compact is None:
+            compact = self.compact_form_pays()
         skip, check_theta = None, None
         if theta is not None:
             if fused_check:

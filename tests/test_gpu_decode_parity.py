@@ -448,6 +448,22 @@ def test_check_inside_the_score_launch_equals_the_separate_check(gpu, dtype, H, 
     assert 0 < hits < 2 * steps * w.B
 
 
+def test_step_picks_a_form_by_size_and_both_give_the_oracles_selection(gpu):
+    from paper_2411_02886_amd.runtime import to_host
+    w = W.config2(N=5000, k=300, seed=91)
+    layer, q = make_layer(w)
+    assert not layer.compact_form_pays()
+    ora = oracle_decode(w, 0, score_scale=1.0)
+    for form in (None, True, False):
+        layer.idx.fill_(-3)
+        layer.step(q, score_scale=1.0, compact=form, ranked_vote=True)
+        torch.cuda.synchronize()
+        compare_index_sets(to_host(layer.idx)[0], int(to_host(layer.count)[0]), ora, "form %s" % form)
+    big = W.make_workload("big", dtype=W.BF16, H=32, H_kv=8, D=128, P=16, seq_lens=[300], k=16, seed=92)
+    lb, _ = make_layer(big, max_seq_len=262144)
+    assert lb.compact_form_pays()
+
+
 def test_kernels_are_deterministic(gpu):
     from paper_2411_02886_amd.runtime import to_host
     w = W.config2(N=3000, k=200, seed=3)
