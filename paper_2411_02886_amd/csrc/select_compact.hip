@@ -302,7 +302,10 @@ __global__ __launch_bounds__(kRefineThreads) void topk_refine_kernel(RefineArgs 
   const int LO = min(ta.head, Nb), N = max(LO, Nb - ta.tail);      // ranked range [LO, N)
   const uint32_t k_eff = (uint32_t)min(ta.k, N - LO);
   const int H = a.H;
-  const int base = blockIdx.x * kTopkChunk;
+  // a.parts workgroups share a chunk: each finds the threshold and compacts the chunk for itself (cheap, and the same
+  // in all of them), then re-evaluates its share of the candidates -- few chunks then still fill the machine
+  const int chunk = blockIdx.x / a.parts, part = blockIdx.x - chunk * a.parts;
+  const int base = chunk * kTopkChunk;
   const int t0 = base + threadIdx.x * PER;      // PER consecutive tokens per thread: order is preserved
   const float* v = ta.votes + (size_t)b * ta.max_seq_len;
   uint32_t key[PER];
@@ -357,7 +360,7 @@ __global__ __launch_bounds__(kRefineThreads) void topk_refine_kernel(RefineArgs 
       cpid[pos] = a.page_indices[indptr + min((t0 + e) >> a.p_shift, npages - 1)];
       ++pos;
     }
-  if (threadIdx.x == 0) ta.blk[(size_t)b * ta.nblk + blockIdx.x] = total;
+  if (threadIdx.x == 0 && part == 0) ta.blk[(size_t)b * ta.nblk + chunk] = total;
   __syncthreads();
   if (total == 0) return;
 
@@ -370,10 +373,11 @@ __global__ __launch_bounds__(kRefineThreads) void topk_refine_kernel(RefineArgs 
   const int tps_shift = 3 - a.hb_shift;
   const int ngroups = ((int)total + (1 << tps_shift) - 1) >> tps_shift;
   const double c2d = (double)a.scale * 1.44269504088896340736;
-  uint2* list = ta.list + ((size_t)b * ta.nblk + blockIdx.x) * kTopkChunk;
-  for (int g0 = wave; g0 < ngroups; g0 += kRefineWaves * UB) {   // group uu of this round: g0 + uu * kRefineWaves
+  uint2* list = ta.list + ((size_t)b * ta.nblk + chunk) * kTopkChunk;
+  const int g_begin = (int)((long)part * ngroups / a.parts), g_end = (int)((long)(part + 1) * ngroups / a.parts);   // this workgroup's groups
+  for (int g0 = g_begin + wave; g0 < g_end; g0 += kRefineWaves * UB) {   // group uu of this round: g0 + uu * kRefineWaves
     // groups of this round that exist (the same for the whole wave): the others cost neither loads nor arithmetic
-    const int nact = min(UB, (ngroups - g0 + kRefineWaves - 1) / kRefineWaves);
+    const int nact = min(UB, (g_end - g0 + kRefineWaves - 1) / kRefineWaves);
     double vote[UB];
 #pragma unroll
     for (int uu = 0; uu < UB; ++uu) vote[uu] = 0.0;
@@ -447,7 +451,7 @@ __global__ __launch_bounds__(kRefineThreads) void topk_refine_kernel(RefineArgs 
 #pragma unroll
     for (int uu = 0; uu < UB; ++uu) {
       const int ci = ((g0 + uu * kRefineWaves) << tps_shift) + tis;
-      if (ci < (int)total && kvh_l == 0 && j == 0) list[ci] = make_uint2(float_key((float)vote[uu]), (uint32_t)ctok[ci]);
+      if (uu < nact && ci < (int)total && kvh_l == 0 && j == 0) list[ci] = make_uint2(float_key((float)vote[uu]), (uint32_t)ctok[ci]);
     }
   }
 }
@@ -484,7 +488,7 @@ static hipError_t refine_g(int G, const RefineArgs& a, dim3 grid, hipStream_t s)
 }
 
 hipError_t launch_topk_refine(int dtype, int D, int G, const RefineArgs& a, int B, hipStream_t s) {
-  const dim3 grid(a.t.nblk, B);
+  const dim3 grid(a.t.nblk * a.parts, B);
   if (dtype == TS_F32) return D == 64 ? refine_g<TS_F32, 64>(G, a, grid, s) : refine_g<TS_F32, 128>(G, a, grid, s);
   return D == 64 ? refine_g<TS_BF16, 64>(G, a, grid, s) : refine_g<TS_BF16, 128>(G, a, grid, s);
 }

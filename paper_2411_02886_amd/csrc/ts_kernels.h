@@ -100,6 +100,7 @@ struct RefineArgs {
   int H, H_kv, P, p_shift;
   int HB, hb_shift, NU;
   float scale;
+  int parts;              // workgroups per 2048-token chunk: each re-evaluates its share of the chunk's candidates
 };
 
 struct SelcacheArgs {
