@@ -219,6 +219,20 @@ def test_matrix_core_score_pass_run_lengths_and_grids(gpu, rr, wg, heads):
         gpu.ts_debug_set_codes_path(1, 0); gpu.ts_debug_set_score_variant(2, 0, 0)
 
 
+@pytest.mark.parametrize("lens,parts", [([70000, 66000, 41000], 2), ([150000, 9000], 1), ([30000], 4), ([70000, 70000, 70000, 3000], 1)],
+                         ids=["2-per-chunk", "1-per-chunk", "4-per-chunk", "1-per-chunk-batch4"])
+def test_refine_with_several_workgroups_per_chunk(gpu, lens, parts):
+    """The exact re-evaluation runs 256 / (chunks x batch) workgroups per 2048-token chunk, four at most: every split
+    gives the oracle's selection."""
+    w = W.make_workload("parts", dtype=W.BF16, H=8, H_kv=2, D=64, P=16, B=len(lens), seq_lens=lens, k=700, beta=2.5,
+                        planted_per_head=2, seed=sum(lens) % 977)
+    layer, q = make_layer(w)
+    nblk = (max(lens) + 2047) // 2048
+    assert max(1, min(4, 256 // (nblk * len(lens)))) == parts
+    print("compact refine parts", parts, lens, flush=True)
+    check_compact(w, layer, q, score_scale=1.0, label="parts%d" % parts)
+
+
 def test_batch_ragged_and_forced(gpu):
     w = W.make_workload("ragged", dtype=W.BF16, H=32, H_kv=8, D=128, P=16, B=6, seq_lens=[4100, 0, 37, 2048, 9999, 1],
                         k=256, beta=2.5, planted_per_head=0, seed=11)
