@@ -530,19 +530,28 @@ __global__ __launch_bounds__(kFinalThreads) void topk_final_kernel(TopkArgs a) {
   uint32_t d1, krem1;
   final_find_digit<kTopkBins>(h, krem0, &d1, &krem1, scan_lds, res);
   const uint32_t prefix1 = (d0 << 21) | ((d1 & 2047u) << 10);
-  // ---- digit 2: the last 10 bits
-  for (int i = tid; i < 1024; i += kFinalThreads) h[i] = 0u;
-  __syncthreads();
-  for (uint32_t base = 0; base < total; base += kFinalThreads * kFinalPer) {
-    if (!single) load_batch(base, e);
+  // ---- digit 2: the last 10 bits -- unless every entry that shares the threshold's 22-bit prefix is a winner (the
+  // usual case: a few thousand entries over 2^22 prefixes leave the threshold's bin with one or two), when the
+  // prefix alone decides
+  uint32_t thr, need_eq;
+  const uint32_t cnt1 = d1 < (uint32_t)kTopkBins ? h[d1] : 0xffffffffu;
+  if (krem1 == cnt1 && prefix1 != 0u) {
+    thr = prefix1 - 1u; need_eq = 0u;          // "above thr" = "prefix at least prefix1"; nothing equals thr among the winners
+  } else {
+    __syncthreads();                            // every thread has read cnt1 before the histogram is cleared
+    for (int i = tid; i < 1024; i += kFinalThreads) h[i] = 0u;
+    __syncthreads();
+    for (uint32_t base = 0; base < total; base += kFinalThreads * kFinalPer) {
+      if (!single) load_batch(base, e);
 #pragma unroll
-    for (int i = 0; i < kFinalPer; ++i)
-      if (e[i].y != 0xffffffffu && (e[i].x >> 10) == (prefix1 >> 10)) atomicAdd(&h[e[i].x & 1023u], 1u);
+      for (int i = 0; i < kFinalPer; ++i)
+        if (e[i].y != 0xffffffffu && (e[i].x >> 10) == (prefix1 >> 10)) atomicAdd(&h[e[i].x & 1023u], 1u);
+    }
+    __syncthreads();
+    uint32_t d2;
+    final_find_digit<1024>(h, krem1, &d2, &need_eq, scan_lds, res);
+    thr = prefix1 | (d2 & 1023u);
   }
-  __syncthreads();
-  uint32_t d2, need_eq;
-  final_find_digit<1024>(h, krem1, &d2, &need_eq, scan_lds, res);
-  const uint32_t thr = prefix1 | (d2 & 1023u);
   // ---- emit in token order: every key above the threshold, and the first need_eq keys equal to it
   uint32_t gt_done = 0, eq_done = 0;
   for (uint32_t base = 0; base < total; base += kFinalThreads * kFinalPer) {
