@@ -7,7 +7,8 @@ Selection Cache check (Alg. 1) -> paged q.k score pass (Alg. 2) -> head soft vot
 (Qwen2-7B-shaped layer, bf16, 1048576 cached tokens in 16-token pages, k = 4096); configuration 2
 (Llama-3-8B-shaped layer, 131072 tokens, k = 2048), the other end of the 128K-1M range, is run after it with
 the same protocol and reported as `secondary`.  The selection runs in its compact form by default (no fp32
-score matrix in memory; --path dense times the five-call form).  To keep neither the L2s nor the 256 MB
+score matrix in memory; --path dense times the five-call form), with Algorithm 1's test taken inside the score
+launch (--check call: as the ts_selcache_check call of its own; the default for configuration 3).  To keep neither the L2s nor the 256 MB
 last-level cache warm, the steps rotate over R physical copies of the pool (same logical sequence,
 different random page permutation each) and over R different queries, so that every step is a
 Selection Cache miss (cosine of independent queries ~ 0 < theta = 0.9) and scans all cached tokens.
