@@ -6,7 +6,7 @@
 // of a sequence (selected tokens, then the chunk's tokens) to physical slots.  In the main kernel a
 // workgroup owns 128 rows (query x head pairs of one KV head; 32 per wave, fragments pinned in
 // registers) and walks the key list in tiles of 32: K rows and V rows of the tile are gathered once
-// into LDS (V transposed, so that both products read 16-byte fragments), S = Q K^T and O += P V run
+// into LDS (row-major both; the V operand of P V is read as eight 2-byte pieces down a column), S = Q K^T and O += P V run
 // on v_mfma_f32_32x32x16_bf16, P goes through a wave-private LDS tile to change from the result
 // layout to the operand layout.  The softmax uses a per-row reference exponent that is raised only
 // when a logit would exceed it by 2^16, so the common tile needs no cross-lane traffic; row sums
@@ -55,7 +55,7 @@ __global__ __launch_bounds__(256) void chunk_attn_kernel(ChunkAttnArgs a) {
   constexpr float TH = 16.f;
   static_assert(NLD >= 1, "tile too small for the workgroup");
   __shared__ __attribute__((aligned(16))) uint8_t s_k[2][kCaTile * LROW];
-  __shared__ __attribute__((aligned(16))) uint8_t s_vt[2][D * VROW];
+  __shared__ __attribute__((aligned(16))) uint8_t s_v[2][kCaTile * LROW];    // V rows as gathered ([key][d]); transposed on the way out
   __shared__ __attribute__((aligned(16))) uint8_t s_p[4][32 * VROW];
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -137,12 +137,7 @@ __global__ __launch_bounds__(256) void chunk_attn_kernel(ChunkAttnArgs a) {
     for (int it = 0; it < NLD; ++it) {
       const int key = st_key + it * KPP;
       *reinterpret_cast<uint4*>(&s_k[buf][key * LROW + st_piece * 16]) = r.k[it];
-      const uint32_t w[4] = {r.v[it].x, r.v[it].y, r.v[it].z, r.v[it].w};
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {                            // V^T[d][key]
-        const uint16_t x = (uint16_t)(w[i >> 1] >> ((i & 1) * 16));
-        *reinterpret_cast<uint16_t*>(&s_vt[buf][(st_piece * 8 + i) * VROW + key * 2]) = x;
-      }
+      *reinterpret_cast<uint4*>(&s_v[buf][key * LROW + st_piece * 16]) = r.v[it];
     }
   };
 
@@ -220,7 +215,18 @@ __global__ __launch_bounds__(256) void chunk_attn_kernel(ChunkAttnArgs a) {
       const uint4 pa = *reinterpret_cast<const uint4*>(&pw[col * VROW + (ks * 16 + 8 * half) * 2]);
 #pragma unroll
       for (int nb = 0; nb < NBO; ++nb) {
-        const uint4 vb = *reinterpret_cast<const uint4*>(&s_vt[buf][(nb * 32 + col) * VROW + (ks * 16 + 8 * half) * 2]);
+        // B operand: column d = 32 * nb + col of eight consecutive keys -- eight 2-byte reads down a column of the
+        // row-major V tile (a wave's 32 columns of one key are 64 contiguous bytes: no bank conflicts; writing V
+        // transposed instead cost 16-way conflicts on 2-byte stores)
+        const uint8_t* vcol = &s_v[buf][(ks * 16 + 8 * half) * LROW + (nb * 32 + col) * 2];
+        uint32_t vw[4];
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          const uint32_t lo16 = *reinterpret_cast<const uint16_t*>(vcol + (2 * jj) * LROW);
+          const uint32_t hi16 = *reinterpret_cast<const uint16_t*>(vcol + (2 * jj + 1) * LROW);
+          vw[jj] = lo16 | (hi16 << 16);
+        }
+        const uint4 vb = make_uint4(vw[0], vw[1], vw[2], vw[3]);
         oacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, pa), __builtin_bit_cast(bf16x8_t, vb),
                                                             oacc[nb], 0, 0, 0);
       }
