@@ -58,6 +58,7 @@ def parse():
     ap.add_argument("--pools", type=int, default=0, help="physical pool copies to rotate over (0 = enough for >= 2 GiB)")
     ap.add_argument("--variant", type=int, default=-1, help="score pass of the five-call form: 0 fma, 1 bf16 dot2, 2 matrix cores, -1 library default (2)")
     ap.add_argument("--score-wg", type=int, default=0)
+    ap.add_argument("--run-tiles", type=int, default=0, help="tiles per run of the matrix-core score kernel (tuning; 0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tokens", type=int, default=0, help="override the number of cached tokens (profiling only)")
     ap.add_argument("--theta", type=float, default=0.9, help="Selection Cache threshold of the config-3 run")
@@ -297,6 +298,8 @@ def decode_bench(cfg, args, *, steps, warmup, with_cpu_baseline, with_graph):
     N = int(w.seq_lens[0])
     if args.variant >= 0 or args.score_wg:
         ts.ts_debug_set_score_variant(args.variant if args.variant >= 0 else 2, args.score_wg)
+    if args.run_tiles:
+        ts.ts_debug_set_codes_path(1, args.run_tiles)
     compact = args.path != "dense" and args.selection == "soft"
     layer = DecodeLayer.from_workload(w, device=dev, num_initial=args.n_init, num_local=args.n_local)
     esize = w.esize()
