@@ -369,7 +369,7 @@ def decode_bench(cfg, args, *, steps, warmup, with_cpu_baseline, with_graph):
         if kev is not None:
             ts.ts_debug_set_score_timing_events(None, None)
         if compact:
-            ts.ts_soft_vote_bounds(p, layer.codes, scale, layer.row_stats, layer.vote_hi, layer.vote_lo, layer.reuse, layer.ws, stream)
+            ts.ts_soft_vote_bounds(p, layer.codes, scale, layer.row_stats, layer.vote_hi, None, layer.reuse, layer.ws, stream)
             ts.ts_topk_exact(p, q, layer.vote_hi, layer.row_stats, scale, layer.k, layer.idx, layer.count, layer.reuse, layer.ws, stream)
         else:
             if args.selection == "soft" and ranked_vote:

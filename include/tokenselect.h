@@ -191,7 +191,8 @@ int32_t ts_topk_noalloc(const ts_problem* p, const float* votes, int32_t k, int3
  *                      lower token index, ascending token ids, unused slots -1); sel_votes [device] float [B][k],
  *                      if not NULL, receives the vote of idx[b][j] at [b][j] (0 in unused slots).  Must follow
  *                      ts_soft_vote_bounds with the same problem, workspace, q and score_scale.  Two launches.
- * codes [device] uint8 [B][max_seq_len][H]; vote_hi, vote_lo [device] float [B][max_seq_len]; the other arguments
+ * codes [device] uint8 [B][max_seq_len][H]; vote_hi, vote_lo [device] float [B][max_seq_len] (vote_lo may be NULL:
+ * ts_topk_exact needs the upper bounds only, the lower ones live on in the workspace as a histogram); the other arguments
  * as for the three calls they stand in for.  Sequences with skip[b] != 0 are left untouched.  The cost of
  * ts_topk_exact grows with the number of candidates: flat votes (a small score_scale) give more of them, never a
  * wrong result. */

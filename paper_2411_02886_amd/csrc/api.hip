@@ -364,7 +364,7 @@ int32_t ts_soft_vote_bounds(const ts_problem* p, const uint8_t* codes, float sco
                             float* vote_hi, float* vote_lo, const uint8_t* skip, void* ws, size_t ws_bytes, void* stream) {
   int32_t st = check_problem(p);
   if (st != TS_OK) return st;
-  if (codes == nullptr || row_stats == nullptr || vote_hi == nullptr || vote_lo == nullptr) return TS_ERR_INVALID_ARG;
+  if (codes == nullptr || row_stats == nullptr || vote_hi == nullptr) return TS_ERR_INVALID_ARG;   // vote_lo is optional
   if (!(score_scale >= 0.f) || !(score_scale < 1e30f)) return TS_ERR_INVALID_ARG;
   if (p->chunk != 1) return TS_ERR_UNSUPPORTED;
   const WsLayout w = ws_layout(p, 1);

@@ -27,9 +27,9 @@ constexpr float kBoundUp = 1.0002f;               // factor on the summed upper 
 constexpr float kBoundDown = 0.9998f;             // factor on the summed lower bound
 
 // One lane per token: a lane reads its token's H bytes (a wave reads 64 consecutive rows) and sums, head by head,
-// weight(block, head) * 2^((byte - 255) / 4), both factors from LDS tables: the weight of a byte-255 score of
-// each 32-token block this workgroup meets (2^(c2 * (block max - max_h)) / sumexp_h, exponent formed in double)
-// and the 256 powers.  The next 256 tokens' bytes are in flight while the current ones are summed.  The
+// weight(block, head) * 2^((byte - 255) / 4): the weight of a byte-255 score of each 32-token block this workgroup
+// meets (2^(c2 * (block max - max_h)) / sumexp_h, exponent formed in double) from an LDS table, the power from the
+// hardware exponential.  The next 256 tokens' bytes are in flight while the current ones are summed.  The
 // workgroup's histogram of the lower bounds is flushed once.
 template <int HW>                                // dwords per token row (H / 4); 0 = any H, byte loads
 __global__ __launch_bounds__(256) void vote_bounds_kernel(BoundArgs a, int tokens_per_wg) {
@@ -38,7 +38,6 @@ __global__ __launch_bounds__(256) void vote_bounds_kernel(BoundArgs a, int token
   __shared__ double s_km[128];                  // c2 * max_h + log2(sumexp_h)
   __shared__ float s_absmax[4];
   __shared__ uint32_t hist[kTopkBins];
-  __shared__ float s_pow[256];                  // 2^((byte - 255) / 4)
   extern __shared__ float s_off[];              // [blocks of this workgroup][H]
   const int b = blockIdx.y;
   const int H = a.H;
@@ -77,7 +76,6 @@ __global__ __launch_bounds__(256) void vote_bounds_kernel(BoundArgs a, int token
   for (int off = 32; off > 0; off >>= 1) am = fmaxf(am, __shfl_xor(am, off));
   if ((threadIdx.x & 63) == 0) s_absmax[threadIdx.x >> 6] = am;
   for (int i = threadIdx.x; i < kTopkBins; i += 256) hist[i] = 0u;
-  s_pow[threadIdx.x] = __builtin_amdgcn_exp2f(((float)threadIdx.x - 255.f) * 0.25f);
   __syncthreads();
   am = fmaxf(fmaxf(s_absmax[0], s_absmax[1]), fmaxf(s_absmax[2], s_absmax[3]));
   const float guard = kCodeGuard + (float)c2d * am * kScoreGuard;
@@ -90,6 +88,11 @@ __global__ __launch_bounds__(256) void vote_bounds_kernel(BoundArgs a, int token
     s_off[i] = __builtin_amdgcn_exp2f((float)(c2d * (double)m - s_km[i % H]) + guard);   // exponent <= guard; 0 for an empty block
   }
   __syncthreads();
+  // Byte 0 is open towards minus infinity: a head with byte 0 gives no lower bound.  Instead of leaving such heads out
+  // of the sum one by one (a compare, a select and an add per score), the most they can have put into the upper sum
+  // is taken off once per token: 2^(-255/4) times the sum of the block's weights over the heads, and a weight is at
+  // most 2^guard / sumexp_h <= 2^guard.
+  const float zero_byte_total = __builtin_amdgcn_exp2f(-63.75f) * (float)H * __builtin_amdgcn_exp2f(guard) * 1.00001f;
   const int r_lo = min(a.n_init, N), r_hi = max(r_lo, N - a.n_local);
   for (int t0 = tbeg; t0 < tend; t0 += 256) {
     uint32_t qc[NW];
@@ -97,33 +100,36 @@ __global__ __launch_bounds__(256) void vote_bounds_kernel(BoundArgs a, int token
     for (int w = 0; w < NW; ++w) qc[w] = qn[w];
     if (t0 + 256 < tend) load_codes(t0 + 256);
     const int t = t0 + (int)threadIdx.x;
-    const float* offp = s_off + (min(t, tend - 1) / BT - blk0) * H;
-    float up = 0.f, lo = 0.f;
+    const int tblk = min(t, tend - 1) / BT - blk0;
+    const float* offp = s_off + tblk * H;
+    float up = 0.f;
     if (HW > 0) {
 #pragma unroll
       for (int w = 0; w < NW; ++w) {
         const float4 o4 = *reinterpret_cast<const float4*>(offp + w * 4);
         const uint32_t c0 = qc[w] & 255u, c1 = (qc[w] >> 8) & 255u, c2b = (qc[w] >> 16) & 255u, c3 = qc[w] >> 24;
-        const float t0f = o4.x * s_pow[c0], t1f = o4.y * s_pow[c1], t2f = o4.z * s_pow[c2b], t3f = o4.w * s_pow[c3];
-        up += (t0f + t1f) + (t2f + t3f);
-        // byte 0 is open towards minus infinity: no lower bound from it
-        lo += ((c0 != 0u ? t0f : 0.f) + (c1 != 0u ? t1f : 0.f)) + ((c2b != 0u ? t2f : 0.f) + (c3 != 0u ? t3f : 0.f));
+        // 2^((byte - 255) / 4) from the hardware exponential: a 256-entry LDS table read at random addresses by 64 lanes
+        // conflicts on its banks and was what bounded the kernel (1M tokens: 15.2 us with the table, 14.2 us without)
+        const float p2 = __builtin_amdgcn_exp2f(fmaf((float)c2b, 0.25f, -63.75f));
+        const float p3 = __builtin_amdgcn_exp2f(fmaf((float)c3, 0.25f, -63.75f));
+        const float p1 = __builtin_amdgcn_exp2f(fmaf((float)c1, 0.25f, -63.75f));
+        const float p0 = __builtin_amdgcn_exp2f(fmaf((float)c0, 0.25f, -63.75f));
+        up = fmaf(o4.x, p0, up); up = fmaf(o4.y, p1, up);
+        up = fmaf(o4.z, p2, up); up = fmaf(o4.w, p3, up);
       }
     } else {
       const uint8_t* cp = a.codes + ((size_t)b * a.max_seq_len + min(t, N - 1)) * H;
       for (int h = 0; h < H; ++h) {
         const uint32_t c = cp[h];
-        const float tu = offp[h] * s_pow[c];
-        up += tu;
-        lo += c != 0u ? tu : 0.f;
+        up = fmaf(offp[h], __builtin_amdgcn_exp2f(fmaf((float)c, 0.25f, -63.75f)), up);
       }
     }
+    float lo = fmaxf(up - zero_byte_total, 0.f) * lo_scale;
     up *= kBoundUp;
-    lo *= lo_scale;
     if (t < tend) {
       const bool ranked = t >= r_lo && t < r_hi;
       a.vote_hi[(size_t)b * a.max_seq_len + t] = ranked ? up : 0.f;
-      a.vote_lo[(size_t)b * a.max_seq_len + t] = ranked ? lo : 0.f;
+      if (a.vote_lo != nullptr) a.vote_lo[(size_t)b * a.max_seq_len + t] = ranked ? lo : 0.f;
       if (ranked) atomicAdd(&hist[float_key(lo) >> 21], 1u);
     }
   }

@@ -116,7 +116,7 @@ class DecodeLayer:
             raise ValueError(kind)
         ts.ts_topk(self.problem, self.votes, self.k, self.idx, self.count, skip, self.ws)
 
-    def select_compact(self, q, score_scale=1.0, skip=None, check_theta=None):
+    def select_compact(self, q, score_scale=1.0, skip=None, check_theta=None, lower_bounds=True):
         """Eq. 5 selection without the score matrix in memory: one byte per score, vote bounds, exact votes of
         the candidates.  Same idx / count as select(kind="soft")."""
         if getattr(self, "codes", None) is None:
@@ -132,7 +132,8 @@ class DecodeLayer:
             skip = self.reuse
         else:
             ts.ts_paged_qk_codes(self.problem, q, self.codes, score_scale, skip, self.ws)
-        ts.ts_soft_vote_bounds(self.problem, self.codes, score_scale, self.row_stats, self.vote_hi, self.vote_lo, skip,
+        ts.ts_soft_vote_bounds(self.problem, self.codes, score_scale, self.row_stats, self.vote_hi,
+                               self.vote_lo if lower_bounds else None, skip,
                                self.ws)
         ts.ts_topk_exact(self.problem, q, self.vote_hi, self.row_stats, score_scale, self.k, self.idx, self.count, skip,
                          self.ws, sel_votes=getattr(self, "sel_votes", None))
@@ -162,7 +163,7 @@ class DecodeLayer:
                 self.selcache_check(q, theta)
                 skip = self.reuse
         if compact:
-            self.select_compact(q, score_scale, skip, check_theta=check_theta)
+            self.select_compact(q, score_scale, skip, check_theta=check_theta, lower_bounds=False)
         else:
             self.select(q, score_scale, skip, check_theta=check_theta, ranked_vote=ranked_vote)
         self.attend(q, sm)
