@@ -8,6 +8,7 @@
 // lanes per K row, a local softmax sits in LDS, the P.V product uses 16-byte V pieces per lane.  A
 // second small kernel merges the (max, sum, partial output) triples of the splits.
 #include "ts_kernels.h"
+#include "ts_score_math.h"
 
 namespace ts {
 
@@ -111,14 +112,24 @@ __global__ __launch_bounds__(256) void sparse_attn_decode_kernel(AttnArgs a) {
     for (int g = 0; g < G; ++g) acc[g] = 0.f;
 #pragma unroll
     for (int i = 0; i < L; ++i) {
-      float kf[EPL];
-      unpack16<DT>(kraw[s][i], kf);
+      if (DT == TS_BF16) {
+        // packed bf16 dot products (exact products, float accumulation): a quarter of the instructions of
+        // unpacking both operands and multiplying element by element
 #pragma unroll
-      for (int g = 0; g < G; ++g) {
-        float qf[EPL];
-        unpack16<DT>(qraw[g][i], qf);
+        for (int g = 0; g < G; ++g) {
+          Piece<TS_BF16, true>::Q qq; qq.w = qraw[g][i];
+          acc[g] = Piece<TS_BF16, true>::dot(kraw[s][i], qq, acc[g]);
+        }
+      } else {
+        float kf[EPL];
+        unpack16<DT>(kraw[s][i], kf);
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) acc[g] = fmaf(kf[e], qf[e], acc[g]);
+        for (int g = 0; g < G; ++g) {
+          float qf[EPL];
+          unpack16<DT>(qraw[g][i], qf);
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) acc[g] = fmaf(kf[e], qf[e], acc[g]);
+        }
       }
     }
 #pragma unroll
