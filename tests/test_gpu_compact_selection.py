@@ -114,11 +114,15 @@ def _check_compact(w, layer, q_dev, *, score_scale=1.0, label="", exact_bytes=Tr
         assert np.all(vl <= vd) and np.all(vd <= vh), (lab, "bounds vs dense votes")
         vo = ora["votes"][lo:hi]
         assert np.all(vl * (1 - 1e-5) <= vo) and np.all(vo <= vh * (1 + 1e-5)), (lab, "bounds vs oracle votes")
-        pos = vl > 0
+        # a quarter octave plus twice the guard (1e-3 octaves + c2 * |largest head maximum| * 2^-18 for the float
+        # scores' own rounding).  Heads whose byte is 0 are open towards minus infinity: the kernel takes the most they
+        # can have put into the upper sum, 2^(-63.75 + guard) * H, off every token's lower bound once.  That widens
+        # tokens whose whole vote is within 2^14 of this floor by more than the 1.0005 allows for (with one to three
+        # heads the median token can lie there: votes below 2^-49 * H), so the width is checked on the tokens above
+        # it; single tokens with a byte-0 head are wider, hence the median.
+        guard = 1e-3 + float(c2) * float(np.abs(st_c[b, :, 0]).max()) / 262144.0 if hi > lo else 0.0
+        pos = vl > w.H * 2.0 ** (-63.75 + guard + 14)
         if pos.any():
-            # a quarter octave plus twice the guard (1e-3 octaves + c2 * |largest head maximum| * 2^-18 for the float
-            # scores' own rounding); heads whose byte is 0 (open towards minus infinity) widen single tokens
-            guard = 1e-3 + float(c2) * float(np.abs(st_c[b, :, 0]).max()) / 262144.0
             width = 2 ** (0.25 + 2 * guard) * 1.0005
             assert np.median(vh[pos] / vl[pos]) <= width, (lab, "bounds too wide", np.median(vh[pos] / vl[pos]), width)
         assert not hi_g[b, :lo].any() and not hi_g[b, hi:N].any() and not lo_g[b, :lo].any() and not lo_g[b, hi:N].any(), lab
@@ -178,6 +182,9 @@ SHAPES = [
     (W.BF16, 64, 16, 64, 2, 400, 40),
     (W.BF16, 20, 4, 128, 1, 350, 30),
     (W.BF16, 32, 8, 64, 16, 1234, 77),
+    # one and two heads, D = 128: most tokens' votes lie near the byte-0 floor of the bounds
+    (W.BF16, 1, 1, 128, 16, 3000, 100),
+    (W.F32, 2, 1, 128, 1, 2600, 16),
 ]
 
 
