@@ -33,8 +33,9 @@ def run_chunk_selection(ts, w, k, scale, n_init=0, n_local=0):
             to_host(sel.out, bits16=True), to_host(sel.lse))
 
 
-def check_chunk(ts, w, k, scale, label, n_init=0, n_local=0):
-    st_g, v_g, idx_g, cnt_g, out_g, lse_g_attn = run_chunk_selection(ts, w, k, scale, n_init, n_local)
+def check_chunk(ts, w, k, scale, label, n_init=0, n_local=0, gpu_w=None):
+    """gpu_w: the workload as the GPU sees it when that is not w itself (same tokens, other pools and page ids)."""
+    st_g, v_g, idx_g, cnt_g, out_g, lse_g_attn = run_chunk_selection(ts, gpu_w if gpu_w is not None else w, k, scale, n_init, n_local)
     sm = float(np.float32(1.0 / math.sqrt(w.D)))
     c = float(np.float32(scale))
     for b in range(w.B):
