@@ -177,6 +177,20 @@ def test_topk_with_more_tied_candidates_than_one_batch(gpu):
     check_decode_against_oracle(w, layer, q, score_scale=0.05, label="many ties 20k")
 
 
+@pytest.mark.parametrize("forced", [(0, 0), (128, 640)])
+def test_largest_selection_the_attention_takes(gpu, forced):
+    # k + forced tokens = 32768, the most the decode attention merges (512 splits of 64 tokens); both forms
+    from test_gpu_compact_selection import check_compact
+    ni, nl = forced
+    k = 32768 - ni - nl
+    print("largest k", k, forced, flush=True)
+    w = W.make_workload("kmax", dtype=W.BF16, B=2, H=8, H_kv=2, D=64, P=16, seq_lens=[40000, 33000], k=k, beta=2.0,
+                        planted_per_head=4, seed=91 + ni)
+    layer, q = make_layer(w, num_initial=ni, num_local=nl)
+    check_decode_against_oracle(w, layer, q, score_scale=0.125, label="largest k %d" % k)
+    check_compact(w, layer, q, score_scale=0.125, label="largest k %d" % k)
+
+
 def test_five_pass_topk_path_gives_the_same_result(gpu):
     # the five-pass radix select (kept for sequences beyond 16 Mi tokens) forced on small inputs
     from paper_2411_02886_amd.runtime import to_host
