@@ -135,6 +135,18 @@ def test_large_batch_of_short_sequences(gpu):
     check_decode_against_oracle(w, layer, q, score_scale=0.2, label="batch40")
 
 
+def test_serving_sized_batch(gpu):
+    # 600 sequences in one call (grid extents in the hundreds along the batch axis), both forms, every sequence checked
+    from test_gpu_compact_selection import check_compact
+    rng = np.random.Generator(np.random.PCG64(73))
+    lens = [int(x) for x in rng.integers(0, 260, size=600)]
+    w = W.make_workload("batch600", dtype=W.BF16, B=600, H=8, H_kv=2, D=64, P=16, seq_lens=lens, k=24, seed=74)
+    layer, q = make_layer(w, num_initial=2, num_local=8)
+    print("batch of 600", flush=True)
+    check_decode_against_oracle(w, layer, q, score_scale=0.25, label="batch600")
+    check_compact(w, layer, q, score_scale=0.25, label="batch600")
+
+
 def test_max_seq_len_larger_than_every_sequence(gpu):
     w = W.make_workload("odd", dtype=W.F32, H=4, H_kv=2, D=64, P=16, seq_lens=[203], k=20, seed=12)
     layer, q = make_layer(w, max_seq_len=205)
