@@ -64,7 +64,7 @@ def parse():
     ap.add_argument("--theta", type=float, default=0.9, help="Selection Cache threshold of the config-3 run")
     ap.add_argument("--theta-sweep", action="store_true",
                     help="config 3: also run the thresholds of the paper's theta study (0.5 ... 1.0) and report reuse rate and steps/s for each")
-    ap.add_argument("--no-graph", action="store_true", help="config 3: time the host-driven loop only (no HIP-graph replay)")
+    ap.add_argument("--no-graph", action="store_true", help="time the host-driven single-stream loop only (no HIP-graph replay, no two-steps-in-flight run)")
     ap.add_argument("--page-size", type=int, default=16, help="tokens per page (16 in the configurations; 1 is the paper's own setting)")
     ap.add_argument("--selection", choices=["soft", "sum", "head"], default="soft",
                     help="selection function: soft = Eq. 5 (the method, default), sum = Eq. 3, head = Eq. 4 (ablation baselines)")
@@ -282,7 +282,7 @@ def chunked_prefill_run(args):
     print(json.dumps(res))
 
 
-def decode_bench(cfg, args, *, steps, warmup, with_cpu_baseline, with_graph):
+def decode_bench(cfg, args, *, steps, warmup, with_cpu_baseline, with_graph, with_overlap=None):
     """One decode configuration (1, 2 or 4): whole steps in the timed region, then a separate sampled loop that
     times the score kernel alone with HIP events bound to its dispatch."""
     import torch
@@ -342,7 +342,7 @@ def decode_bench(cfg, args, *, steps, warmup, with_cpu_baseline, with_graph):
     fused_check = args.check == "fused"       # Algorithm 1's test inside the score launch (one launch less)
     ranked_vote = args.vote == "ranked"       # five-call form: the TopK's first histogram is built inside the vote launch
 
-    def score_pass(p, q, stream):
+    def score_pass(p, q, stream, layer):
         if fused_check:
             st = (layer.cached_q, layer.cached_q_next, layer.first, layer.first_next, layer.reuse, theta)
             if compact:
@@ -355,17 +355,18 @@ def decode_bench(cfg, args, *, steps, warmup, with_cpu_baseline, with_graph):
         else:
             ts.ts_paged_qk_scores(p, q, layer.scores, scale, layer.reuse, layer.ws, stream)
 
-    def step(i, ev=None, kev=None):
+    def step(i, ev=None, kev=None, layer=layer, problems=problems, stream=None):
         p = problems[i % R]
         q = qs[i % R]
-        stream = torch.cuda.current_stream()      # the capture stream while a graph is being recorded
+        if stream is None:
+            stream = torch.cuda.current_stream()  # the capture stream while a graph is being recorded
         if not fused_check:
             ts.ts_selcache_check(p, q, layer.cached_q, layer.first, theta, layer.reuse, stream)
         if ev is not None:
             ev[0].record(stream)
         if kev is not None:          # HIP events bound to the score kernel's own start and end
             ts.ts_debug_set_score_timing_events(kev[0], kev[1])
-        score_pass(p, q, stream)
+        score_pass(p, q, stream, layer)
         if kev is not None:
             ts.ts_debug_set_score_timing_events(None, None)
         if compact:
@@ -443,6 +444,49 @@ def decode_bench(cfg, args, *, steps, warmup, with_cpu_baseline, with_graph):
     score_avg_ms = float(score_ms.mean())
     achieved = k_bytes / (score_avg_ms * 1e-3) / 1e9
 
+    # Two independent steps in flight: a second layer state (own workspace, score / code / vote buffers, Selection
+    # Cache state; same pools) takes every other step on a second stream, as two micro-batches of a server would.
+    # The small latency-bound launches of one step then run beside the other step's score pass.  Informational:
+    # `value` stays the single-stream loop above, where a step's launches depend on each other.
+    overlap_info = None
+    if (with_graph if with_overlap is None else with_overlap) and args.selection == "soft":
+        try:
+            layer_b = DecodeLayer(dtype=w.dtype, H=w.H, H_kv=w.H_kv, D=w.D, P=w.P, k=w.k, k_pool=layer.k_pool,
+                                  v_pool=layer.v_pool, page_indptr=w.page_indptr, page_indices=w.page_indices,
+                                  seq_lens=w.seq_lens, device=dev, num_initial=args.n_init, num_local=args.n_local)
+            if compact:
+                layer_b.codes = torch.empty_like(layer.codes); layer_b.vote_hi = torch.empty_like(layer.vote_hi)
+                layer_b.vote_lo = torch.empty_like(layer.vote_lo)
+            problems_b = []
+            for kp, vp, pi in pools:
+                layer_b.swap_pool(kp, vp, pi)
+                problems_b.append(layer_b.problem)
+            # what each layer must hold after its last step, from the single-stream path
+            n2 = max(8, steps // 2)
+            want = []
+            for j in (n2 - 1, n2):
+                step(j); torch.cuda.synchronize(); want.append(to_host(layer.idx).copy())
+            layer.first.fill_(1)
+            sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+            for timed in (False, True):
+                torch.cuda.synchronize()
+                sa.wait_stream(torch.cuda.current_stream()); sb.wait_stream(torch.cuda.current_stream())
+                tt = time.perf_counter()
+                for i in range(n2):
+                    step(i, layer=layer, problems=problems, stream=sa)
+                    step(i + 1, layer=layer_b, problems=problems_b, stream=sb)      # one query on: every step a miss
+                torch.cuda.synchronize()
+                tt = time.perf_counter() - tt
+            ok = (np.array_equal(to_host(layer.idx), want[0]) and np.array_equal(to_host(layer_b.idx), want[1])
+                  and int((to_host(layer.reuse) == 0).sum()) == w.B and int((to_host(layer_b.reuse) == 0).sum()) == w.B)
+            overlap_info = {"what": "two layer states on two streams, each running whole steps back to back",
+                            "ms_per_step": tt * 1e3 / (2 * n2), "steps": 2 * n2, "selections_match_single_stream": bool(ok),
+                            "whole_step_roofline_frac": (k_bytes + gather_bytes) / (tt / (2 * n2)) / 1e9 / HBM_PEAK_GBS}
+            del layer_b, problems_b
+        except Exception as e:
+            overlap_info = {"error": str(e)[:200]}
+        layer.first.fill_(1)
+
     # The same steps as one HIP graph (R consecutive steps, one per pool copy), replayed: what the step costs
     # without the host in the loop.  Informational; `value` is the host-driven loop above.
     graph_info = None
@@ -503,6 +547,7 @@ def decode_bench(cfg, args, *, steps, warmup, with_cpu_baseline, with_graph):
         "planted_token_quality": quality,
         "compact_vs_five_call_index_overlap": dense_agrees,
         "hip_graph_replay": graph_info,
+        "two_steps_in_flight": overlap_info,
         "selection_ms": {"what": "score pass + vote + top-k (the selection of Eq. 5), stream-ordered events, %d steps after the timed region" % nsample,
                          "avg": float(select_ms.mean()), "median": float(np.median(select_ms)), "min": float(select_ms.min())},
         "whole_step_roofline": {"what": "(K bytes of the score pass + K/V rows gathered by sparse attention) / ms_per_step / 8 TB/s",
@@ -551,14 +596,16 @@ def main():
         "dtype": head["dtype"], "data": "synthetic",
     }
     for k in ("config", "decode_steps_per_s", "launches_per_step", "selection_cache_check", "planted_token_quality", "compact_vs_five_call_index_overlap",
-              "hip_graph_replay", "selection_ms", "whole_step_roofline", "roofline", "cpu_baseline"):
+              "hip_graph_replay", "two_steps_in_flight", "selection_ms", "whole_step_roofline", "roofline", "cpu_baseline"):
         if k in head:
             res[k] = head[k]
     # the other end of the 128K-1M range rides along (its own timed region, same protocol)
     if args.config == 4 and not args.no_secondary and not args.tokens:
-        sec = decode_bench(2, args, steps=args.steps, warmup=args.warmup, with_cpu_baseline=False, with_graph=False)
+        sec = decode_bench(2, args, steps=args.steps, warmup=args.warmup, with_cpu_baseline=False, with_graph=False,
+                           with_overlap=not args.no_graph)
         res["secondary"] = {k: sec[k] for k in ("config", "ms_per_step", "tokens_scanned_per_s", "decode_steps_per_s",
-                                                 "launches_per_step", "selection_ms", "whole_step_roofline", "roofline")}
+                                                 "launches_per_step", "selection_ms", "whole_step_roofline", "roofline",
+                                                 "two_steps_in_flight")}
         if args.path != "dense" and args.selection == "soft":
             # at 128K tokens the five-call form (fp32 score matrix in memory) is the faster step although its score
             # pass is the slower kernel: both on record
