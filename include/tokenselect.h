@@ -25,7 +25,9 @@
  *   - Inputs containing NaN/Inf give unspecified results (no fault).
  *   - Sequences whose skip[b] byte is non-zero are left untouched by the three selection calls
  *     (their previous idx / count stay valid: Algorithm 1's "I <- C_I" branch).
- *   - Calls that share a workspace must not overlap in time (one stream, or ordered streams).
+ *   - Calls that share a workspace must not overlap in time (one stream, or ordered streams).  Calls on different
+ *     workspaces and different output buffers may overlap on different streams (they may share the pools, the page
+ *     table and the query): the library keeps no state of its own between calls besides the ts_debug_* knobs.
  *
  * Paged KV layout (the paper's K in R^{N_kv x H_kv x D} with index list I, Algorithm 2, grouped in
  * pages): pool[num_pages][page_size][H_kv][D]; logical token t of sequence b lives in physical slot

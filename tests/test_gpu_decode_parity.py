@@ -147,6 +147,42 @@ def test_serving_sized_batch(gpu):
     check_compact(w, layer, q, score_scale=0.25, label="batch600")
 
 
+def test_two_layers_on_two_streams_give_their_single_stream_results(gpu):
+    """Calls on different workspaces may overlap in time: two layers of different shapes run whole steps on two
+    streams, launches interleaved on the host, and each must end with the results of its own single-stream run."""
+    from paper_2411_02886_amd.runtime import to_host
+    wa = W.config2(N=30000, k=512, seed=301)
+    wb = W.make_workload("other_stream", dtype=W.BF16, B=3, H=28, H_kv=4, D=128, P=16, seq_lens=[9000, 0, 14001], k=300,
+                         beta=2.5, planted_per_head=2, seed=302)
+    sm = 1.0 / math.sqrt(128)
+    runs = []
+    for w in (wa, wb):
+        layer, q = make_layer(w, num_initial=4, num_local=32)
+        want = {}
+        for compact in (False, True):
+            layer.idx.fill_(-5); layer.out.zero_()
+            layer.first.fill_(1)
+            layer.step(q, theta=0.9, score_scale=1.0, sm_scale=sm, compact=compact)
+            torch.cuda.synchronize()
+            want[compact] = (to_host(layer.idx).copy(), to_host(layer.count).copy(), to_host(layer.out).copy())
+        runs.append((w, layer, q, want))
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for compact in (False, True):
+        for _, layer, _, _ in runs:
+            layer.idx.fill_(-5); layer.out.zero_()
+        torch.cuda.synchronize()
+        for it in range(6):
+            for (w, layer, q, _), st in zip(runs, streams):
+                with torch.cuda.stream(st):
+                    layer.first.fill_(1)                      # every step a miss: the whole chain runs each time
+                    layer.step(q, theta=0.9, score_scale=1.0, sm_scale=sm, compact=compact)
+        torch.cuda.synchronize()
+        for w, layer, q, want in runs:
+            idx, cnt, out = want[compact]
+            assert np.array_equal(to_host(layer.idx), idx) and np.array_equal(to_host(layer.count), cnt), (w.name, compact)
+            assert np.array_equal(to_host(layer.out), out), (w.name, compact, "attention output")
+
+
 def test_max_seq_len_larger_than_every_sequence(gpu):
     w = W.make_workload("odd", dtype=W.F32, H=4, H_kv=2, D=64, P=16, seq_lens=[203], k=20, seed=12)
     layer, q = make_layer(w, max_seq_len=205)
