@@ -22,7 +22,8 @@
  *     host.  `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *   - Every function returns TS_OK (0) or a negative ts_status.  Argument errors are detected on
  *     the host before anything is launched; nothing has been written in that case.
- *   - Inputs containing NaN/Inf give unspecified results (no fault).
+ *   - Inputs containing NaN/Inf give unspecified results, but no fault: count[b] stays within [0, min(k, N_b)] and
+ *     every idx entry is a token of the sequence or -1.
  *   - Sequences whose skip[b] byte is non-zero are left untouched by the three selection calls
  *     (their previous idx / count stay valid: Algorithm 1's "I <- C_I" branch).
  *   - Calls that share a workspace must not overlap in time (one stream, or ordered streams).  Calls on different

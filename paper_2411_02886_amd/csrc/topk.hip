@@ -449,7 +449,9 @@ __global__ __launch_bounds__(kFinalThreads) void topk_final_kernel(TopkArgs a) {
   int32_t* out = as_votes ? nullptr : a.idx + (size_t)b * a.k;
   float* acc = as_votes ? a.vote_acc + (size_t)(b / a.heads) * a.max_seq_len : nullptr;
   if (!as_votes) {
-    for (int i = k_eff + tid; i < a.k; i += kFinalThreads) out[i] = -1;
+    // FULL: the candidates come from float comparisons; with NaN among the votes fewer than k_eff of them may
+    // arrive, and the slots that then stay empty must not keep an older selection's ids (finite votes fill them all)
+    for (int i = (FULL ? 0 : k_eff) + tid; i < a.k; i += kFinalThreads) out[i] = -1;
     if (FULL && a.sel_votes != nullptr)
       for (int i = k_eff + tid; i < a.k; i += kFinalThreads) a.sel_votes[(size_t)b * a.k + i] = 0.f;
     if (tid == 0) a.count[b] = k_eff;
