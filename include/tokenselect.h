@@ -268,7 +268,8 @@ int32_t ts_paged_qk_codes_checked(const ts_problem* p, const void* q, const ts_s
  * Chunk form (chunk = C > 1, bf16): query c of the chunk (logical token N_b - C + c) attends over the
  * count[b] selected tokens and the chunk's own tokens 0..c in one joint softmax (Eq. 2's
  * [K_select, K_current] with a causal mask inside the chunk); the weights that multiply V are rounded
- * to bf16 (matrix-core operand). */
+ * to bf16 (matrix-core operand).  A sequence with N_b < C holds no chunk (an idle slot of the batch): its rows of
+ * out are zero, its lse -inf, and nothing is read through its page table (the selection calls give it count 0). */
 int32_t ts_sparse_paged_attn(const ts_problem* p, const void* q, const int32_t* idx, int32_t idx_stride,
                              const int32_t* count, float sm_scale, void* out, float* lse, void* ws,
                              size_t ws_bytes, void* stream);

@@ -29,6 +29,7 @@ __global__ __launch_bounds__(256) void chunk_slots_kernel(ChunkAttnArgs a) {
   const int j = blockIdx.x * 256 + threadIdx.x;
   const int cnt = min(max(a.count[b], 0), a.idx_stride);
   const int N = min(max(a.seq_lens[b], 0), a.max_seq_len);
+  if (N < a.C) return;                                          // shorter than a chunk: holds none, nothing is attended
   const int Nc = max(N - a.C, 0);                               // cached tokens before the chunk
   const int f_lo = min(a.n_init, Nc), f_hi = max(f_lo, Nc - a.n_local);   // forced blocks [0, f_lo) and [f_hi, Nc)
   const int nsel = f_lo + cnt + (Nc - f_hi);                    // keys every query of the chunk sees
@@ -69,6 +70,23 @@ __global__ __launch_bounds__(256) void chunk_attn_kernel(ChunkAttnArgs a) {
   const int cnt = f_lo_ + min(max(a.count[b], 0), a.idx_stride) + (Nc_ - f_hi_);
   const int r0 = rb * kCaRows;
   if (r0 >= nrows) return;
+  if (min(max(a.seq_lens[b], 0), a.max_seq_len) < C) {
+    // a sequence shorter than the chunk holds no chunk (an idle slot of the batch): its rows are zero, and nothing is
+    // read through its page table, which may be empty
+    for (int i = threadIdx.x; i < kCaRows * D; i += 256) {
+      const int row = r0 + i / D, d = i % D;
+      if (row >= nrows) break;
+      const size_t hb = ((size_t)b * C + row / G) * H + kvh * G + row % G;
+      if (a.nsplit == 1) {
+        reinterpret_cast<uint16_t*>(a.out)[hb * D + d] = 0;
+        if (d == 0 && a.lse != nullptr) a.lse[hb] = -INFINITY;
+      } else {
+        a.part_o[(hb * a.nsplit + split) * D + d] = 0.f;
+        if (d == 0) { float* pm = a.part_ml + (hb * a.nsplit + split) * 2; pm[0] = -INFINITY; pm[1] = 0.f; }
+      }
+    }
+    return;
+  }
   const int c_last = min(C - 1, (r0 + kCaRows - 1) / G);      // last query of this row block
   const int nkeys = cnt + c_last + 1;                          // keys any row of the block may see
   const int ntile_all = (nkeys + kCaTile - 1) / kCaTile;

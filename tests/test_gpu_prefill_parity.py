@@ -42,6 +42,11 @@ def check_chunk(ts, w, k, scale, label, n_init=0, n_local=0, gpu_w=None):
         Nc = max(int(w.seq_lens[b]) - w.C, 0)
         lo, hi = oracle.ranked_range(Nc, n_init, n_local)          # forced blocks are taken from the cached tokens
         lab = "%s b=%d Nc=%d" % (label, b, Nc)
+        if int(w.seq_lens[b]) < w.C:
+            # shorter than the chunk (an idle slot of the batch): nothing selected, nothing attended, rows zero
+            assert cnt_g[b] == 0 and np.all(idx_g[b] == -1), lab
+            assert not out_g[b].any() and np.all(np.isneginf(lse_g_attn[b])), (lab, "idle sequence")
+            continue
         if hi <= lo:
             assert cnt_g[b] == 0 and np.all(idx_g[b] == -1), lab
         # Eq. 2, chunk form: query c over the forced and selected tokens plus the chunk's tokens 0..c (one softmax)
@@ -109,6 +114,17 @@ def test_chunk_selection_with_forced_tokens(gpu, forced):
     check_chunk(gpu, w, 50, 0.0884, "chunk forced %d+%d" % forced, n_init=ni, n_local=nl)
     w = W.make_workload("chunkf2", dtype=W.BF16, C=130, H=32, H_kv=8, D=128, P=16, seq_lens=[130 + 4000], k=256, seed=43)
     check_chunk(gpu, w, 256, 1.0, "chunk forced cfg5 heads %d+%d" % forced, n_init=ni, n_local=nl)
+
+
+def test_chunk_batch_with_idle_sequences(gpu):
+    # sequences shorter than the chunk, the last one with no page at all: they hold no chunk; their rows come back
+    # zero and nothing is read through their page table entries
+    C = 48
+    lens = [C + 1500, 0, 7, C - 1, C + 300, 0]
+    w = W.make_workload("chunk_idle", dtype=W.BF16, B=len(lens), C=C, H=16, H_kv=4, D=128, P=16, seq_lens=lens, k=64, seed=88)
+    print("chunk idle", lens, flush=True)
+    for forced in ((0, 0), (16, 32)):
+        check_chunk(gpu, w, 64, 1.0, "idle %d+%d" % forced, n_init=forced[0], n_local=forced[1])
 
 
 def test_chunk_selection_ragged_batch(gpu):
