@@ -264,7 +264,9 @@ int32_t ts_paged_qk_codes_checked(const ts_problem* p, const void* q, const ts_s
  * over j < count[b]; float accumulation, result rounded to p->dtype.  idx [device] int32 [B][k]
  * (logical token ids, k = idx_stride); count [device] int32 [B]; out [device] [B][C][H][D];
  * lse [device] float [B][C][H] or NULL (log-sum-exp of the scaled logits).  count[b] == 0 gives
- * out = 0 and lse = -inf.
+ * out = 0 and lse = -inf.  idx and count are read defensively (they may be a cached selection of an earlier step):
+ * token ids are clamped into [0, N_b), count[b] into [0, k], and a sequence with N_b == 0 attends nothing whatever its
+ * count says.  The page table itself is trusted: every page id of a sequence must lie inside the pools.
  * Chunk form (chunk = C > 1, bf16): query c of the chunk (logical token N_b - C + c) attends over the
  * count[b] selected tokens and the chunk's own tokens 0..c in one joint softmax (Eq. 2's
  * [K_select, K_current] with a causal mask inside the chunk); the weights that multiply V are rounded

@@ -49,7 +49,7 @@ __global__ __launch_bounds__(256) void sparse_attn_decode_kernel(AttnArgs a) {
   // attended list = forced initial tokens [0, f_lo), the cnt selected tokens, forced recent tokens [f_hi, nb)
   const int nb = min(max(a.seq_lens[b], 0), a.max_seq_len);
   const int f_lo = min(a.n_init, nb), f_hi = max(f_lo, nb - a.n_local);
-  const int cnt = min(max(a.count[b], 0), a.idx_stride);
+  const int cnt = nb > 0 ? min(max(a.count[b], 0), a.idx_stride) : 0;   // an empty sequence attends nothing, whatever count says: its page table may be empty
   const int total = f_lo + cnt + (nb - f_hi);
   const int j0 = split * CH;
   const int nj = min(max(total - j0, 0), CH);
@@ -217,7 +217,7 @@ __global__ __launch_bounds__(D * kMergeGroups) void sparse_attn_merge_kernel(Att
   const float* ml = a.part_ml + hb * a.nsplit * 2;
   const int nb = min(max(a.seq_lens[b], 0), a.max_seq_len);
   const int f_lo = min(a.n_init, nb), f_hi = max(f_lo, nb - a.n_local);
-  const int total = f_lo + min(max(a.count[b], 0), a.idx_stride) + (nb - f_hi);
+  const int total = f_lo + (nb > 0 ? min(max(a.count[b], 0), a.idx_stride) : 0) + (nb - f_hi);
   const int ns = min(a.nsplit, (total + kAttnChunk - 1) / kAttnChunk);   // splits that hold tokens
   // the partial outputs do not depend on the weights: their loads go out first
   const float* po = a.part_out + hb * a.nsplit * D + d;

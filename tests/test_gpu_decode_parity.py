@@ -183,6 +183,35 @@ def test_two_layers_on_two_streams_give_their_single_stream_results(gpu):
             assert np.array_equal(to_host(layer.out), out), (w.name, compact, "attention output")
 
 
+def test_attention_bounds_stale_and_corrupt_selection_state(gpu):
+    """idx and count live in device memory between steps (the cached selection of Algorithm 1); the attention kernels
+    bound what they read from them: token ids are clamped into the sequence, counts into [0, k], and an empty
+    sequence attends nothing whatever its count says (it may own no page at all)."""
+    from paper_2411_02886_amd.runtime import to_device, to_host
+    lens = [900, 300, 0]
+    w = W.make_workload("stale", dtype=W.BF16, B=3, H=8, H_kv=2, D=128, P=16, seq_lens=lens, k=32, seed=17)
+    layer, q = make_layer(w)
+    layer.select(q, 1.0, None)
+    torch.cuda.synchronize()
+    idx = to_host(layer.idx).copy(); cnt = to_host(layer.count).copy()
+    idx[0, 3] = -12; idx[0, 5] = 10 ** 9; idx[1, 0] = 300
+    cnt[1] = 1000
+    cnt[2] = 17; idx[2, :17] = 5
+    layer.idx.copy_(to_device(idx)); layer.count.copy_(to_device(cnt))
+    sm = 1.0 / math.sqrt(w.D)
+    layer.attend(q, sm)
+    torch.cuda.synchronize()
+    out = W.as_f32(to_host(layer.out, bits16=True), w.dtype).astype(np.float64)
+    for b, N in enumerate(lens):
+        if N == 0:
+            assert not out[b].any()
+            continue
+        att = np.clip(idx[b, :min(max(int(cnt[b]), 0), w.k)], 0, N - 1).astype(np.int32)
+        ref = oracle.sparse_attn(np.ascontiguousarray(w.q[b, 0]), w.k_pool, w.v_pool, w.dtype, w.H_kv, w.P, w.pages_of(b),
+                                 att, len(att), float(np.float32(sm)))
+        assert np.abs(out[b, 0] - ref).max() <= 2e-2, b
+
+
 def test_max_seq_len_larger_than_every_sequence(gpu):
     w = W.make_workload("odd", dtype=W.F32, H=4, H_kv=2, D=64, P=16, seq_lens=[203], k=20, seed=12)
     layer, q = make_layer(w, max_seq_len=205)
