@@ -125,6 +125,8 @@ def test_chunk_batch_with_idle_sequences(gpu):
     print("chunk idle", lens, flush=True)
     for forced in ((0, 0), (16, 32)):
         check_chunk(gpu, w, 64, 1.0, "idle %d+%d" % forced, n_init=forced[0], n_local=forced[1])
+    # a key list long enough to be split over workgroups: the idle rows go through the merge of the splits
+    check_chunk(gpu, w, 1024, 1.0, "idle, split key list")
 
 
 def test_chunk_selection_ragged_batch(gpu):
