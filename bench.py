@@ -15,7 +15,8 @@ Selection Cache miss (cosine of independent queries ~ 0 < theta = 0.9) and scans
 
 Prints ONE JSON line: metric, value (tokens scanned per second over whole steps), ms_per_step, the score
 kernel's roofline (achieved GB/s from HIP events bound to its dispatch, on at least 32 steps run right after the
-timed region), and the CPU oracle timed on the same workload.
+timed region), and the CPU oracle timed on the same workload.  Beside it, informational: the same steps replayed as a
+HIP graph (`hip_graph_replay`) and with two independent steps in flight on two streams (`two_steps_in_flight`).
 """
 from __future__ import annotations
 
