@@ -3,9 +3,10 @@
 // indices, never as gathered K/V copies).
 //
 // Split-k: a workgroup takes 64 selected tokens (kAttnChunk) of one KV head (all G query heads of the group share
-// the gathered K and V rows).  Memory latency, not bandwidth, bounds this step (a few MiB are
+// the gathered K and V rows).  For one sequence memory latency, not bandwidth, bounds this step (a few MiB are
 // gathered), so every K and V load of a wave is issued before the first multiply; logits use eight
-// lanes per K row, a local softmax sits in LDS, the P.V product uses 16-byte V pieces per lane.  A
+// lanes per K row, a local softmax sits in LDS, the P.V product uses 16-byte V pieces per lane.  With
+// thousands of such workgroups (large batches) a workgroup takes several chunks in a row instead (MULTI).  A
 // second small kernel merges the (max, sum, partial output) triples of the splits.
 #include "ts_kernels.h"
 #include "ts_score_math.h"
@@ -26,7 +27,13 @@ template <> __device__ __forceinline__ void unpack16<TS_BF16>(uint4 w, float* f)
   f[4] = bf16_lo(w.z); f[5] = bf16_hi(w.z); f[6] = bf16_lo(w.w); f[7] = bf16_hi(w.w);
 }
 
-template <int DT, int D, int G>
+// MULTI: a workgroup takes up to kAttnMaxRun consecutive chunks of 64 tokens (a.nch of them) and folds them into one
+// partial with a running (max, sum): the next chunk's K and V rows are in flight while the current chunk is worked
+// on.  For batches whose splits alone give thousands of workgroups the step is a throughput problem, and a workgroup
+// that loads, then computes, then leaves keeps the memory system busy about half of its life; a plain random gather
+// of 256-byte pieces from the same pools runs at 5.9 TB/s.  With few workgroups (one sequence) the single-chunk form
+// stays: there the chain of one workgroup is the latency that counts.
+template <int DT, int D, int G, bool MULTI>
 __global__ __launch_bounds__(256) void sparse_attn_decode_kernel(AttnArgs a) {
   constexpr int ES = AElt<DT>::size;
   constexpr int RB = D * ES;
@@ -34,14 +41,15 @@ __global__ __launch_bounds__(256) void sparse_attn_decode_kernel(AttnArgs a) {
   constexpr int EPL = 16 / ES;         // elements per 16-byte piece
   constexpr int LPR = RB / 16;         // lanes per V row
   constexpr int RPL = 64 / LPR;        // V rows per wave load
-  constexpr int CH = kAttnChunk;       // selected tokens per workgroup
-  constexpr int WT = CH / 4;           // tokens per wave
+  constexpr int CH = kAttnChunk;       // selected tokens per chunk
+  constexpr int WT = CH / 4;           // tokens per wave and chunk
   constexpr int KS = WT / 8;           // K steps per wave (eight rows each)
   constexpr int VS = WT / RPL;         // V loads per lane
-  __shared__ long long s_slot[CH];
+  constexpr int NSL = MULTI ? kAttnMaxRun * CH : CH;
+  __shared__ long long s_slot[NSL];
   __shared__ float s_p[G][CH];
   __shared__ __attribute__((aligned(16))) float s_red[4 * (64 / (D * AElt<DT>::size / 16))][G][D];   // [wave x row group][head][d]
-  __shared__ float s_ml[G][2];
+  __shared__ float s_ml[G][3];         // running max, running sum, factor that rescales what was summed before this chunk
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
@@ -51,8 +59,9 @@ __global__ __launch_bounds__(256) void sparse_attn_decode_kernel(AttnArgs a) {
   const int f_lo = min(a.n_init, nb), f_hi = max(f_lo, nb - a.n_local);
   const int cnt = nb > 0 ? min(max(a.count[b], 0), a.idx_stride) : 0;   // an empty sequence attends nothing, whatever count says: its page table may be empty
   const int total = f_lo + cnt + (nb - f_hi);
-  const int j0 = split * CH;
-  const int nj = min(max(total - j0, 0), CH);
+  const int span = MULTI ? CH * a.nch : CH;     // a.nch <= kAttnMaxRun
+  const int j0 = split * span;
+  const int nj = min(max(total - j0, 0), span);
   if (nj <= 0) {                       // nothing attended in this split: publish an empty partial
     if (threadIdx.x < G) {
       float* ml = a.part_ml + (((size_t)b * H + kvh * G + threadIdx.x) * a.nsplit + split) * 2;
@@ -60,10 +69,11 @@ __global__ __launch_bounds__(256) void sparse_attn_decode_kernel(AttnArgs a) {
     }
     return;
   }
-  if (threadIdx.x < CH) {
+  const int nchunk = MULTI ? (nj + CH - 1) / CH : 1;
+  if (threadIdx.x < NSL) {             // one thread per list entry of the workgroup's span
     long long slot = -1;
     const int jj = j0 + threadIdx.x;
-    if (jj < total) {
+    if ((int)threadIdx.x < span && jj < total) {
       int t;
       if (jj < f_lo) t = jj;
       else if (jj < f_lo + cnt) t = a.idx[(size_t)b * a.idx_stride + (jj - f_lo)];
@@ -84,104 +94,128 @@ __global__ __launch_bounds__(256) void sparse_attn_decode_kernel(AttnArgs a) {
       qraw[g][i] = *reinterpret_cast<const uint4*>(a.q + ((size_t)b * H + (size_t)kvh * G + g) * RB + i * 128 + j * 16);
   __syncthreads();
 
-  // ---- issue every K and V load of this wave before any arithmetic: one memory round trip
-  const long long slot0 = s_slot[0];   // valid because nj > 0; stands in for the padding rows
-  uint4 kraw[KS][L];
-  bool kvalid[KS];
-#pragma unroll
-  for (int s = 0; s < KS; ++s) {
-    const long long slot = s_slot[wave * WT + s * 8 + r];
-    kvalid[s] = slot >= 0;
-    const uint8_t* kp = a.k_pool + ((size_t)(kvalid[s] ? slot : slot0) * a.H_kv + kvh) * RB + j * 16;
-#pragma unroll
-    for (int i = 0; i < L; ++i) kraw[s][i] = *reinterpret_cast<const uint4*>(kp + i * 128);
-  }
+  // ---- every K and V load of a wave and chunk is issued before any arithmetic on it: one memory round trip
   const int piece = lane % LPR, rsub = lane / LPR;
-  uint4 vraw[VS];
+  struct Raw { uint4 k[KS][L]; uint4 v[VS]; bool kvalid[KS]; };
+  auto issue = [&](int c, Raw& x) {
+    const long long* sl = s_slot + c * CH;
+    const long long slot0 = sl[0];     // valid: every chunk of the span holds a token; stands in for the padding rows
 #pragma unroll
-  for (int it = 0; it < VS; ++it) {
-    const long long slot = s_slot[wave * WT + it * RPL + rsub];
-    vraw[it] = *reinterpret_cast<const uint4*>(a.v_pool + ((size_t)(slot >= 0 ? slot : slot0) * a.H_kv + kvh) * RB + piece * 16);
-  }
-
-  // ---- logits
+    for (int s = 0; s < KS; ++s) {
+      const long long slot = sl[wave * WT + s * 8 + r];
+      x.kvalid[s] = slot >= 0;
+      const uint8_t* kp = a.k_pool + ((size_t)(x.kvalid[s] ? slot : slot0) * a.H_kv + kvh) * RB + j * 16;
 #pragma unroll
-  for (int s = 0; s < KS; ++s) {
-    float acc[G];
-#pragma unroll
-    for (int g = 0; g < G; ++g) acc[g] = 0.f;
-#pragma unroll
-    for (int i = 0; i < L; ++i) {
-      if (DT == TS_BF16) {
-        // packed bf16 dot products (exact products, float accumulation): a quarter of the instructions of
-        // unpacking both operands and multiplying element by element
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-          Piece<TS_BF16, true>::Q qq; qq.w = qraw[g][i];
-          acc[g] = Piece<TS_BF16, true>::dot(kraw[s][i], qq, acc[g]);
-        }
-      } else {
-        float kf[EPL];
-        unpack16<DT>(kraw[s][i], kf);
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-          float qf[EPL];
-          unpack16<DT>(qraw[g][i], qf);
-#pragma unroll
-          for (int e = 0; e < EPL; ++e) acc[g] = fmaf(kf[e], qf[e], acc[g]);
-        }
-      }
+      for (int i = 0; i < L; ++i) x.k[s][i] = *reinterpret_cast<const uint4*>(kp + i * 128);
     }
 #pragma unroll
-    for (int g = 0; g < G; ++g) acc[g] = group8_sum(acc[g]);
-    float v = acc[0];
-#pragma unroll
-    for (int g = 1; g < G; ++g) v = (j == g) ? acc[g] : v;
-    if (j < G) s_p[j][wave * WT + s * 8 + r] = kvalid[s] ? v * a.sm_scale : -INFINITY;
-  }
-  __syncthreads();
-
-  // ---- local softmax: eight lanes per head, eight tokens per lane, the lanes of a head meet through DPP
-  if (threadIdx.x < G * 8) {
-    constexpr int TPL = CH / 8;                  // tokens per lane
-    const int g = threadIdx.x >> 3, part = threadIdx.x & 7;
-    float x[TPL];
-    float m = -INFINITY;
-#pragma unroll
-    for (int e = 0; e < TPL; ++e) { x[e] = s_p[g][part + 8 * e]; m = fmaxf(m, x[e]); }
-    m = group8_max(m);
-    float l = 0.f;
-#pragma unroll
-    for (int e = 0; e < TPL; ++e) {
-      const float p = (x[e] == -INFINITY) ? 0.f : expf(x[e] - m);
-      s_p[g][part + 8 * e] = p;
-      l += p;
+    for (int it = 0; it < VS; ++it) {
+      const long long slot = sl[wave * WT + it * RPL + rsub];
+      x.v[it] = *reinterpret_cast<const uint4*>(a.v_pool + ((size_t)(slot >= 0 ? slot : slot0) * a.H_kv + kvh) * RB + piece * 16);
     }
-    l = group8_sum(l);
-    if (part == 0) { s_ml[g][0] = m; s_ml[g][1] = l; }
-  }
-  __syncthreads();
-
-  // ---- P.V from the V pieces already in registers
+  };
+  Raw cur, nxt;
+  issue(0, cur);
   float acc[G][EPL];
 #pragma unroll
   for (int g = 0; g < G; ++g)
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
-#pragma unroll
-  for (int it = 0; it < VS; ++it) {
-    const int jl = wave * WT + it * RPL + rsub;
-    float vf[EPL];
-    unpack16<DT>(vraw[it], vf);
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      const float p = s_p[g][jl];        // 0 for padding rows
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(p, vf[e], acc[g][e]);
+  float m_run = -INFINITY, l_run = 0.f;          // of head threadIdx.x / 8, in the threads of the softmax stage
+
+  for (int c = 0; c < nchunk; ++c) {
+    if (MULTI) {
+      if (c > 0) __syncthreads();                // the previous chunk's weights have been read by every wave
+      if (c + 1 < nchunk) issue(c + 1, nxt);
     }
+    // ---- logits
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      float lg[G];
+#pragma unroll
+      for (int g = 0; g < G; ++g) lg[g] = 0.f;
+#pragma unroll
+      for (int i = 0; i < L; ++i) {
+        if (DT == TS_BF16) {
+          // packed bf16 dot products (exact products, float accumulation): a quarter of the instructions of
+          // unpacking both operands and multiplying element by element
+#pragma unroll
+          for (int g = 0; g < G; ++g) {
+            Piece<TS_BF16, true>::Q qq; qq.w = qraw[g][i];
+            lg[g] = Piece<TS_BF16, true>::dot(cur.k[s][i], qq, lg[g]);
+          }
+        } else {
+          float kf[EPL];
+          unpack16<DT>(cur.k[s][i], kf);
+#pragma unroll
+          for (int g = 0; g < G; ++g) {
+            float qf[EPL];
+            unpack16<DT>(qraw[g][i], qf);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) lg[g] = fmaf(kf[e], qf[e], lg[g]);
+          }
+        }
+      }
+#pragma unroll
+      for (int g = 0; g < G; ++g) lg[g] = group8_sum(lg[g]);
+      float v = lg[0];
+#pragma unroll
+      for (int g = 1; g < G; ++g) v = (j == g) ? lg[g] : v;
+      if (j < G) s_p[j][wave * WT + s * 8 + r] = cur.kvalid[s] ? v * a.sm_scale : -INFINITY;
+    }
+    __syncthreads();
+
+    // ---- softmax of the chunk against the running maximum: eight lanes per head, eight tokens per lane, the lanes of
+    // a head meet through DPP
+    if (threadIdx.x < G * 8) {
+      constexpr int TPL = CH / 8;                  // tokens per lane
+      const int g = threadIdx.x >> 3, part = threadIdx.x & 7;
+      float x[TPL];
+      float m = -INFINITY;
+#pragma unroll
+      for (int e = 0; e < TPL; ++e) { x[e] = s_p[g][part + 8 * e]; m = fmaxf(m, x[e]); }
+      m = fmaxf(group8_max(m), m_run);             // a chunk holds a token, so m is finite unless every logit is -inf / NaN
+      float l = 0.f;
+#pragma unroll
+      for (int e = 0; e < TPL; ++e) {
+        const float p = (x[e] == -INFINITY) ? 0.f : expf(x[e] - m);
+        s_p[g][part + 8 * e] = p;
+        l += p;
+      }
+      l = group8_sum(l);
+      const float f = (MULTI && m_run != -INFINITY) ? expf(m_run - m) : 0.f;   // nothing summed before the first chunk
+      l_run = fmaf(l_run, f, l);
+      m_run = m;
+      if (part == 0) { s_ml[g][0] = m_run; s_ml[g][1] = l_run; s_ml[g][2] = f; }
+    }
+    __syncthreads();
+
+    // ---- P.V from the V pieces already in registers
+    if (MULTI && c > 0) {
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const float f = s_ml[g][2];
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[g][e] *= f;
+      }
+    }
+#pragma unroll
+    for (int it = 0; it < VS; ++it) {
+      const int jl = wave * WT + it * RPL + rsub;
+      float vf[EPL];
+      unpack16<DT>(cur.v[it], vf);
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const float p = s_p[g][jl];        // 0 for padding rows
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(p, vf[e], acc[g][e]);
+      }
+    }
+    if (MULTI) cur = nxt;
   }
   // lanes with the same piece but different rsub hold partial sums of the same outputs: all of them go to LDS (16-byte
-  // stores) and meet there -- a cross-lane exchange of the G * EPL accumulators costs more LDS operations than that
+  // stores) and meet there -- a cross-lane exchange of the G * EPL accumulators costs more LDS operations than that,
+  // and one strip per wave filled by the row groups in turn (a quarter of the LDS) costs 1-2 us of latency
 #pragma unroll
   for (int g = 0; g < G; ++g)
 #pragma unroll
@@ -218,7 +252,8 @@ __global__ __launch_bounds__(D * kMergeGroups) void sparse_attn_merge_kernel(Att
   const int nb = min(max(a.seq_lens[b], 0), a.max_seq_len);
   const int f_lo = min(a.n_init, nb), f_hi = max(f_lo, nb - a.n_local);
   const int total = f_lo + (nb > 0 ? min(max(a.count[b], 0), a.idx_stride) : 0) + (nb - f_hi);
-  const int ns = min(a.nsplit, (total + kAttnChunk - 1) / kAttnChunk);   // splits that hold tokens
+  const int span = kAttnChunk * a.nch;
+  const int ns = min(a.nsplit, (total + span - 1) / span);   // splits that hold tokens
   // the partial outputs do not depend on the weights: their loads go out first
   const float* po = a.part_out + hb * a.nsplit * D + d;
   float v[8];
@@ -270,7 +305,8 @@ __global__ __launch_bounds__(D * kMergeGroups) void sparse_attn_merge_kernel(Att
 
 template <int DT, int D>
 static hipError_t attn_launch_g(int G, const AttnArgs& a, dim3 grid, hipStream_t s) {
-#define TS_CASE(g) case g: hipLaunchKernelGGL((sparse_attn_decode_kernel<DT, D, g>), grid, dim3(256), 0, s, a); break;
+#define TS_CASE(g) case g: if (a.nch > 1) hipLaunchKernelGGL((sparse_attn_decode_kernel<DT, D, g, true>), grid, dim3(256), 0, s, a); \
+                   else hipLaunchKernelGGL((sparse_attn_decode_kernel<DT, D, g, false>), grid, dim3(256), 0, s, a); break;
   switch (G) {
     TS_CASE(1) TS_CASE(2) TS_CASE(3) TS_CASE(4) TS_CASE(5) TS_CASE(6) TS_CASE(7) TS_CASE(8)
     default: return hipErrorInvalidValue;
@@ -281,6 +317,7 @@ static hipError_t attn_launch_g(int G, const AttnArgs& a, dim3 grid, hipStream_t
 }
 
 hipError_t launch_sparse_attn_decode(int dtype, int D, int G, const AttnArgs& a, int B, hipStream_t s) {
+  if (a.nch < 1 || a.nch > kAttnMaxRun) return hipErrorInvalidValue;
   dim3 grid(a.nsplit, a.H_kv, B);
   if (dtype == TS_F32) return D == 64 ? attn_launch_g<TS_F32, 64>(G, a, grid, s) : attn_launch_g<TS_F32, 128>(G, a, grid, s);
   return D == 64 ? attn_launch_g<TS_BF16, 64>(G, a, grid, s) : attn_launch_g<TS_BF16, 128>(G, a, grid, s);

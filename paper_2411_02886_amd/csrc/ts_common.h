@@ -15,6 +15,7 @@ constexpr int kTopkBins = 2048;        // 11-bit radix digit
 constexpr int kTopkChunk = 2048;       // keys per workgroup in the top-k passes
 constexpr int kBoundHistCopies = 8;    // replicas of the lower-bound histogram (same-address atomics are what its flush costs)
 constexpr int kAttnChunk = 64;         // selected tokens per workgroup in sparse attention
+constexpr int kAttnMaxRun = 4;        // chunks one attention workgroup folds into its partial, at most (256 list entries: one per thread)
 constexpr int kAttnMaxSplit = 512;     // splits the merge kernel can stage (k <= 32768)
 
 // ---------------------------------------------------------------- workspace layout (host + device)

@@ -128,6 +128,7 @@ struct AttnArgs {
   float* part_ml;      // [B][H][nsplit][2]
   int H, H_kv, P, p_shift, idx_stride, nsplit, max_seq_len;
   int n_init, n_local;  // forced tokens attended before / after the selected ones
+  int nch;              // chunks of kAttnChunk tokens per workgroup (1 .. kAttnMaxRun); nsplit counts workgroups
   float sm_scale;
 };
 

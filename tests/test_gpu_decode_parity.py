@@ -212,6 +212,26 @@ def test_attention_bounds_stale_and_corrupt_selection_state(gpu):
         assert np.abs(out[b, 0] - ref).max() <= 2e-2, b
 
 
+def test_attention_with_several_chunks_per_workgroup(gpu):
+    # 8192 and more chunk workgroups: a workgroup folds four chunks of 64 tokens into its partial with a running
+    # maximum and sum; ragged ends (a last workgroup with one, two or three chunks, a last chunk of a few tokens),
+    # empty sequences and forced tokens included
+    rng = np.random.Generator(np.random.PCG64(75))
+    lens = [int(x) for x in rng.integers(1100, 1500, size=70)]
+    lens[3] = 0; lens[10] = 5; lens[20] = 129; lens[30] = 64 * 4 + 1; lens[40] = 64 * 7; lens[69] = 0
+    w = W.make_workload("multichunk", dtype=W.BF16, B=70, H=16, H_kv=8, D=128, P=16, seq_lens=lens, k=900, seed=76)
+    for forced in ((0, 0), (10, 50)):
+        layer, q = make_layer(w, num_initial=forced[0], num_local=forced[1])
+        nsplit = (w.k + sum(forced) + 63) // 64
+        assert nsplit * w.H_kv * w.B >= 8192
+        print("multi-chunk attention", forced, nsplit, flush=True)
+        check_decode_against_oracle(w, layer, q, score_scale=0.2, label="multichunk %d+%d" % forced)
+    w = W.make_workload("multichunk32", dtype=W.F32, B=40, H=8, H_kv=8, D=64, P=4, seq_lens=[700] * 39 + [3], k=1700, seed=77)
+    layer, q = make_layer(w)
+    assert ((1700 + 63) // 64) * 8 * 40 >= 8192
+    check_decode_against_oracle(w, layer, q, score_scale=0.125, label="multichunk fp32")
+
+
 def test_max_seq_len_larger_than_every_sequence(gpu):
     w = W.make_workload("odd", dtype=W.F32, H=4, H_kv=2, D=64, P=16, seq_lens=[203], k=20, seed=12)
     layer, q = make_layer(w, max_seq_len=205)
