@@ -35,12 +35,12 @@ import numpy as np  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the score kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
-# counters read for plain copy kernels of known size in the same run (FETCH_SIZE x 1.966 / 1.983, WRITE_SIZE x 1.00:
+# counters read for plain copy kernels of known size in the same run (FETCH_SIZE x 1.966 / 1.982, WRITE_SIZE x 1.00:
 # profiles/decode_step_cfg4_hbm_traffic.md, profiles/decode_step_cfg2_hbm_traffic.md)
 MEASURED_TRAFFIC_BYTES = {(4, "compact"): int((512.30 * 1.966 + 31.73 * 1.00) * 2**20),
-                          (2, "compact"): int((128.26 * 1.983 + 4.63 * 1.00) * 2**20),
+                          (2, "compact"): int((128.26 * 1.982 + 4.63 * 1.00) * 2**20),
                           (4, "dense"): int((512.26 * 1.966 + 112.38 * 1.00) * 2**20),
-                          (2, "dense"): int((128.21 * 1.983 + 16.13 * 1.00) * 2**20)}
+                          (2, "dense"): int((128.21 * 1.982 + 16.13 * 1.00) * 2**20)}
 
 
 def parse():
