@@ -57,7 +57,7 @@ typedef enum ts_dtype { TS_F32 = 0, TS_BF16 = 1 } ts_dtype;
 
 /* Shape and paged-pool description shared by all calls.  Passed by const pointer [host]. */
 typedef struct ts_problem {
-  int32_t batch;        /* B  >= 1                                                               */
+  int32_t batch;        /* B  in [1, 65535]                                                      */
   int32_t chunk;        /* C  queries per sequence; 1 = decode                                   */
   int32_t num_q_heads;  /* H  (<= 128)                                                           */
   int32_t num_kv_heads; /* H_kv, a power of two, H % H_kv == 0, H / H_kv <= 8                    */

@@ -68,6 +68,7 @@ static int32_t check_problem(const ts_problem* p) {
   if (p->page_indptr == nullptr || p->page_indices == nullptr || p->seq_lens == nullptr) return TS_ERR_INVALID_ARG;
   if (p->head_dim != 64 && p->head_dim != 128) return TS_ERR_UNSUPPORTED;
   if (p->num_q_heads > 128) return TS_ERR_UNSUPPORTED;
+  if (p->batch > 65535) return TS_ERR_UNSUPPORTED;           // the sequence is a grid dimension of every kernel
   if (!is_pow2(p->num_kv_heads) || p->num_kv_heads > 32) return TS_ERR_UNSUPPORTED;
   if (p->num_q_heads / p->num_kv_heads > 8) return TS_ERR_UNSUPPORTED;
   if (!is_pow2(p->page_size)) return TS_ERR_UNSUPPORTED;

@@ -40,7 +40,7 @@ def test_workspace_bytes_and_shape_validation():
     for kw in bad:
         assert L.ts_workspace_bytes(ctypes.byref(cproblem(**kw)), 256, ctypes.byref(out)) == -1, kw
     unsup = [dict(head_dim=96), dict(num_kv_heads=3, num_q_heads=6), dict(page_size=12), dict(num_q_heads=32, num_kv_heads=2),
-             dict(num_q_heads=256, num_kv_heads=32), dict(num_local=1 << 21)]
+             dict(num_q_heads=256, num_kv_heads=32), dict(num_local=1 << 21), dict(batch=65536)]
     for kw in unsup:
         assert L.ts_workspace_bytes(ctypes.byref(cproblem(**kw)), 256, ctypes.byref(out)) == -2, kw
     assert L.ts_workspace_bytes(ctypes.byref(cproblem()), 0, ctypes.byref(out)) == -1
